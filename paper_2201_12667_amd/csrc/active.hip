@@ -1,0 +1,346 @@
+// Active-set retrieval (paper Algorithm 1 "retrieve active neurons"; Figure 1: the union of the
+// neurons returned by every table) and the index structures the float kernels consume.
+//
+//  lookup_union : one workgroup per sample.  Reads one bucket per table, sets one bit per candidate
+//                 and per label in an LDS bitmap over the neuron ids (deduplication and sorting
+//                 are free: the bitmap is swept in id order), writes the sample's row of the
+//                 [B][words] active bit matrix and per-tile population counts.
+//  scan_samples : exclusive scans over the B samples (offsets of the compact id lists, forward
+//                 work items).
+//  emit         : compact ascending id list per sample + label flags.
+//  transpose    : the bit matrix read tile-by-tile across all samples gives, for every touched row,
+//                 the ascending list of samples that touch it (wave ballots), i.e. the row-major
+//                 pair lists of the gradient/Adam kernel -- no sort, no atomics on data.
+#include "slide_internal.h"
+
+namespace slide {
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t t = __shfl_up(v, d);
+    if (lane >= d) v += t;
+  }
+  return v;
+}
+
+// Exclusive scan over a workgroup of up to 1024 threads; sm: 17 words of LDS.
+__device__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const uint32_t inc = wave_incl_scan_u32(v);
+  __syncthreads();
+  if (lane == 63) sm[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+  for (int w = 0; w < nw; ++w) { const uint32_t x = sm[w]; if (w < wave) base += x; tot += x; }
+  *total = tot;
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(1024) void lookup_union_kernel(
+    ActiveDev ad, const uint32_t* __restrict__ off, const int32_t* __restrict__ ids, uint32_t nb,
+    const uint32_t* __restrict__ codes, const int32_t* __restrict__ y_indptr,
+    const int32_t* __restrict__ y_indices, int include_labels, int32_t* __restrict__ ncand,
+    Ctrl* ctrl, int segw) {
+  extern __shared__ uint32_t lds[];
+  uint32_t* bm = lds;                    // [segw] bitmap segment
+  uint32_t* o0s = bm + segw;             // [L] bucket start inside its table
+  uint32_t* pos = o0s + ad.L;            // [L+1] exclusive prefix of the bucket lengths
+  uint32_t* sm = pos + ad.L + 1;         // [20] scan scratch + counters
+  const int i = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
+  const int lane = tid & 63;
+  if (tid == 0) { sm[17] = 0; sm[18] = 0; }
+
+  uint32_t carry = 0;
+  for (int base = 0; base < ad.L; base += nthr) {
+    const int t = base + tid;
+    uint32_t len = 0;
+    if (t < ad.L) {
+      const uint32_t code = codes[(size_t)i * ad.L + t];
+      const uint32_t a = off[(size_t)t * (nb + 1) + code];
+      const uint32_t b = off[(size_t)t * (nb + 1) + code + 1];
+      len = min(b - a, (uint32_t)ad.C);
+      o0s[t] = a;
+    }
+    uint32_t total;
+    const uint32_t ex = block_excl_scan(len, sm, &total);
+    if (t < ad.L) pos[t] = carry + ex;
+    carry += total;
+    __syncthreads();
+  }
+  if (tid == 0) pos[ad.L] = carry;
+  __syncthreads();
+  const uint32_t T = pos[ad.L];
+  const int y0 = include_labels ? y_indptr[i] : 0;
+  const int nlab = include_labels ? y_indptr[i + 1] - y0 : 0;
+
+  uint32_t my_cnt = 0;
+  for (int seg0 = 0; seg0 < ad.NWpad; seg0 += segw) {
+    const int sw = min(segw, ad.NWpad - seg0);
+    const int64_t lo = (int64_t)seg0 * 32, hi = lo + (int64_t)sw * 32;
+    for (int w = tid; w < sw; w += nthr) bm[w] = 0;
+    __syncthreads();
+    for (int q = tid; q < nlab; q += nthr) {
+      const int y = y_indices[y0 + q];
+      if (y < 0 || y >= ad.N) { if (seg0 == 0) atomicOr(&ctrl->status, SLIDE_FLAG_BAD_LABEL); continue; }
+      if (y >= lo && y < hi) {
+        const uint32_t bit = 1u << (y & 31);
+        const uint32_t old = atomicOr(&bm[(y - lo) >> 5], bit);
+        if (!(old & bit)) atomicAdd(&sm[17], 1u);       // distinct labels
+      }
+    }
+    __syncthreads();                                    // labels first: their "new bit" test must not
+    for (uint32_t c = tid; c < T; c += nthr) {          // see candidate bits
+      int a = 0, b = ad.L;                              // last t with pos[t] <= c
+      while (b - a > 1) { const int mid = (a + b) >> 1; if (pos[mid] <= c) a = mid; else b = mid; }
+      const int j = ids[(size_t)a * ad.N + o0s[a] + (c - pos[a])];
+      if (j >= lo && j < hi) atomicOr(&bm[(j - lo) >> 5], 1u << (j & 31));
+    }
+    __syncthreads();
+    for (int wb = 0; wb < sw; wb += nthr) {
+      const int w = wb + tid;
+      const uint32_t word = w < sw ? bm[w] : 0u;
+      uint32_t c = __popc(word);
+      my_cnt += c;
+      if (w < sw) ad.act[(size_t)i * ad.NWpad + seg0 + w] = word;
+      for (int d = 1; d < ad.TW; d <<= 1) c += __shfl_xor(c, d);
+      if (w < sw && (lane & (ad.TW - 1)) == 0) ad.rankT[(size_t)i * ad.NT + (seg0 + w) / ad.TW] = c;
+    }
+    __syncthreads();
+  }
+  for (int d = 32; d > 0; d >>= 1) my_cnt += __shfl_xor(my_cnt, d);
+  if (lane == 0) atomicAdd(&sm[18], my_cnt);
+  __syncthreads();
+  if (tid == 0) { ad.cnt[i] = (int32_t)sm[18]; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; }
+}
+
+__global__ __launch_bounds__(1024) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
+                                                            Ctrl* ctrl) {
+  __shared__ uint32_t sm[20];
+  uint32_t carry_a = 0, carry_c = 0;
+  unsigned long long cand = 0;
+  for (int base = 0; base < ad.B; base += blockDim.x) {
+    const int i = base + threadIdx.x;
+    const uint32_t n = i < ad.B ? (uint32_t)ad.cnt[i] : 0u;
+    const uint32_t ch = (n + kChunk - 1) / kChunk;
+    uint32_t ta, tc;
+    const uint32_t ea = block_excl_scan(n, sm, &ta);
+    __syncthreads();
+    const uint32_t ec = block_excl_scan(ch, sm, &tc);
+    if (i < ad.B) {
+      ad.as_ptr[i] = (int32_t)(carry_a + ea);
+      ad.chunk_ptr[i] = (int32_t)(carry_c + ec);
+      for (uint32_t k = 0; k < ch; ++k) ad.chunk_sample[carry_c + ec + k] = i;
+      cand += (unsigned long long)ncand[i];
+    }
+    carry_a += ta; carry_c += tc;
+    __syncthreads();
+  }
+  // total of the candidate counts (statistics only)
+  __shared__ unsigned long long cs[16];
+  for (int d = 32; d > 0; d >>= 1) cand += __shfl_xor(cand, d);
+  if ((threadIdx.x & 63) == 0) cs[threadIdx.x >> 6] = cand;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long c = 0;
+    for (unsigned w = 0; w < blockDim.x / 64; ++w) c += cs[w];
+    ad.as_ptr[ad.B] = (int32_t)carry_a;
+    ad.chunk_ptr[ad.B] = (int32_t)carry_c;
+    ctrl->total_pairs = carry_a;
+    ctrl->total_chunks = carry_c;
+    ctrl->candidates_lo = (uint32_t)c;
+    ctrl->candidates_hi = (uint32_t)(c >> 32);
+    ctrl->u2 = ctrl->p2 = ctrl->u1 = ctrl->p1 = 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void emit_kernel(ActiveDev ad, const int32_t* __restrict__ y_indptr,
+                                                   const int32_t* __restrict__ y_indices, int include_labels) {
+  __shared__ uint32_t sm[20];
+  const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  uint32_t* rk = ad.rankT + (size_t)i * ad.NT;
+  uint32_t carry = 0;
+  for (int base = 0; base < ad.NT; base += 256) {
+    const int t = base + tid;
+    const uint32_t v = t < ad.NT ? rk[t] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_excl_scan(v, sm, &total);
+    if (t < ad.NT) rk[t] = carry + ex;
+    carry += total;
+    __syncthreads();
+  }
+  const int base_i = ad.as_ptr[i];
+  const uint32_t* arow = ad.act + (size_t)i * ad.NWpad;
+  for (int wb = 0; wb < ad.NWpad; wb += 256) {
+    const int w = wb + tid;
+    uint32_t word = w < ad.NWpad ? arow[w] : 0u;
+    const uint32_t c = __popc(word);
+    uint32_t inc = c;
+    for (int d = 1; d < ad.TW; d <<= 1) {
+      const uint32_t t = __shfl_up(inc, d, ad.TW);
+      if ((lane & (ad.TW - 1)) >= d) inc += t;
+    }
+    if (word) {
+      int slot = base_i + (int)(rk[w / ad.TW] + inc - c);
+      while (word) {
+        const int b = __ffs(word) - 1;
+        ad.as_ids[slot] = w * 32 + b;
+        ad.as_lab[slot] = 0;
+        ++slot;
+        word &= word - 1;
+      }
+    }
+  }
+  __syncthreads();
+  if (!include_labels) return;
+  const int n = ad.cnt[i], y0 = y_indptr[i], nlab = y_indptr[i + 1] - y0;
+  for (int q = tid; q < nlab; q += 256) {
+    const int y = y_indices[y0 + q];
+    int slot = -1;
+    if (y >= 0 && y < ad.N) {
+      int a = 0, b = n;
+      while (a < b) { const int mid = (a + b) >> 1; if (ad.as_ids[base_i + mid] < y) a = mid + 1; else b = mid; }
+      if (a < n && ad.as_ids[base_i + a] == y) {
+        ad.as_lab[base_i + a] = 1;
+        slot = base_i + a;
+        for (int q2 = 0; q2 < q; ++q2) if (y_indices[y0 + q2] == y) { slot = -1; break; }   // repeated label
+      }
+    }
+    ad.ylist[y0 + q] = slot;
+  }
+}
+
+// One workgroup per tile of TW bitmap words, all samples.  FEAT = false: the active bit matrix
+// (coefficient index = slot of the pair in the sample-major arrays).  FEAT = true: the feature bit
+// matrix of the batch (coefficient index = position in the CSR value array; the matrix is
+// cleared behind the read so it is all-zero again for the next batch).
+template <bool FEAT>
+__global__ __launch_bounds__(256) void transpose_kernel(int B, int Bpad, int TW, int NWpad, uint32_t* bits,
+                                                        const uint32_t* __restrict__ rankT, int NT,
+                                                        const int32_t* __restrict__ as_ptr,
+                                                        const int32_t* __restrict__ x_indptr,
+                                                        const int32_t* __restrict__ x_indices, PairsDev pd) {
+  extern __shared__ uint32_t lds[];
+  uint32_t* tile = lds;                                  // [TW][Bpad]
+  uint32_t* sb = tile + (size_t)TW * Bpad;                // [Bpad] slot base of the sample in this tile
+  uint16_t* rk = (uint16_t*)(sb + Bpad);                 // [TW][Bpad] in-tile rank before the word
+  const int tileno = blockIdx.x, tid = threadIdx.x;
+  for (int i = tid; i < Bpad; i += 256) {
+    uint32_t run = 0;
+    uint32_t* src = bits + (size_t)i * NWpad + (size_t)tileno * TW;
+    for (int w = 0; w < TW; ++w) {
+      uint32_t x = 0;
+      if (i < B) {
+        x = src[w];
+        if (FEAT && x) src[w] = 0;
+      }
+      tile[w * Bpad + i] = x;
+      if (!FEAT) rk[w * Bpad + i] = (uint16_t)run;
+      run += __popc(x);
+    }
+    if (!FEAT) sb[i] = i < B ? (uint32_t)as_ptr[i] + rankT[(size_t)i * NT + tileno] : 0u;
+  }
+  __syncthreads();
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int groups = Bpad >> 6;
+  for (int w = wave; w < TW; w += 4) {
+    uint32_t u = 0, np = 0;
+    for (int k = 0; k < groups; ++k) { const uint32_t x = tile[w * Bpad + k * 64 + lane]; u |= x; np += __popc(x); }
+    for (int d = 32; d > 0; d >>= 1) { u |= __shfl_xor(u, d); np += __shfl_xor(np, d); }
+    u = __builtin_amdgcn_readfirstlane(u);
+    if (u == 0) continue;
+    uint32_t ubase = 0, po = 0;
+    if (lane == 0) { ubase = atomicAdd(pd.ucount, (uint32_t)__popc(u)); po = atomicAdd(pd.pcount, np); }
+    ubase = __builtin_amdgcn_readfirstlane(ubase);
+    po = __builtin_amdgcn_readfirstlane(po);
+    while (u) {
+      const int b = __ffs(u) - 1;
+      u &= u - 1;
+      const int row = (tileno * TW + w) * 32 + b;
+      uint32_t cntj = 0;
+      for (int k = 0; k < groups; ++k) {
+        const int i = k * 64 + lane;
+        const uint32_t x = tile[w * Bpad + i];
+        const bool has = (x >> b) & 1u;
+        const unsigned long long mk = __ballot(has);
+        if (has) {
+          const uint32_t p = po + cntj + __popcll(mk & ((1ull << lane) - 1ull));
+          pd.psample[p] = i;
+          if (!FEAT) {
+            pd.psrc[p] = (int32_t)(sb[i] + rk[w * Bpad + i] + __popc(x & ((1u << b) - 1u)));
+          } else {
+            int a = x_indptr[i], e = x_indptr[i + 1];
+            while (a < e) { const int mid = (a + e) >> 1; if (x_indices[mid] < row) a = mid + 1; else e = mid; }
+            pd.psrc[p] = a;
+          }
+        }
+        cntj += (uint32_t)__popcll(mk);
+      }
+      if (lane == 0) { pd.urow[ubase] = row; pd.ustart[ubase] = po; pd.ucnt[ubase] = (int32_t)cntj; }
+      ++ubase;
+      po += cntj;
+    }
+  }
+}
+
+static size_t transpose_lds(int TW, int Bpad) { return (size_t)TW * Bpad * 6 + (size_t)Bpad * 4; }
+
+hipError_t launch_transpose_active(const ActiveDev& ad, const PairsDev& pd, hipStream_t s) {
+  const int Bpad = (ad.B + 63) & ~63;
+  hipLaunchKernelGGL(transpose_kernel<false>, dim3(ad.NT), dim3(256), transpose_lds(ad.TW, Bpad), s, ad.B, Bpad,
+                     ad.TW, ad.NWpad, ad.act, ad.rankT, ad.NT, ad.as_ptr, nullptr, nullptr, pd);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_features(int B, int TW, int DWpad, uint32_t* xbm, const int32_t* x_indptr,
+                                     const int32_t* x_indices, const PairsDev& pd, hipStream_t s) {
+  const int Bpad = (B + 63) & ~63;
+  hipLaunchKernelGGL(transpose_kernel<true>, dim3(DWpad / TW), dim3(256), transpose_lds(TW, Bpad), s, B, Bpad, TW,
+                     DWpad, xbm, nullptr, 0, nullptr, x_indptr, x_indices, pd);
+  return hipGetLastError();
+}
+
+hipError_t active_setup_attributes(size_t* lds_limit_out) {
+  int dev = 0, lim = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  e = hipDeviceGetAttribute(&lim, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+  if (e != hipSuccess) return e;
+  if (lim > 160 * 1024) lim = 160 * 1024;
+  e = hipFuncSetAttribute((const void*)lookup_union_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)transpose_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)transpose_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  if (e != hipSuccess) return e;
+  *lds_limit_out = (size_t)lim;
+  return hipSuccess;
+}
+
+hipError_t launch_lookup_union(const ActiveDev& ad, const TablesDev& td, const uint32_t* codes,
+                               const int32_t* y_indptr, const int32_t* y_indices, int include_labels,
+                               int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s) {
+  const size_t fixed = ((size_t)2 * ad.L + 1 + 20) * 4;
+  size_t avail = (lds_limit - fixed) / 4;
+  int segw = (int)(avail / 32 * 32);
+  if (segw > ad.NWpad) segw = ad.NWpad;
+  const size_t bytes = (size_t)segw * 4 + fixed;
+  hipLaunchKernelGGL(lookup_union_kernel, dim3(ad.B), dim3(1024), bytes, s, ad, td.off, td.ids, td.nb, codes,
+                     y_indptr, y_indices, include_labels, ncand, ctrl, segw);
+  return hipGetLastError();
+}
+
+hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, hipStream_t s) {
+  hipLaunchKernelGGL(scan_samples_kernel, dim3(1), dim3(1024), 0, s, ad, ncand, ctrl);
+  return hipGetLastError();
+}
+
+hipError_t launch_emit(const ActiveDev& ad, const int32_t* y_indptr, const int32_t* y_indices,
+                       int include_labels, hipStream_t s) {
+  hipLaunchKernelGGL(emit_kernel, dim3(ad.B), dim3(256), 0, s, ad, y_indptr, y_indices, include_labels);
+  return hipGetLastError();
+}
+
+}  // namespace slide

@@ -1,0 +1,515 @@
+// Host side of the C ABI: validation, workspace layout, kernel sequencing on the caller's stream.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "slide_internal.h"
+
+using namespace slide;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+  // derived sizes
+  int Bmax, Bpad, H, L, K, C, TW, NWpad, NT, DWpad, bits;
+  int64_t N, D, Amax, max_chunks, U2max, U1max, P1max;
+  uint32_t nb, nseg, wl_cap;
+  size_t hash_words;
+  // workspace offsets
+  size_t ctrl, hashw, xbm, h, dh, codes, act, rankT, cnt, ny, ncand, as_ptr, chunk_ptr, chunk_sample, as_ids,
+      as_lab, ylist, z, delta, partials, msum, loss_i, urow2, ustart2, ucnt2, psample2, psrc2, urow1, ustart1,
+      ucnt1, psample1, psrc1, codes_t, rank_t, segsum, worklist, ws_total;
+  // tables offsets
+  size_t t_off, t_ids, tables_total;
+};
+
+int ilog2_exact(int x) {
+  int b = 0;
+  while ((1 << b) < x) ++b;
+  return (1 << b) == x ? b : -1;
+}
+
+#define FAIL(code, ...)                                  \
+  do {                                                   \
+    char buf_[512];                                      \
+    snprintf(buf_, sizeof(buf_), __VA_ARGS__);           \
+    err = buf_;                                          \
+    return code;                                         \
+  } while (0)
+
+int make_layout(const slide_config* c, Layout* lo, std::string& err) {
+  if (!c) FAIL(SLIDE_EINVAL, "config is NULL");
+  if (c->struct_size != sizeof(slide_config) || c->abi_version != SLIDE_ABI_VERSION)
+    FAIL(SLIDE_EINVAL, "slide_config size/version mismatch (got %u/%u, want %zu/%u)", c->struct_size,
+         c->abi_version, sizeof(slide_config), SLIDE_ABI_VERSION);
+  if (c->hidden_dim < 4 || c->hidden_dim > 2048 || c->hidden_dim % 4) FAIL(SLIDE_EINVAL, "hidden_dim must be a multiple of 4 in [4, 2048]");
+  if (c->num_classes < 1 || c->num_classes > (int64_t)1 << 30) FAIL(SLIDE_EINVAL, "num_classes out of range");
+  if (c->input_dim < 0 || c->input_dim > (int64_t)1 << 30) FAIL(SLIDE_EINVAL, "input_dim out of range");
+  if (c->max_batch < 1 || c->max_batch > 4096) FAIL(SLIDE_EINVAL, "max_batch must be in [1, 4096]");
+  if (c->K < 1 || c->L < 1 || c->L > 65535) FAIL(SLIDE_EINVAL, "K and L must be positive (L <= 65535)");
+  if (c->bucket_cap < 1 || c->bucket_cap > 1024) FAIL(SLIDE_EINVAL, "bucket_cap must be in [1, 1024]");
+  if (c->max_labels_per_batch < 0 || c->max_nnz_per_batch < 0) FAIL(SLIDE_EINVAL, "negative batch capacity");
+  if (c->input_dim > 0 && c->max_nnz_per_batch < 1) FAIL(SLIDE_EINVAL, "max_nnz_per_batch must be positive in sparse-input mode");
+  if (c->overflow_policy != SLIDE_KEEP_LOWEST_ID && c->overflow_policy != SLIDE_KEEP_PRIORITY) FAIL(SLIDE_EINVAL, "unknown overflow_policy");
+  if (c->rebuild_every < 0) FAIL(SLIDE_EINVAL, "rebuild_every must be >= 0");
+  if (!(c->lr > 0) || !(c->beta1 >= 0 && c->beta1 < 1) || !(c->beta2 >= 0 && c->beta2 < 1) || !(c->eps > 0))
+    FAIL(SLIDE_EINVAL, "Adam constants out of range");
+  lo->H = c->hidden_dim; lo->L = c->L; lo->K = c->K; lo->C = c->bucket_cap; lo->N = c->num_classes; lo->D = c->input_dim;
+  if (c->hash_kind == SLIDE_HASH_DWTA) {
+    const int lg = ilog2_exact(c->dwta_bin);
+    if (lg < 1 || lg > 4) FAIL(SLIDE_EINVAL, "dwta_bin must be 2, 4, 8 or 16");
+    if (c->hidden_dim % c->dwta_bin) FAIL(SLIDE_EINVAL, "hidden_dim must be a multiple of dwta_bin");
+    lo->bits = c->K * lg;
+    lo->hash_words = (size_t)c->K * c->L * (c->dwta_bin / 2);
+  } else if (c->hash_kind == SLIDE_HASH_SIMHASH) {
+    if (c->srp_nnz < 1 || c->srp_nnz > c->hidden_dim) FAIL(SLIDE_EINVAL, "srp_nnz must be in [1, hidden_dim]");
+    lo->bits = c->K;
+    lo->hash_words = (size_t)c->K * c->L * ((c->srp_nnz + 1) / 2);
+  } else {
+    FAIL(SLIDE_EINVAL, "unknown hash_kind");
+  }
+  if (lo->bits > 28) FAIL(SLIDE_EINVAL, "hash code wider than 28 bits");
+  lo->nb = 1u << lo->bits;
+  lo->nseg = (lo->nb + kScanSeg - 1) / kScanSeg;
+  lo->Bmax = c->max_batch;
+  lo->Bpad = (c->max_batch + 63) & ~63;
+  int tw = 32;
+  while (tw > 1 && tw * lo->Bpad > 8192) tw >>= 1;
+  lo->TW = tw;
+  lo->NWpad = (int)(((lo->N + 31) / 32 + 31) / 32 * 32);
+  lo->NT = lo->NWpad / tw;
+  lo->DWpad = (int)(((lo->D + 31) / 32 + 31) / 32 * 32);
+  const int64_t per_sample = std::min<int64_t>((int64_t)c->L * c->bucket_cap, lo->N);
+  lo->Amax = std::min<int64_t>((int64_t)c->max_batch * lo->N, (int64_t)c->max_batch * per_sample + c->max_labels_per_batch);
+  if (lo->Amax >= ((int64_t)1 << 31) - 64) FAIL(SLIDE_EINVAL, "max_batch * L * bucket_cap does not fit 31 bits");
+  if ((int64_t)c->L * lo->N >= ((int64_t)1 << 32)) FAIL(SLIDE_EINVAL, "L * num_classes does not fit 32 bits");
+  lo->max_chunks = lo->Amax / kChunk + c->max_batch + 1;
+  lo->U2max = std::min<int64_t>(lo->N, lo->Amax);
+  lo->P1max = c->max_nnz_per_batch;
+  lo->U1max = std::min<int64_t>(lo->D, lo->P1max);
+  const int small = std::min(kSmallBucket, c->bucket_cap);
+  const uint64_t wl = (uint64_t)c->L * (uint64_t)(lo->N / (small + 1) + 1);
+  lo->wl_cap = (uint32_t)std::min<uint64_t>(wl, 0xfffffff0u);
+
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  const size_t B = lo->Bmax, H = lo->H, A = (size_t)lo->Amax;
+  lo->ctrl = take(sizeof(Ctrl));
+  lo->hashw = take(lo->hash_words * 4);
+  lo->xbm = take(lo->D ? B * lo->DWpad * 4 : 0);
+  lo->h = take(lo->D ? B * H * 4 : 0);
+  lo->dh = take(B * H * 4);
+  lo->codes = take(B * lo->L * 4);
+  lo->act = take(B * lo->NWpad * 4);
+  lo->rankT = take(B * lo->NT * 4);
+  lo->cnt = take(B * 4); lo->ny = take(B * 4); lo->ncand = take(B * 4);
+  lo->as_ptr = take((B + 1) * 4); lo->chunk_ptr = take((B + 1) * 4);
+  lo->chunk_sample = take((size_t)lo->max_chunks * 4);
+  lo->as_ids = take(A * 4); lo->as_lab = take(A); lo->ylist = take((size_t)c->max_labels_per_batch * 4 + 4);
+  lo->z = take(A * 4); lo->delta = take(A * 4);
+  lo->partials = take((size_t)lo->max_chunks * (H + 4) * 4);
+  lo->msum = take(B * 8); lo->loss_i = take(B * 4);
+  lo->urow2 = take((size_t)lo->U2max * 4); lo->ustart2 = take((size_t)lo->U2max * 4); lo->ucnt2 = take((size_t)lo->U2max * 4);
+  lo->psample2 = take(A * 4); lo->psrc2 = take(A * 4);
+  lo->urow1 = take((size_t)lo->U1max * 4); lo->ustart1 = take((size_t)lo->U1max * 4); lo->ucnt1 = take((size_t)lo->U1max * 4);
+  lo->psample1 = take((size_t)lo->P1max * 4); lo->psrc1 = take((size_t)lo->P1max * 4);
+  lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->rank_t = take((size_t)lo->L * lo->N * 4);
+  lo->segsum = take((size_t)lo->L * lo->nseg * 4);
+  lo->worklist = take((size_t)lo->wl_cap * 8);
+  lo->ws_total = o;
+  o = 0;
+  lo->t_off = take((size_t)lo->L * (lo->nb + 1) * 4);
+  lo->t_ids = take((size_t)lo->L * lo->N * 4);
+  lo->tables_total = o;
+  return SLIDE_OK;
+}
+
+}  // namespace
+
+struct slide_ctx {
+  slide_config cfg;
+  slide_buffers buf;
+  Layout lo;
+  HashDev hd;
+  TablesDev td;
+  uint32_t prio_a, prio_b;
+  size_t lds_limit;
+  int64_t t = 0, r = 0;
+  bool built = false;
+  int last_B = 0;
+  const float* last_h = nullptr;
+  float* last_dh = nullptr;
+  std::string err;
+  char* ws() const { return (char*)buf.workspace; }
+  template <typename T> T* at(size_t off) const { return (T*)(ws() + off); }
+  Ctrl* ctrl() const { return at<Ctrl>(lo.ctrl); }
+};
+
+namespace {
+
+int set_err(slide_ctx* ctx, int code, const char* fmt, ...) {
+  char b[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(b, sizeof(b), fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = b; else g_last_error = b;
+  return code;
+}
+
+#define HIPCHK(ctx, expr)                                                                         \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return set_err(ctx, SLIDE_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+ActiveDev make_active(const slide_ctx* c, int B) {
+  ActiveDev ad;
+  const Layout& lo = c->lo;
+  ad.B = B; ad.L = lo.L; ad.C = lo.C; ad.TW = lo.TW; ad.N = lo.N; ad.NWpad = lo.NWpad; ad.NT = lo.NT;
+  ad.act = c->at<uint32_t>(lo.act); ad.rankT = c->at<uint32_t>(lo.rankT);
+  ad.cnt = c->at<int32_t>(lo.cnt); ad.ny = c->at<int32_t>(lo.ny);
+  ad.as_ptr = c->at<int32_t>(lo.as_ptr); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
+  ad.chunk_sample = c->at<int32_t>(lo.chunk_sample);
+  ad.as_ids = c->at<int32_t>(lo.as_ids); ad.as_lab = c->at<uint8_t>(lo.as_lab); ad.ylist = c->at<int32_t>(lo.ylist);
+  return ad;
+}
+
+int check_batch(slide_ctx* ctx, const slide_batch* b, bool need_labels) {
+  const slide_config& c = ctx->cfg;
+  if (!b) return set_err(ctx, SLIDE_EINVAL, "batch is NULL");
+  if (b->batch < 1 || b->batch > c.max_batch) return set_err(ctx, SLIDE_EINVAL, "batch size %d outside [1, max_batch=%d]", b->batch, c.max_batch);
+  if (c.input_dim > 0) {
+    if (!b->x_indptr || (b->nnz > 0 && (!b->x_indices || !b->x_values))) return set_err(ctx, SLIDE_EINVAL, "sparse-input mode needs x_indptr/x_indices/x_values");
+    if (b->nnz < 0 || b->nnz > c.max_nnz_per_batch) return set_err(ctx, SLIDE_ENOMEM, "batch nnz %d exceeds max_nnz_per_batch %d", b->nnz, c.max_nnz_per_batch);
+  } else if (!b->hidden) {
+    return set_err(ctx, SLIDE_EINVAL, "dense-hidden mode needs batch->hidden");
+  }
+  if (need_labels) {
+    if (!b->y_indptr || (b->num_labels > 0 && !b->y_indices)) return set_err(ctx, SLIDE_EINVAL, "training needs y_indptr/y_indices");
+    if (b->num_labels < 0 || b->num_labels > c.max_labels_per_batch) return set_err(ctx, SLIDE_ENOMEM, "batch labels %d exceed max_labels_per_batch %d", b->num_labels, c.max_labels_per_batch);
+  }
+  return SLIDE_OK;
+}
+
+// Hidden activations (a1), codes (a2), active sets (a3) and the logits pass (a4).
+int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out) {
+  const Layout& lo = ctx->lo;
+  const int B = b->batch;
+  const float* h = b->hidden;
+  if (lo.D > 0) {
+    float* hw = ctx->at<float>(lo.h);
+    HIPCHK(ctx, launch_spmm_relu(B, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
+                                 ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), lo.DWpad, ctx->ctrl(), s));
+    h = hw;
+  }
+  ctx->last_h = h;
+  ctx->last_B = B;
+  uint32_t* codes = ctx->at<uint32_t>(lo.codes);
+  HIPCHK(ctx, launch_hash(ctx->hd, h, B, codes, lo.L, 1, nullptr, nullptr, lo.nb, 4, s));
+  ActiveDev ad = make_active(ctx, B);
+  int32_t* ncand = ctx->at<int32_t>(lo.ncand);
+  HIPCHK(ctx, launch_lookup_union(ad, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0, ncand,
+                                  ctx->ctrl(), ctx->lds_limit, s));
+  HIPCHK(ctx, launch_scan_samples(ad, ncand, ctx->ctrl(), s));
+  HIPCHK(ctx, launch_emit(ad, b->y_indptr, b->y_indices, with_labels ? 1 : 0, s));
+  HIPCHK(ctx, launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
+                             ctx->at<float>(lo.partials), ctx->ctrl(), s));
+  *ad_out = ad;
+  return SLIDE_OK;
+}
+
+int do_build(slide_ctx* ctx, hipStream_t s) {
+  const Layout& lo = ctx->lo;
+  HIPCHK(ctx, launch_build_tables(ctx->hd, ctx->td, ctx->buf.W2, ctx->at<uint32_t>(lo.codes_t),
+                                  ctx->at<uint32_t>(lo.rank_t), ctx->at<uint32_t>(lo.segsum),
+                                  ctx->at<uint64_t>(lo.worklist), lo.wl_cap, ctx->ctrl(), ctx->cfg.overflow_policy,
+                                  (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, 40, s));
+  return SLIDE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int slide_query_memory(const slide_config* cfg, slide_mem_req* out) {
+  Layout lo;
+  std::string err;
+  if (!out) { g_last_error = "out is NULL"; return SLIDE_EINVAL; }
+  const int rc = make_layout(cfg, &lo, err);
+  if (rc != SLIDE_OK) { g_last_error = err; return rc; }
+  out->tables_bytes = lo.tables_total;
+  out->workspace_bytes = lo.ws_total;
+  return SLIDE_OK;
+}
+
+int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_hash_params* hp, slide_ctx** out) {
+  if (!out) return set_err(nullptr, SLIDE_EINVAL, "out is NULL");
+  *out = nullptr;
+  Layout lo;
+  std::string err;
+  int rc = make_layout(cfg, &lo, err);
+  if (rc != SLIDE_OK) { g_last_error = err; return rc; }
+  if (!buf || !hp) return set_err(nullptr, SLIDE_EINVAL, "buffers / hash params are NULL");
+  if (!buf->W2 || !buf->b2 || !buf->mW2 || !buf->vW2 || !buf->mb2 || !buf->vb2)
+    return set_err(nullptr, SLIDE_EINVAL, "output-layer parameter / Adam-state pointer is NULL");
+  if (cfg->input_dim > 0 && (!buf->W1 || !buf->b1 || !buf->mW1 || !buf->vW1 || !buf->mb1 || !buf->vb1))
+    return set_err(nullptr, SLIDE_EINVAL, "hidden-layer parameter / Adam-state pointer is NULL");
+  const void* al[] = {buf->W1, buf->W2, buf->mW1, buf->vW1, buf->mW2, buf->vW2, buf->b1, buf->workspace, buf->tables};
+  for (const void* p : al)
+    if (((uintptr_t)p) & 15) return set_err(nullptr, SLIDE_EINVAL, "device buffers must be 16-byte aligned");
+  if (!buf->tables || buf->tables_bytes < lo.tables_total)
+    return set_err(nullptr, SLIDE_ENOMEM, "tables buffer too small: %zu < %zu", buf->tables_bytes, lo.tables_total);
+  if (!buf->workspace || buf->workspace_bytes < lo.ws_total)
+    return set_err(nullptr, SLIDE_ENOMEM, "workspace too small: %zu < %zu", buf->workspace_bytes, lo.ws_total);
+
+  // hash-function parameters -> packed 16-bit coordinate words
+  const int H = cfg->hidden_dim, NH = cfg->K * cfg->L;
+  std::vector<uint32_t> words(lo.hash_words, 0u);
+  if (cfg->hash_kind == SLIDE_HASH_DWTA) {
+    if (!hp->dwta_perm) return set_err(nullptr, SLIDE_EINVAL, "dwta_perm is NULL");
+    const int m = cfg->dwta_bin, P = H / m;
+    std::vector<uint8_t> seen(H);
+    const int NP = (NH + P - 1) / P;
+    for (int q = 0; q < NP; ++q) {
+      std::fill(seen.begin(), seen.end(), 0);
+      for (int c = 0; c < H; ++c) {
+        const int v = hp->dwta_perm[(size_t)q * H + c];
+        if (v < 0 || v >= H || seen[v]) return set_err(nullptr, SLIDE_EINVAL, "dwta_perm row %d is not a permutation of 0..H-1", q);
+        seen[v] = 1;
+      }
+    }
+    for (int e = 0; e < NH; ++e) {
+      const int q = e / P, b = e % P;
+      for (int p = 0; p < m; ++p) {
+        const uint32_t c = (uint32_t)hp->dwta_perm[(size_t)q * H + (size_t)b * m + p];
+        words[(size_t)e * (m / 2) + p / 2] |= c << (16 * (p & 1));
+      }
+    }
+  } else {
+    if (!hp->srp_idx || !hp->srp_sign) return set_err(nullptr, SLIDE_EINVAL, "srp_idx / srp_sign is NULL");
+    const int S = cfg->srp_nnz, half = (S + 1) / 2;
+    for (int e = 0; e < NH; ++e)
+      for (int s = 0; s < S; ++s) {
+        const int c = hp->srp_idx[(size_t)e * S + s];
+        const int sg = hp->srp_sign[(size_t)e * S + s];
+        if (c < 0 || c >= H || (sg != 1 && sg != -1)) return set_err(nullptr, SLIDE_EINVAL, "bad sparse-projection entry (bit %d, position %d)", e, s);
+        const uint32_t v = (uint32_t)c | (sg < 0 ? 0x8000u : 0u);
+        words[(size_t)e * half + s / 2] |= v << (16 * (s & 1));
+      }
+  }
+  if (!(hp->dens_a & 1u) || !(hp->dens_b & 1u) || !(hp->prio_a & 1u) || !(hp->prio_b & 1u))
+    return set_err(nullptr, SLIDE_EINVAL, "dens_a, dens_b, prio_a, prio_b must be odd");
+
+  slide_ctx* ctx = new slide_ctx();
+  ctx->cfg = *cfg; ctx->buf = *buf; ctx->lo = lo;
+  ctx->prio_a = hp->prio_a; ctx->prio_b = hp->prio_b;
+  const char* what = "hipMemset(ctrl)";
+  hipError_t e = hipMemset(ctx->ws() + lo.ctrl, 0, sizeof(Ctrl));
+  if (e == hipSuccess && lo.D) { what = "hipMemset(feature bits)"; e = hipMemset(ctx->ws() + lo.xbm, 0, (size_t)lo.Bmax * lo.DWpad * 4); }
+  if (e == hipSuccess && !words.empty()) { what = "hipMemcpy(hash parameters)"; e = hipMemcpy(ctx->ws() + lo.hashw, words.data(), words.size() * 4, hipMemcpyHostToDevice); }
+  if (e == hipSuccess) { what = "hipFuncSetAttribute(hash kernels)"; e = hash_setup_attributes(H); }
+  if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
+  if (e == hipSuccess) { what = "hipDeviceSynchronize"; e = hipDeviceSynchronize(); }
+  if (e != hipSuccess) {
+    set_err(nullptr, SLIDE_EHIP, "slide_init: %s failed: %s", what, hipGetErrorString(e));
+    delete ctx;
+    return SLIDE_EHIP;
+  }
+  if (hash_lds_bytes(H) > ctx->lds_limit) {
+    set_err(nullptr, SLIDE_EINVAL, "hidden_dim %d needs %zu bytes of LDS, device offers %zu", H, hash_lds_bytes(H), ctx->lds_limit);
+    delete ctx;
+    return SLIDE_EINVAL;
+  }
+  HashDev& hd = ctx->hd;
+  hd.kind = cfg->hash_kind; hd.H = H; hd.K = cfg->K; hd.L = cfg->L; hd.NH = NH;
+  hd.m = cfg->dwta_bin; hd.lgm = cfg->hash_kind == SLIDE_HASH_DWTA ? ilog2_exact(cfg->dwta_bin) : 0;
+  hd.S = cfg->srp_nnz; hd.Spad = (cfg->srp_nnz + 1) / 2 * 2;
+  hd.words = ctx->at<uint32_t>(lo.hashw);
+  hd.dens_a = hp->dens_a; hd.dens_b = hp->dens_b;
+  TablesDev& td = ctx->td;
+  td.off = (uint32_t*)((char*)buf->tables + lo.t_off);
+  td.ids = (int32_t*)((char*)buf->tables + lo.t_ids);
+  td.nb = lo.nb; td.N = lo.N; td.L = lo.L; td.C = lo.C;
+  *out = ctx;
+  return SLIDE_OK;
+}
+
+int slide_build_tables(slide_ctx* ctx, void* hip_stream) {
+  if (!ctx) return SLIDE_EINVAL;
+  if (ctx->built) ctx->r += 1;
+  const int rc = do_build(ctx, (hipStream_t)hip_stream);
+  if (rc == SLIDE_OK) ctx->built = true;
+  return rc;
+}
+
+int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* hip_stream) {
+  if (!ctx) return SLIDE_EINVAL;
+  if (!ctx->built) return set_err(ctx, SLIDE_ESTATE, "slide_build_tables must run before slide_train_step");
+  if (!d_loss) return set_err(ctx, SLIDE_EINVAL, "d_loss is NULL");
+  int rc = check_batch(ctx, b, true);
+  if (rc != SLIDE_OK) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const Layout& lo = ctx->lo;
+  const slide_config& c = ctx->cfg;
+  ActiveDev ad;
+  if ((rc = forward_common(ctx, b, true, s, &ad)) != SLIDE_OK) return rc;
+  float* dh = ctx->at<float>(lo.dh);
+  float* delta = ctx->at<float>(lo.delta);
+  HIPCHK(ctx, launch_combine(ad, lo.H, ctx->last_h, ctx->at<float>(lo.z), ctx->at<float>(lo.partials), ctx->buf.W2,
+                             b->y_indptr, ad.ylist, delta, dh, b->dhidden_out, ctx->at<float>(lo.loss_i),
+                             ctx->at<float>(lo.msum), s));
+  ctx->last_dh = dh;
+  const int64_t t = ctx->t + 1;
+  AdamDev a;
+  a.beta1 = (float)c.beta1; a.omb1 = (float)(1.0 - c.beta1);
+  a.beta2 = (float)c.beta2; a.omb2 = (float)(1.0 - c.beta2);
+  a.lr = (float)c.lr; a.eps = (float)c.eps;
+  a.inv_bc1 = (float)(1.0 / (1.0 - std::pow(c.beta1, (double)t)));
+  a.inv_bc2 = (float)(1.0 / (1.0 - std::pow(c.beta2, (double)t)));
+  PairsDev p2;
+  p2.urow = ctx->at<int32_t>(lo.urow2); p2.ustart = ctx->at<uint32_t>(lo.ustart2); p2.ucnt = ctx->at<int32_t>(lo.ucnt2);
+  p2.psample = ctx->at<int32_t>(lo.psample2); p2.psrc = ctx->at<int32_t>(lo.psrc2);
+  p2.ucount = &ctx->ctrl()->u2; p2.pcount = &ctx->ctrl()->p2;
+  HIPCHK(ctx, launch_transpose_active(ad, p2, s));
+  HIPCHK(ctx, launch_rowgrad_adam(lo.H, p2, delta, ctx->last_h, ctx->buf.W2, ctx->buf.mW2, ctx->buf.vW2,
+                                  ctx->buf.b2, ctx->buf.mb2, ctx->buf.vb2, a, s));
+  if (lo.D > 0) {
+    PairsDev p1;
+    p1.urow = ctx->at<int32_t>(lo.urow1); p1.ustart = ctx->at<uint32_t>(lo.ustart1); p1.ucnt = ctx->at<int32_t>(lo.ucnt1);
+    p1.psample = ctx->at<int32_t>(lo.psample1); p1.psrc = ctx->at<int32_t>(lo.psrc1);
+    p1.ucount = &ctx->ctrl()->u1; p1.pcount = &ctx->ctrl()->p1;
+    HIPCHK(ctx, launch_transpose_features(b->batch, lo.TW, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
+                                          b->x_indices, p1, s));
+    HIPCHK(ctx, launch_rowgrad_adam(lo.H, p1, b->x_values, dh, ctx->buf.W1, ctx->buf.mW1, ctx->buf.vW1, nullptr,
+                                    nullptr, nullptr, a, s));
+    HIPCHK(ctx, launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, ctx->buf.b1, ctx->buf.mb1,
+                              ctx->buf.vb1, a, s));
+  } else {
+    HIPCHK(ctx, launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, nullptr, nullptr, nullptr, a, s));
+  }
+  ctx->t = t;
+  if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
+    ctx->r += 1;
+    if ((rc = do_build(ctx, s)) != SLIDE_OK) return rc;
+  }
+  return SLIDE_OK;
+}
+
+int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int32_t* d_out_ids,
+                  float* d_out_scores, void* hip_stream) {
+  if (!ctx) return SLIDE_EINVAL;
+  if (!ctx->built) return set_err(ctx, SLIDE_ESTATE, "slide_build_tables must run before slide_predict");
+  if (topk < 1 || topk > 64 || !d_out_ids || !d_out_scores) return set_err(ctx, SLIDE_EINVAL, "topk must be in [1, 64] and outputs non-NULL");
+  if (mode != 0) return set_err(ctx, SLIDE_EINVAL, "only mode 0 (scores over the retrieved neurons) is available");
+  int rc = check_batch(ctx, b, false);
+  if (rc != SLIDE_OK) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  ActiveDev ad;
+  if ((rc = forward_common(ctx, b, false, s, &ad)) != SLIDE_OK) return rc;
+  if (ctx->lo.D > 0)   // the feature bit matrix is only consumed by training: clear it again
+    HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(ctx->lo.xbm), (size_t)b->batch * ctx->lo.DWpad, 0u, s));
+  HIPCHK(ctx, launch_topk(ad, ctx->at<float>(ctx->lo.z), topk, d_out_ids, d_out_scores, s));
+  ctx->last_dh = nullptr;
+  return SLIDE_OK;
+}
+
+int slide_status(slide_ctx* ctx, void* hip_stream, uint32_t* flags) {
+  if (!ctx) return SLIDE_EINVAL;
+  HIPCHK(ctx, hipStreamSynchronize((hipStream_t)hip_stream));
+  uint32_t st = 0;
+  HIPCHK(ctx, hipMemcpy(&st, &ctx->ctrl()->status, 4, hipMemcpyDeviceToHost));
+  if (flags) *flags = st;
+  if (st) {
+    HIPCHK(ctx, hipMemset(&ctx->ctrl()->status, 0, 4));
+    return set_err(ctx, SLIDE_EDATA, "device flagged bad batch data (flags 0x%x)", st);
+  }
+  return SLIDE_OK;
+}
+
+int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out) {
+  if (!ctx || !out) return SLIDE_EINVAL;
+  HIPCHK(ctx, hipStreamSynchronize((hipStream_t)hip_stream));
+  Ctrl c;
+  HIPCHK(ctx, hipMemcpy(&c, ctx->ctrl(), sizeof(Ctrl), hipMemcpyDeviceToHost));
+  out->active_pairs = c.total_pairs;
+  out->unique_out_rows = c.u2;
+  out->unique_in_rows = c.u1;
+  out->candidates = ((int64_t)c.candidates_hi << 32) | c.candidates_lo;
+  out->overflowed_buckets = c.overflowed;
+  out->steps = ctx->t;
+  out->rebuilds = ctx->r;
+  return SLIDE_OK;
+}
+
+int slide_destroy(slide_ctx* ctx) {
+  delete ctx;
+  return SLIDE_OK;
+}
+
+const char* slide_last_error(const slide_ctx* ctx) { return ctx ? ctx->err.c_str() : g_last_error.c_str(); }
+
+int slide_debug_hash(slide_ctx* ctx, const float* d_vectors, int64_t rows, uint32_t* d_codes, void* hip_stream) {
+  if (!ctx || !d_vectors || !d_codes || rows < 0) return SLIDE_EINVAL;
+  HIPCHK(ctx, launch_hash(ctx->hd, d_vectors, rows, d_codes, ctx->lo.L, 1, nullptr, nullptr, ctx->lo.nb, 4,
+                          (hipStream_t)hip_stream));
+  return SLIDE_OK;
+}
+
+int slide_debug_get_bucket(slide_ctx* ctx, int table, uint32_t code, int32_t* h_ids, int cap, int* h_count) {
+  if (!ctx || !h_count) return SLIDE_EINVAL;
+  if (!ctx->built) return set_err(ctx, SLIDE_ESTATE, "tables not built");
+  if (table < 0 || table >= ctx->lo.L || code >= ctx->lo.nb) return set_err(ctx, SLIDE_EINVAL, "table / code out of range");
+  HIPCHK(ctx, hipDeviceSynchronize());
+  uint32_t o[2];
+  HIPCHK(ctx, hipMemcpy(o, ctx->td.off + (size_t)table * (ctx->lo.nb + 1) + code, 8, hipMemcpyDeviceToHost));
+  const int n = (int)std::min<uint32_t>(o[1] - o[0], (uint32_t)ctx->lo.C);
+  *h_count = n;
+  const int m = std::min(n, cap);
+  if (m > 0 && h_ids)
+    HIPCHK(ctx, hipMemcpy(h_ids, ctx->td.ids + (size_t)table * ctx->lo.N + o[0], (size_t)m * 4, hipMemcpyDeviceToHost));
+  return SLIDE_OK;
+}
+
+int slide_debug_get_active(slide_ctx* ctx, int64_t* h_as_ptr, int32_t* h_as_ids, uint8_t* h_is_label,
+                           float* h_logits, float* h_delta, int64_t capacity) {
+  if (!ctx || !h_as_ptr) return SLIDE_EINVAL;
+  if (ctx->last_B < 1) return set_err(ctx, SLIDE_ESTATE, "no step has run yet");
+  HIPCHK(ctx, hipDeviceSynchronize());
+  const int B = ctx->last_B;
+  std::vector<int32_t> p(B + 1);
+  HIPCHK(ctx, hipMemcpy(p.data(), ctx->at<int32_t>(ctx->lo.as_ptr), (size_t)(B + 1) * 4, hipMemcpyDeviceToHost));
+  for (int i = 0; i <= B; ++i) h_as_ptr[i] = p[i];
+  const int64_t A = p[B];
+  if (A > capacity) return set_err(ctx, SLIDE_ENOMEM, "capacity %lld < active pairs %lld", (long long)capacity, (long long)A);
+  if (A == 0) return SLIDE_OK;
+  if (h_as_ids) HIPCHK(ctx, hipMemcpy(h_as_ids, ctx->at<int32_t>(ctx->lo.as_ids), (size_t)A * 4, hipMemcpyDeviceToHost));
+  if (h_is_label) HIPCHK(ctx, hipMemcpy(h_is_label, ctx->at<uint8_t>(ctx->lo.as_lab), (size_t)A, hipMemcpyDeviceToHost));
+  if (h_logits) HIPCHK(ctx, hipMemcpy(h_logits, ctx->at<float>(ctx->lo.z), (size_t)A * 4, hipMemcpyDeviceToHost));
+  if (h_delta) HIPCHK(ctx, hipMemcpy(h_delta, ctx->at<float>(ctx->lo.delta), (size_t)A * 4, hipMemcpyDeviceToHost));
+  return SLIDE_OK;
+}
+
+int slide_debug_get_hidden(slide_ctx* ctx, float* h_hidden, float* h_dhidden) {
+  if (!ctx) return SLIDE_EINVAL;
+  if (ctx->last_B < 1 || !ctx->last_h) return set_err(ctx, SLIDE_ESTATE, "no step has run yet");
+  HIPCHK(ctx, hipDeviceSynchronize());
+  const size_t n = (size_t)ctx->last_B * ctx->lo.H * 4;
+  if (h_hidden) HIPCHK(ctx, hipMemcpy(h_hidden, ctx->last_h, n, hipMemcpyDeviceToHost));
+  if (h_dhidden) {
+    if (!ctx->last_dh) return set_err(ctx, SLIDE_ESTATE, "the last call was not a training step");
+    HIPCHK(ctx, hipMemcpy(h_dhidden, ctx->last_dh, n, hipMemcpyDeviceToHost));
+  }
+  return SLIDE_OK;
+}
+
+}  // extern "C"

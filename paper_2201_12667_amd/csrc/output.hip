@@ -1,0 +1,302 @@
+// Float half of the forward pass: sparse-input hidden layer, logits + softmax over the active set
+// only, the gradient with respect to the hidden activations, and top-k for inference
+// (paper Section 2.1: activations are computed for the retrieved neurons only; Section 3.6: the
+// first layer is fed by index/value arrays, the second by the first layer's activations).
+#include "slide_internal.h"
+
+namespace slide {
+
+// ---------------------------------------------------------------------------------------------
+// h[i][:] = max(0, b1 + sum_k x_ik * W1[k][:]), one fused multiply-add per stored feature, in
+// storage order (so any other fp32 implementation using the same order gets the same bits).
+// One wave per (sample, 128 columns); each lane owns two columns and reads a float2 per W1 row.
+// The first column block also records the sample's features in the feature bit matrix.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz_total,
+                                                       const int32_t* __restrict__ x_indptr,
+                                                       const int32_t* __restrict__ x_indices,
+                                                       const float* __restrict__ x_values,
+                                                       const float* __restrict__ W1, const float* __restrict__ b1,
+                                                       float* __restrict__ h, uint32_t* xbm, int DWpad, Ctrl* ctrl) {
+  const int i = blockIdx.x, lane = threadIdx.x;
+  const int c0 = (blockIdx.y * 64 + lane) * 2;
+  const bool col_ok = c0 < H;
+  int p0 = x_indptr[i], p1 = x_indptr[i + 1];
+  p0 = max(p0, 0);
+  p1 = min(p1, nnz_total);
+  float2 acc = col_ok ? *(const float2*)(b1 + c0) : make_float2(0.f, 0.f);
+  int prev = -1;
+  uint32_t flags = 0;
+  constexpr int UN = 8;
+  for (int p = p0; p < p1; p += UN) {
+    int k[UN];
+    float v[UN];
+    float2 w[UN];
+#pragma unroll
+    for (int q = 0; q < UN; ++q) {
+      const bool in = p + q < p1;
+      k[q] = in ? x_indices[p + q] : -1;
+      v[q] = in ? x_values[p + q] : 0.f;
+      if (in && (k[q] < 0 || k[q] >= D)) { flags |= SLIDE_FLAG_BAD_FEATURE; k[q] = -1; }
+    }
+#pragma unroll
+    for (int q = 0; q < UN; ++q)
+      w[q] = (k[q] >= 0 && col_ok) ? *(const float2*)(W1 + (size_t)k[q] * H + c0) : make_float2(0.f, 0.f);
+#pragma unroll
+    for (int q = 0; q < UN; ++q) {
+      if (k[q] < 0) continue;
+      if (k[q] <= prev) flags |= SLIDE_FLAG_UNSORTED;
+      prev = k[q];
+      acc.x = fmaf(v[q], w[q].x, acc.x);
+      acc.y = fmaf(v[q], w[q].y, acc.y);
+      if (blockIdx.y == 0 && lane == 0) atomicOr(&xbm[(size_t)i * DWpad + (k[q] >> 5)], 1u << (k[q] & 31));
+    }
+  }
+  if (col_ok) *(float2*)(h + (size_t)i * H + c0) = make_float2(acc.x > 0.f ? acc.x : 0.f, acc.y > 0.f ? acc.y : 0.f);
+  if (flags && lane == 0 && blockIdx.y == 0) atomicOr(&ctrl->status, flags);
+}
+
+hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
+                            const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
+                            float* h, uint32_t* xbm, int DWpad, Ctrl* ctrl, hipStream_t s) {
+  hipLaunchKernelGGL(spmm_relu_kernel, dim3(B, ceil_div(H, 128)), dim3(64), 0, s, D, H, nnz_total, x_indptr,
+                     x_indices, x_values, W1, b1, h, xbm, DWpad, ctrl);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward over the active set, one pass over the gathered rows of W2.
+// Work item = up to kChunk consecutive active neurons of one sample, handled by one wave.  A row
+// is read by LPR lanes (float4 each, CH of them per lane), so 64/LPR rows are in flight per wave.
+// For each row: logit z = w.h + b (stored), and a running soft-max state (max M, sum s of
+// exp(z - M), acc = sum of exp(z - M) * w) that is rescaled when the maximum moves.  acc/s is the
+// probability-weighted sum of the rows, which is all the hidden-layer gradient needs, so the rows
+// are not read a second time.  Partial states are merged per sample by combine_kernel.
+// ---------------------------------------------------------------------------------------------
+template <int LPR, int CH>
+__global__ __launch_bounds__(256) void forward_kernel(ActiveDev ad, int H, const float* __restrict__ h,
+                                                      const float* __restrict__ W2, const float* __restrict__ b2,
+                                                      float* __restrict__ z, float* __restrict__ partials,
+                                                      const Ctrl* __restrict__ ctrl) {
+  constexpr int RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
+  const int nwaves = gridDim.x * 4;
+  const int nitems = (int)ctrl->total_chunks;
+  const int PS = H + 4;
+  for (int item = blockIdx.x * 4 + (threadIdx.x >> 6); item < nitems; item += nwaves) {
+    const int i = ad.chunk_sample[item];
+    const int first = ad.as_ptr[i] + (item - ad.chunk_ptr[i]) * kChunk;
+    const int n = min(kChunk, ad.as_ptr[i + 1] - first);
+    float4 hv[CH], acc[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int col = (c * LPR + sub) * 4;
+      hv[c] = col < H ? *(const float4*)(h + (size_t)i * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+      acc[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float M = -INFINITY, s = 0.f;
+    for (int q0 = 0; q0 < n; q0 += RPW) {
+      const int q = q0 + grp;
+      const bool valid = q < n;
+      const int slot = first + (valid ? q : 0);
+      const int j = ad.as_ids[slot];
+      const float* wr = W2 + (size_t)j * H;
+      float4 row[CH];
+      float dot = 0.f;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int col = (c * LPR + sub) * 4;
+        row[c] = col < H ? *(const float4*)(wr + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+        dot += row[c].x * hv[c].x + row[c].y * hv[c].y + row[c].z * hv[c].z + row[c].w * hv[c].w;
+      }
+#pragma unroll
+      for (int d = 1; d < LPR; d <<= 1) dot += __shfl_xor(dot, d);
+      const float zz = dot + b2[j];
+      if (valid) {
+        if (sub == 0) z[slot] = zz;
+        const float Mn = fmaxf(M, zz);
+        const float sc = __expf(M - Mn), e = __expf(zz - Mn);
+        s = s * sc + e;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          acc[c].x = acc[c].x * sc + e * row[c].x;
+          acc[c].y = acc[c].y * sc + e * row[c].y;
+          acc[c].z = acc[c].z * sc + e * row[c].z;
+          acc[c].w = acc[c].w * sc + e * row[c].w;
+        }
+        M = Mn;
+      }
+    }
+#pragma unroll
+    for (int d = LPR; d < 64; d <<= 1) {               // merge the row groups of the wave
+      const float Mo = __shfl_xor(M, d), so = __shfl_xor(s, d);
+      const float Mn = fmaxf(M, Mo);
+      const float a = M == -INFINITY ? 0.f : __expf(M - Mn);
+      const float b = Mo == -INFINITY ? 0.f : __expf(Mo - Mn);
+      s = s * a + so * b;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        acc[c].x = acc[c].x * a + __shfl_xor(acc[c].x, d) * b;
+        acc[c].y = acc[c].y * a + __shfl_xor(acc[c].y, d) * b;
+        acc[c].z = acc[c].z * a + __shfl_xor(acc[c].z, d) * b;
+        acc[c].w = acc[c].w * a + __shfl_xor(acc[c].w, d) * b;
+      }
+      M = Mn;
+    }
+    if (grp == 0) {
+      float* pp = partials + (size_t)item * PS;
+      if (sub == 0) { pp[0] = M; pp[1] = s; }
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int col = (c * LPR + sub) * 4;
+        if (col < H) *(float4*)(pp + 4 + col) = acc[c];
+      }
+    }
+  }
+}
+
+template <int LPR, int CH>
+static hipError_t launch_forward_t(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2,
+                                   float* z, float* partials, const Ctrl* ctrl, hipStream_t s) {
+  hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(2048), dim3(256), 0, s, ad, H, h, W2, b2, z, partials, ctrl);
+  return hipGetLastError();
+}
+
+hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2,
+                          float* z, float* partials, const Ctrl* ctrl, hipStream_t s) {
+#define SLIDE_FWD(L_, C_) return launch_forward_t<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, s)
+  if (H <= 32) SLIDE_FWD(8, 1);
+  if (H <= 64) SLIDE_FWD(8, 2);
+  if (H <= 128) SLIDE_FWD(8, 4);
+  if (H <= 256) SLIDE_FWD(16, 4);
+  if (H <= 512) SLIDE_FWD(32, 4);
+  if (H <= 1024) SLIDE_FWD(64, 4);
+  SLIDE_FWD(64, 8);
+#undef SLIDE_FWD
+}
+
+// ---------------------------------------------------------------------------------------------
+// One workgroup per sample: merges the forward partials into the soft-max normaliser, then
+//   delta_ij = (p_ij - y_ij) / B,  loss_i = -sum_{j in Y_i} log(p_ij) / |Y_i|,
+//   dh_i = [h_i > 0] * (sum_j p_ij w_j - mean_{j in Y_i} w_j) / B
+// (the first sum is acc/s from the forward pass; the label rows are read here, in label order).
+// A sample without labels contributes nothing.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const float* __restrict__ h,
+                                                      const float* __restrict__ z,
+                                                      const float* __restrict__ partials,
+                                                      const float* __restrict__ W2,
+                                                      const int32_t* __restrict__ y_indptr,
+                                                      const int32_t* __restrict__ ylist,
+                                                      float* __restrict__ delta, float* __restrict__ dh,
+                                                      float* __restrict__ dh_copy, float* __restrict__ loss_i,
+                                                      float* __restrict__ msum) {
+  __shared__ float red[4];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  const int c0 = ad.chunk_ptr[i], nch = ad.chunk_ptr[i + 1] - c0;
+  const int first = ad.as_ptr[i], n = ad.as_ptr[i + 1] - first;
+  const int ny = ad.ny[i];
+  const int PS = H + 4;
+  const float invB = 1.0f / (float)ad.B;
+  float Mi = -INFINITY;
+  for (int c = 0; c < nch; ++c) Mi = fmaxf(Mi, partials[(size_t)(c0 + c) * PS]);
+  float s = 0.f;
+  for (int c = 0; c < nch; ++c) {
+    const float* pp = partials + (size_t)(c0 + c) * PS;
+    s += pp[1] * __expf(pp[0] - Mi);
+  }
+  if (tid == 0) { msum[2 * i] = Mi; msum[2 * i + 1] = s; }
+  const bool live = n > 0 && ny > 0;
+  for (int u = tid; u < H; u += 256) {
+    float g = 0.f;
+    if (live && h[(size_t)i * H + u] > 0.f) {
+      float acc = 0.f;
+      for (int c = 0; c < nch; ++c) {
+        const float* pp = partials + (size_t)(c0 + c) * PS;
+        acc += pp[4 + u] * __expf(pp[0] - Mi);
+      }
+      float accy = 0.f;
+      for (int q = y_indptr[i]; q < y_indptr[i + 1]; ++q) {
+        const int slot = ylist[q];
+        if (slot >= 0) accy += W2[(size_t)ad.as_ids[slot] * H + u];
+      }
+      g = (acc / s - accy / (float)ny) * invB;
+    }
+    dh[(size_t)i * H + u] = g;
+    if (dh_copy) dh_copy[(size_t)i * H + u] = g;
+  }
+  float lacc = 0.f;
+  const float logs = live ? __logf(s) : 0.f;
+  const float yv = ny > 0 ? 1.0f / (float)ny : 0.f;
+  for (int q = tid; q < n; q += 256) {
+    const int slot = first + q;
+    float d = 0.f;
+    if (live) {
+      const float zz = z[slot];
+      const bool lab = ad.as_lab[slot] != 0;
+      d = (__expf(zz - Mi) / s - (lab ? yv : 0.f)) * invB;
+      if (lab) lacc -= yv * (zz - Mi - logs);
+    }
+    delta[slot] = d;
+  }
+  for (int d = 32; d > 0; d >>= 1) lacc += __shfl_xor(lacc, d);
+  if ((tid & 63) == 0) red[tid >> 6] = lacc;
+  __syncthreads();
+  if (tid == 0) loss_i[i] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
+                          const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
+                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s) {
+  hipLaunchKernelGGL(combine_kernel, dim3(ad.B), dim3(256), 0, s, ad, H, h, z, partials, W2, y_indptr, ylist,
+                     delta, dh, dh_copy, loss_i, msum);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Top-k of the logits of each sample's active set: k rounds of "largest score strictly after the
+// previous pick" in the order (score descending, id ascending).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void topk_kernel(ActiveDev ad, const float* __restrict__ z, int topk,
+                                                   int32_t* __restrict__ out_ids, float* __restrict__ out_scores) {
+  __shared__ float rz[4];
+  __shared__ int rj[4];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  const int first = ad.as_ptr[i], n = ad.as_ptr[i + 1] - first;
+  float pz = INFINITY;
+  int pj = -1;
+  for (int k = 0; k < topk; ++k) {
+    float bz = -INFINITY;
+    int bj = -1;
+    for (int q = tid; q < n; q += 256) {
+      const float zz = z[first + q];
+      const int j = ad.as_ids[first + q];
+      const bool after = zz < pz || (zz == pz && j > pj);
+      if (after && (bj < 0 || zz > bz || (zz == bz && j < bj))) { bz = zz; bj = j; }
+    }
+    for (int d = 32; d > 0; d >>= 1) {
+      const float oz = __shfl_xor(bz, d);
+      const int oj = __shfl_xor(bj, d);
+      if (oj >= 0 && (bj < 0 || oz > bz || (oz == bz && oj < bj))) { bz = oz; bj = oj; }
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) { rz[tid >> 6] = bz; rj[tid >> 6] = bj; }
+    __syncthreads();
+    bz = rz[0]; bj = rj[0];
+    for (int w = 1; w < 4; ++w)
+      if (rj[w] >= 0 && (bj < 0 || rz[w] > bz || (rz[w] == bz && rj[w] < bj))) { bz = rz[w]; bj = rj[w]; }
+    if (tid == 0) {
+      out_ids[(size_t)i * topk + k] = bj;
+      out_scores[(size_t)i * topk + k] = bj >= 0 ? bz : -INFINITY;
+    }
+    if (bj < 0) { pz = -INFINITY; pj = 0x7fffffff; } else { pz = bz; pj = bj; }
+  }
+}
+
+hipError_t launch_topk(const ActiveDev& ad, const float* z, int topk, int32_t* out_ids, float* out_scores,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(topk_kernel, dim3(ad.B), dim3(256), 0, s, ad, z, topk, out_ids, out_scores);
+  return hipGetLastError();
+}
+
+}  // namespace slide

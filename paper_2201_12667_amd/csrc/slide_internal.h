@@ -1,0 +1,131 @@
+// Internal declarations shared by the HIP translation units of the SLIDE step library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "slide.h"
+
+namespace slide {
+
+constexpr int kWave = 64;
+constexpr int kChunk = 64;         // active pairs per forward work item
+constexpr int kSmallBucket = 8;    // buckets up to this size are sorted by one thread
+constexpr int kSortCap = 2048;     // keys held in LDS by the big-bucket sorter
+constexpr int kScanSeg = 4096;     // bucket counters scanned per workgroup
+
+// Device-side counters, one block at the start of the workspace.
+struct Ctrl {
+  uint32_t status;        // sticky SLIDE_FLAG_* bits
+  uint32_t u2, p2;        // unique rows / pairs emitted by the output-layer transposition
+  uint32_t u1, p1;        // same for the input layer
+  uint32_t wl_count;      // big-bucket worklist length
+  uint32_t overflowed;    // buckets with more than C members at the last build
+  uint32_t total_pairs;   // A
+  uint32_t total_chunks;
+  uint32_t candidates_lo, candidates_hi;
+  uint32_t pad[5];
+};
+
+// Hash functions as the kernels read them.
+struct HashDev {
+  int kind, H, K, L, NH;
+  int m, lgm;             // DWTA bin size and its log2
+  int S, Spad;            // SimHash coordinates per bit, padded to even
+  const uint32_t* words;  // DWTA: NH*m/2 words of two u16 coordinates; SimHash: NH*Spad/2 words of
+                          // two u16 (bit 15 = subtract)
+  uint32_t dens_a, dens_b;
+};
+
+struct AdamDev {
+  float beta1, omb1, beta2, omb2, lr, inv_bc1, inv_bc2, eps;
+};
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---- hash.hip -------------------------------------------------------------------------
+// codes[r*row_stride + t*tab_stride] for r < rows, t < L.  With hist != nullptr also
+// pos = atomicAdd(&hist[t*(nb+1) + code], 1) and rank[t*rows + r] = pos.
+hipError_t launch_hash(const HashDev& hd, const float* V, int64_t rows, uint32_t* codes,
+                       int64_t row_stride, int64_t tab_stride, uint32_t* hist, uint32_t* rank,
+                       uint32_t nb, int tables_per_block, hipStream_t s);
+hipError_t hash_setup_attributes(int H);
+size_t hash_lds_bytes(int H);
+
+// ---- tables.hip -----------------------------------------------------------------------
+struct TablesDev {
+  uint32_t* off;          // [L][nb+1]
+  int32_t* ids;           // [L][N]
+  uint32_t nb;
+  int64_t N;
+  int L, C;
+};
+hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2,
+                               uint32_t* codes_t, uint32_t* rank_t, uint32_t* segsum,
+                               uint64_t* worklist, uint32_t wl_cap, Ctrl* ctrl, int policy,
+                               uint32_t r, uint32_t prio_a, uint32_t prio_b, int tables_per_block,
+                               hipStream_t s);
+
+// ---- active.hip -----------------------------------------------------------------------
+struct ActiveDev {
+  int B, L, C, TW;                 // TW: bitmap words per rank tile (power of two <= 32)
+  int64_t N;
+  int NWpad, NT;                   // bitmap words per sample (multiple of TW), tiles per sample
+  uint32_t* act;                   // [B][NWpad] active-set bit matrix
+  uint32_t* rankT;                 // [B][NT] tile counts, then exclusive prefix
+  int32_t* cnt;                    // [B] |AS_i|
+  int32_t* ny;                     // [B] distinct labels
+  int32_t* as_ptr;                 // [B+1]
+  int32_t* chunk_ptr;              // [B+1]
+  int32_t* chunk_sample;           // [max chunks]
+  int32_t* as_ids;                 // [A]
+  uint8_t* as_lab;                 // [A]
+  int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
+};
+hipError_t active_setup_attributes(size_t* lds_limit_out);
+hipError_t launch_lookup_union(const ActiveDev& ad, const TablesDev& td, const uint32_t* codes,
+                               const int32_t* y_indptr, const int32_t* y_indices, int include_labels,
+                               int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
+hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, hipStream_t s);
+hipError_t launch_emit(const ActiveDev& ad, const int32_t* y_indptr, const int32_t* y_indices,
+                       int include_labels, hipStream_t s);
+
+// Transposition of a [B][words] bit matrix into per-row pair lists.
+struct PairsDev {
+  int32_t* urow;    // [U] row id
+  uint32_t* ustart; // [U] first pair
+  int32_t* ucnt;    // [U] pairs
+  int32_t* psample; // [pairs] sample
+  int32_t* psrc;    // [pairs] index into the coefficient array
+  uint32_t* ucount; // device counters inside Ctrl
+  uint32_t* pcount;
+};
+hipError_t launch_transpose_active(const ActiveDev& ad, const PairsDev& pd, hipStream_t s);
+hipError_t launch_transpose_features(int B, int TW, int DWpad, uint32_t* xbm, const int32_t* x_indptr,
+                                     const int32_t* x_indices, const PairsDev& pd, hipStream_t s);
+
+// ---- output.hip -----------------------------------------------------------------------
+hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
+                            const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
+                            float* h, uint32_t* xbm, int DWpad, Ctrl* ctrl, hipStream_t s);
+hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2,
+                          float* z, float* partials, const Ctrl* ctrl, hipStream_t s);
+hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
+                          const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
+                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s);
+hipError_t launch_topk(const ActiveDev& ad, const float* z, int topk, int32_t* out_ids,
+                       float* out_scores, hipStream_t s);
+hipError_t launch_dense_topk(int B, int64_t N, int H, const float* h, const float* W2, const float* b2,
+                             int topk, int32_t* out_ids, float* out_scores, hipStream_t s);
+
+// ---- update.hip -----------------------------------------------------------------------
+// For every listed row r: g = sum over its pairs of coef[psrc] * V[psample][:], then Adam on
+// W[r][:] (and on bias[r] with the sum of the coefficients when bias != nullptr).
+hipError_t launch_rowgrad_adam(int H, const PairsDev& pd, const float* coef, const float* V,
+                               float* W, float* M, float* Vv, float* bias, float* mbias, float* vbias,
+                               const AdamDev& ad, hipStream_t s);
+// loss = mean(loss_i); with b1 != nullptr also gb1 = column sums of dh and Adam on b1.
+hipError_t launch_finish(int B, int H, const float* loss_i, float* d_loss, const float* dh, float* b1,
+                         float* mb1, float* vb1, const AdamDev& ad, hipStream_t s);
+hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
+
+}  // namespace slide

@@ -1,0 +1,89 @@
+"""Shared helpers of the GPU parity tests: build the HIP model and the oracle from the same seeded
+arrays, and the floating-point comparison rule."""
+import numpy as np
+
+from oracle import slide_oracle as so
+from paper_2201_12667_amd import slide, synth
+
+# fp32 tolerance: |gpu - ref| <= REL*|ref| + FLOOR*max|ref| (REL from the stated 1e-4 relative bar; the
+# floor absorbs cancellation in sums of up to H = 2048 products: a few hundred fp32 ulps of the
+# largest element).
+REL, FLOOR = 1e-4, 2e-6
+
+
+def close(a, ref, rel=REL, floor=FLOOR):
+    a, ref = np.asarray(a, np.float64), np.asarray(ref, np.float64)
+    if a.shape != ref.shape:
+        return False
+    if ref.size == 0:
+        return True
+    return bool(np.all(np.abs(a - ref) <= rel * np.abs(ref) + floor * np.abs(ref).max() + 1e-30))
+
+
+def worst(a, ref):
+    a, ref = np.asarray(a, np.float64), np.asarray(ref, np.float64)
+    if ref.size == 0:
+        return 0.0
+    return float(np.max(np.abs(a - ref) / (REL * np.abs(ref) + FLOOR * np.abs(ref).max() + 1e-30)))
+
+
+def make_oracle(wl, weights, hp):
+    return so.SlideOracle(input_dim=wl.input_dim, hidden_dim=wl.hidden_dim, num_classes=wl.num_classes,
+                          hash_kind=wl.hash_kind, K=wl.K, L=wl.L, bucket_cap=wl.bucket_cap,
+                          rebuild_every=wl.rebuild_every, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
+                          dwta_bin=wl.dwta_bin, overflow_policy=wl.overflow_policy, weights=weights,
+                          hash_params=hp)
+
+
+def make_pair(wl, seed=0, **cfg_over):
+    gen = synth.Generator(wl, seed)
+    weights, hp = gen.weights(), gen.hash_params()
+    cfg = slide.config_from_workload(wl, **cfg_over)
+    model = slide.Slide(cfg, weights, hp)
+    return gen, model, make_oracle(wl, weights, hp)
+
+
+def load_state(model, orc):
+    """Copies the oracle's parameters, Adam state and counters' worth of state into the HIP model."""
+    import torch
+    for n in model.p:
+        model.p[n].copy_(torch.from_numpy(orc.p[n]))
+        model.m[n].copy_(torch.from_numpy(orc.m[n]))
+        model.v[n].copy_(torch.from_numpy(orc.v[n]))
+    torch.cuda.synchronize()
+
+
+def compare_step(model, orc, batch, check_state=True):
+    """Runs one step on both from their current states and compares everything.  Returns a dict of
+    worst tolerance ratios (<= 1 passes); raises AssertionError on any integer mismatch."""
+    db = model.to_device(batch)
+    loss = float(model.train_step(db).item())
+    assert model.status() == 0
+    ref = orc.train_step(batch)
+    h, dh = model.debug_hidden()
+    as_ptr, ids, lab, z, d = model.debug_active()
+    if not orc.dense_hidden:
+        assert np.array_equal(h, ref["h"]), "hidden activations are not bit-identical"
+    assert np.array_equal(as_ptr, ref["as_ptr"]), "active-set sizes differ"
+    assert np.array_equal(ids, ref["as_ids"]), "active-set ids differ"
+    assert np.array_equal(lab, ref["is_label"]), "label flags differ"
+    st = model.stats()
+    assert st["active_pairs"] == len(ids) and st["unique_out_rows"] == len(ref["uniq"])
+    assert st["candidates"] == ref["candidates"]
+    if not orc.dense_hidden:
+        assert st["unique_in_rows"] == len(ref["uniq1"])
+    res = {"z": worst(z, ref["z"]), "delta": worst(d, ref["delta"]), "dh": worst(dh, ref["dh"]),
+           "loss": abs(loss - ref["loss"]) / (REL * max(abs(ref["loss"]), 1e-12))}
+    if check_state:
+        for n in model.p:
+            res["w:" + n] = worst(model.p[n].cpu().numpy(), orc.p[n])
+            res["m:" + n] = worst(model.m[n].cpu().numpy(), orc.m[n])
+            res["v:" + n] = worst(model.v[n].cpu().numpy(), orc.v[n])
+    res["_loss"] = (loss, ref["loss"])
+    res["_ref"] = ref
+    return res
+
+
+def assert_ok(res):
+    bad = {k: v for k, v in res.items() if not k.startswith("_") and not (v <= 1.0)}
+    assert not bad, bad

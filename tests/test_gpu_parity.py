@@ -1,0 +1,240 @@
+"""HIP path against the CPU oracle, through the C ABI, on the same seeded inputs.
+
+Bar: bit-exact for hash codes, bucket contents, active sets and (sparse-input mode) hidden
+activations; 1e-4 relative (helpers.close) for logits, errors, gradients-as-Adam-state and updated
+weights; 1e-3 on the 10-step loss."""
+import numpy as np
+import pytest
+
+from paper_2201_12667_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("needs a GPU", allow_module_level=True)
+
+from helpers import assert_ok, close, compare_step, load_state, make_pair  # noqa: E402
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.mark.parametrize("kind,H,K,L", [(synth.HASH_DWTA, 128, 6, 40), (synth.HASH_SIMHASH, 128, 9, 50),
+                                        (synth.HASH_DWTA, 1024, 8, 20), (synth.HASH_SIMHASH, 32, 4, 8),
+                                        (synth.HASH_DWTA, 200, 4, 33), (synth.HASH_SIMHASH, 1024, 9, 7)])
+def test_hash_codes_bit_exact(kind, H, K, L):
+    _say("hash", kind, H, K, L)
+    wl = synth.small(kind, hidden_dim=H, K=K, L=L, input_dim=0, num_classes=300, batch=8)
+    gen, model, orc = make_pair(wl)
+    rng = np.random.default_rng(5)
+    V = rng.standard_normal((203, H)).astype(np.float32)        # several tiles + a ragged tail
+    V[:70] = np.maximum(V[:70], 0)                              # ReLU-like rows: empty DWTA bins
+    V[3] = 0                                                    # all-zero vector
+    V[4, 5:] = 0                                                # almost empty vector
+    V[5] *= 1e-30                                               # tiny magnitudes
+    V[6, ::2] = np.nan
+    got = model.debug_hash(V)
+    want = orc.hash.codes(V)
+    assert np.array_equal(got, want), np.argwhere(got != want)[:5]
+    model.destroy()
+
+
+@pytest.mark.parametrize("kind,policy,C,N", [(synth.HASH_SIMHASH, 1, 16, 2000), (synth.HASH_SIMHASH, 0, 5, 1500),
+                                             (synth.HASH_DWTA, 1, 16, 20011), (synth.HASH_DWTA, 0, 3, 5000),
+                                             (synth.HASH_SIMHASH, 1, 128, 30000)])
+def test_tables_bit_exact_first_build_and_rebuild(kind, policy, C, N):
+    _say("tables", kind, policy, C, N)
+    K = 3 if kind == synth.HASH_DWTA else 6
+    wl = synth.small(kind, K=K, L=7, bucket_cap=C, num_classes=N, overflow_policy=policy, input_dim=0)
+    gen, model, orc = make_pair(wl)
+    for rebuild in (False, True):
+        model.build_tables()
+        T = orc.build_tables(first=not rebuild)
+        assert model.stats()["overflowed_buckets"] == T.overflowed
+        for t in range(wl.L):
+            for c in range(wl.num_buckets):
+                assert np.array_equal(model.debug_bucket(t, c), T.bucket(t, c)), (rebuild, t, c)
+    model.destroy()
+
+
+def test_degenerate_tables_all_rows_identical():
+    _say("tables degenerate")
+    wl = synth.small(synth.HASH_DWTA, K=2, L=3, bucket_cap=8, num_classes=5000, input_dim=0)
+    gen = synth.Generator(wl, 0)
+    w = gen.weights()
+    w["W2"][:] = w["W2"][0]                    # one bucket per table holds every neuron
+    w["W2"][4000:] = 0                         # and the all-zero rows go to code 0
+    from helpers import make_oracle
+    from paper_2201_12667_amd import slide
+    hp = gen.hash_params()
+    model, orc = slide.Slide(slide.config_from_workload(wl), w, hp), make_oracle(wl, w, hp)
+    model.build_tables()
+    T = orc.build_tables()
+    for t in range(wl.L):
+        for c in range(wl.num_buckets):
+            assert np.array_equal(model.debug_bucket(t, c), T.bucket(t, c)), (t, c)
+    model.destroy()
+
+
+@pytest.mark.parametrize("name,wl", [
+    ("dwta-small", synth.small(synth.HASH_DWTA)),
+    ("simhash-small", synth.small(synth.HASH_SIMHASH)),
+    ("dense-hidden", synth.small(synth.HASH_DWTA, input_dim=0, batch=70, num_classes=9973)),
+    ("cfg0", synth.config(0)),
+    ("h1024-b130", synth.small(synth.HASH_DWTA, hidden_dim=1024, K=4, L=11, batch=130, num_classes=7001,
+                               input_dim=2500, bucket_cap=64)),
+    ("h32-uniform", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=5, L=9, batch=5, num_classes=900,
+                                input_dim=400, nnz_mean=6.0, feat_zipf_s=None, lab_zipf_s=None)),
+    ("h200", synth.small(synth.HASH_DWTA, hidden_dim=200, K=3, L=13, batch=33, num_classes=4099,
+                         input_dim=1200)),
+])
+def test_single_step_from_identical_state(name, wl):
+    _say("step", name)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    res = compare_step(model, orc, gen.batch(0))
+    _say({k: round(v, 3) for k, v in res.items() if not k.startswith("_")}, res["_loss"])
+    assert_ok(res)
+    # rows that were not touched are bit-identical to the initial weights
+    w0 = gen.weights()["W2"]
+    untouched = np.setdiff1d(np.arange(wl.num_classes), res["_ref"]["uniq"])
+    assert np.array_equal(model.p["W2"].cpu().numpy()[untouched], w0[untouched])
+    assert not model.m["W2"].cpu().numpy()[untouched].any()
+    model.destroy()
+
+
+@pytest.mark.parametrize("kind", [synth.HASH_DWTA, synth.HASH_SIMHASH])
+def test_every_step_of_a_run_from_the_oracles_state(kind):
+    """Steps 1..6 (rebuild after every 3rd): before each step the HIP model is given the oracle's
+    state, so each step is compared on its own, including the rebuilt tables."""
+    _say("run", kind)
+    wl = synth.small(kind)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    for s in range(wl.steps):
+        load_state(model, orc)
+        res = compare_step(model, orc, gen.batch(s))
+        _say(s, {k: round(v, 3) for k, v in res.items() if not k.startswith("_")})
+        assert_ok(res)
+    assert model.stats()["rebuilds"] == orc.r == 2
+    model.destroy()
+
+
+def test_rebuild_inside_step_matches_oracle_tables():
+    _say("rebuild-in-step")
+    wl = synth.small(synth.HASH_SIMHASH, rebuild_every=1, bucket_cap=8)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    res = compare_step(model, orc, gen.batch(0))
+    assert_ok(res)
+    assert res["_ref"]["rebuilt"] and model.stats()["rebuilds"] == 1
+    same = total = 0
+    for t in range(wl.L):
+        for c in range(wl.num_buckets):
+            total += 1
+            same += np.array_equal(model.debug_bucket(t, c), orc.tables.bucket(t, c))
+    _say("identical buckets after in-step rebuild:", same, "/", total)
+    assert same >= 0.98 * total        # weights agree to 1e-4, so a few sign bits may flip
+
+
+def test_ten_step_loss_tiny_config():
+    _say("ten steps cfg0")
+    wl = synth.config(0)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    first_diff = None
+    for s in range(10):
+        b = gen.batch(s)
+        loss = float(model.train_step(model.to_device(b)).item())
+        ref = orc.train_step(b)
+        as_ptr, ids, _, _, _ = model.debug_active()
+        if first_diff is None and not (np.array_equal(as_ptr, ref["as_ptr"]) and np.array_equal(ids, ref["as_ids"])):
+            first_diff = s
+        _say(s, loss, ref["loss"])
+        assert abs(loss - ref["loss"]) < 1e-3
+    _say("active sets first differ at step:", first_diff)
+    assert model.stats()["steps"] == 10 and model.stats()["rebuilds"] == 2
+    model.destroy()
+
+
+def test_edge_cases_labels_and_empty_samples():
+    _say("edge cases")
+    wl = synth.small(synth.HASH_DWTA, batch=6, num_classes=3000, input_dim=500)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    b = gen.batch(0)
+    # sample 0: no features; sample 1: no labels; sample 2: a repeated label; sample 3: unsorted labels
+    xp, xi, xv = b["x_indptr"], b["x_indices"], b["x_values"]
+    n0 = xp[1]
+    xi, xv = xi[n0:], xv[n0:]
+    xp = np.concatenate([[0], xp[1:] - n0]).astype(np.int32)
+    ys = [b["y_indices"][b["y_indptr"][i]:b["y_indptr"][i + 1]].tolist() for i in range(6)]
+    ys[1] = []
+    ys[2] = ys[2] + [ys[2][0]]
+    ys[3] = [2999, 0, 17]
+    yp = np.zeros(7, np.int32)
+    yp[1:] = np.cumsum([len(y) for y in ys])
+    b2 = dict(batch=6, x_indptr=xp, x_indices=xi, x_values=xv, y_indptr=yp,
+              y_indices=np.array(sum(ys, []), np.int32))
+    res = compare_step(model, orc, b2)
+    assert_ok(res)
+    assert not res["_ref"]["dh"][1].any()
+    model.destroy()
+
+
+def test_bad_batch_data_is_flagged_not_fatal():
+    _say("bad data")
+    from paper_2201_12667_amd import slide
+    wl = synth.small(synth.HASH_DWTA, batch=4, num_classes=3000, input_dim=500)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    b = gen.batch(0)
+    b["x_indices"] = b["x_indices"].copy()
+    b["y_indices"] = b["y_indices"].copy()
+    b["x_indices"][0] = 500                      # out of range
+    b["y_indices"][0] = -3                       # out of range
+    b["x_indices"][b["x_indptr"][1]:b["x_indptr"][1] + 2] = b["x_indices"][b["x_indptr"][1]:b["x_indptr"][1] + 2][::-1]
+    model.train_step(model.to_device(b))
+    flags = model.status()
+    assert flags == slide.FLAG_BAD_FEATURE | slide.FLAG_BAD_LABEL | slide.FLAG_UNSORTED
+    assert model.status() == 0                   # cleared after being reported
+    # host-detected errors
+    with pytest.raises(slide.SlideError) as e:
+        db = model.to_device(gen.batch(1))
+        db["batch"] = wl.batch + 1
+        model.train_step(db)
+    assert e.value.code == slide.SLIDE_EINVAL
+    model.destroy()
+    gen2, fresh, _ = make_pair(wl)
+    with pytest.raises(slide.SlideError) as e:
+        fresh.train_step(fresh.to_device(gen2.batch(0)))
+    assert e.value.code == slide.SLIDE_ESTATE
+    fresh.destroy()
+
+
+@pytest.mark.parametrize("kind", [synth.HASH_DWTA, synth.HASH_SIMHASH])
+def test_predict_mode0_matches_oracle(kind):
+    _say("predict", kind)
+    wl = synth.small(kind)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    b = gen.batch(0)
+    ids, sc = model.predict(model.to_device(b), 5)
+    want_ids, want_sc = orc.predict(b, 5)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    as_ptr, got_set, _, _, _ = model.debug_active()
+    assert np.array_equal(ids, want_ids)
+    fin = np.isfinite(want_sc)
+    assert close(sc[fin], want_sc[fin]) and np.array_equal(np.isfinite(sc), fin)
+    # a training step afterwards still works (the feature bit matrix was left clean)
+    res = compare_step(model, orc, gen.batch(1))
+    assert_ok(res)
+    model.destroy()
