@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the SLIDE training step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i]
+
+A step is one pass of the whole hot path (hidden layer, hashing, bucket lookup + union, forward over
+the active set, sparse backward, row-sparse Adam) over one fresh synthetic batch already resident in
+HBM.  Prints one JSON line: whole-job samples/s, the HBM roofline of the dominant kernel (row
+gradient + Adam on the touched output rows, timed with HIP events inside the library on the step's
+own stream), and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
+# scaled by the same counters on a plain copy kernel); see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes_adam_out(U: float, A: float, B: int, H: int) -> float:
+    """Bytes the row-gradient + Adam kernel must move per launch: every touched row of W2 and of its
+    momentum and velocity read once and written once (6 rows of H floats), the same for the bias
+    (6 floats), the row's list header (12 bytes), and per active pair its sample index, coefficient
+    index and coefficient (12 bytes).  The hidden activations (B*H floats) are read once from HBM."""
+    return U * (6.0 * H * 4 + 6 * 4 + 12) + A * 12.0 + B * H * 4.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="0..4; 2 = the 670K-class model the metric is quoted on")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-steps", type=int, default=3, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--breakdown", action="store_true", help="also time every stage on extra steps")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2201_12667_amd import slide, synth
+
+    wl = synth.config(args.config)
+    gen = synth.Generator(wl, args.seed)
+    weights, hp = gen.weights(), gen.hash_params()
+    model = slide.Slide(slide.config_from_workload(wl), weights, hp)
+    W, K = args.warmup, args.steps
+    host_batches = [gen.batch(s) for s in range(W + K)]
+    batches = [model.to_device(b) for b in host_batches]
+
+    # table build, timed on its own (it is not part of a step unless the schedule fires)
+    model.profile(1 << slide.STAGES.index("rebuild"))
+    model.build_tables()
+    ms, n = model.profile_read()
+    build_ms = float(ms[slide.STAGES.index("rebuild")])
+    model.profile(0)
+
+    for s in range(W):
+        model.train_step(batches[s])
+    torch.cuda.synchronize()
+    assert model.status() == 0, "device flagged bad batch data"
+    model.reset_stats()
+    dom = slide.STAGES.index("adam_out")
+    model.profile(1 << dom)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(W, W + K):
+        model.train_step(batches[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms, n = model.profile_read()
+    model.profile(0)
+    st = model.stats()
+    loss = float(model.d_loss.item())
+    assert np.isfinite(loss), "loss is not finite"
+    steps_done = max(st["sum_steps"], 1)
+    A, U, U1 = (st[k] / steps_done for k in ("sum_active_pairs", "sum_unique_out_rows", "sum_unique_in_rows"))
+    step_ms = (t1 - t0) * 1e3 / K
+    value = wl.batch * K / (t1 - t0)
+    dom_ms = float(ms[dom]) / max(int(n[dom]), 1)
+    dom_bytes = algorithmic_bytes_adam_out(U, A, wl.batch, wl.hidden_dim)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    rebuilds_in_region = sum(1 for t in range(W + 1, W + K + 1) if wl.rebuild_every and t % wl.rebuild_every == 0)
+
+    out = {
+        "metric": "train samples/s (fwd+bwd+Adam), 670K-class SLIDE step",
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "config_index": args.config, "batch": wl.batch,
+                   "input_dim": wl.input_dim, "hidden_dim": wl.hidden_dim, "num_classes": wl.num_classes,
+                   "hash": "dwta" if wl.hash_kind == synth.HASH_DWTA else "simhash", "K": wl.K, "L": wl.L,
+                   "bucket_cap": wl.bucket_cap, "rebuild_every": wl.rebuild_every,
+                   "rebuilds_in_timed_region": rebuilds_in_region, "seed": args.seed},
+        "roofline": {"bound": "hbm", "kernel": "rowgrad_adam_kernel (output layer)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "algorithmic_bytes_per_launch": dom_bytes,
+                     "avg_launch_ms": dom_ms, "launches": int(n[dom])},
+        "workload_stats": {"active_pairs_per_step": A, "unique_out_rows_per_step": U,
+                           "unique_in_rows_per_step": U1,
+                           "candidates_per_step": st["sum_candidates"] / steps_done,
+                           "overflowed_buckets_at_build": st["overflowed_buckets"], "last_loss": loss},
+        "step_bytes": {"compulsory": 7.0 * wl.hidden_dim * 4 * (U + U1) + 40.0 * A,
+                       "compulsory_GBs": (7.0 * wl.hidden_dim * 4 * (U + U1) + 40.0 * A) / (step_ms * 1e-3) / 1e9},
+        "table_build_ms": build_ms,
+    }
+    if wl.rebuild_every:
+        out["ms_per_step_amortised_rebuild"] = step_ms + (0 if rebuilds_in_region else build_ms / wl.rebuild_every)
+
+    if args.breakdown:
+        model.profile((1 << slide.NUM_STAGES) - 1)
+        for s in range(W, W + K):
+            model.train_step(batches[s])
+        ms, n = model.profile_read()
+        model.profile(0)
+        out["stage_ms"] = {slide.STAGES[i]: float(ms[i]) / int(n[i]) for i in range(slide.NUM_STAGES) if n[i]}
+
+    if args.cpu_steps > 0:
+        from oracle import slide_oracle as so
+        orc = so.SlideOracle(input_dim=wl.input_dim, hidden_dim=wl.hidden_dim, num_classes=wl.num_classes,
+                             hash_kind=wl.hash_kind, K=wl.K, L=wl.L, bucket_cap=wl.bucket_cap, rebuild_every=0,
+                             lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, dwta_bin=wl.dwta_bin,
+                             overflow_policy=wl.overflow_policy, weights=weights, hash_params=hp)
+        tb0 = time.perf_counter()
+        orc.build_tables()
+        tb1 = time.perf_counter()
+        c0 = time.perf_counter()
+        for s in range(args.cpu_steps):
+            orc.train_step(host_batches[s])
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": wl.batch * args.cpu_steps / (c1 - c0), "unit": "samples/s",
+                               "cores": so.num_threads(), "kind": "oracle",
+                               "sample": "%d full steps (batch %d) of the same workload, tables prebuilt "
+                                         "(table build took %.1f s and is not in the timed sample)"
+                                         % (args.cpu_steps, wl.batch, tb1 - tb0)}
+    print(json.dumps(out))
+    model.destroy()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -127,6 +127,8 @@ typedef struct {
   int64_t overflowed_buckets;/* buckets that held more than C neurons at last build */
   int64_t steps;             /* t, training steps done                              */
   int64_t rebuilds;          /* r, rebuilds done after the first build              */
+  /* totals over the training steps since the last slide_reset_stats */
+  int64_t sum_active_pairs, sum_unique_out_rows, sum_unique_in_rows, sum_candidates, sum_steps;
 } slide_stats;
 
 /* Sizes of the tables and workspace buffers for this configuration (host only). */
@@ -163,6 +165,35 @@ int slide_status(slide_ctx* ctx, void* hip_stream, uint32_t* flags);
 
 /* Synchronises the stream and copies the counters. */
 int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out);
+
+/* Stages of a step, in launch order, for slide_profile. */
+enum slide_stage {
+  SLIDE_STAGE_HIDDEN = 0,        /* sparse-input hidden layer                       */
+  SLIDE_STAGE_HASH = 1,          /* hash codes of the hidden activations            */
+  SLIDE_STAGE_LOOKUP = 2,        /* bucket reads + union bitmap                     */
+  SLIDE_STAGE_SCAN = 3,          /* offsets over the samples                        */
+  SLIDE_STAGE_EMIT = 4,          /* sorted id lists + label flags                   */
+  SLIDE_STAGE_FORWARD = 5,       /* logits + running soft-max over gathered rows    */
+  SLIDE_STAGE_COMBINE = 6,       /* normaliser, errors, loss, hidden gradient       */
+  SLIDE_STAGE_TRANSPOSE_OUT = 7, /* touched output rows -> sample lists             */
+  SLIDE_STAGE_ADAM_OUT = 8,      /* output-layer gradient + Adam on touched rows    */
+  SLIDE_STAGE_TRANSPOSE_IN = 9,  /* touched input rows -> sample lists              */
+  SLIDE_STAGE_ADAM_IN = 10,      /* hidden-layer gradient + Adam on touched rows    */
+  SLIDE_STAGE_FINISH = 11,       /* loss mean, hidden bias                          */
+  SLIDE_STAGE_REBUILD = 12,      /* table build / rebuild (all its kernels)         */
+  SLIDE_NUM_STAGES = 13
+};
+
+/* Measurement aid: for every stage whose bit (1 << slide_stage) is set in stage_mask, later calls
+ * bracket that stage's launches with a pair of HIP events on the call's stream.  0 turns it off.
+ * slide_profile_read synchronises the stream, adds up the elapsed milliseconds and the number of
+ * launches per stage since the last read into ms_sum / launches (SLIDE_NUM_STAGES entries each,
+ * host), and resets them. */
+int slide_profile(slide_ctx* ctx, uint32_t stage_mask);
+int slide_profile_read(slide_ctx* ctx, void* hip_stream, double* ms_sum, int64_t* launches);
+
+/* Synchronises the stream and zeroes the running totals of slide_stats. */
+int slide_reset_stats(slide_ctx* ctx, void* hip_stream);
 
 int slide_destroy(slide_ctx* ctx);
 

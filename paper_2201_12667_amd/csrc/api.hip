@@ -149,6 +149,13 @@ struct slide_ctx {
   const float* last_h = nullptr;
   float* last_dh = nullptr;
   std::string err;
+  // per-stage HIP-event timing (slide_profile)
+  struct ProfRec { int stage; hipEvent_t a, b; };
+  uint32_t prof_mask = 0;
+  std::vector<ProfRec> prof_live;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pool;
+  double prof_ms[SLIDE_NUM_STAGES] = {};
+  int64_t prof_n[SLIDE_NUM_STAGES] = {};
   char* ws() const { return (char*)buf.workspace; }
   template <typename T> T* at(size_t off) const { return (T*)(ws() + off); }
   Ctrl* ctrl() const { return at<Ctrl>(lo.ctrl); }
@@ -171,6 +178,27 @@ int set_err(slide_ctx* ctx, int code, const char* fmt, ...) {
     hipError_t e_ = (expr);                                                                       \
     if (e_ != hipSuccess) return set_err(ctx, SLIDE_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
+
+// Runs one stage; with profiling enabled for it, brackets the launch with a pair of events on the
+// same stream.
+template <typename F>
+hipError_t stage(slide_ctx* ctx, int id, hipStream_t s, F&& launch) {
+  if (!(ctx->prof_mask & (1u << id))) return launch();
+  std::pair<hipEvent_t, hipEvent_t> ev;
+  if (!ctx->prof_pool.empty()) {
+    ev = ctx->prof_pool.back();
+    ctx->prof_pool.pop_back();
+  } else {
+    hipError_t e = hipEventCreate(&ev.first);
+    if (e == hipSuccess) e = hipEventCreate(&ev.second);
+    if (e != hipSuccess) return e;
+  }
+  hipError_t e = hipEventRecord(ev.first, s);
+  if (e == hipSuccess) e = launch();
+  if (e == hipSuccess) e = hipEventRecord(ev.second, s);
+  ctx->prof_live.push_back({id, ev.first, ev.second});
+  return e;
+}
 
 ActiveDev make_active(const slide_ctx* c, int B) {
   ActiveDev ad;
@@ -208,32 +236,38 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   const float* h = b->hidden;
   if (lo.D > 0) {
     float* hw = ctx->at<float>(lo.h);
-    HIPCHK(ctx, launch_spmm_relu(B, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
-                                 ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), lo.DWpad, ctx->ctrl(), s));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] {
+      return launch_spmm_relu(B, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
+                              ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), lo.DWpad, ctx->ctrl(), s); }));
     h = hw;
   }
   ctx->last_h = h;
   ctx->last_B = B;
   uint32_t* codes = ctx->at<uint32_t>(lo.codes);
-  HIPCHK(ctx, launch_hash(ctx->hd, h, B, codes, lo.L, 1, nullptr, nullptr, lo.nb, 4, s));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HASH, s, [&] {
+    return launch_hash(ctx->hd, h, B, codes, lo.L, 1, nullptr, nullptr, lo.nb, 4, s); }));
   ActiveDev ad = make_active(ctx, B);
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
-  HIPCHK(ctx, launch_lookup_union(ad, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0, ncand,
-                                  ctx->ctrl(), ctx->lds_limit, s));
-  HIPCHK(ctx, launch_scan_samples(ad, ncand, ctx->ctrl(), s));
-  HIPCHK(ctx, launch_emit(ad, b->y_indptr, b->y_indices, with_labels ? 1 : 0, s));
-  HIPCHK(ctx, launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
-                             ctx->at<float>(lo.partials), ctx->ctrl(), s));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
+    return launch_lookup_union(ad, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0, ncand,
+                               ctx->ctrl(), ctx->lds_limit, s); }));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), s); }));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_EMIT, s, [&] {
+    return launch_emit(ad, b->y_indptr, b->y_indices, with_labels ? 1 : 0, s); }));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
+    return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
+                          ctx->at<float>(lo.partials), ctx->ctrl(), s); }));
   *ad_out = ad;
   return SLIDE_OK;
 }
 
 int do_build(slide_ctx* ctx, hipStream_t s) {
   const Layout& lo = ctx->lo;
-  HIPCHK(ctx, launch_build_tables(ctx->hd, ctx->td, ctx->buf.W2, ctx->at<uint32_t>(lo.codes_t),
-                                  ctx->at<uint32_t>(lo.rank_t), ctx->at<uint32_t>(lo.segsum),
-                                  ctx->at<uint64_t>(lo.worklist), lo.wl_cap, ctx->ctrl(), ctx->cfg.overflow_policy,
-                                  (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, 40, s));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_REBUILD, s, [&] {
+    return launch_build_tables(ctx->hd, ctx->td, ctx->buf.W2, ctx->at<uint32_t>(lo.codes_t),
+                               ctx->at<uint32_t>(lo.rank_t), ctx->at<uint32_t>(lo.segsum),
+                               ctx->at<uint64_t>(lo.worklist), lo.wl_cap, ctx->ctrl(), ctx->cfg.overflow_policy,
+                               (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, 40, s); }));
   return SLIDE_OK;
 }
 
@@ -365,9 +399,10 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   if ((rc = forward_common(ctx, b, true, s, &ad)) != SLIDE_OK) return rc;
   float* dh = ctx->at<float>(lo.dh);
   float* delta = ctx->at<float>(lo.delta);
-  HIPCHK(ctx, launch_combine(ad, lo.H, ctx->last_h, ctx->at<float>(lo.z), ctx->at<float>(lo.partials), ctx->buf.W2,
-                             b->y_indptr, ad.ylist, delta, dh, b->dhidden_out, ctx->at<float>(lo.loss_i),
-                             ctx->at<float>(lo.msum), s));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_COMBINE, s, [&] {
+    return launch_combine(ad, lo.H, ctx->last_h, ctx->at<float>(lo.z), ctx->at<float>(lo.partials), ctx->buf.W2,
+                          b->y_indptr, ad.ylist, delta, dh, b->dhidden_out, ctx->at<float>(lo.loss_i),
+                          ctx->at<float>(lo.msum), s); }));
   ctx->last_dh = dh;
   const int64_t t = ctx->t + 1;
   AdamDev a;
@@ -380,22 +415,28 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   p2.urow = ctx->at<int32_t>(lo.urow2); p2.ustart = ctx->at<uint32_t>(lo.ustart2); p2.ucnt = ctx->at<int32_t>(lo.ucnt2);
   p2.psample = ctx->at<int32_t>(lo.psample2); p2.psrc = ctx->at<int32_t>(lo.psrc2);
   p2.ucount = &ctx->ctrl()->u2; p2.pcount = &ctx->ctrl()->p2;
-  HIPCHK(ctx, launch_transpose_active(ad, p2, s));
-  HIPCHK(ctx, launch_rowgrad_adam(lo.H, p2, delta, ctx->last_h, ctx->buf.W2, ctx->buf.mW2, ctx->buf.vW2,
-                                  ctx->buf.b2, ctx->buf.mb2, ctx->buf.vb2, a, s));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_OUT, s, [&] { return launch_transpose_active(ad, p2, s); }));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_OUT, s, [&] {
+    return launch_rowgrad_adam(lo.H, p2, delta, ctx->last_h, ctx->buf.W2, ctx->buf.mW2, ctx->buf.vW2,
+                               ctx->buf.b2, ctx->buf.mb2, ctx->buf.vb2, a, s); }));
   if (lo.D > 0) {
     PairsDev p1;
     p1.urow = ctx->at<int32_t>(lo.urow1); p1.ustart = ctx->at<uint32_t>(lo.ustart1); p1.ucnt = ctx->at<int32_t>(lo.ucnt1);
     p1.psample = ctx->at<int32_t>(lo.psample1); p1.psrc = ctx->at<int32_t>(lo.psrc1);
     p1.ucount = &ctx->ctrl()->u1; p1.pcount = &ctx->ctrl()->p1;
-    HIPCHK(ctx, launch_transpose_features(b->batch, lo.TW, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
-                                          b->x_indices, p1, s));
-    HIPCHK(ctx, launch_rowgrad_adam(lo.H, p1, b->x_values, dh, ctx->buf.W1, ctx->buf.mW1, ctx->buf.vW1, nullptr,
-                                    nullptr, nullptr, a, s));
-    HIPCHK(ctx, launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, ctx->buf.b1, ctx->buf.mb1,
-                              ctx->buf.vb1, a, s));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_IN, s, [&] {
+      return launch_transpose_features(b->batch, lo.TW, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
+                                       b->x_indices, p1, s); }));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_IN, s, [&] {
+      return launch_rowgrad_adam(lo.H, p1, b->x_values, dh, ctx->buf.W1, ctx->buf.mW1, ctx->buf.vW1, nullptr,
+                                 nullptr, nullptr, a, s); }));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, s, [&] {
+      return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, ctx->buf.b1, ctx->buf.mb1,
+                           ctx->buf.vb1, a, ctx->ctrl(), s); }));
   } else {
-    HIPCHK(ctx, launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, nullptr, nullptr, nullptr, a, s));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, s, [&] {
+      return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, nullptr, nullptr, nullptr, a,
+                           ctx->ctrl(), s); }));
   }
   ctx->t = t;
   if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
@@ -448,10 +489,47 @@ int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out) {
   out->overflowed_buckets = c.overflowed;
   out->steps = ctx->t;
   out->rebuilds = ctx->r;
+  out->sum_active_pairs = (int64_t)c.sum_pairs;
+  out->sum_unique_out_rows = (int64_t)c.sum_u2;
+  out->sum_unique_in_rows = (int64_t)c.sum_u1;
+  out->sum_candidates = (int64_t)c.sum_candidates;
+  out->sum_steps = (int64_t)c.sum_steps;
+  return SLIDE_OK;
+}
+
+int slide_reset_stats(slide_ctx* ctx, void* hip_stream) {
+  if (!ctx) return SLIDE_EINVAL;
+  HIPCHK(ctx, hipStreamSynchronize((hipStream_t)hip_stream));
+  HIPCHK(ctx, hipMemset(&ctx->ctrl()->sum_pairs, 0, 5 * sizeof(unsigned long long)));
+  return SLIDE_OK;
+}
+
+int slide_profile(slide_ctx* ctx, uint32_t stage_mask) {
+  if (!ctx) return SLIDE_EINVAL;
+  ctx->prof_mask = stage_mask & ((1u << SLIDE_NUM_STAGES) - 1u);
+  return SLIDE_OK;
+}
+
+int slide_profile_read(slide_ctx* ctx, void* hip_stream, double* ms_sum, int64_t* launches) {
+  if (!ctx || !ms_sum || !launches) return SLIDE_EINVAL;
+  HIPCHK(ctx, hipStreamSynchronize((hipStream_t)hip_stream));
+  for (auto& r : ctx->prof_live) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) { ctx->prof_ms[r.stage] += ms; ctx->prof_n[r.stage] += 1; }
+    ctx->prof_pool.emplace_back(r.a, r.b);
+  }
+  ctx->prof_live.clear();
+  for (int i = 0; i < SLIDE_NUM_STAGES; ++i) {
+    ms_sum[i] = ctx->prof_ms[i]; launches[i] = ctx->prof_n[i];
+    ctx->prof_ms[i] = 0; ctx->prof_n[i] = 0;
+  }
   return SLIDE_OK;
 }
 
 int slide_destroy(slide_ctx* ctx) {
+  if (!ctx) return SLIDE_OK;
+  for (auto& r : ctx->prof_live) ctx->prof_pool.emplace_back(r.a, r.b);
+  for (auto& e : ctx->prof_pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
   delete ctx;
   return SLIDE_OK;
 }

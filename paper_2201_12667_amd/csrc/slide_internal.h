@@ -24,6 +24,8 @@ struct Ctrl {
   uint32_t total_chunks;
   uint32_t candidates_lo, candidates_hi;
   uint32_t pad[5];
+  // running totals since the last slide_reset_stats (updated once per training step)
+  unsigned long long sum_pairs, sum_u2, sum_u1, sum_candidates, sum_steps;
 };
 
 // Hash functions as the kernels read them.
@@ -125,7 +127,7 @@ hipError_t launch_rowgrad_adam(int H, const PairsDev& pd, const float* coef, con
                                const AdamDev& ad, hipStream_t s);
 // loss = mean(loss_i); with b1 != nullptr also gb1 = column sums of dh and Adam on b1.
 hipError_t launch_finish(int B, int H, const float* loss_i, float* d_loss, const float* dh, float* b1,
-                         float* mb1, float* vb1, const AdamDev& ad, hipStream_t s);
+                         float* mb1, float* vb1, const AdamDev& ad, Ctrl* ctrl, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 
 }  // namespace slide

@@ -120,9 +120,16 @@ hipError_t launch_rowgrad_adam(int H, const PairsDev& pd, const float* coef, con
 __global__ __launch_bounds__(256) void finish_kernel(int B, int H, const float* __restrict__ loss_i,
                                                      float* __restrict__ d_loss, const float* __restrict__ dh,
                                                      float* __restrict__ b1, float* __restrict__ mb1,
-                                                     float* __restrict__ vb1, AdamDev ad) {
+                                                     float* __restrict__ vb1, AdamDev ad, Ctrl* ctrl) {
   __shared__ float red[256];
   const int tid = threadIdx.x;
+  if (blockIdx.x == 0 && tid == 0) {          // statistics: totals over the steps
+    ctrl->sum_pairs += ctrl->total_pairs;
+    ctrl->sum_u2 += ctrl->u2;
+    ctrl->sum_u1 += ctrl->u1;
+    ctrl->sum_candidates += ((unsigned long long)ctrl->candidates_hi << 32) | ctrl->candidates_lo;
+    ctrl->sum_steps += 1;
+  }
   if (blockIdx.x == 0 && d_loss) {
     float acc = 0.f;
     for (int i = tid; i < B; i += 256) acc += loss_i[i];
@@ -145,9 +152,9 @@ __global__ __launch_bounds__(256) void finish_kernel(int B, int H, const float* 
 }
 
 hipError_t launch_finish(int B, int H, const float* loss_i, float* d_loss, const float* dh, float* b1,
-                         float* mb1, float* vb1, const AdamDev& ad, hipStream_t s) {
+                         float* mb1, float* vb1, const AdamDev& ad, Ctrl* ctrl, hipStream_t s) {
   hipLaunchKernelGGL(finish_kernel, dim3(ceil_div(H, 256)), dim3(256), 0, s, B, H, loss_i, d_loss, dh, b1, mb1,
-                     vb1, ad);
+                     vb1, ad, ctrl);
   return hipGetLastError();
 }
 

@@ -17,9 +17,12 @@ HASH_SIMHASH, HASH_DWTA = 0, 1
 KEEP_LOWEST_ID, KEEP_PRIORITY = 0, 1
 FLAG_BAD_FEATURE, FLAG_UNSORTED, FLAG_BAD_LABEL = 1, 2, 4
 ABI_VERSION = 1
+STAGES = ["hidden", "hash", "lookup", "scan", "emit", "forward", "combine", "transpose_out", "adam_out",
+          "transpose_in", "adam_in", "finish", "rebuild"]
+NUM_STAGES = len(STAGES)
 
 EXPORTS = ["slide_query_memory", "slide_init", "slide_build_tables", "slide_train_step", "slide_predict",
-           "slide_status", "slide_get_stats", "slide_destroy", "slide_last_error", "slide_debug_hash",
+           "slide_status", "slide_get_stats", "slide_profile", "slide_profile_read", "slide_reset_stats", "slide_destroy", "slide_last_error", "slide_debug_hash",
            "slide_debug_get_bucket", "slide_debug_get_active", "slide_debug_get_hidden"]
 
 
@@ -59,7 +62,9 @@ class slide_batch(C.Structure):
 
 class slide_stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("active_pairs", "unique_out_rows", "unique_in_rows", "candidates",
-                                         "overflowed_buckets", "steps", "rebuilds")]
+                                         "overflowed_buckets", "steps", "rebuilds", "sum_active_pairs",
+                                         "sum_unique_out_rows", "sum_unique_in_rows", "sum_candidates",
+                                         "sum_steps")]
 
 
 _lib = None
@@ -86,6 +91,9 @@ def load_library(path: str = LIB_PATH):
     L.slide_predict.argtypes = [vp, C.POINTER(slide_batch), i32, i32, vp, vp, vp]
     L.slide_status.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
     L.slide_get_stats.argtypes = [vp, vp, C.POINTER(slide_stats)]
+    L.slide_profile.argtypes = [vp, C.c_uint32]
+    L.slide_profile_read.argtypes = [vp, vp, vp, vp]
+    L.slide_reset_stats.argtypes = [vp, vp]
     L.slide_destroy.argtypes = [vp]
     L.slide_last_error.argtypes = [vp]
     L.slide_last_error.restype = C.c_char_p
@@ -234,6 +242,18 @@ class Slide:
         s = slide_stats()
         self._check(self.L.slide_get_stats(self.ctx, self._stream(), C.byref(s)))
         return {n: int(getattr(s, n)) for n, _ in slide_stats._fields_}
+
+    def reset_stats(self):
+        self._check(self.L.slide_reset_stats(self.ctx, self._stream()))
+
+    def profile(self, stage_mask: int):
+        self._check(self.L.slide_profile(self.ctx, stage_mask))
+
+    def profile_read(self):
+        ms = np.zeros(NUM_STAGES, dtype=np.float64)
+        n = np.zeros(NUM_STAGES, dtype=np.int64)
+        self._check(self.L.slide_profile_read(self.ctx, self._stream(), ms.ctypes.data, n.ctypes.data))
+        return ms, n
 
     def destroy(self):
         if self.ctx:

@@ -27,6 +27,26 @@ def worst(a, ref):
     return float(np.max(np.abs(a - ref) / (REL * np.abs(ref) + FLOOR * np.abs(ref).max() + 1e-30)))
 
 
+def worst_weight(w, orc, name):
+    """Tolerance ratio of an updated parameter tensor.  On top of the direct bar
+    (REL*|w| + FLOOR*max|w|) it grants what the tolerances already granted to Adam's momentum and
+    velocity amount to once propagated through the update u = lr * mh / (sqrt(vh) + eps),
+    mh = m/(1-b1^t), vh = v/(1-b2^t):  |du| <= lr/(sqrt(vh)+eps) * |dmh| + lr*|mh| / (2 sqrt(vh)
+    (sqrt(vh)+eps)^2) * |dvh|.  Adam normalises the gradient, so an element whose gradient is tiny
+    (a sum that cancels to ~eps) amplifies its absolute rounding error by up to lr/eps; every
+    quantity below comes from the oracle."""
+    ref = orc.p[name].astype(np.float64)
+    m, v = orc.m[name].astype(np.float64), orc.v[name].astype(np.float64)
+    bc1, bc2 = 1 - orc.beta1 ** orc.t, 1 - orc.beta2 ** orc.t
+    tol_m = (REL * np.abs(m) + FLOOR * np.abs(m).max()) / bc1
+    tol_v = (REL * np.abs(v) + FLOOR * np.abs(v).max()) / bc2
+    sv = np.sqrt(v / bc2)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        dv = np.where(sv > 0, np.abs(m / bc1) / (2 * sv * (sv + orc.eps) ** 2), 0.0)
+    tol = REL * np.abs(ref) + FLOOR * np.abs(ref).max() + orc.lr * (tol_m / (sv + orc.eps) + dv * tol_v) + 1e-30
+    return float(np.max(np.abs(np.asarray(w, np.float64) - ref) / tol))
+
+
 def make_oracle(wl, weights, hp):
     return so.SlideOracle(input_dim=wl.input_dim, hidden_dim=wl.hidden_dim, num_classes=wl.num_classes,
                           hash_kind=wl.hash_kind, K=wl.K, L=wl.L, bucket_cap=wl.bucket_cap,
@@ -76,7 +96,7 @@ def compare_step(model, orc, batch, check_state=True):
            "loss": abs(loss - ref["loss"]) / (REL * max(abs(ref["loss"]), 1e-12))}
     if check_state:
         for n in model.p:
-            res["w:" + n] = worst(model.p[n].cpu().numpy(), orc.p[n])
+            res["w:" + n] = worst_weight(model.p[n].cpu().numpy(), orc, n)
             res["m:" + n] = worst(model.m[n].cpu().numpy(), orc.m[n])
             res["v:" + n] = worst(model.v[n].cpu().numpy(), orc.v[n])
     res["_loss"] = (loss, ref["loss"])
