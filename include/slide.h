@@ -170,9 +170,9 @@ int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out);
 enum slide_stage {
   SLIDE_STAGE_HIDDEN = 0,        /* sparse-input hidden layer                       */
   SLIDE_STAGE_HASH = 1,          /* hash codes of the hidden activations            */
-  SLIDE_STAGE_LOOKUP = 2,        /* bucket reads + union bitmap                     */
-  SLIDE_STAGE_SCAN = 3,          /* offsets over the samples                        */
-  SLIDE_STAGE_EMIT = 4,          /* sorted id lists + label flags                   */
+  SLIDE_STAGE_LOOKUP = 2,        /* bucket reads, union bitmap, sorted id lists     */
+  SLIDE_STAGE_SCAN = 3,          /* forward work items over the samples             */
+  SLIDE_STAGE_RESERVED = 4,      /* (unused)                                        */
   SLIDE_STAGE_FORWARD = 5,       /* logits + running soft-max over gathered rows    */
   SLIDE_STAGE_COMBINE = 6,       /* normaliser, errors, loss, hidden gradient       */
   SLIDE_STAGE_TRANSPOSE_OUT = 7, /* touched output rows -> sample lists             */

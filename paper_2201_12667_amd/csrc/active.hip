@@ -72,8 +72,13 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   if (tid == 0) pos[ad.L] = carry;
   __syncthreads();
   const uint32_t T = pos[ad.L];
-  const int y0 = include_labels ? y_indptr[i] : 0;
-  const int nlab = include_labels ? y_indptr[i + 1] - y0 : 0;
+  // the sample's slice of the sample-major arrays: room for every candidate plus its labels
+  int y0 = 0, nlab = 0;
+  if (include_labels) {
+    y0 = min(max(y_indptr[i], 0), ad.num_labels);
+    nlab = min(max(y_indptr[i + 1], y0), ad.num_labels) - y0;
+  }
+  const int base_i = i * ad.PS + y0;
 
   uint32_t my_cnt = 0;
   for (int seg0 = 0; seg0 < ad.NWpad; seg0 += segw) {
@@ -112,56 +117,13 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   for (int d = 32; d > 0; d >>= 1) my_cnt += __shfl_xor(my_cnt, d);
   if (lane == 0) atomicAdd(&sm[18], my_cnt);
   __syncthreads();
-  if (tid == 0) { ad.cnt[i] = (int32_t)sm[18]; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; }
-}
+  const int n = (int)sm[18];
+  if (tid == 0) { ad.cnt[i] = n; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; ad.as_base[i] = base_i; }
 
-__global__ __launch_bounds__(1024) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
-                                                            Ctrl* ctrl) {
-  __shared__ uint32_t sm[20];
-  uint32_t carry_a = 0, carry_c = 0;
-  unsigned long long cand = 0;
-  for (int base = 0; base < ad.B; base += blockDim.x) {
-    const int i = base + threadIdx.x;
-    const uint32_t n = i < ad.B ? (uint32_t)ad.cnt[i] : 0u;
-    const uint32_t ch = (n + kChunk - 1) / kChunk;
-    uint32_t ta, tc;
-    const uint32_t ea = block_excl_scan(n, sm, &ta);
-    __syncthreads();
-    const uint32_t ec = block_excl_scan(ch, sm, &tc);
-    if (i < ad.B) {
-      ad.as_ptr[i] = (int32_t)(carry_a + ea);
-      ad.chunk_ptr[i] = (int32_t)(carry_c + ec);
-      for (uint32_t k = 0; k < ch; ++k) ad.chunk_sample[carry_c + ec + k] = i;
-      cand += (unsigned long long)ncand[i];
-    }
-    carry_a += ta; carry_c += tc;
-    __syncthreads();
-  }
-  // total of the candidate counts (statistics only)
-  __shared__ unsigned long long cs[16];
-  for (int d = 32; d > 0; d >>= 1) cand += __shfl_xor(cand, d);
-  if ((threadIdx.x & 63) == 0) cs[threadIdx.x >> 6] = cand;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned long long c = 0;
-    for (unsigned w = 0; w < blockDim.x / 64; ++w) c += cs[w];
-    ad.as_ptr[ad.B] = (int32_t)carry_a;
-    ad.chunk_ptr[ad.B] = (int32_t)carry_c;
-    ctrl->total_pairs = carry_a;
-    ctrl->total_chunks = carry_c;
-    ctrl->candidates_lo = (uint32_t)c;
-    ctrl->candidates_hi = (uint32_t)(c >> 32);
-    ctrl->u2 = ctrl->p2 = ctrl->u1 = ctrl->p1 = 0;
-  }
-}
-
-__global__ __launch_bounds__(256) void emit_kernel(ActiveDev ad, const int32_t* __restrict__ y_indptr,
-                                                   const int32_t* __restrict__ y_indices, int include_labels) {
-  __shared__ uint32_t sm[20];
-  const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  // per-tile counts -> exclusive prefix inside the sample (rank of the tile's first active neuron)
   uint32_t* rk = ad.rankT + (size_t)i * ad.NT;
-  uint32_t carry = 0;
-  for (int base = 0; base < ad.NT; base += 256) {
+  carry = 0;
+  for (int base = 0; base < ad.NT; base += nthr) {
     const int t = base + tid;
     const uint32_t v = t < ad.NT ? rk[t] : 0u;
     uint32_t total;
@@ -170,11 +132,12 @@ __global__ __launch_bounds__(256) void emit_kernel(ActiveDev ad, const int32_t* 
     carry += total;
     __syncthreads();
   }
-  const int base_i = ad.as_ptr[i];
+  // compact ascending id list: sweep the bitmap (still in LDS if it fitted in one segment)
+  const bool in_lds = segw >= ad.NWpad;
   const uint32_t* arow = ad.act + (size_t)i * ad.NWpad;
-  for (int wb = 0; wb < ad.NWpad; wb += 256) {
+  for (int wb = 0; wb < ad.NWpad; wb += nthr) {
     const int w = wb + tid;
-    uint32_t word = w < ad.NWpad ? arow[w] : 0u;
+    uint32_t word = w < ad.NWpad ? (in_lds ? bm[w] : arow[w]) : 0u;
     const uint32_t c = __popc(word);
     uint32_t inc = c;
     for (int d = 1; d < ad.TW; d <<= 1) {
@@ -193,9 +156,8 @@ __global__ __launch_bounds__(256) void emit_kernel(ActiveDev ad, const int32_t* 
     }
   }
   __syncthreads();
-  if (!include_labels) return;
-  const int n = ad.cnt[i], y0 = y_indptr[i], nlab = y_indptr[i + 1] - y0;
-  for (int q = tid; q < nlab; q += 256) {
+  // label flags, and for every label entry its slot (-1 for invalid or repeated entries)
+  for (int q = tid; q < nlab; q += nthr) {
     const int y = y_indices[y0 + q];
     int slot = -1;
     if (y >= 0 && y < ad.N) {
@@ -204,29 +166,80 @@ __global__ __launch_bounds__(256) void emit_kernel(ActiveDev ad, const int32_t* 
       if (a < n && ad.as_ids[base_i + a] == y) {
         ad.as_lab[base_i + a] = 1;
         slot = base_i + a;
-        for (int q2 = 0; q2 < q; ++q2) if (y_indices[y0 + q2] == y) { slot = -1; break; }   // repeated label
+        for (int q2 = 0; q2 < q; ++q2) if (y_indices[y0 + q2] == y) { slot = -1; break; }
       }
     }
     ad.ylist[y0 + q] = slot;
   }
 }
 
-// One workgroup per tile of TW bitmap words, all samples.  FEAT = false: the active bit matrix
-// (coefficient index = slot of the pair in the sample-major arrays).  FEAT = true: the feature bit
-// matrix of the batch (coefficient index = position in the CSR value array; the matrix is
-// cleared behind the read so it is all-zero again for the next batch).
+// Forward work items (chunks of kChunk active neurons) over the samples, totals for the statistics,
+// and the reset of the per-step device counters.
+__global__ __launch_bounds__(1024) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
+                                                            Ctrl* ctrl) {
+  __shared__ uint32_t sm[20];
+  __shared__ unsigned long long cs[16], as[16];
+  uint32_t carry_c = 0;
+  unsigned long long cand = 0, pairs = 0;
+  for (int base = 0; base < ad.B; base += blockDim.x) {
+    const int i = base + threadIdx.x;
+    const uint32_t n = i < ad.B ? (uint32_t)ad.cnt[i] : 0u;
+    const uint32_t ch = (n + kChunk - 1) / kChunk;
+    uint32_t tc;
+    const uint32_t ec = block_excl_scan(ch, sm, &tc);
+    if (i < ad.B) {
+      ad.chunk_ptr[i] = (int32_t)(carry_c + ec);
+      for (uint32_t k = 0; k < ch; ++k) ad.chunk_sample[carry_c + ec + k] = i;
+      cand += (unsigned long long)ncand[i];
+      pairs += n;
+    }
+    carry_c += tc;
+    __syncthreads();
+  }
+  for (int d = 32; d > 0; d >>= 1) { cand += __shfl_xor(cand, d); pairs += __shfl_xor(pairs, d); }
+  if ((threadIdx.x & 63) == 0) { cs[threadIdx.x >> 6] = cand; as[threadIdx.x >> 6] = pairs; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long c = 0, a = 0;
+    for (unsigned w = 0; w < blockDim.x / 64; ++w) { c += cs[w]; a += as[w]; }
+    ad.chunk_ptr[ad.B] = (int32_t)carry_c;
+    ctrl->total_pairs = (uint32_t)a;
+    ctrl->total_chunks = carry_c;
+    ctrl->candidates_lo = (uint32_t)c;
+    ctrl->candidates_hi = (uint32_t)(c >> 32);
+    ctrl->p1 = 0; ctrl->nlong2 = 0; ctrl->nlong1 = 0;
+  }
+}
+
+// One workgroup per tile of TW bitmap words, all samples: the tile's touched rows, in row order,
+// each with the ascending list of the samples that touch it.  Row slots of tile t are
+// [t*TW*32, t*TW*32 + tile_nu[t]).  FEAT = false: the active bit matrix; a pair's coefficient
+// index is its slot in the sample-major arrays, and the tile's first pair position is the sum over
+// the samples of their in-sample ranks at the tile start (no atomics: the layout is a pure function
+// of the bit matrix).  FEAT = true: the feature bit matrix of the batch; the coefficient index is the
+// position in the CSR value array, pair space is handed out per workgroup, and the matrix is cleared
+// behind the read so that it is all-zero again for the next batch.
+constexpr int kTransposeWaves = 8;
+
 template <bool FEAT>
-__global__ __launch_bounds__(256) void transpose_kernel(int B, int Bpad, int TW, int NWpad, uint32_t* bits,
+__global__ __launch_bounds__(512) void transpose_kernel(int B, int Bpad, int TW, int NWpad, uint32_t* bits,
                                                         const uint32_t* __restrict__ rankT, int NT,
-                                                        const int32_t* __restrict__ as_ptr,
+                                                        const int32_t* __restrict__ as_base,
                                                         const int32_t* __restrict__ x_indptr,
                                                         const int32_t* __restrict__ x_indices, PairsDev pd) {
   extern __shared__ uint32_t lds[];
   uint32_t* tile = lds;                                  // [TW][Bpad]
-  uint32_t* sb = tile + (size_t)TW * Bpad;                // [Bpad] slot base of the sample in this tile
-  uint16_t* rk = (uint16_t*)(sb + Bpad);                 // [TW][Bpad] in-tile rank before the word
+  uint32_t* sb = tile + (size_t)TW * Bpad;                // [Bpad] slot of the sample's first pair in this tile
+  uint32_t* wu = sb + Bpad;                              // [32] union word
+  uint32_t* wnp = wu + 32;                               // [32] pairs per word, then exclusive prefix
+  uint32_t* wou = wnp + 32;                              // [32] rows before the word
+  uint32_t* blk = wou + 32;                              // [2] pair base of the tile, sum of ranks
+  uint16_t* rk = (uint16_t*)(blk + 2);                   // [TW][Bpad] in-tile rank before the word
   const int tileno = blockIdx.x, tid = threadIdx.x;
-  for (int i = tid; i < Bpad; i += 256) {
+  if (tid == 0) { blk[0] = 0; blk[1] = 0; }
+  __syncthreads();
+  uint32_t ranksum = 0;
+  for (int i = tid; i < Bpad; i += 64 * kTransposeWaves) {
     uint32_t run = 0;
     uint32_t* src = bits + (size_t)i * NWpad + (size_t)tileno * TW;
     for (int w = 0; w < TW; ++w) {
@@ -239,37 +252,59 @@ __global__ __launch_bounds__(256) void transpose_kernel(int B, int Bpad, int TW,
       if (!FEAT) rk[w * Bpad + i] = (uint16_t)run;
       run += __popc(x);
     }
-    if (!FEAT) sb[i] = i < B ? (uint32_t)as_ptr[i] + rankT[(size_t)i * NT + tileno] : 0u;
+    if (!FEAT) {
+      const uint32_t r0 = i < B ? rankT[(size_t)i * NT + tileno] : 0u;
+      sb[i] = i < B ? (uint32_t)as_base[i] + r0 : 0u;
+      ranksum += r0;
+    }
   }
+  if (!FEAT) atomicAdd(&blk[1], ranksum);                // integer sum: order does not matter
   __syncthreads();
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int groups = Bpad >> 6;
-  for (int w = wave; w < TW; w += 4) {
+  for (int w = wave; w < TW; w += kTransposeWaves) {
     uint32_t u = 0, np = 0;
     for (int k = 0; k < groups; ++k) { const uint32_t x = tile[w * Bpad + k * 64 + lane]; u |= x; np += __popc(x); }
     for (int d = 32; d > 0; d >>= 1) { u |= __shfl_xor(u, d); np += __shfl_xor(np, d); }
-    u = __builtin_amdgcn_readfirstlane(u);
+    if (lane == 0) { wu[w] = u; wnp[w] = np; }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t nu = 0, np = 0;
+    for (int w = 0; w < TW; ++w) { wou[w] = nu; nu += __popc(wu[w]); const uint32_t c = wnp[w]; wnp[w] = np; np += c; }
+    pd.tile_nu[tileno] = (int32_t)nu;
+    blk[0] = FEAT ? (np ? atomicAdd(pd.pcount, np) : 0u) : blk[1];
+  }
+  __syncthreads();
+  const uint32_t slot0 = (uint32_t)tileno * (uint32_t)(TW * 32);
+  constexpr int KG = 4;                                  // sample groups held in registers
+  for (int w = wave; w < TW; w += kTransposeWaves) {
+    uint32_t u = __builtin_amdgcn_readfirstlane(wu[w]);
     if (u == 0) continue;
-    uint32_t ubase = 0, po = 0;
-    if (lane == 0) { ubase = atomicAdd(pd.ucount, (uint32_t)__popc(u)); po = atomicAdd(pd.pcount, np); }
-    ubase = __builtin_amdgcn_readfirstlane(ubase);
-    po = __builtin_amdgcn_readfirstlane(po);
+    uint32_t us = slot0 + __builtin_amdgcn_readfirstlane(wou[w]);
+    uint32_t po = __builtin_amdgcn_readfirstlane(blk[0] + wnp[w]);
+    uint32_t xr[KG], sr[KG];
+#pragma unroll
+    for (int k = 0; k < KG; ++k) {
+      const int i = k * 64 + lane;
+      xr[k] = k < groups ? tile[w * Bpad + i] : 0u;
+      sr[k] = (!FEAT && k < groups) ? sb[i] + rk[w * Bpad + i] : 0u;
+    }
     while (u) {
       const int b = __ffs(u) - 1;
       u &= u - 1;
       const int row = (tileno * TW + w) * 32 + b;
       uint32_t cntj = 0;
-      for (int k = 0; k < groups; ++k) {
+      auto take = [&](int k, uint32_t x, uint32_t sbase) {
         const int i = k * 64 + lane;
-        const uint32_t x = tile[w * Bpad + i];
         const bool has = (x >> b) & 1u;
         const unsigned long long mk = __ballot(has);
         if (has) {
           const uint32_t p = po + cntj + __popcll(mk & ((1ull << lane) - 1ull));
           pd.psample[p] = i;
           if (!FEAT) {
-            pd.psrc[p] = (int32_t)(sb[i] + rk[w * Bpad + i] + __popc(x & ((1u << b) - 1u)));
+            pd.psrc[p] = (int32_t)(sbase + __popc(x & ((1u << b) - 1u)));
           } else {
             int a = x_indptr[i], e = x_indptr[i + 1];
             while (a < e) { const int mid = (a + e) >> 1; if (x_indices[mid] < row) a = mid + 1; else e = mid; }
@@ -277,27 +312,40 @@ __global__ __launch_bounds__(256) void transpose_kernel(int B, int Bpad, int TW,
           }
         }
         cntj += (uint32_t)__popcll(mk);
+      };
+#pragma unroll
+      for (int k = 0; k < KG; ++k)
+        if (k < groups) take(k, xr[k], sr[k]);
+      for (int k = KG; k < groups; ++k) {
+        const int i = k * 64 + lane;
+        take(k, tile[w * Bpad + i], FEAT ? 0u : sb[i] + rk[w * Bpad + i]);
       }
-      if (lane == 0) { pd.urow[ubase] = row; pd.ustart[ubase] = po; pd.ucnt[ubase] = (int32_t)cntj; }
-      ++ubase;
+      if (lane == 0) {
+        pd.urow[us] = row; pd.ustart[us] = po; pd.ucnt[us] = (int32_t)cntj;
+        if ((int)cntj > kLongRow) {
+          const uint32_t l = atomicAdd(pd.nlong, 1u);
+          if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
+        }
+      }
+      ++us;
       po += cntj;
     }
   }
 }
 
-static size_t transpose_lds(int TW, int Bpad) { return (size_t)TW * Bpad * 6 + (size_t)Bpad * 4; }
+static size_t transpose_lds(int TW, int Bpad) { return (size_t)TW * Bpad * 6 + (size_t)Bpad * 4 + 98 * 4; }
 
 hipError_t launch_transpose_active(const ActiveDev& ad, const PairsDev& pd, hipStream_t s) {
   const int Bpad = (ad.B + 63) & ~63;
-  hipLaunchKernelGGL(transpose_kernel<false>, dim3(ad.NT), dim3(256), transpose_lds(ad.TW, Bpad), s, ad.B, Bpad,
-                     ad.TW, ad.NWpad, ad.act, ad.rankT, ad.NT, ad.as_ptr, nullptr, nullptr, pd);
+  hipLaunchKernelGGL(transpose_kernel<false>, dim3(ad.NT), dim3(64 * kTransposeWaves), transpose_lds(ad.TW, Bpad), s, ad.B, Bpad,
+                     ad.TW, ad.NWpad, ad.act, ad.rankT, ad.NT, ad.as_base, nullptr, nullptr, pd);
   return hipGetLastError();
 }
 
 hipError_t launch_transpose_features(int B, int TW, int DWpad, uint32_t* xbm, const int32_t* x_indptr,
                                      const int32_t* x_indices, const PairsDev& pd, hipStream_t s) {
   const int Bpad = (B + 63) & ~63;
-  hipLaunchKernelGGL(transpose_kernel<true>, dim3(DWpad / TW), dim3(256), transpose_lds(TW, Bpad), s, B, Bpad, TW,
+  hipLaunchKernelGGL(transpose_kernel<true>, dim3(DWpad / TW), dim3(64 * kTransposeWaves), transpose_lds(TW, Bpad), s, B, Bpad, TW,
                      DWpad, xbm, nullptr, 0, nullptr, x_indptr, x_indices, pd);
   return hipGetLastError();
 }
@@ -311,9 +359,10 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
   if (lim > 160 * 1024) lim = 160 * 1024;
   e = hipFuncSetAttribute((const void*)lookup_union_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)transpose_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  const int tl = lim < 72 * 1024 ? lim : 72 * 1024;
+  e = hipFuncSetAttribute((const void*)transpose_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, tl);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)transpose_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  e = hipFuncSetAttribute((const void*)transpose_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, tl);
   if (e != hipSuccess) return e;
   *lds_limit_out = (size_t)lim;
   return hipSuccess;
@@ -334,12 +383,6 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const TablesDev& td, const u
 
 hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, hipStream_t s) {
   hipLaunchKernelGGL(scan_samples_kernel, dim3(1), dim3(1024), 0, s, ad, ncand, ctrl);
-  return hipGetLastError();
-}
-
-hipError_t launch_emit(const ActiveDev& ad, const int32_t* y_indptr, const int32_t* y_indices,
-                       int include_labels, hipStream_t s) {
-  hipLaunchKernelGGL(emit_kernel, dim3(ad.B), dim3(256), 0, s, ad, y_indptr, y_indices, include_labels);
   return hipGetLastError();
 }
 

@@ -20,12 +20,12 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   // derived sizes
-  int Bmax, Bpad, H, L, K, C, TW, NWpad, NT, DWpad, bits;
-  int64_t N, D, Amax, max_chunks, U2max, U1max, P1max;
+  int Bmax, Bpad, H, L, K, C, TW, TWF, NWpad, NT, NT1, DWpad, bits, PS;
+  int64_t N, D, Amax, max_chunks, U2max, U1max, P1max, long2, long1;
   uint32_t nb, nseg, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, xbm, h, dh, codes, act, rankT, cnt, ny, ncand, as_ptr, chunk_ptr, chunk_sample, as_ids,
+  size_t ctrl, hashw, xbm, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, urow2, ustart2, ucnt2, psample2, psrc2, urow1, ustart1,
       ucnt1, psample1, psrc1, codes_t, rank_t, segsum, worklist, ws_total;
   // tables offsets
@@ -85,17 +85,22 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   int tw = 32;
   while (tw > 1 && tw * lo->Bpad > 8192) tw >>= 1;
   lo->TW = tw;
+  lo->TWF = std::min(tw, 8);
   lo->NWpad = (int)(((lo->N + 31) / 32 + 31) / 32 * 32);
   lo->NT = lo->NWpad / tw;
   lo->DWpad = (int)(((lo->D + 31) / 32 + 31) / 32 * 32);
+  lo->NT1 = lo->DWpad / lo->TWF;
   const int64_t per_sample = std::min<int64_t>((int64_t)c->L * c->bucket_cap, lo->N);
-  lo->Amax = std::min<int64_t>((int64_t)c->max_batch * lo->N, (int64_t)c->max_batch * per_sample + c->max_labels_per_batch);
+  lo->PS = (int)per_sample;
+  lo->Amax = (int64_t)c->max_batch * per_sample + c->max_labels_per_batch;
   if (lo->Amax >= ((int64_t)1 << 31) - 64) FAIL(SLIDE_EINVAL, "max_batch * L * bucket_cap does not fit 31 bits");
   if ((int64_t)c->L * lo->N >= ((int64_t)1 << 32)) FAIL(SLIDE_EINVAL, "L * num_classes does not fit 32 bits");
   lo->max_chunks = lo->Amax / kChunk + c->max_batch + 1;
-  lo->U2max = std::min<int64_t>(lo->N, lo->Amax);
+  lo->U2max = (int64_t)lo->NWpad * 32;
   lo->P1max = c->max_nnz_per_batch;
-  lo->U1max = std::min<int64_t>(lo->D, lo->P1max);
+  lo->U1max = (int64_t)lo->DWpad * 32;
+  lo->long2 = lo->Amax / kLongRow + 1;
+  lo->long1 = lo->P1max / kLongRow + 1;
   const int small = std::min(kSmallBucket, c->bucket_cap);
   const uint64_t wl = (uint64_t)c->L * (uint64_t)(lo->N / (small + 1) + 1);
   lo->wl_cap = (uint32_t)std::min<uint64_t>(wl, 0xfffffff0u);
@@ -112,7 +117,9 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->act = take(B * lo->NWpad * 4);
   lo->rankT = take(B * lo->NT * 4);
   lo->cnt = take(B * 4); lo->ny = take(B * 4); lo->ncand = take(B * 4);
-  lo->as_ptr = take((B + 1) * 4); lo->chunk_ptr = take((B + 1) * 4);
+  lo->as_base = take(B * 4); lo->chunk_ptr = take((B + 1) * 4);
+  lo->tile_nu2 = take((size_t)lo->NT * 4); lo->tile_nu1 = take((size_t)lo->NT1 * 4 + 4);
+  lo->longlist2 = take((size_t)lo->long2 * 4); lo->longlist1 = take((size_t)lo->long1 * 4);
   lo->chunk_sample = take((size_t)lo->max_chunks * 4);
   lo->as_ids = take(A * 4); lo->as_lab = take(A); lo->ylist = take((size_t)c->max_labels_per_batch * 4 + 4);
   lo->z = take(A * 4); lo->delta = take(A * 4);
@@ -206,7 +213,8 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ad.B = B; ad.L = lo.L; ad.C = lo.C; ad.TW = lo.TW; ad.N = lo.N; ad.NWpad = lo.NWpad; ad.NT = lo.NT;
   ad.act = c->at<uint32_t>(lo.act); ad.rankT = c->at<uint32_t>(lo.rankT);
   ad.cnt = c->at<int32_t>(lo.cnt); ad.ny = c->at<int32_t>(lo.ny);
-  ad.as_ptr = c->at<int32_t>(lo.as_ptr); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
+  ad.PS = lo.PS; ad.num_labels = 0;
+  ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
   ad.chunk_sample = c->at<int32_t>(lo.chunk_sample);
   ad.as_ids = c->at<int32_t>(lo.as_ids); ad.as_lab = c->at<uint8_t>(lo.as_lab); ad.ylist = c->at<int32_t>(lo.ylist);
   return ad;
@@ -247,13 +255,12 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HASH, s, [&] {
     return launch_hash(ctx->hd, h, B, codes, lo.L, 1, nullptr, nullptr, lo.nb, 4, s); }));
   ActiveDev ad = make_active(ctx, B);
+  ad.num_labels = with_labels ? b->num_labels : 0;
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
     return launch_lookup_union(ad, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0, ncand,
                                ctx->ctrl(), ctx->lds_limit, s); }));
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), s); }));
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_EMIT, s, [&] {
-    return launch_emit(ad, b->y_indptr, b->y_indices, with_labels ? 1 : 0, s); }));
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
                           ctx->at<float>(lo.partials), ctx->ctrl(), s); }));
@@ -412,31 +419,35 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   a.inv_bc1 = (float)(1.0 / (1.0 - std::pow(c.beta1, (double)t)));
   a.inv_bc2 = (float)(1.0 / (1.0 - std::pow(c.beta2, (double)t)));
   PairsDev p2;
+  p2.rows_per_tile = lo.TW * 32; p2.ntiles = lo.NT; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
   p2.urow = ctx->at<int32_t>(lo.urow2); p2.ustart = ctx->at<uint32_t>(lo.ustart2); p2.ucnt = ctx->at<int32_t>(lo.ucnt2);
   p2.psample = ctx->at<int32_t>(lo.psample2); p2.psrc = ctx->at<int32_t>(lo.psrc2);
-  p2.ucount = &ctx->ctrl()->u2; p2.pcount = &ctx->ctrl()->p2;
+  p2.pcount = nullptr; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
+  p2.long_cap = (int)lo.long2;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_OUT, s, [&] { return launch_transpose_active(ad, p2, s); }));
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_OUT, s, [&] {
     return launch_rowgrad_adam(lo.H, p2, delta, ctx->last_h, ctx->buf.W2, ctx->buf.mW2, ctx->buf.vW2,
                                ctx->buf.b2, ctx->buf.mb2, ctx->buf.vb2, a, s); }));
   if (lo.D > 0) {
     PairsDev p1;
+    p1.rows_per_tile = lo.TWF * 32; p1.ntiles = lo.NT1; p1.tile_nu = ctx->at<int32_t>(lo.tile_nu1);
     p1.urow = ctx->at<int32_t>(lo.urow1); p1.ustart = ctx->at<uint32_t>(lo.ustart1); p1.ucnt = ctx->at<int32_t>(lo.ucnt1);
     p1.psample = ctx->at<int32_t>(lo.psample1); p1.psrc = ctx->at<int32_t>(lo.psrc1);
-    p1.ucount = &ctx->ctrl()->u1; p1.pcount = &ctx->ctrl()->p1;
+    p1.pcount = &ctx->ctrl()->p1; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
+    p1.long_cap = (int)lo.long1;
     HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_IN, s, [&] {
-      return launch_transpose_features(b->batch, lo.TW, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
+      return launch_transpose_features(b->batch, lo.TWF, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
                                        b->x_indices, p1, s); }));
     HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_IN, s, [&] {
       return launch_rowgrad_adam(lo.H, p1, b->x_values, dh, ctx->buf.W1, ctx->buf.mW1, ctx->buf.vW1, nullptr,
                                  nullptr, nullptr, a, s); }));
     HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, s, [&] {
       return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, ctx->buf.b1, ctx->buf.mb1,
-                           ctx->buf.vb1, a, ctx->ctrl(), s); }));
+                           ctx->buf.vb1, a, ctx->ctrl(), p2.tile_nu, p2.ntiles, p1.tile_nu, p1.ntiles, s); }));
   } else {
     HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, s, [&] {
       return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, nullptr, nullptr, nullptr, a,
-                           ctx->ctrl(), s); }));
+                           ctx->ctrl(), p2.tile_nu, p2.ntiles, nullptr, 0, s); }));
   }
   ctx->t = t;
   if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
@@ -564,16 +575,22 @@ int slide_debug_get_active(slide_ctx* ctx, int64_t* h_as_ptr, int32_t* h_as_ids,
   if (ctx->last_B < 1) return set_err(ctx, SLIDE_ESTATE, "no step has run yet");
   HIPCHK(ctx, hipDeviceSynchronize());
   const int B = ctx->last_B;
-  std::vector<int32_t> p(B + 1);
-  HIPCHK(ctx, hipMemcpy(p.data(), ctx->at<int32_t>(ctx->lo.as_ptr), (size_t)(B + 1) * 4, hipMemcpyDeviceToHost));
-  for (int i = 0; i <= B; ++i) h_as_ptr[i] = p[i];
-  const int64_t A = p[B];
+  std::vector<int32_t> base(B), cnt(B);
+  HIPCHK(ctx, hipMemcpy(base.data(), ctx->at<int32_t>(ctx->lo.as_base), (size_t)B * 4, hipMemcpyDeviceToHost));
+  HIPCHK(ctx, hipMemcpy(cnt.data(), ctx->at<int32_t>(ctx->lo.cnt), (size_t)B * 4, hipMemcpyDeviceToHost));
+  h_as_ptr[0] = 0;
+  for (int i = 0; i < B; ++i) h_as_ptr[i + 1] = h_as_ptr[i] + cnt[i];
+  const int64_t A = h_as_ptr[B];
   if (A > capacity) return set_err(ctx, SLIDE_ENOMEM, "capacity %lld < active pairs %lld", (long long)capacity, (long long)A);
-  if (A == 0) return SLIDE_OK;
-  if (h_as_ids) HIPCHK(ctx, hipMemcpy(h_as_ids, ctx->at<int32_t>(ctx->lo.as_ids), (size_t)A * 4, hipMemcpyDeviceToHost));
-  if (h_is_label) HIPCHK(ctx, hipMemcpy(h_is_label, ctx->at<uint8_t>(ctx->lo.as_lab), (size_t)A, hipMemcpyDeviceToHost));
-  if (h_logits) HIPCHK(ctx, hipMemcpy(h_logits, ctx->at<float>(ctx->lo.z), (size_t)A * 4, hipMemcpyDeviceToHost));
-  if (h_delta) HIPCHK(ctx, hipMemcpy(h_delta, ctx->at<float>(ctx->lo.delta), (size_t)A * 4, hipMemcpyDeviceToHost));
+  // the device keeps each sample's slice at its own base; the caller gets them back to back
+  for (int i = 0; i < B; ++i) {
+    const size_t n = (size_t)cnt[i], src = (size_t)base[i], dst = (size_t)h_as_ptr[i];
+    if (!n) continue;
+    if (h_as_ids) HIPCHK(ctx, hipMemcpy(h_as_ids + dst, ctx->at<int32_t>(ctx->lo.as_ids) + src, n * 4, hipMemcpyDeviceToHost));
+    if (h_is_label) HIPCHK(ctx, hipMemcpy(h_is_label + dst, ctx->at<uint8_t>(ctx->lo.as_lab) + src, n, hipMemcpyDeviceToHost));
+    if (h_logits) HIPCHK(ctx, hipMemcpy(h_logits + dst, ctx->at<float>(ctx->lo.z) + src, n * 4, hipMemcpyDeviceToHost));
+    if (h_delta) HIPCHK(ctx, hipMemcpy(h_delta + dst, ctx->at<float>(ctx->lo.delta) + src, n * 4, hipMemcpyDeviceToHost));
+  }
   return SLIDE_OK;
 }
 

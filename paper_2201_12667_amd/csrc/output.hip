@@ -27,29 +27,37 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
   float2 acc = col_ok ? *(const float2*)(b1 + c0) : make_float2(0.f, 0.f);
   int prev = -1;
   uint32_t flags = 0;
-  constexpr int UN = 8;
-  for (int p = p0; p < p1; p += UN) {
-    int k[UN];
-    float v[UN];
-    float2 w[UN];
+  constexpr int UN = 16;
+  for (int pb = p0; pb < p1; pb += 64) {
+    // one coalesced read of the next 64 (index, value) pairs; lane q holds pair pb + q
+    const int mine = pb + lane < p1 ? x_indices[pb + lane] : -1;
+    const float myv = pb + lane < p1 ? x_values[pb + lane] : 0.f;
+    const bool bad = pb + lane < p1 && (mine < 0 || mine >= D);
+    if (__any(bad)) flags |= SLIDE_FLAG_BAD_FEATURE;
+    const int kk = bad ? -1 : mine;
+    if (blockIdx.y == 0 && kk >= 0) atomicOr(&xbm[(size_t)i * DWpad + (kk >> 5)], 1u << (kk & 31));
+    const int cnt = min(64, p1 - pb);
+    for (int q0 = 0; q0 < cnt; q0 += UN) {
+      int k[UN];
+      float v[UN];
+      float2 w[UN];
 #pragma unroll
-    for (int q = 0; q < UN; ++q) {
-      const bool in = p + q < p1;
-      k[q] = in ? x_indices[p + q] : -1;
-      v[q] = in ? x_values[p + q] : 0.f;
-      if (in && (k[q] < 0 || k[q] >= D)) { flags |= SLIDE_FLAG_BAD_FEATURE; k[q] = -1; }
-    }
+      for (int q = 0; q < UN; ++q) {                       // broadcast pair q0 + q to the whole wave
+        k[q] = __shfl(kk, q0 + q);
+        v[q] = __shfl(myv, q0 + q);
+      }
 #pragma unroll
-    for (int q = 0; q < UN; ++q)
-      w[q] = (k[q] >= 0 && col_ok) ? *(const float2*)(W1 + (size_t)k[q] * H + c0) : make_float2(0.f, 0.f);
+      for (int q = 0; q < UN; ++q)
+        w[q] = (q0 + q < cnt && k[q] >= 0 && col_ok) ? *(const float2*)(W1 + (size_t)k[q] * H + c0)
+                                                    : make_float2(0.f, 0.f);
 #pragma unroll
-    for (int q = 0; q < UN; ++q) {
-      if (k[q] < 0) continue;
-      if (k[q] <= prev) flags |= SLIDE_FLAG_UNSORTED;
-      prev = k[q];
-      acc.x = fmaf(v[q], w[q].x, acc.x);
-      acc.y = fmaf(v[q], w[q].y, acc.y);
-      if (blockIdx.y == 0 && lane == 0) atomicOr(&xbm[(size_t)i * DWpad + (k[q] >> 5)], 1u << (k[q] & 31));
+      for (int q = 0; q < UN; ++q) {
+        if (q0 + q >= cnt || k[q] < 0) continue;
+        if (k[q] <= prev) flags |= SLIDE_FLAG_UNSORTED;
+        prev = k[q];
+        acc.x = fmaf(v[q], w[q].x, acc.x);
+        acc.y = fmaf(v[q], w[q].y, acc.y);
+      }
     }
   }
   if (col_ok) *(float2*)(h + (size_t)i * H + c0) = make_float2(acc.x > 0.f ? acc.x : 0.f, acc.y > 0.f ? acc.y : 0.f);
@@ -85,8 +93,9 @@ __global__ __launch_bounds__(256) void forward_kernel(ActiveDev ad, int H, const
   const int PS = H + 4;
   for (int item = blockIdx.x * 4 + (threadIdx.x >> 6); item < nitems; item += nwaves) {
     const int i = ad.chunk_sample[item];
-    const int first = ad.as_ptr[i] + (item - ad.chunk_ptr[i]) * kChunk;
-    const int n = min(kChunk, ad.as_ptr[i + 1] - first);
+    const int done = (item - ad.chunk_ptr[i]) * kChunk;
+    const int first = ad.as_base[i] + done;
+    const int n = min(kChunk, ad.cnt[i] - done);
     float4 hv[CH], acc[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
@@ -194,7 +203,7 @@ __global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const
   __shared__ float red[4];
   const int i = blockIdx.x, tid = threadIdx.x;
   const int c0 = ad.chunk_ptr[i], nch = ad.chunk_ptr[i + 1] - c0;
-  const int first = ad.as_ptr[i], n = ad.as_ptr[i + 1] - first;
+  const int first = ad.as_base[i], n = ad.cnt[i];
   const int ny = ad.ny[i];
   const int PS = H + 4;
   const float invB = 1.0f / (float)ad.B;
@@ -262,7 +271,7 @@ __global__ __launch_bounds__(256) void topk_kernel(ActiveDev ad, const float* __
   __shared__ float rz[4];
   __shared__ int rj[4];
   const int i = blockIdx.x, tid = threadIdx.x;
-  const int first = ad.as_ptr[i], n = ad.as_ptr[i + 1] - first;
+  const int first = ad.as_base[i], n = ad.cnt[i];
   float pz = INFINITY;
   int pj = -1;
   for (int k = 0; k < topk; ++k) {

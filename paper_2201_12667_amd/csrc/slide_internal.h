@@ -12,18 +12,20 @@ constexpr int kChunk = 64;         // active pairs per forward work item
 constexpr int kSmallBucket = 8;    // buckets up to this size are sorted by one thread
 constexpr int kSortCap = 2048;     // keys held in LDS by the big-bucket sorter
 constexpr int kScanSeg = 4096;     // bucket counters scanned per workgroup
+constexpr int kLongRow = 32;       // rows touched by more samples than this are reduced by a whole wave
 
 // Device-side counters, one block at the start of the workspace.
 struct Ctrl {
   uint32_t status;        // sticky SLIDE_FLAG_* bits
-  uint32_t u2, p2;        // unique rows / pairs emitted by the output-layer transposition
-  uint32_t u1, p1;        // same for the input layer
+  uint32_t u2, p2;        // touched rows of W2 (statistics) / unused
+  uint32_t u1, p1;        // touched rows of W1 (statistics) / pair space handed out for the input layer
   uint32_t wl_count;      // big-bucket worklist length
   uint32_t overflowed;    // buckets with more than C members at the last build
   uint32_t total_pairs;   // A
   uint32_t total_chunks;
   uint32_t candidates_lo, candidates_hi;
-  uint32_t pad[5];
+  uint32_t nlong2, nlong1; // long rows queued by the two transpositions
+  uint32_t pad[3];
   // running totals since the last slide_reset_stats (updated once per training step)
   unsigned long long sum_pairs, sum_u2, sum_u1, sum_candidates, sum_steps;
 };
@@ -72,15 +74,17 @@ struct ActiveDev {
   int B, L, C, TW;                 // TW: bitmap words per rank tile (power of two <= 32)
   int64_t N;
   int NWpad, NT;                   // bitmap words per sample (multiple of TW), tiles per sample
+  int PS;                          // slots reserved per sample for candidates: min(L*C, N)
+  int num_labels;                  // label entries in the batch
   uint32_t* act;                   // [B][NWpad] active-set bit matrix
   uint32_t* rankT;                 // [B][NT] tile counts, then exclusive prefix
   int32_t* cnt;                    // [B] |AS_i|
   int32_t* ny;                     // [B] distinct labels
-  int32_t* as_ptr;                 // [B+1]
+  int32_t* as_base;                // [B] first slot of sample i = i*PS + (label entries before sample i)
   int32_t* chunk_ptr;              // [B+1]
   int32_t* chunk_sample;           // [max chunks]
-  int32_t* as_ids;                 // [A]
-  uint8_t* as_lab;                 // [A]
+  int32_t* as_ids;                 // [slots] ascending ids of sample i at as_base[i] .. +cnt[i]
+  uint8_t* as_lab;                 // [slots]
   int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
 };
 hipError_t active_setup_attributes(size_t* lds_limit_out);
@@ -88,18 +92,21 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const TablesDev& td, const u
                                const int32_t* y_indptr, const int32_t* y_indices, int include_labels,
                                int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
 hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, hipStream_t s);
-hipError_t launch_emit(const ActiveDev& ad, const int32_t* y_indptr, const int32_t* y_indices,
-                       int include_labels, hipStream_t s);
 
-// Transposition of a [B][words] bit matrix into per-row pair lists.
+// Transposition of a [B][words] bit matrix into per-row pair lists.  Row slots are grouped by tile:
+// tile t owns slots [t*rows_per_tile, t*rows_per_tile + tile_nu[t]).
 struct PairsDev {
-  int32_t* urow;    // [U] row id
-  uint32_t* ustart; // [U] first pair
-  int32_t* ucnt;    // [U] pairs
+  int rows_per_tile, ntiles;
+  int32_t* tile_nu; // [ntiles] touched rows in the tile
+  int32_t* urow;    // [slots] row id
+  uint32_t* ustart; // [slots] first pair
+  int32_t* ucnt;    // [slots] pairs
   int32_t* psample; // [pairs] sample
   int32_t* psrc;    // [pairs] index into the coefficient array
-  uint32_t* ucount; // device counters inside Ctrl
-  uint32_t* pcount;
+  uint32_t* pcount; // pair space counter (input layer only)
+  int32_t* longlist; // [long_cap] slots of rows with more than kLongRow pairs
+  uint32_t* nlong;
+  int long_cap;
 };
 hipError_t launch_transpose_active(const ActiveDev& ad, const PairsDev& pd, hipStream_t s);
 hipError_t launch_transpose_features(int B, int TW, int DWpad, uint32_t* xbm, const int32_t* x_indptr,
@@ -127,7 +134,8 @@ hipError_t launch_rowgrad_adam(int H, const PairsDev& pd, const float* coef, con
                                const AdamDev& ad, hipStream_t s);
 // loss = mean(loss_i); with b1 != nullptr also gb1 = column sums of dh and Adam on b1.
 hipError_t launch_finish(int B, int H, const float* loss_i, float* d_loss, const float* dh, float* b1,
-                         float* mb1, float* vb1, const AdamDev& ad, Ctrl* ctrl, hipStream_t s);
+                         float* mb1, float* vb1, const AdamDev& ad, Ctrl* ctrl, const int32_t* tile_nu2,
+                         int ntiles2, const int32_t* tile_nu1, int ntiles1, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 
 }  // namespace slide
