@@ -169,8 +169,8 @@ int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out);
 /* Stages of a step, in launch order, for slide_profile. */
 enum slide_stage {
   SLIDE_STAGE_HIDDEN = 0,        /* sparse-input hidden layer                       */
-  SLIDE_STAGE_HASH = 1,          /* hash codes of the hidden activations            */
-  SLIDE_STAGE_LOOKUP = 2,        /* bucket reads, union bitmap, sorted id lists     */
+  SLIDE_STAGE_HASH = 1,          /* (unused: hashing runs inside the lookup stage)  */
+  SLIDE_STAGE_LOOKUP = 2,        /* hash codes, bucket reads, union, sorted id lists */
   SLIDE_STAGE_SCAN = 3,          /* forward work items over the samples             */
   SLIDE_STAGE_RESERVED = 4,      /* (unused)                                        */
   SLIDE_STAGE_FORWARD = 5,       /* logits + running soft-max over gathered rows    */

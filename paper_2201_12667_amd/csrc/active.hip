@@ -38,26 +38,98 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t* total) {
   return base + inc - v;
 }
 
+// Hash codes of one vector held in LDS, one thread per elementary hash (same arithmetic, in the
+// same order, as the row-tile kernel in hash.hip).  raw[e]: DWTA winner position or -1, SimHash bit.
+__device__ void sample_hash_codes(const HashDev& hd, const float* hvec, int8_t* raw, uint32_t* codes_out,
+                                  uint32_t* __restrict__ codes_global) {
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  if (hd.kind == SLIDE_HASH_SIMHASH) {
+    const int half = hd.Spad / 2;
+    for (int e = tid; e < hd.NH; e += nthr) {
+      const uint32_t* __restrict__ sw = hd.words + (size_t)e * half;
+      float acc = 0.0f;
+      for (int s2 = 0; s2 < half; ++s2) {
+        const uint32_t w = sw[s2];
+        const float x0 = hvec[w & 0x7fffu];
+        acc = (w & 0x8000u) ? acc - x0 : acc + x0;
+        if (2 * s2 + 1 < hd.S) {
+          const float x1 = hvec[(w >> 16) & 0x7fffu];
+          acc = (w & 0x80000000u) ? acc - x1 : acc + x1;
+        }
+      }
+      raw[e] = acc > 0.0f ? 1 : 0;
+    }
+    __syncthreads();
+    for (int t = tid; t < hd.L; t += nthr) {
+      uint32_t c = 0;
+      for (int k = 0; k < hd.K; ++k) c |= (uint32_t)raw[t * hd.K + k] << k;
+      codes_out[t] = c;
+      codes_global[t] = c;
+    }
+  } else {
+    const int half = hd.m / 2;
+    for (int e = tid; e < hd.NH; e += nthr) {
+      int best_p = -1;
+      float best = 0.0f;
+      for (int p2 = 0; p2 < half; ++p2) {
+        const uint32_t w = hd.words[(size_t)e * half + p2];
+        const float x0 = hvec[w & 0xffffu], x1 = hvec[w >> 16];
+        if (x0 != 0.0f && x0 == x0 && (best_p < 0 || x0 > best)) { best_p = 2 * p2; best = x0; }
+        if (x1 != 0.0f && x1 == x1 && (best_p < 0 || x1 > best)) { best_p = 2 * p2 + 1; best = x1; }
+      }
+      raw[e] = (int8_t)best_p;
+    }
+    __syncthreads();
+    for (int t = tid; t < hd.L; t += nthr) {
+      uint32_t c = 0;
+      for (int k = 0; k < hd.K; ++k) {
+        const int e = t * hd.K + k;
+        int val = raw[e];
+        if (val < 0) {                                   // empty bin: borrow from the probe sequence
+          val = 0;
+          for (uint32_t tr = 1; tr <= 100; ++tr) {
+            const uint32_t u = hd.dens_a * (uint32_t)(e + 1) + hd.dens_b * tr;
+            const int r2 = raw[(u >> 8) % (uint32_t)hd.NH];
+            if (r2 >= 0) { val = r2; break; }
+          }
+        }
+        c |= (uint32_t)val << (k * hd.lgm);
+      }
+      codes_out[t] = c;
+      codes_global[t] = c;
+    }
+  }
+  __syncthreads();
+}
+
 __global__ __launch_bounds__(1024) void lookup_union_kernel(
-    ActiveDev ad, const uint32_t* __restrict__ off, const int32_t* __restrict__ ids, uint32_t nb,
-    const uint32_t* __restrict__ codes, const int32_t* __restrict__ y_indptr,
-    const int32_t* __restrict__ y_indices, int include_labels, int32_t* __restrict__ ncand,
-    Ctrl* ctrl, int segw) {
+    ActiveDev ad, HashDev hd, const float* __restrict__ h, const uint32_t* __restrict__ off,
+    const int32_t* __restrict__ ids, uint32_t nb, uint32_t* __restrict__ codes,
+    const int32_t* __restrict__ y_indptr, const int32_t* __restrict__ y_indices, int include_labels,
+    int32_t* __restrict__ ncand, Ctrl* ctrl, int segw) {
   extern __shared__ uint32_t lds[];
   uint32_t* bm = lds;                    // [segw] bitmap segment
-  uint32_t* o0s = bm + segw;             // [L] bucket start inside its table
+  uint32_t* o0s = bm + segw;             // [L] bucket start inside its table (first: the table codes)
   uint32_t* pos = o0s + ad.L;            // [L+1] exclusive prefix of the bucket lengths
   uint32_t* sm = pos + ad.L + 1;         // [20] scan scratch + counters
+  float* hvec = (float*)(sm + 20);       // [H] the sample's hidden activations
+  int8_t* raw = (int8_t*)(hvec + hd.H);  // [NH] elementary hash values
   const int i = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
   const int lane = tid & 63;
   if (tid == 0) { sm[17] = 0; sm[18] = 0; }
+  if (i == 0 && tid == 0) { ctrl->nlong2 = 0; ctrl->max_nu2 = 0; }   // consumed after this kernel
+
+  // a2: hash codes of this sample's hidden activations
+  for (int c = tid; c < hd.H; c += nthr) hvec[c] = h[(size_t)i * hd.H + c];
+  __syncthreads();
+  sample_hash_codes(hd, hvec, raw, o0s, codes + (size_t)i * ad.L);
 
   uint32_t carry = 0;
   for (int base = 0; base < ad.L; base += nthr) {
     const int t = base + tid;
     uint32_t len = 0;
     if (t < ad.L) {
-      const uint32_t code = codes[(size_t)i * ad.L + t];
+      const uint32_t code = o0s[t];
       const uint32_t a = off[(size_t)t * (nb + 1) + code];
       const uint32_t b = off[(size_t)t * (nb + 1) + code + 1];
       len = min(b - a, (uint32_t)ad.C);
@@ -207,7 +279,6 @@ __global__ __launch_bounds__(1024) void scan_samples_kernel(ActiveDev ad, const 
     ctrl->total_chunks = carry_c;
     ctrl->candidates_lo = (uint32_t)c;
     ctrl->candidates_hi = (uint32_t)(c >> 32);
-    ctrl->p1 = 0; ctrl->nlong2 = 0; ctrl->nlong1 = 0;
   }
 }
 
@@ -274,6 +345,7 @@ __global__ __launch_bounds__(512) void transpose_kernel(int B, int Bpad, int TW,
     uint32_t nu = 0, np = 0;
     for (int w = 0; w < TW; ++w) { wou[w] = nu; nu += __popc(wu[w]); const uint32_t c = wnp[w]; wnp[w] = np; np += c; }
     pd.tile_nu[tileno] = (int32_t)nu;
+    if (nu) atomicMax(pd.max_nu, nu);
     blk[0] = FEAT ? (np ? atomicAdd(pd.pcount, np) : 0u) : blk[1];
   }
   __syncthreads();
@@ -302,14 +374,15 @@ __global__ __launch_bounds__(512) void transpose_kernel(int B, int Bpad, int TW,
         const unsigned long long mk = __ballot(has);
         if (has) {
           const uint32_t p = po + cntj + __popcll(mk & ((1ull << lane) - 1ull));
-          pd.psample[p] = i;
+          int src;
           if (!FEAT) {
-            pd.psrc[p] = (int32_t)(sbase + __popc(x & ((1u << b) - 1u)));
+            src = (int)(sbase + __popc(x & ((1u << b) - 1u)));
           } else {
             int a = x_indptr[i], e = x_indptr[i + 1];
             while (a < e) { const int mid = (a + e) >> 1; if (x_indices[mid] < row) a = mid + 1; else e = mid; }
-            pd.psrc[p] = a;
+            src = a;
           }
+          pd.pairs[p] = make_int2(i, src);
         }
         cntj += (uint32_t)__popcll(mk);
       };
@@ -321,7 +394,7 @@ __global__ __launch_bounds__(512) void transpose_kernel(int B, int Bpad, int TW,
         take(k, tile[w * Bpad + i], FEAT ? 0u : sb[i] + rk[w * Bpad + i]);
       }
       if (lane == 0) {
-        pd.urow[us] = row; pd.ustart[us] = po; pd.ucnt[us] = (int32_t)cntj;
+        pd.umeta[us] = make_int4(row, (int)po, (int)cntj, 0);
         if ((int)cntj > kLongRow) {
           const uint32_t l = atomicAdd(pd.nlong, 1u);
           if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
@@ -368,16 +441,16 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
   return hipSuccess;
 }
 
-hipError_t launch_lookup_union(const ActiveDev& ad, const TablesDev& td, const uint32_t* codes,
-                               const int32_t* y_indptr, const int32_t* y_indices, int include_labels,
-                               int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s) {
-  const size_t fixed = ((size_t)2 * ad.L + 1 + 20) * 4;
+hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
+                               uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
+                               int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s) {
+  const size_t fixed = ((size_t)2 * ad.L + 1 + 20 + hd.H) * 4 + (((size_t)hd.NH + 3) & ~(size_t)3);
   size_t avail = (lds_limit - fixed) / 4;
   int segw = (int)(avail / 32 * 32);
   if (segw > ad.NWpad) segw = ad.NWpad;
   const size_t bytes = (size_t)segw * 4 + fixed;
-  hipLaunchKernelGGL(lookup_union_kernel, dim3(ad.B), dim3(1024), bytes, s, ad, td.off, td.ids, td.nb, codes,
-                     y_indptr, y_indices, include_labels, ncand, ctrl, segw);
+  hipLaunchKernelGGL(lookup_union_kernel, dim3(ad.B), dim3(1024), bytes, s, ad, hd, h, td.off, td.ids, td.nb,
+                     codes, y_indptr, y_indices, include_labels, ncand, ctrl, segw);
   return hipGetLastError();
 }
 

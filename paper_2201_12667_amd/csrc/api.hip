@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <string>
 #include <vector>
 
@@ -26,8 +27,7 @@ struct Layout {
   size_t hash_words;
   // workspace offsets
   size_t ctrl, hashw, xbm, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
-      as_lab, ylist, z, delta, partials, msum, loss_i, urow2, ustart2, ucnt2, psample2, psrc2, urow1, ustart1,
-      ucnt1, psample1, psrc1, codes_t, rank_t, segsum, worklist, ws_total;
+      as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, rank_t, segsum, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
 };
@@ -125,10 +125,8 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->z = take(A * 4); lo->delta = take(A * 4);
   lo->partials = take((size_t)lo->max_chunks * (H + 4) * 4);
   lo->msum = take(B * 8); lo->loss_i = take(B * 4);
-  lo->urow2 = take((size_t)lo->U2max * 4); lo->ustart2 = take((size_t)lo->U2max * 4); lo->ucnt2 = take((size_t)lo->U2max * 4);
-  lo->psample2 = take(A * 4); lo->psrc2 = take(A * 4);
-  lo->urow1 = take((size_t)lo->U1max * 4); lo->ustart1 = take((size_t)lo->U1max * 4); lo->ucnt1 = take((size_t)lo->U1max * 4);
-  lo->psample1 = take((size_t)lo->P1max * 4); lo->psrc1 = take((size_t)lo->P1max * 4);
+  lo->umeta2 = take((size_t)lo->U2max * 16); lo->pairs2 = take(A * 8);
+  lo->umeta1 = take((size_t)lo->U1max * 16); lo->pairs1 = take((size_t)lo->P1max * 8);
   lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->rank_t = take((size_t)lo->L * lo->N * 4);
   lo->segsum = take((size_t)lo->L * lo->nseg * 4);
   lo->worklist = take((size_t)lo->wl_cap * 8);
@@ -156,6 +154,9 @@ struct slide_ctx {
   const float* last_h = nullptr;
   float* last_dh = nullptr;
   std::string err;
+  // second stream for the work that does not depend on the logits (the two transpositions)
+  hipStream_t side = nullptr;
+  hipEvent_t ev_hidden = nullptr, ev_lookup = nullptr, ev_join = nullptr, ev_combine = nullptr, ev_done = nullptr;
   // per-stage HIP-event timing (slide_profile)
   struct ProfRec { int stage; hipEvent_t a, b; };
   uint32_t prof_mask = 0;
@@ -237,8 +238,12 @@ int check_batch(slide_ctx* ctx, const slide_batch* b, bool need_labels) {
   return SLIDE_OK;
 }
 
-// Hidden activations (a1), codes (a2), active sets (a3) and the logits pass (a4).
-int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out) {
+// Hidden activations, hash codes + active sets, and the logits pass.  The two hooks run right after
+// the hidden layer and right after the active sets exist (used by training to fork the transpositions
+// onto the side stream).
+int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out,
+                   const std::function<int()>& after_hidden = nullptr,
+                   const std::function<int(const ActiveDev&)>& after_lookup = nullptr) {
   const Layout& lo = ctx->lo;
   const int B = b->batch;
   const float* h = b->hidden;
@@ -251,15 +256,16 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   }
   ctx->last_h = h;
   ctx->last_B = B;
+  int rc;
+  if (after_hidden && (rc = after_hidden()) != SLIDE_OK) return rc;
   uint32_t* codes = ctx->at<uint32_t>(lo.codes);
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HASH, s, [&] {
-    return launch_hash(ctx->hd, h, B, codes, lo.L, 1, nullptr, nullptr, lo.nb, 4, s); }));
   ActiveDev ad = make_active(ctx, B);
   ad.num_labels = with_labels ? b->num_labels : 0;
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
-    return launch_lookup_union(ad, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0, ncand,
-                               ctx->ctrl(), ctx->lds_limit, s); }));
+    return launch_lookup_union(ad, ctx->hd, h, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0,
+                               ncand, ctx->ctrl(), ctx->lds_limit, s); }));
+  if (after_lookup && (rc = after_lookup(ad)) != SLIDE_OK) return rc;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), s); }));
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
@@ -360,15 +366,18 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   if (e == hipSuccess && !words.empty()) { what = "hipMemcpy(hash parameters)"; e = hipMemcpy(ctx->ws() + lo.hashw, words.data(), words.size() * 4, hipMemcpyHostToDevice); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(hash kernels)"; e = hash_setup_attributes(H); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
+  if (e == hipSuccess) { what = "hipStreamCreateWithFlags"; e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking); }
+  for (hipEvent_t* ev : {&ctx->ev_hidden, &ctx->ev_lookup, &ctx->ev_join, &ctx->ev_combine, &ctx->ev_done})
+    if (e == hipSuccess) { what = "hipEventCreateWithFlags"; e = hipEventCreateWithFlags(ev, hipEventDisableTiming); }
   if (e == hipSuccess) { what = "hipDeviceSynchronize"; e = hipDeviceSynchronize(); }
   if (e != hipSuccess) {
     set_err(nullptr, SLIDE_EHIP, "slide_init: %s failed: %s", what, hipGetErrorString(e));
-    delete ctx;
+    slide_destroy(ctx);
     return SLIDE_EHIP;
   }
   if (hash_lds_bytes(H) > ctx->lds_limit) {
     set_err(nullptr, SLIDE_EINVAL, "hidden_dim %d needs %zu bytes of LDS, device offers %zu", H, hash_lds_bytes(H), ctx->lds_limit);
-    delete ctx;
+    slide_destroy(ctx);
     return SLIDE_EINVAL;
   }
   HashDev& hd = ctx->hd;
@@ -402,8 +411,36 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   hipStream_t s = (hipStream_t)hip_stream;
   const Layout& lo = ctx->lo;
   const slide_config& c = ctx->cfg;
+  PairsDev p2, p1;
+  p2.rows_per_tile = lo.TW * 32; p2.ntiles = lo.NT; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
+  p2.umeta = ctx->at<int4>(lo.umeta2); p2.pairs = ctx->at<int2>(lo.pairs2);
+  p2.pcount = nullptr; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
+  p2.long_cap = (int)lo.long2; p2.max_nu = &ctx->ctrl()->max_nu2;
+  p1.rows_per_tile = lo.TWF * 32; p1.ntiles = lo.NT1; p1.tile_nu = ctx->at<int32_t>(lo.tile_nu1);
+  p1.umeta = ctx->at<int4>(lo.umeta1); p1.pairs = ctx->at<int2>(lo.pairs1);
+  p1.pcount = &ctx->ctrl()->p1; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
+  p1.long_cap = (int)lo.long1; p1.max_nu = &ctx->ctrl()->max_nu1;
+  hipStream_t side = ctx->side;
+  // Neither transposition needs the logits: they run on the side stream next to the forward pass
+  // and join before the first kernel that consumes their pair lists.
+  auto after_hidden = [&]() -> int {
+    if (lo.D == 0) return SLIDE_OK;
+    HIPCHK(ctx, hipEventRecord(ctx->ev_hidden, s));
+    HIPCHK(ctx, hipStreamWaitEvent(side, ctx->ev_hidden, 0));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_IN, side, [&] {
+      return launch_transpose_features(b->batch, lo.TWF, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
+                                       b->x_indices, p1, side); }));
+    return SLIDE_OK;
+  };
+  auto after_lookup = [&](const ActiveDev& ad) -> int {
+    HIPCHK(ctx, hipEventRecord(ctx->ev_lookup, s));
+    HIPCHK(ctx, hipStreamWaitEvent(side, ctx->ev_lookup, 0));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_OUT, side, [&] { return launch_transpose_active(ad, p2, side); }));
+    HIPCHK(ctx, hipEventRecord(ctx->ev_join, side));
+    return SLIDE_OK;
+  };
   ActiveDev ad;
-  if ((rc = forward_common(ctx, b, true, s, &ad)) != SLIDE_OK) return rc;
+  if ((rc = forward_common(ctx, b, true, s, &ad, after_hidden, after_lookup)) != SLIDE_OK) return rc;
   float* dh = ctx->at<float>(lo.dh);
   float* delta = ctx->at<float>(lo.delta);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_COMBINE, s, [&] {
@@ -418,37 +455,29 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   a.lr = (float)c.lr; a.eps = (float)c.eps;
   a.inv_bc1 = (float)(1.0 / (1.0 - std::pow(c.beta1, (double)t)));
   a.inv_bc2 = (float)(1.0 / (1.0 - std::pow(c.beta2, (double)t)));
-  PairsDev p2;
-  p2.rows_per_tile = lo.TW * 32; p2.ntiles = lo.NT; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
-  p2.urow = ctx->at<int32_t>(lo.urow2); p2.ustart = ctx->at<uint32_t>(lo.ustart2); p2.ucnt = ctx->at<int32_t>(lo.ucnt2);
-  p2.psample = ctx->at<int32_t>(lo.psample2); p2.psrc = ctx->at<int32_t>(lo.psrc2);
-  p2.pcount = nullptr; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
-  p2.long_cap = (int)lo.long2;
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_OUT, s, [&] { return launch_transpose_active(ad, p2, s); }));
+  // The output-layer update (the long, bandwidth-bound kernel) runs on the caller's stream; the
+  // hidden-layer update, the hidden bias, the loss and the statistics are small and latency-bound
+  // and run beside it on the side stream.  Both need the errors / hidden gradient (combine).
+  HIPCHK(ctx, hipEventRecord(ctx->ev_combine, s));
+  HIPCHK(ctx, hipStreamWaitEvent(side, ctx->ev_combine, 0));
+  HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_join, 0));
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_OUT, s, [&] {
     return launch_rowgrad_adam(lo.H, p2, delta, ctx->last_h, ctx->buf.W2, ctx->buf.mW2, ctx->buf.vW2,
                                ctx->buf.b2, ctx->buf.mb2, ctx->buf.vb2, a, s); }));
   if (lo.D > 0) {
-    PairsDev p1;
-    p1.rows_per_tile = lo.TWF * 32; p1.ntiles = lo.NT1; p1.tile_nu = ctx->at<int32_t>(lo.tile_nu1);
-    p1.urow = ctx->at<int32_t>(lo.urow1); p1.ustart = ctx->at<uint32_t>(lo.ustart1); p1.ucnt = ctx->at<int32_t>(lo.ucnt1);
-    p1.psample = ctx->at<int32_t>(lo.psample1); p1.psrc = ctx->at<int32_t>(lo.psrc1);
-    p1.pcount = &ctx->ctrl()->p1; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
-    p1.long_cap = (int)lo.long1;
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_IN, s, [&] {
-      return launch_transpose_features(b->batch, lo.TWF, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
-                                       b->x_indices, p1, s); }));
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_IN, s, [&] {
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_IN, side, [&] {
       return launch_rowgrad_adam(lo.H, p1, b->x_values, dh, ctx->buf.W1, ctx->buf.mW1, ctx->buf.vW1, nullptr,
-                                 nullptr, nullptr, a, s); }));
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, s, [&] {
+                                 nullptr, nullptr, a, side); }));
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, side, [&] {
       return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, ctx->buf.b1, ctx->buf.mb1,
-                           ctx->buf.vb1, a, ctx->ctrl(), p2.tile_nu, p2.ntiles, p1.tile_nu, p1.ntiles, s); }));
+                           ctx->buf.vb1, a, ctx->ctrl(), p2.tile_nu, p2.ntiles, p1.tile_nu, p1.ntiles, side); }));
   } else {
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, s, [&] {
+    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, side, [&] {
       return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, nullptr, nullptr, nullptr, a,
-                           ctx->ctrl(), p2.tile_nu, p2.ntiles, nullptr, 0, s); }));
+                           ctx->ctrl(), p2.tile_nu, p2.ntiles, nullptr, 0, side); }));
   }
+  HIPCHK(ctx, hipEventRecord(ctx->ev_done, side));
+  HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_done, 0));
   ctx->t = t;
   if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
     ctx->r += 1;
@@ -541,6 +570,8 @@ int slide_destroy(slide_ctx* ctx) {
   if (!ctx) return SLIDE_OK;
   for (auto& r : ctx->prof_live) ctx->prof_pool.emplace_back(r.a, r.b);
   for (auto& e : ctx->prof_pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+  for (hipEvent_t ev : {ctx->ev_hidden, ctx->ev_lookup, ctx->ev_join, ctx->ev_combine, ctx->ev_done}) if (ev) (void)hipEventDestroy(ev);
+  if (ctx->side) { (void)hipStreamSynchronize(ctx->side); (void)hipStreamDestroy(ctx->side); }
   delete ctx;
   return SLIDE_OK;
 }

@@ -19,6 +19,7 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
                                                        const float* __restrict__ W1, const float* __restrict__ b1,
                                                        float* __restrict__ h, uint32_t* xbm, int DWpad, Ctrl* ctrl) {
   const int i = blockIdx.x, lane = threadIdx.x;
+  if (i == 0 && blockIdx.y == 0 && lane == 0) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }  // used after this kernel
   const int c0 = (blockIdx.y * 64 + lane) * 2;
   const bool col_ok = c0 < H;
   int p0 = x_indptr[i], p1 = x_indptr[i + 1];
@@ -176,7 +177,9 @@ hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const floa
 #define SLIDE_FWD(L_, C_) return launch_forward_t<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, s)
   if (H <= 32) SLIDE_FWD(8, 1);
   if (H <= 64) SLIDE_FWD(8, 2);
-  if (H <= 128) SLIDE_FWD(8, 4);
+  if (H <= 128) {
+    SLIDE_FWD(8, 4);
+  }
   if (H <= 256) SLIDE_FWD(16, 4);
   if (H <= 512) SLIDE_FWD(32, 4);
   if (H <= 1024) SLIDE_FWD(64, 4);

@@ -25,7 +25,8 @@ struct Ctrl {
   uint32_t total_chunks;
   uint32_t candidates_lo, candidates_hi;
   uint32_t nlong2, nlong1; // long rows queued by the two transpositions
-  uint32_t pad[3];
+  uint32_t max_nu2, max_nu1; // most touched rows in any tile
+  uint32_t pad[1];
   // running totals since the last slide_reset_stats (updated once per training step)
   unsigned long long sum_pairs, sum_u2, sum_u1, sum_candidates, sum_steps;
 };
@@ -88,9 +89,9 @@ struct ActiveDev {
   int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
 };
 hipError_t active_setup_attributes(size_t* lds_limit_out);
-hipError_t launch_lookup_union(const ActiveDev& ad, const TablesDev& td, const uint32_t* codes,
-                               const int32_t* y_indptr, const int32_t* y_indices, int include_labels,
-                               int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
+hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
+                               uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
+                               int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
 hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, hipStream_t s);
 
 // Transposition of a [B][words] bit matrix into per-row pair lists.  Row slots are grouped by tile:
@@ -98,15 +99,13 @@ hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* 
 struct PairsDev {
   int rows_per_tile, ntiles;
   int32_t* tile_nu; // [ntiles] touched rows in the tile
-  int32_t* urow;    // [slots] row id
-  uint32_t* ustart; // [slots] first pair
-  int32_t* ucnt;    // [slots] pairs
-  int32_t* psample; // [pairs] sample
-  int32_t* psrc;    // [pairs] index into the coefficient array
+  int4* umeta;      // [slots] (row id, first pair, pairs, 0)
+  int2* pairs;      // [pairs] (sample, index into the coefficient array)
   uint32_t* pcount; // pair space counter (input layer only)
   int32_t* longlist; // [long_cap] slots of rows with more than kLongRow pairs
   uint32_t* nlong;
   int long_cap;
+  uint32_t* max_nu; // largest tile_nu (bounds the work items of the row kernel)
 };
 hipError_t launch_transpose_active(const ActiveDev& ad, const PairsDev& pd, hipStream_t s);
 hipError_t launch_transpose_features(int B, int TW, int DWpad, uint32_t* xbm, const int32_t* x_indptr,

@@ -28,8 +28,9 @@ __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd,
 #pragma unroll
     for (int a = 0; a < UNR; ++a) {
       const bool ok = q + a * stride < cn;
-      const int si = ok ? pd.psample[st + q + a * stride] : 0;
-      d[a] = ok ? coef[pd.psrc[st + q + a * stride]] : 0.f;
+      const int2 pr = ok ? pd.pairs[st + q + a * stride] : make_int2(0, 0);
+      const int si = pr.x;
+      d[a] = ok ? coef[pr.y] : 0.f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col = (c * LPR + sub) * 4;
@@ -54,17 +55,16 @@ __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd,
 // CH float4 per lane).  Rows with more than kLongRow pairs are skipped here and taken afterwards by
 // a whole wave each: its RPW lane groups accumulate interleaved shares of the pair list and the
 // shares are added in a fixed butterfly order.
-template <int LPR, int CH>
+template <int LPR, int CH, int UNR>
 __global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, const float* __restrict__ coef,
                                                            const float* __restrict__ V, float* __restrict__ W,
                                                            float* __restrict__ M, float* __restrict__ Vv,
                                                            float* __restrict__ bias, float* __restrict__ mbias,
                                                            float* __restrict__ vbias, AdamDev ad) {
   constexpr int RPW = 64 / LPR;
-  constexpr int UNR = CH <= 4 ? 4 : 2;
   const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
   const int wave_global = blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = gridDim.x * 4;
-  const int cpt = pd.rows_per_tile / RPW;                  // items per tile
+  const int cpt = ((int)*pd.max_nu + RPW - 1) / RPW;       // items per tile that can hold rows
   const int nitems = pd.ntiles * cpt;
   for (int item = wave_global; item < nitems; item += nwaves) {
     // chunk-major order: the non-empty items (low chunk numbers of every tile) are contiguous, so
@@ -74,12 +74,13 @@ __global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, c
     if (ch * RPW >= nu) continue;
     const int r = ch * RPW + grp;
     const int slot = t * pd.rows_per_tile + r;
-    int cn = r < nu ? pd.ucnt[slot] : 0;
+    const int4 meta = r < nu ? pd.umeta[slot] : make_int4(0, 0, 0, 0);
+    int cn = meta.z;
     const bool valid = r < nu && (RPW == 1 || cn <= kLongRow);
     if (!valid) cn = 0;
-    const int j = valid ? pd.urow[slot] : 0;
+    const int j = valid ? meta.x : 0;
     const size_t ro = (size_t)j * H;
-    const uint32_t st = valid ? pd.ustart[slot] : 0u;
+    const uint32_t st = (uint32_t)meta.y;
     float4 w[CH], m[CH], v[CH], g[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
@@ -115,9 +116,10 @@ __global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, c
   const int nlong = min((int)*pd.nlong, pd.long_cap);
   for (int l = wave_global; l < nlong; l += nwaves) {
     const int slot = pd.longlist[l];
-    const int j = pd.urow[slot], cn = pd.ucnt[slot];
+    const int4 meta = pd.umeta[slot];
+    const int j = meta.x, cn = meta.z;
     const size_t ro = (size_t)j * H;
-    const uint32_t st = pd.ustart[slot];
+    const uint32_t st = (uint32_t)meta.y;
     float4 w[CH], m[CH], v[CH], g[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
@@ -160,10 +162,10 @@ __global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, c
   }
 }
 
-template <int LPR, int CH>
+template <int LPR, int CH, int UNR = (CH <= 4 ? 4 : 2)>
 static hipError_t launch_rg(int H, const PairsDev& pd, const float* coef, const float* V, float* W, float* M,
                             float* Vv, float* bias, float* mbias, float* vbias, const AdamDev& ad, hipStream_t s) {
-  hipLaunchKernelGGL((rowgrad_adam_kernel<LPR, CH>), dim3(2048), dim3(256), 0, s, H, pd, coef, V, W, M, Vv, bias,
+  hipLaunchKernelGGL((rowgrad_adam_kernel<LPR, CH, UNR>), dim3(2048), dim3(256), 0, s, H, pd, coef, V, W, M, Vv, bias,
                      mbias, vbias, ad);
   return hipGetLastError();
 }
@@ -174,7 +176,9 @@ hipError_t launch_rowgrad_adam(int H, const PairsDev& pd, const float* coef, con
 #define SLIDE_RG(L_, C_) return launch_rg<L_, C_>(H, pd, coef, V, W, M, Vv, bias, mbias, vbias, ad, s)
   if (H <= 32) SLIDE_RG(8, 1);
   if (H <= 64) SLIDE_RG(8, 2);
-  if (H <= 128) SLIDE_RG(8, 4);
+  if (H <= 128) {
+    return launch_rg<8, 4, 2>(H, pd, coef, V, W, M, Vv, bias, mbias, vbias, ad, s);
+  }
   if (H <= 256) SLIDE_RG(16, 4);
   if (H <= 512) SLIDE_RG(32, 4);
   if (H <= 1024) SLIDE_RG(64, 4);
