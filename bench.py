@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-steps", type=int, default=3, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--breakdown", action="store_true", help="also time every stage on extra steps")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run the library's plain copy kernel on MIB mebibytes (10 launches) and print "
+                         "its bandwidth: the yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -54,6 +57,24 @@ def main() -> int:
     import numpy as np
     import torch
     from paper_2201_12667_amd import slide, synth
+
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        st = torch.cuda.current_stream().cuda_stream
+        for _ in range(3):
+            slide.debug_copy(dst, src, st)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            slide.debug_copy(dst, src, st)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        print(json.dumps({"kernel": "copy_kernel", "bytes_read": n, "bytes_written": n, "avg_launch_ms": ms,
+                          "GBs": 2 * n / (ms * 1e-3) / 1e9}))
+        return 0
 
     wl = synth.config(args.config)
     gen = synth.Generator(wl, args.seed)
@@ -107,7 +128,7 @@ def main() -> int:
                    "hash": "dwta" if wl.hash_kind == synth.HASH_DWTA else "simhash", "K": wl.K, "L": wl.L,
                    "bucket_cap": wl.bucket_cap, "rebuild_every": wl.rebuild_every,
                    "rebuilds_in_timed_region": rebuilds_in_region, "seed": args.seed},
-        "roofline": {"bound": "hbm", "kernel": "rowgrad_adam_kernel (output layer)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "rowgrad_adam_kernel<..., true> (output-layer rows: gradient + Adam)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "algorithmic_bytes_per_launch": dom_bytes,
                      "avg_launch_ms": dom_ms, "launches": int(n[dom])},

@@ -280,7 +280,8 @@ int do_build(slide_ctx* ctx, hipStream_t s) {
     return launch_build_tables(ctx->hd, ctx->td, ctx->buf.W2, ctx->at<uint32_t>(lo.codes_t),
                                ctx->at<uint32_t>(lo.rank_t), ctx->at<uint32_t>(lo.segsum),
                                ctx->at<uint64_t>(lo.worklist), lo.wl_cap, ctx->ctrl(), ctx->cfg.overflow_policy,
-                               (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, 40, s); }));
+                               (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, /*tables per block: all, so W2
+                               is staged once*/ lo.L, s); }));
   return SLIDE_OK;
 }
 
@@ -577,6 +578,11 @@ int slide_destroy(slide_ctx* ctx) {
 }
 
 const char* slide_last_error(const slide_ctx* ctx) { return ctx ? ctx->err.c_str() : g_last_error.c_str(); }
+
+int slide_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream) {
+  if (!d_dst || !d_src || (bytes & 15) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15)) return SLIDE_EINVAL;
+  return launch_copy(d_dst, d_src, bytes, (hipStream_t)hip_stream) == hipSuccess ? SLIDE_OK : SLIDE_EHIP;
+}
 
 int slide_debug_hash(slide_ctx* ctx, const float* d_vectors, int64_t rows, uint32_t* d_codes, void* hip_stream) {
   if (!ctx || !d_vectors || !d_codes || rows < 0) return SLIDE_EINVAL;

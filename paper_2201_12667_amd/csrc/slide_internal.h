@@ -136,5 +136,6 @@ hipError_t launch_finish(int B, int H, const float* loss_i, float* d_loss, const
                          float* mb1, float* vb1, const AdamDev& ad, Ctrl* ctrl, const int32_t* tile_nu2,
                          int ntiles2, const int32_t* tile_nu1, int ntiles1, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 }  // namespace slide

@@ -55,7 +55,7 @@ __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd,
 // CH float4 per lane).  Rows with more than kLongRow pairs are skipped here and taken afterwards by
 // a whole wave each: its RPW lane groups accumulate interleaved shares of the pair list and the
 // shares are added in a fixed butterfly order.
-template <int LPR, int CH, int UNR>
+template <int LPR, int CH, int UNR, bool OUTPUT_LAYER>
 __global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, const float* __restrict__ coef,
                                                            const float* __restrict__ V, float* __restrict__ W,
                                                            float* __restrict__ M, float* __restrict__ Vv,
@@ -165,8 +165,13 @@ __global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, c
 template <int LPR, int CH, int UNR = (CH <= 4 ? 4 : 2)>
 static hipError_t launch_rg(int H, const PairsDev& pd, const float* coef, const float* V, float* W, float* M,
                             float* Vv, float* bias, float* mbias, float* vbias, const AdamDev& ad, hipStream_t s) {
-  hipLaunchKernelGGL((rowgrad_adam_kernel<LPR, CH, UNR>), dim3(2048), dim3(256), 0, s, H, pd, coef, V, W, M, Vv, bias,
-                     mbias, vbias, ad);
+  // OUTPUT_LAYER only gives the two uses distinct kernel names in profiles (bias present = output layer)
+  if (bias)
+    hipLaunchKernelGGL((rowgrad_adam_kernel<LPR, CH, UNR, true>), dim3(2048), dim3(256), 0, s, H, pd, coef, V, W, M,
+                       Vv, bias, mbias, vbias, ad);
+  else
+    hipLaunchKernelGGL((rowgrad_adam_kernel<LPR, CH, UNR, false>), dim3(2048), dim3(256), 0, s, H, pd, coef, V, W, M,
+                       Vv, bias, mbias, vbias, ad);
   return hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ STAGES = ["hidden", "hash", "lookup", "scan", "reserved", "forward", "combine", 
 NUM_STAGES = len(STAGES)
 
 EXPORTS = ["slide_query_memory", "slide_init", "slide_build_tables", "slide_train_step", "slide_predict",
-           "slide_status", "slide_get_stats", "slide_profile", "slide_profile_read", "slide_reset_stats", "slide_destroy", "slide_last_error", "slide_debug_hash",
+           "slide_status", "slide_get_stats", "slide_profile", "slide_profile_read", "slide_reset_stats", "slide_destroy", "slide_last_error", "slide_debug_copy", "slide_debug_hash",
            "slide_debug_get_bucket", "slide_debug_get_active", "slide_debug_get_hidden"]
 
 
@@ -97,6 +97,7 @@ def load_library(path: str = LIB_PATH):
     L.slide_destroy.argtypes = [vp]
     L.slide_last_error.argtypes = [vp]
     L.slide_last_error.restype = C.c_char_p
+    L.slide_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.slide_debug_hash.argtypes = [vp, vp, i64, vp, vp]
     L.slide_debug_get_bucket.argtypes = [vp, i32, C.c_uint32, vp, i32, C.POINTER(C.c_int)]
     L.slide_debug_get_active.argtypes = [vp, vp, vp, vp, vp, vp, i64]
@@ -125,6 +126,15 @@ def make_config(*, input_dim, hidden_dim, num_classes, max_batch, max_nnz_per_ba
     c.overflow_policy, c.rebuild_every = overflow_policy, rebuild_every
     c.lr, c.beta1, c.beta2, c.eps = lr, beta1, beta2, eps
     return c
+
+
+def debug_copy(dst, src, stream_ptr: int):
+    """Plain copy kernel of the library on two equally sized device tensors (measurement aid)."""
+    L = load_library()
+    nbytes = src.numel() * src.element_size()
+    rc = L.slide_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, C.c_void_p(stream_ptr))
+    if rc:
+        raise SlideError(rc, "slide_debug_copy")
 
 
 def query_memory(cfg: slide_config) -> slide_mem_req:
