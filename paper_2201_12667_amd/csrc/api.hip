@@ -23,11 +23,11 @@ struct Layout {
   // derived sizes
   int Bmax, Bpad, H, L, K, C, TW, TWF, NWpad, NT, NT1, DWpad, bits, PS;
   int64_t N, D, Amax, max_chunks, U2max, U1max, P1max, long2, long1;
-  uint32_t nb, nseg, wl_cap;
+  uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
   size_t ctrl, hashw, xbm, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
-      as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, rank_t, segsum, worklist, ws_total;
+      as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
 };
@@ -77,9 +77,8 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   } else {
     FAIL(SLIDE_EINVAL, "unknown hash_kind");
   }
-  if (lo->bits > 28) FAIL(SLIDE_EINVAL, "hash code wider than 28 bits");
+  if (lo->bits > 24) FAIL(SLIDE_EINVAL, "hash code wider than 24 bits");
   lo->nb = 1u << lo->bits;
-  lo->nseg = (lo->nb + kScanSeg - 1) / kScanSeg;
   lo->Bmax = c->max_batch;
   lo->Bpad = (c->max_batch + 63) & ~63;
   int tw = 32;
@@ -127,8 +126,9 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->msum = take(B * 8); lo->loss_i = take(B * 4);
   lo->umeta2 = take((size_t)lo->U2max * 16); lo->pairs2 = take(A * 8);
   lo->umeta1 = take((size_t)lo->U1max * 16); lo->pairs1 = take((size_t)lo->P1max * 8);
-  lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->rank_t = take((size_t)lo->L * lo->N * 4);
-  lo->segsum = take((size_t)lo->L * lo->nseg * 4);
+  lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->entries = take((size_t)lo->L * lo->N * 8);
+  lo->bh = take(tables_bh_words(lo->bits, lo->N, lo->L) * 4);
+  lo->pbase = take(tables_pbase_words(lo->bits, lo->N, lo->L) * 4);
   lo->worklist = take((size_t)lo->wl_cap * 8);
   lo->ws_total = o;
   o = 0;
@@ -278,10 +278,9 @@ int do_build(slide_ctx* ctx, hipStream_t s) {
   const Layout& lo = ctx->lo;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_REBUILD, s, [&] {
     return launch_build_tables(ctx->hd, ctx->td, ctx->buf.W2, ctx->at<uint32_t>(lo.codes_t),
-                               ctx->at<uint32_t>(lo.rank_t), ctx->at<uint32_t>(lo.segsum),
+                               ctx->at<uint2>(lo.entries), ctx->at<uint32_t>(lo.bh), ctx->at<uint32_t>(lo.pbase),
                                ctx->at<uint64_t>(lo.worklist), lo.wl_cap, ctx->ctrl(), ctx->cfg.overflow_policy,
-                               (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, /*tables per block: all, so W2
-                               is staged once*/ lo.L, s); }));
+                               (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, s); }));
   return SLIDE_OK;
 }
 
@@ -367,6 +366,7 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   if (e == hipSuccess && !words.empty()) { what = "hipMemcpy(hash parameters)"; e = hipMemcpy(ctx->ws() + lo.hashw, words.data(), words.size() * 4, hipMemcpyHostToDevice); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(hash kernels)"; e = hash_setup_attributes(H); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
+  if (e == hipSuccess) { what = "hipFuncSetAttribute(table kernels)"; e = tables_setup_attributes(); }
   if (e == hipSuccess) { what = "hipStreamCreateWithFlags"; e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking); }
   for (hipEvent_t* ev : {&ctx->ev_hidden, &ctx->ev_lookup, &ctx->ev_join, &ctx->ev_combine, &ctx->ev_done})
     if (e == hipSuccess) { what = "hipEventCreateWithFlags"; e = hipEventCreateWithFlags(ev, hipEventDisableTiming); }

@@ -11,7 +11,6 @@ constexpr int kWave = 64;
 constexpr int kChunk = 64;         // active pairs per forward work item
 constexpr int kSmallBucket = 8;    // buckets up to this size are sorted by one thread
 constexpr int kSortCap = 2048;     // keys held in LDS by the big-bucket sorter
-constexpr int kScanSeg = 4096;     // bucket counters scanned per workgroup
 constexpr int kLongRow = 32;       // rows touched by more samples than this are reduced by a whole wave
 
 // Device-side counters, one block at the start of the workspace.
@@ -64,11 +63,13 @@ struct TablesDev {
   int64_t N;
   int L, C;
 };
-hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2,
-                               uint32_t* codes_t, uint32_t* rank_t, uint32_t* segsum,
-                               uint64_t* worklist, uint32_t wl_cap, Ctrl* ctrl, int policy,
-                               uint32_t r, uint32_t prio_a, uint32_t prio_b, int tables_per_block,
-                               hipStream_t s);
+hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
+                               uint2* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
+                               uint32_t wl_cap, Ctrl* ctrl, int policy, uint32_t r, uint32_t prio_a,
+                               uint32_t prio_b, hipStream_t s);
+size_t tables_bh_words(int bits, int64_t N, int L);      // per-slab histograms
+size_t tables_pbase_words(int bits, int64_t N, int L);   // partition starts
+hipError_t tables_setup_attributes();
 
 // ---- active.hip -----------------------------------------------------------------------
 struct ActiveDev {

@@ -4,9 +4,12 @@
 // ascending by id; which members are kept when size > C is decided by the smallest
 // (priority, id) keys.
 //
-// Passes: (1) hash every row of W2 and take a ticket in its bucket's counter, (2) exclusive scan
-// of the counters per table, (3) scatter ids to bucket start + ticket, (4) sort every bucket by id
-// (tickets arrive in arbitrary order) and apply the capacity rule.
+// The build is a two-level counting sort with every counter in LDS (no global atomics on the
+// tables): (1) hash every row of W2, codes stored table-major; (2) split each table's rows by the
+// high bits of the code: per-slab LDS histograms, a scan over slabs and digits, and a scatter of
+// (code, id) entries into their partition; (3) one workgroup per (table, partition) counts the low
+// bits in LDS, writes that partition's offsets, places the ids, and sorts the small buckets in
+// place; (4) buckets that are long or over capacity are queued and handled by one workgroup each.
 #include "slide_internal.h"
 
 namespace slide {
@@ -65,89 +68,146 @@ __device__ uint32_t block_excl_scan256(uint32_t v, uint32_t* sm, uint32_t* total
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(256) void seg_sum_kernel(const uint32_t* __restrict__ off, uint32_t nb,
-                                                      uint32_t nseg, uint32_t* __restrict__ segsum) {
-  __shared__ uint32_t sm[8];
-  const uint32_t seg = blockIdx.x, t = blockIdx.y;
-  const uint32_t* p = off + (size_t)t * (nb + 1);
-  uint32_t acc = 0;
-  for (int k = 0; k < kScanSeg / 256; ++k) {
-    const uint32_t i = seg * kScanSeg + k * 256 + threadIdx.x;
-    if (i < nb) acc += p[i];
+constexpr int kSlab = 16384;       // rows per workgroup in the partition passes
+
+__global__ __launch_bounds__(1024) void part_hist_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,
+                                                         int nbins, uint32_t* __restrict__ bh, int nslab) {
+  extern __shared__ uint32_t hst[];
+  const int slab = blockIdx.x, tid = threadIdx.x;
+  const size_t t = blockIdx.y;
+  for (int b = tid; b < nbins; b += 1024) hst[b] = 0;
+  __syncthreads();
+  const int64_t j0 = (int64_t)slab * kSlab;
+  for (int k = 0; k < kSlab / 1024; ++k) {
+    const int64_t j = j0 + k * 1024 + tid;
+    if (j < N) atomicAdd(&hst[codes_t[t * N + j] >> lb], 1u);
   }
-  uint32_t total;
-  block_excl_scan256(acc, sm, &total);
-  if (threadIdx.x == 0) segsum[(size_t)t * nseg + seg] = total;
+  __syncthreads();
+  for (int b = tid; b < nbins; b += 1024) bh[(t * nslab + slab) * nbins + b] = hst[b];
 }
 
-__global__ __launch_bounds__(256) void seg_scan_kernel(uint32_t* segsum, uint32_t nseg, Ctrl* ctrl) {
-  __shared__ uint32_t sm[8];
-  uint32_t* p = segsum + (size_t)blockIdx.x * nseg;
+// Exclusive scan over a workgroup of 1024 threads; sm: 17 words of LDS.
+__device__ uint32_t block_excl_scan1024(uint32_t v, uint32_t* sm, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t inc = wave_incl_scan(v);
+  __syncthreads();
+  if (lane == 63) sm[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+  for (int w = 0; w < 16; ++w) { const uint32_t x = sm[w]; if (w < wave) base += x; tot += x; }
+  *total = tot;
+  return base + inc - v;
+}
+
+// One workgroup per table: bh[t][slab][d] becomes the number of rows of digit d in earlier slabs,
+// pbase[t][d] the start of partition d.
+__global__ __launch_bounds__(1024) void part_scan_kernel(uint32_t* bh, int nslab, int nbins, uint32_t* pbase,
+                                                         Ctrl* ctrl) {
+  __shared__ uint32_t sm[20];
+  const size_t t = blockIdx.x;
+  const int tid = threadIdx.x;
   uint32_t carry = 0;
-  for (uint32_t base = 0; base < nseg; base += 256) {
-    const uint32_t i = base + threadIdx.x;
-    const uint32_t v = i < nseg ? p[i] : 0;
+  for (int base = 0; base < nbins; base += 1024) {
+    const int d = base + tid;
+    uint32_t run = 0;
+    if (d < nbins)
+      for (int slab = 0; slab < nslab; ++slab) {
+        uint32_t* p = bh + (t * nslab + slab) * nbins + d;
+        const uint32_t v = *p;
+        *p = run;
+        run += v;
+      }
     uint32_t total;
-    const uint32_t ex = block_excl_scan256(v, sm, &total);
-    if (i < nseg) p[i] = carry + ex;
+    const uint32_t ex = block_excl_scan1024(run, sm, &total);
+    if (d < nbins) pbase[t * (nbins + 1) + d] = carry + ex;
     carry += total;
     __syncthreads();
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) { ctrl->wl_count = 0; ctrl->overflowed = 0; }
+  if (tid == 0) pbase[t * (nbins + 1) + nbins] = carry;
+  if (t == 0 && tid == 0) { ctrl->wl_count = 0; ctrl->overflowed = 0; }
 }
 
-__global__ __launch_bounds__(256) void seg_apply_kernel(uint32_t* off, uint32_t nb, uint32_t nseg,
-                                                        const uint32_t* __restrict__ segsum, uint32_t N) {
-  __shared__ uint32_t sm[8];
-  constexpr int PER = kScanSeg / 256;
-  const uint32_t seg = blockIdx.x, t = blockIdx.y;
-  uint32_t* p = off + (size_t)t * (nb + 1);
-  const uint32_t first = seg * kScanSeg + threadIdx.x * PER;
-  uint32_t v[PER], sum = 0;
-#pragma unroll
-  for (int k = 0; k < PER; ++k) { v[k] = first + k < nb ? p[first + k] : 0; sum += v[k]; }
-  uint32_t total;
-  uint32_t run = block_excl_scan256(sum, sm, &total) + segsum[(size_t)t * nseg + seg];
-#pragma unroll
-  for (int k = 0; k < PER; ++k) { if (first + k < nb) p[first + k] = run; run += v[k]; }
-  if (seg == 0 && threadIdx.x == 0) p[nb] = N;
-}
-
-__global__ __launch_bounds__(256) void scatter_ids_kernel(const uint32_t* __restrict__ codes_t,
-                                                          const uint32_t* __restrict__ rank_t,
-                                                          const uint32_t* __restrict__ off, int32_t* ids,
-                                                          uint32_t nb, int64_t N) {
-  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(1024) void part_scatter_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,
+                                                            int nbins, const uint32_t* __restrict__ bh, int nslab,
+                                                            const uint32_t* __restrict__ pbase,
+                                                            uint2* __restrict__ entries) {
+  extern __shared__ uint32_t cur[];
+  const int slab = blockIdx.x, tid = threadIdx.x;
   const size_t t = blockIdx.y;
-  if (j >= N) return;
-  const uint32_t code = codes_t[t * N + j];
-  ids[t * N + off[t * (nb + 1) + code] + rank_t[t * N + j]] = (int32_t)j;
+  for (int b = tid; b < nbins; b += 1024) cur[b] = pbase[t * (nbins + 1) + b] + bh[(t * nslab + slab) * nbins + b];
+  __syncthreads();
+  const int64_t j0 = (int64_t)slab * kSlab;
+  for (int k = 0; k < kSlab / 1024; ++k) {
+    const int64_t j = j0 + k * 1024 + tid;
+    if (j < N) {
+      const uint32_t code = codes_t[t * N + j];
+      const uint32_t pos = atomicAdd(&cur[code >> lb], 1u);
+      entries[t * N + pos] = make_uint2(code, (uint32_t)j);
+    }
+  }
 }
 
-// One thread per bucket: sorts small buckets in place, queues the others.
-__global__ __launch_bounds__(256) void small_buckets_kernel(const uint32_t* __restrict__ off, int32_t* ids,
-                                                            uint32_t nb, int lgnb, int64_t N, int L, int C,
-                                                            uint64_t* worklist, uint32_t wl_cap, Ctrl* ctrl) {
-  const uint64_t b = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-  const uint64_t t = b >> lgnb;
-  if (t >= (uint64_t)L) return;
-  const uint32_t c = (uint32_t)(b & (nb - 1));
-  const uint32_t o0 = off[t * (nb + 1) + c];
-  const uint32_t s = off[t * (nb + 1) + c + 1] - o0;
-  if (s > (uint32_t)C) atomicAdd(&ctrl->overflowed, 1u);
-  if (s < 2) return;
-  if (s <= (uint32_t)kSmallBucket && s <= (uint32_t)C) {
-    int32_t* p = ids + t * N + o0;
-    for (uint32_t a = 1; a < s; ++a) {
-      const int32_t key = p[a];
-      int q = (int)a - 1;
-      while (q >= 0 && p[q] > key) { p[q + 1] = p[q]; --q; }
-      p[q + 1] = key;
-    }
-  } else {
-    const uint32_t slot = atomicAdd(&ctrl->wl_count, 1u);
-    if (slot < wl_cap) worklist[slot] = (t << 32) | c;
+// One workgroup per (partition d, table t): buckets (d << lb) .. (d << lb) + 2^lb - 1.
+__global__ __launch_bounds__(256) void part_buckets_kernel(const uint2* __restrict__ entries,
+                                                           const uint32_t* __restrict__ pbase, int nbins, int lb,
+                                                           uint32_t nb, int64_t N, int C, uint32_t* __restrict__ off,
+                                                           int32_t* ids, uint64_t* worklist, uint32_t wl_cap,
+                                                           Ctrl* ctrl) {
+  extern __shared__ uint32_t lds[];
+  const int nlo = 1 << lb, tid = threadIdx.x;
+  uint32_t* start = lds;                 // [nlo + 1] first position of each bucket inside the partition
+  uint32_t* cur = lds + nlo + 1;         // [nlo] counters, then cursors
+  uint32_t* sm = cur + nlo;              // [8]
+  const uint32_t d = blockIdx.x;
+  const size_t t = blockIdx.y;
+  const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
+  const uint32_t mask = (uint32_t)nlo - 1u;
+  const uint2* ent = entries + t * N;
+  for (int b = tid; b < nlo; b += 256) cur[b] = 0;
+  __syncthreads();
+  for (uint32_t e = s0 + tid; e < s1; e += 256) atomicAdd(&cur[ent[e].x & mask], 1u);
+  __syncthreads();
+  uint32_t carry = 0;
+  for (int base = 0; base < nlo; base += 256) {
+    const int b = base + tid;
+    const uint32_t v = b < nlo ? cur[b] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_excl_scan256(v, sm, &total);
+    if (b < nlo) start[b] = carry + ex;
+    carry += total;
+    __syncthreads();
   }
+  if (tid == 0) start[nlo] = carry;
+  __syncthreads();
+  uint32_t* orow = off + t * (nb + 1) + ((size_t)d << lb);
+  for (int b = tid; b < nlo; b += 256) { orow[b] = s0 + start[b]; cur[b] = start[b]; }
+  if (d == (uint32_t)nbins - 1 && tid == 0) off[t * (nb + 1) + nb] = (uint32_t)N;
+  __syncthreads();
+  int32_t* seg = ids + t * N + s0;
+  for (uint32_t e = s0 + tid; e < s1; e += 256) {
+    const uint2 x = ent[e];
+    seg[atomicAdd(&cur[x.x & mask], 1u)] = (int32_t)x.y;
+  }
+  __syncthreads();
+  uint32_t over = 0;
+  for (int b = tid; b < nlo; b += 256) {
+    const uint32_t a = start[b], sz = start[b + 1] - a;
+    if (sz > (uint32_t)C) ++over;
+    if (sz < 2) continue;
+    if (sz <= (uint32_t)kSmallBucket && sz <= (uint32_t)C) {
+      int32_t* p = seg + a;                       // arrival order is arbitrary: restore ascending ids
+      for (uint32_t i = 1; i < sz; ++i) {
+        const int32_t key = p[i];
+        int q = (int)i - 1;
+        while (q >= 0 && p[q] > key) { p[q + 1] = p[q]; --q; }
+        p[q + 1] = key;
+      }
+    } else {
+      const uint32_t slot = atomicAdd(&ctrl->wl_count, 1u);
+      if (slot < wl_cap) worklist[slot] = ((uint64_t)t << 32) | ((d << lb) + (uint32_t)b);
+    }
+  }
+  if (over) atomicAdd(&ctrl->overflowed, over);
 }
 
 __device__ void bitonic_sort_u64(uint64_t* keys, int n) {
@@ -224,30 +284,53 @@ __global__ __launch_bounds__(256) void big_buckets_kernel(const uint32_t* __rest
   }
 }
 
-hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2,
-                               uint32_t* codes_t, uint32_t* rank_t, uint32_t* segsum,
-                               uint64_t* worklist, uint32_t wl_cap, Ctrl* ctrl, int policy,
-                               uint32_t r, uint32_t prio_a, uint32_t prio_b, int tables_per_block,
-                               hipStream_t s) {
+// Split of the code into partition digit (high hb bits) and in-partition digit (low lb bits).
+void tables_split(int bits, int64_t N, int* hb, int* lb) {
+  int want = 0;
+  while (want < 11 && ((int64_t)2048 << want) < N) ++want;     // about 2048 rows per partition
+  int h = want < bits ? want : bits;
+  if (bits - h > 13) h = bits - 13;                            // low digit counters must fit in LDS
+  *hb = h;
+  *lb = bits - h;
+}
+
+size_t tables_bh_words(int bits, int64_t N, int L) {
+  int hb, lb;
+  tables_split(bits, N, &hb, &lb);
+  const int64_t nslab = (N + kSlab - 1) / kSlab;
+  return (size_t)L * (size_t)(nslab > 0 ? nslab : 1) * ((size_t)1 << hb);
+}
+
+size_t tables_pbase_words(int bits, int64_t N, int L) {
+  int hb, lb;
+  tables_split(bits, N, &hb, &lb);
+  return (size_t)L * (((size_t)1 << hb) + 1);
+}
+
+hipError_t tables_setup_attributes() {
+  return hipFuncSetAttribute((const void*)part_buckets_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (2 * 8192 + 16) * 4);
+}
+
+hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
+                               uint2* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
+                               uint32_t wl_cap, Ctrl* ctrl, int policy, uint32_t r, uint32_t prio_a,
+                               uint32_t prio_b, hipStream_t s) {
   hipError_t e;
-  const uint32_t nb = td.nb;
-  const uint32_t nseg = (nb + kScanSeg - 1) / kScanSeg;
-  int lgnb = 0;
-  while ((1u << lgnb) < nb) ++lgnb;
-  if ((e = launch_fill_u32(td.off, (size_t)td.L * (nb + 1), 0u, s)) != hipSuccess) return e;
-  if ((e = launch_hash(hd, W2, td.N, codes_t, 1, td.N, td.off, rank_t, nb, tables_per_block, s)) != hipSuccess)
-    return e;
-  hipLaunchKernelGGL(seg_sum_kernel, dim3(nseg, td.L), dim3(256), 0, s, td.off, nb, nseg, segsum);
-  hipLaunchKernelGGL(seg_scan_kernel, dim3(td.L), dim3(256), 0, s, segsum, nseg, ctrl);
-  hipLaunchKernelGGL(seg_apply_kernel, dim3(nseg, td.L), dim3(256), 0, s, td.off, nb, nseg, segsum,
-                     (uint32_t)td.N);
-  if (td.N > 0)
-    hipLaunchKernelGGL(scatter_ids_kernel, dim3((unsigned)ceil_div(td.N, 256), td.L), dim3(256), 0, s,
-                       codes_t, rank_t, td.off, td.ids, nb, td.N);
-  const uint64_t buckets = (uint64_t)td.L << lgnb;
-  hipLaunchKernelGGL(small_buckets_kernel, dim3((unsigned)((buckets + 255) / 256)), dim3(256), 0, s, td.off,
-                     td.ids, nb, lgnb, td.N, td.L, td.C, worklist, wl_cap, ctrl);
-  hipLaunchKernelGGL(big_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, nb, td.N, td.C, policy,
+  int bits = 0, hb, lb;
+  while ((1u << bits) < td.nb) ++bits;
+  tables_split(bits, td.N, &hb, &lb);
+  const int nbins = 1 << hb;
+  const int nslab = td.N > 0 ? (int)((td.N + kSlab - 1) / kSlab) : 1;
+  if ((e = launch_hash(hd, W2, td.N, codes_t, 1, td.N, nullptr, nullptr, td.nb, hd.L, s)) != hipSuccess) return e;
+  hipLaunchKernelGGL(part_hist_kernel, dim3(nslab, td.L), dim3(1024), (size_t)nbins * 4, s, codes_t, td.N, lb, nbins,
+                     bh, nslab);
+  hipLaunchKernelGGL(part_scan_kernel, dim3(td.L), dim3(1024), 0, s, bh, nslab, nbins, pbase, ctrl);
+  hipLaunchKernelGGL(part_scatter_kernel, dim3(nslab, td.L), dim3(1024), (size_t)nbins * 4, s, codes_t, td.N, lb,
+                     nbins, bh, nslab, pbase, entries);
+  hipLaunchKernelGGL(part_buckets_kernel, dim3(nbins, td.L), dim3(256), (size_t)(2 * (1 << lb) + 16) * 4, s, entries,
+                     pbase, nbins, lb, td.nb, td.N, td.C, td.off, td.ids, worklist, wl_cap, ctrl);
+  hipLaunchKernelGGL(big_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, td.C, policy,
                      r, prio_a, prio_b, worklist, wl_cap, ctrl);
   return hipGetLastError();
 }

@@ -57,5 +57,5 @@ def test_bad_configurations_are_rejected_on_the_host(lib, field, value):
 
 
 def test_code_width_limit(lib):
-    cfg = slide.config_from_workload(synth.small(synth.HASH_DWTA, K=10))      # 30 bits
+    cfg = slide.config_from_workload(synth.small(synth.HASH_DWTA, K=9))       # 27 bits
     assert lib.slide_query_memory(C.byref(cfg), C.byref(slide.slide_mem_req())) == slide.SLIDE_EINVAL
