@@ -166,22 +166,18 @@ int slide_status(slide_ctx* ctx, void* hip_stream, uint32_t* flags);
 /* Synchronises the stream and copies the counters. */
 int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out);
 
-/* Stages of a step, in launch order, for slide_profile. */
+/* Launches of a step, in order, for slide_profile. */
 enum slide_stage {
-  SLIDE_STAGE_HIDDEN = 0,        /* sparse-input hidden layer                       */
-  SLIDE_STAGE_HASH = 1,          /* (unused: hashing runs inside the lookup stage)  */
-  SLIDE_STAGE_LOOKUP = 2,        /* hash codes, bucket reads, union, sorted id lists */
-  SLIDE_STAGE_SCAN = 3,          /* forward work items over the samples             */
-  SLIDE_STAGE_RESERVED = 4,      /* (unused)                                        */
-  SLIDE_STAGE_FORWARD = 5,       /* logits + running soft-max over gathered rows    */
-  SLIDE_STAGE_COMBINE = 6,       /* normaliser, errors, loss, hidden gradient       */
-  SLIDE_STAGE_TRANSPOSE_OUT = 7, /* touched output rows -> sample lists             */
-  SLIDE_STAGE_ADAM_OUT = 8,      /* output-layer gradient + Adam on touched rows    */
-  SLIDE_STAGE_TRANSPOSE_IN = 9,  /* touched input rows -> sample lists              */
-  SLIDE_STAGE_ADAM_IN = 10,      /* hidden-layer gradient + Adam on touched rows    */
-  SLIDE_STAGE_FINISH = 11,       /* loss mean, hidden bias                          */
-  SLIDE_STAGE_REBUILD = 12,      /* table build / rebuild (all its kernels)         */
-  SLIDE_NUM_STAGES = 13
+  SLIDE_STAGE_HIDDEN = 0,   /* sparse-input hidden layer                                              */
+  SLIDE_STAGE_LOOKUP = 1,   /* hash codes, bucket reads, union, sorted id lists                       */
+  SLIDE_STAGE_SCAN = 2,     /* forward work items over the samples; the same launch turns the feature  */
+                            /* bit matrix of the batch into per-row sample lists                       */
+  SLIDE_STAGE_FORWARD = 3,  /* logits + running soft-max over the gathered rows                        */
+  SLIDE_STAGE_COMBINE = 4,  /* normaliser, errors, loss, hidden gradient; the same launch turns the    */
+                            /* active bit matrix into per-row sample lists                             */
+  SLIDE_STAGE_UPDATE = 5,   /* gradient + Adam on the touched rows of W2, b2, W1; b1; loss mean        */
+  SLIDE_STAGE_REBUILD = 6,  /* table build / rebuild (all its kernels)                                */
+  SLIDE_NUM_STAGES = 7
 };
 
 /* Measurement aid: for every stage whose bit (1 << slide_stage) is set in stage_mask, later calls

@@ -12,6 +12,7 @@
 //                 the ascending list of samples that touch it (wave ballots), i.e. the row-major
 //                 pair lists of the gradient/Adam kernel -- no sort, no atomics on data.
 #include "slide_internal.h"
+#include "transpose.h"
 
 namespace slide {
 
@@ -36,6 +37,13 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t* total) {
   for (int w = 0; w < nw; ++w) { const uint32_t x = sm[w]; if (w < wave) base += x; tot += x; }
   *total = tot;
   return base + inc - v;
+}
+
+// Position of bitmap word w of sample i: the bit matrix is stored tile-major, [tile][sample][TW
+// words], so that the transposition reads one contiguous block per tile; the per-sample writer
+// pays the stride instead (full 4*TW-byte records).
+__device__ __forceinline__ size_t act_index(const ActiveDev& ad, int i, int w) {
+  return ((size_t)(w / ad.TW) * ad.B + i) * ad.TW + (w & (ad.TW - 1));
 }
 
 // Hash codes of one vector held in LDS, one thread per elementary hash (same arithmetic, in the
@@ -180,9 +188,9 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       const uint32_t word = w < sw ? bm[w] : 0u;
       uint32_t c = __popc(word);
       my_cnt += c;
-      if (w < sw) ad.act[(size_t)i * ad.NWpad + seg0 + w] = word;
+      if (w < sw) ad.act[act_index(ad, i, seg0 + w)] = word;
       for (int d = 1; d < ad.TW; d <<= 1) c += __shfl_xor(c, d);
-      if (w < sw && (lane & (ad.TW - 1)) == 0) ad.rankT[(size_t)i * ad.NT + (seg0 + w) / ad.TW] = c;
+      if (w < sw && (lane & (ad.TW - 1)) == 0) ad.rankS[(size_t)i * ad.NT + (seg0 + w) / ad.TW] = c;
     }
     __syncthreads();
   }
@@ -193,23 +201,22 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   if (tid == 0) { ad.cnt[i] = n; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; ad.as_base[i] = base_i; }
 
   // per-tile counts -> exclusive prefix inside the sample (rank of the tile's first active neuron)
-  uint32_t* rk = ad.rankT + (size_t)i * ad.NT;
+  uint32_t* rk = ad.rankS + (size_t)i * ad.NT;
   carry = 0;
   for (int base = 0; base < ad.NT; base += nthr) {
     const int t = base + tid;
     const uint32_t v = t < ad.NT ? rk[t] : 0u;
     uint32_t total;
     const uint32_t ex = block_excl_scan(v, sm, &total);
-    if (t < ad.NT) rk[t] = carry + ex;
+    if (t < ad.NT) { rk[t] = carry + ex; ad.rankT[(size_t)t * ad.B + i] = carry + ex; }
     carry += total;
     __syncthreads();
   }
   // compact ascending id list: sweep the bitmap (still in LDS if it fitted in one segment)
   const bool in_lds = segw >= ad.NWpad;
-  const uint32_t* arow = ad.act + (size_t)i * ad.NWpad;
   for (int wb = 0; wb < ad.NWpad; wb += nthr) {
     const int w = wb + tid;
-    uint32_t word = w < ad.NWpad ? (in_lds ? bm[w] : arow[w]) : 0u;
+    uint32_t word = w < ad.NWpad ? (in_lds ? bm[w] : ad.act[act_index(ad, i, w)]) : 0u;
     const uint32_t c = __popc(word);
     uint32_t inc = c;
     for (int d = 1; d < ad.TW; d <<= 1) {
@@ -247,10 +254,14 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
 
 // Forward work items (chunks of kChunk active neurons) over the samples, totals for the statistics,
 // and the reset of the per-step device counters.
-__global__ __launch_bounds__(1024) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
-                                                            Ctrl* ctrl) {
+// Workgroup 0 of the launch does this; the other workgroups transpose the feature bit matrix of the
+// batch (it only needs the batch, and this launch is otherwise a single workgroup).
+__global__ __launch_bounds__(256) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
+                                                           Ctrl* ctrl, TransposeArgs t1) {
+  extern __shared__ uint32_t dyn_lds[];
+  if (blockIdx.x > 0) { transpose_tile<true>(t1, blockIdx.x - 1, dyn_lds); return; }
   __shared__ uint32_t sm[20];
-  __shared__ unsigned long long cs[16], as[16];
+  __shared__ unsigned long long cs[16], as[16];   // (at most 16 waves)
   uint32_t carry_c = 0;
   unsigned long long cand = 0, pairs = 0;
   for (int base = 0; base < ad.B; base += blockDim.x) {
@@ -282,147 +293,6 @@ __global__ __launch_bounds__(1024) void scan_samples_kernel(ActiveDev ad, const 
   }
 }
 
-// One workgroup per tile of TW bitmap words, all samples: the tile's touched rows, in row order,
-// each with the ascending list of the samples that touch it.  Row slots of tile t are
-// [t*TW*32, t*TW*32 + tile_nu[t]).  FEAT = false: the active bit matrix; a pair's coefficient
-// index is its slot in the sample-major arrays, and the tile's first pair position is the sum over
-// the samples of their in-sample ranks at the tile start (no atomics: the layout is a pure function
-// of the bit matrix).  FEAT = true: the feature bit matrix of the batch; the coefficient index is the
-// position in the CSR value array, pair space is handed out per workgroup, and the matrix is cleared
-// behind the read so that it is all-zero again for the next batch.
-constexpr int kTransposeWaves = 8;
-
-template <bool FEAT>
-__global__ __launch_bounds__(512) void transpose_kernel(int B, int Bpad, int TW, int NWpad, uint32_t* bits,
-                                                        const uint32_t* __restrict__ rankT, int NT,
-                                                        const int32_t* __restrict__ as_base,
-                                                        const int32_t* __restrict__ x_indptr,
-                                                        const int32_t* __restrict__ x_indices, PairsDev pd) {
-  extern __shared__ uint32_t lds[];
-  uint32_t* tile = lds;                                  // [TW][Bpad]
-  uint32_t* sb = tile + (size_t)TW * Bpad;                // [Bpad] slot of the sample's first pair in this tile
-  uint32_t* wu = sb + Bpad;                              // [32] union word
-  uint32_t* wnp = wu + 32;                               // [32] pairs per word, then exclusive prefix
-  uint32_t* wou = wnp + 32;                              // [32] rows before the word
-  uint32_t* blk = wou + 32;                              // [2] pair base of the tile, sum of ranks
-  uint16_t* rk = (uint16_t*)(blk + 2);                   // [TW][Bpad] in-tile rank before the word
-  const int tileno = blockIdx.x, tid = threadIdx.x;
-  if (tid == 0) { blk[0] = 0; blk[1] = 0; }
-  __syncthreads();
-  uint32_t ranksum = 0;
-  for (int i = tid; i < Bpad; i += 64 * kTransposeWaves) {
-    uint32_t run = 0;
-    uint32_t* src = bits + (size_t)i * NWpad + (size_t)tileno * TW;
-    for (int w = 0; w < TW; ++w) {
-      uint32_t x = 0;
-      if (i < B) {
-        x = src[w];
-        if (FEAT && x) src[w] = 0;
-      }
-      tile[w * Bpad + i] = x;
-      if (!FEAT) rk[w * Bpad + i] = (uint16_t)run;
-      run += __popc(x);
-    }
-    if (!FEAT) {
-      const uint32_t r0 = i < B ? rankT[(size_t)i * NT + tileno] : 0u;
-      sb[i] = i < B ? (uint32_t)as_base[i] + r0 : 0u;
-      ranksum += r0;
-    }
-  }
-  if (!FEAT) atomicAdd(&blk[1], ranksum);                // integer sum: order does not matter
-  __syncthreads();
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int groups = Bpad >> 6;
-  for (int w = wave; w < TW; w += kTransposeWaves) {
-    uint32_t u = 0, np = 0;
-    for (int k = 0; k < groups; ++k) { const uint32_t x = tile[w * Bpad + k * 64 + lane]; u |= x; np += __popc(x); }
-    for (int d = 32; d > 0; d >>= 1) { u |= __shfl_xor(u, d); np += __shfl_xor(np, d); }
-    if (lane == 0) { wu[w] = u; wnp[w] = np; }
-  }
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t nu = 0, np = 0;
-    for (int w = 0; w < TW; ++w) { wou[w] = nu; nu += __popc(wu[w]); const uint32_t c = wnp[w]; wnp[w] = np; np += c; }
-    pd.tile_nu[tileno] = (int32_t)nu;
-    if (nu) atomicMax(pd.max_nu, nu);
-    blk[0] = FEAT ? (np ? atomicAdd(pd.pcount, np) : 0u) : blk[1];
-  }
-  __syncthreads();
-  const uint32_t slot0 = (uint32_t)tileno * (uint32_t)(TW * 32);
-  constexpr int KG = 4;                                  // sample groups held in registers
-  for (int w = wave; w < TW; w += kTransposeWaves) {
-    uint32_t u = __builtin_amdgcn_readfirstlane(wu[w]);
-    if (u == 0) continue;
-    uint32_t us = slot0 + __builtin_amdgcn_readfirstlane(wou[w]);
-    uint32_t po = __builtin_amdgcn_readfirstlane(blk[0] + wnp[w]);
-    uint32_t xr[KG], sr[KG];
-#pragma unroll
-    for (int k = 0; k < KG; ++k) {
-      const int i = k * 64 + lane;
-      xr[k] = k < groups ? tile[w * Bpad + i] : 0u;
-      sr[k] = (!FEAT && k < groups) ? sb[i] + rk[w * Bpad + i] : 0u;
-    }
-    while (u) {
-      const int b = __ffs(u) - 1;
-      u &= u - 1;
-      const int row = (tileno * TW + w) * 32 + b;
-      uint32_t cntj = 0;
-      auto take = [&](int k, uint32_t x, uint32_t sbase) {
-        const int i = k * 64 + lane;
-        const bool has = (x >> b) & 1u;
-        const unsigned long long mk = __ballot(has);
-        if (has) {
-          const uint32_t p = po + cntj + __popcll(mk & ((1ull << lane) - 1ull));
-          int src;
-          if (!FEAT) {
-            src = (int)(sbase + __popc(x & ((1u << b) - 1u)));
-          } else {
-            int a = x_indptr[i], e = x_indptr[i + 1];
-            while (a < e) { const int mid = (a + e) >> 1; if (x_indices[mid] < row) a = mid + 1; else e = mid; }
-            src = a;
-          }
-          pd.pairs[p] = make_int2(i, src);
-        }
-        cntj += (uint32_t)__popcll(mk);
-      };
-#pragma unroll
-      for (int k = 0; k < KG; ++k)
-        if (k < groups) take(k, xr[k], sr[k]);
-      for (int k = KG; k < groups; ++k) {
-        const int i = k * 64 + lane;
-        take(k, tile[w * Bpad + i], FEAT ? 0u : sb[i] + rk[w * Bpad + i]);
-      }
-      if (lane == 0) {
-        pd.umeta[us] = make_int4(row, (int)po, (int)cntj, 0);
-        if ((int)cntj > kLongRow) {
-          const uint32_t l = atomicAdd(pd.nlong, 1u);
-          if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
-        }
-      }
-      ++us;
-      po += cntj;
-    }
-  }
-}
-
-static size_t transpose_lds(int TW, int Bpad) { return (size_t)TW * Bpad * 6 + (size_t)Bpad * 4 + 98 * 4; }
-
-hipError_t launch_transpose_active(const ActiveDev& ad, const PairsDev& pd, hipStream_t s) {
-  const int Bpad = (ad.B + 63) & ~63;
-  hipLaunchKernelGGL(transpose_kernel<false>, dim3(ad.NT), dim3(64 * kTransposeWaves), transpose_lds(ad.TW, Bpad), s, ad.B, Bpad,
-                     ad.TW, ad.NWpad, ad.act, ad.rankT, ad.NT, ad.as_base, nullptr, nullptr, pd);
-  return hipGetLastError();
-}
-
-hipError_t launch_transpose_features(int B, int TW, int DWpad, uint32_t* xbm, const int32_t* x_indptr,
-                                     const int32_t* x_indices, const PairsDev& pd, hipStream_t s) {
-  const int Bpad = (B + 63) & ~63;
-  hipLaunchKernelGGL(transpose_kernel<true>, dim3(DWpad / TW), dim3(64 * kTransposeWaves), transpose_lds(TW, Bpad), s, B, Bpad, TW,
-                     DWpad, xbm, nullptr, 0, nullptr, x_indptr, x_indices, pd);
-  return hipGetLastError();
-}
-
 hipError_t active_setup_attributes(size_t* lds_limit_out) {
   int dev = 0, lim = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -431,11 +301,6 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
   if (e != hipSuccess) return e;
   if (lim > 160 * 1024) lim = 160 * 1024;
   e = hipFuncSetAttribute((const void*)lookup_union_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e != hipSuccess) return e;
-  const int tl = lim < 72 * 1024 ? lim : 72 * 1024;
-  e = hipFuncSetAttribute((const void*)transpose_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, tl);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)transpose_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, tl);
   if (e != hipSuccess) return e;
   *lds_limit_out = (size_t)lim;
   return hipSuccess;
@@ -454,8 +319,10 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const flo
   return hipGetLastError();
 }
 
-hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, hipStream_t s) {
-  hipLaunchKernelGGL(scan_samples_kernel, dim3(1), dim3(1024), 0, s, ad, ncand, ctrl);
+hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, const TransposeArgs& t1,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(scan_samples_kernel, dim3(1 + t1.ntiles), dim3(256),
+                     t1.ntiles ? transpose_lds(t1.TS, t1.Bpad) : 0, s, ad, ncand, ctrl, t1);
   return hipGetLastError();
 }
 

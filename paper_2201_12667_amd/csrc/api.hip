@@ -4,7 +4,6 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
-#include <functional>
 #include <string>
 #include <vector>
 
@@ -21,12 +20,12 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   // derived sizes
-  int Bmax, Bpad, H, L, K, C, TW, TWF, NWpad, NT, NT1, DWpad, bits, PS;
+  int Bmax, Bpad, H, L, K, C, TW, TS, TWF, NWpad, NT, NT2, NT1, DWpad, bits, PS;
   int64_t N, D, Amax, max_chunks, U2max, U1max, P1max, long2, long1;
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, xbm, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, xbm, h, dh, codes, act, rankS, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -85,8 +84,10 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   while (tw > 1 && tw * lo->Bpad > 8192) tw >>= 1;
   lo->TW = tw;
   lo->TWF = std::min(tw, 8);
+  lo->TS = tw;
   lo->NWpad = (int)(((lo->N + 31) / 32 + 31) / 32 * 32);
   lo->NT = lo->NWpad / tw;
+  lo->NT2 = lo->NWpad / lo->TS;
   lo->DWpad = (int)(((lo->D + 31) / 32 + 31) / 32 * 32);
   lo->NT1 = lo->DWpad / lo->TWF;
   const int64_t per_sample = std::min<int64_t>((int64_t)c->L * c->bucket_cap, lo->N);
@@ -114,10 +115,11 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->dh = take(B * H * 4);
   lo->codes = take(B * lo->L * 4);
   lo->act = take(B * lo->NWpad * 4);
+  lo->rankS = take(B * lo->NT * 4);
   lo->rankT = take(B * lo->NT * 4);
   lo->cnt = take(B * 4); lo->ny = take(B * 4); lo->ncand = take(B * 4);
   lo->as_base = take(B * 4); lo->chunk_ptr = take((B + 1) * 4);
-  lo->tile_nu2 = take((size_t)lo->NT * 4); lo->tile_nu1 = take((size_t)lo->NT1 * 4 + 4);
+  lo->tile_nu2 = take((size_t)lo->NT2 * 4); lo->tile_nu1 = take((size_t)lo->NT1 * 4 + 4);
   lo->longlist2 = take((size_t)lo->long2 * 4); lo->longlist1 = take((size_t)lo->long1 * 4);
   lo->chunk_sample = take((size_t)lo->max_chunks * 4);
   lo->as_ids = take(A * 4); lo->as_lab = take(A); lo->ylist = take((size_t)c->max_labels_per_batch * 4 + 4);
@@ -154,9 +156,6 @@ struct slide_ctx {
   const float* last_h = nullptr;
   float* last_dh = nullptr;
   std::string err;
-  // second stream for the work that does not depend on the logits (the two transpositions)
-  hipStream_t side = nullptr;
-  hipEvent_t ev_hidden = nullptr, ev_lookup = nullptr, ev_join = nullptr, ev_combine = nullptr, ev_done = nullptr;
   // per-stage HIP-event timing (slide_profile)
   struct ProfRec { int stage; hipEvent_t a, b; };
   uint32_t prof_mask = 0;
@@ -212,7 +211,7 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ActiveDev ad;
   const Layout& lo = c->lo;
   ad.B = B; ad.L = lo.L; ad.C = lo.C; ad.TW = lo.TW; ad.N = lo.N; ad.NWpad = lo.NWpad; ad.NT = lo.NT;
-  ad.act = c->at<uint32_t>(lo.act); ad.rankT = c->at<uint32_t>(lo.rankT);
+  ad.act = c->at<uint32_t>(lo.act); ad.rankS = c->at<uint32_t>(lo.rankS); ad.rankT = c->at<uint32_t>(lo.rankT);
   ad.cnt = c->at<int32_t>(lo.cnt); ad.ny = c->at<int32_t>(lo.ny);
   ad.PS = lo.PS; ad.num_labels = 0;
   ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
@@ -238,12 +237,10 @@ int check_batch(slide_ctx* ctx, const slide_batch* b, bool need_labels) {
   return SLIDE_OK;
 }
 
-// Hidden activations, hash codes + active sets, and the logits pass.  The two hooks run right after
-// the hidden layer and right after the active sets exist (used by training to fork the transpositions
-// onto the side stream).
+// Hidden activations, hash codes + active sets, and the logits pass; t1 (training only) is the
+// feature transposition that rides in the scan launch.
 int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out,
-                   const std::function<int()>& after_hidden = nullptr,
-                   const std::function<int(const ActiveDev&)>& after_lookup = nullptr) {
+                   const TransposeArgs& t1) {
   const Layout& lo = ctx->lo;
   const int B = b->batch;
   const float* h = b->hidden;
@@ -251,13 +248,11 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
     float* hw = ctx->at<float>(lo.h);
     HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] {
       return launch_spmm_relu(B, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
-                              ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), lo.DWpad, ctx->ctrl(), s); }));
+                              ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), lo.TWF, ctx->ctrl(), s); }));
     h = hw;
   }
   ctx->last_h = h;
   ctx->last_B = B;
-  int rc;
-  if (after_hidden && (rc = after_hidden()) != SLIDE_OK) return rc;
   uint32_t* codes = ctx->at<uint32_t>(lo.codes);
   ActiveDev ad = make_active(ctx, B);
   ad.num_labels = with_labels ? b->num_labels : 0;
@@ -265,8 +260,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
     return launch_lookup_union(ad, ctx->hd, h, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0,
                                ncand, ctx->ctrl(), ctx->lds_limit, s); }));
-  if (after_lookup && (rc = after_lookup(ad)) != SLIDE_OK) return rc;
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), s); }));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), t1, s); }));
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
                           ctx->at<float>(lo.partials), ctx->ctrl(), s); }));
@@ -367,9 +361,7 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   if (e == hipSuccess) { what = "hipFuncSetAttribute(hash kernels)"; e = hash_setup_attributes(H); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(table kernels)"; e = tables_setup_attributes(); }
-  if (e == hipSuccess) { what = "hipStreamCreateWithFlags"; e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking); }
-  for (hipEvent_t* ev : {&ctx->ev_hidden, &ctx->ev_lookup, &ctx->ev_join, &ctx->ev_combine, &ctx->ev_done})
-    if (e == hipSuccess) { what = "hipEventCreateWithFlags"; e = hipEventCreateWithFlags(ev, hipEventDisableTiming); }
+  if (e == hipSuccess) { what = "hipFuncSetAttribute(forward kernels)"; e = forward_setup_attributes(ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipDeviceSynchronize"; e = hipDeviceSynchronize(); }
   if (e != hipSuccess) {
     set_err(nullptr, SLIDE_EHIP, "slide_init: %s failed: %s", what, hipGetErrorString(e));
@@ -413,7 +405,7 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   const Layout& lo = ctx->lo;
   const slide_config& c = ctx->cfg;
   PairsDev p2, p1;
-  p2.rows_per_tile = lo.TW * 32; p2.ntiles = lo.NT; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
+  p2.rows_per_tile = lo.TS * 32; p2.ntiles = lo.NT2; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
   p2.umeta = ctx->at<int4>(lo.umeta2); p2.pairs = ctx->at<int2>(lo.pairs2);
   p2.pcount = nullptr; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
   p2.long_cap = (int)lo.long2; p2.max_nu = &ctx->ctrl()->max_nu2;
@@ -421,33 +413,22 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   p1.umeta = ctx->at<int4>(lo.umeta1); p1.pairs = ctx->at<int2>(lo.pairs1);
   p1.pcount = &ctx->ctrl()->p1; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
   p1.long_cap = (int)lo.long1; p1.max_nu = &ctx->ctrl()->max_nu1;
-  hipStream_t side = ctx->side;
-  // Neither transposition needs the logits: they run on the side stream next to the forward pass
-  // and join before the first kernel that consumes their pair lists.
-  auto after_hidden = [&]() -> int {
-    if (lo.D == 0) return SLIDE_OK;
-    HIPCHK(ctx, hipEventRecord(ctx->ev_hidden, s));
-    HIPCHK(ctx, hipStreamWaitEvent(side, ctx->ev_hidden, 0));
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_IN, side, [&] {
-      return launch_transpose_features(b->batch, lo.TWF, lo.DWpad, ctx->at<uint32_t>(lo.xbm), b->x_indptr,
-                                       b->x_indices, p1, side); }));
-    return SLIDE_OK;
-  };
-  auto after_lookup = [&](const ActiveDev& ad) -> int {
-    HIPCHK(ctx, hipEventRecord(ctx->ev_lookup, s));
-    HIPCHK(ctx, hipStreamWaitEvent(side, ctx->ev_lookup, 0));
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_TRANSPOSE_OUT, side, [&] { return launch_transpose_active(ad, p2, side); }));
-    HIPCHK(ctx, hipEventRecord(ctx->ev_join, side));
-    return SLIDE_OK;
-  };
+  const int Bpad = (b->batch + 63) & ~63;
+  TransposeArgs t2{}, t1{};
+  t2.B = b->batch; t2.Bpad = Bpad; t2.TW = lo.TW; t2.TS = lo.TS; t2.ntiles = lo.NT2; t2.pd = p2;
+  if (lo.D > 0) {
+    t1.B = b->batch; t1.Bpad = Bpad; t1.TW = lo.TWF; t1.TS = lo.TWF; t1.ntiles = lo.NT1; t1.pd = p1;
+    t1.bits = ctx->at<uint32_t>(lo.xbm); t1.x_indptr = b->x_indptr; t1.x_indices = b->x_indices;
+  }
   ActiveDev ad;
-  if ((rc = forward_common(ctx, b, true, s, &ad, after_hidden, after_lookup)) != SLIDE_OK) return rc;
+  if ((rc = forward_common(ctx, b, true, s, &ad, t1)) != SLIDE_OK) return rc;
+  t2.bits = ad.act; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
   float* dh = ctx->at<float>(lo.dh);
   float* delta = ctx->at<float>(lo.delta);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_COMBINE, s, [&] {
     return launch_combine(ad, lo.H, ctx->last_h, ctx->at<float>(lo.z), ctx->at<float>(lo.partials), ctx->buf.W2,
                           b->y_indptr, ad.ylist, delta, dh, b->dhidden_out, ctx->at<float>(lo.loss_i),
-                          ctx->at<float>(lo.msum), s); }));
+                          ctx->at<float>(lo.msum), t2, s); }));
   ctx->last_dh = dh;
   const int64_t t = ctx->t + 1;
   AdamDev a;
@@ -456,29 +437,20 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   a.lr = (float)c.lr; a.eps = (float)c.eps;
   a.inv_bc1 = (float)(1.0 / (1.0 - std::pow(c.beta1, (double)t)));
   a.inv_bc2 = (float)(1.0 / (1.0 - std::pow(c.beta2, (double)t)));
-  // The output-layer update (the long, bandwidth-bound kernel) runs on the caller's stream; the
-  // hidden-layer update, the hidden bias, the loss and the statistics are small and latency-bound
-  // and run beside it on the side stream.  Both need the errors / hidden gradient (combine).
-  HIPCHK(ctx, hipEventRecord(ctx->ev_combine, s));
-  HIPCHK(ctx, hipStreamWaitEvent(side, ctx->ev_combine, 0));
-  HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_join, 0));
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_OUT, s, [&] {
-    return launch_rowgrad_adam(lo.H, p2, delta, ctx->last_h, ctx->buf.W2, ctx->buf.mW2, ctx->buf.vW2,
-                               ctx->buf.b2, ctx->buf.mb2, ctx->buf.vb2, a, s); }));
+  RowUpdate out{}, in{};
+  out.pd = p2; out.coef = delta; out.V = ctx->last_h;
+  out.W = ctx->buf.W2; out.M = ctx->buf.mW2; out.Vv = ctx->buf.vW2;
+  out.bias = ctx->buf.b2; out.mbias = ctx->buf.mb2; out.vbias = ctx->buf.vb2;
+  FinishArgs fin{};
+  fin.B = b->batch; fin.loss_i = ctx->at<float>(lo.loss_i); fin.d_loss = d_loss; fin.dh = dh; fin.ctrl = ctx->ctrl();
+  fin.tile_nu2 = p2.tile_nu; fin.ntiles2 = p2.ntiles;
   if (lo.D > 0) {
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_ADAM_IN, side, [&] {
-      return launch_rowgrad_adam(lo.H, p1, b->x_values, dh, ctx->buf.W1, ctx->buf.mW1, ctx->buf.vW1, nullptr,
-                                 nullptr, nullptr, a, side); }));
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, side, [&] {
-      return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, ctx->buf.b1, ctx->buf.mb1,
-                           ctx->buf.vb1, a, ctx->ctrl(), p2.tile_nu, p2.ntiles, p1.tile_nu, p1.ntiles, side); }));
-  } else {
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FINISH, side, [&] {
-      return launch_finish(b->batch, lo.H, ctx->at<float>(lo.loss_i), d_loss, dh, nullptr, nullptr, nullptr, a,
-                           ctx->ctrl(), p2.tile_nu, p2.ntiles, nullptr, 0, side); }));
+    in.pd = p1; in.coef = b->x_values; in.V = dh;
+    in.W = ctx->buf.W1; in.M = ctx->buf.mW1; in.Vv = ctx->buf.vW1;
+    fin.b1 = ctx->buf.b1; fin.mb1 = ctx->buf.mb1; fin.vb1 = ctx->buf.vb1;
+    fin.tile_nu1 = p1.tile_nu; fin.ntiles1 = p1.ntiles;
   }
-  HIPCHK(ctx, hipEventRecord(ctx->ev_done, side));
-  HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_done, 0));
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_UPDATE, s, [&] { return launch_update(lo.H, out, in, fin, a, s); }));
   ctx->t = t;
   if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
     ctx->r += 1;
@@ -497,7 +469,7 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
   if (rc != SLIDE_OK) return rc;
   hipStream_t s = (hipStream_t)hip_stream;
   ActiveDev ad;
-  if ((rc = forward_common(ctx, b, false, s, &ad)) != SLIDE_OK) return rc;
+  if ((rc = forward_common(ctx, b, false, s, &ad, TransposeArgs{})) != SLIDE_OK) return rc;
   if (ctx->lo.D > 0)   // the feature bit matrix is only consumed by training: clear it again
     HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(ctx->lo.xbm), (size_t)b->batch * ctx->lo.DWpad, 0u, s));
   HIPCHK(ctx, launch_topk(ad, ctx->at<float>(ctx->lo.z), topk, d_out_ids, d_out_scores, s));
@@ -571,8 +543,6 @@ int slide_destroy(slide_ctx* ctx) {
   if (!ctx) return SLIDE_OK;
   for (auto& r : ctx->prof_live) ctx->prof_pool.emplace_back(r.a, r.b);
   for (auto& e : ctx->prof_pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
-  for (hipEvent_t ev : {ctx->ev_hidden, ctx->ev_lookup, ctx->ev_join, ctx->ev_combine, ctx->ev_done}) if (ev) (void)hipEventDestroy(ev);
-  if (ctx->side) { (void)hipStreamSynchronize(ctx->side); (void)hipStreamDestroy(ctx->side); }
   delete ctx;
   return SLIDE_OK;
 }

@@ -3,6 +3,7 @@
 // (paper Section 2.1: activations are computed for the retrieved neurons only; Section 3.6: the
 // first layer is fed by index/value arrays, the second by the first layer's activations).
 #include "slide_internal.h"
+#include "transpose.h"
 
 namespace slide {
 
@@ -17,8 +18,8 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
                                                        const int32_t* __restrict__ x_indices,
                                                        const float* __restrict__ x_values,
                                                        const float* __restrict__ W1, const float* __restrict__ b1,
-                                                       float* __restrict__ h, uint32_t* xbm, int DWpad, Ctrl* ctrl) {
-  const int i = blockIdx.x, lane = threadIdx.x;
+                                                       float* __restrict__ h, uint32_t* xbm, int TWF, Ctrl* ctrl) {
+  const int i = blockIdx.x, lane = threadIdx.x, B = gridDim.x;
   if (i == 0 && blockIdx.y == 0 && lane == 0) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }  // used after this kernel
   const int c0 = (blockIdx.y * 64 + lane) * 2;
   const bool col_ok = c0 < H;
@@ -36,7 +37,10 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
     const bool bad = pb + lane < p1 && (mine < 0 || mine >= D);
     if (__any(bad)) flags |= SLIDE_FLAG_BAD_FEATURE;
     const int kk = bad ? -1 : mine;
-    if (blockIdx.y == 0 && kk >= 0) atomicOr(&xbm[(size_t)i * DWpad + (kk >> 5)], 1u << (kk & 31));
+    if (blockIdx.y == 0 && kk >= 0) {     // feature bit matrix, tile-major: [tile][sample][TWF words]
+      const int w = kk >> 5;
+      atomicOr(&xbm[((size_t)(w / TWF) * B + i) * TWF + (w % TWF)], 1u << (kk & 31));
+    }
     const int cnt = min(64, p1 - pb);
     for (int q0 = 0; q0 < cnt; q0 += UN) {
       int k[UN];
@@ -67,9 +71,9 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
 
 hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
                             const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, uint32_t* xbm, int DWpad, Ctrl* ctrl, hipStream_t s) {
+                            float* h, uint32_t* xbm, int TWF, Ctrl* ctrl, hipStream_t s) {
   hipLaunchKernelGGL(spmm_relu_kernel, dim3(B, ceil_div(H, 128)), dim3(64), 0, s, D, H, nnz_total, x_indptr,
-                     x_indices, x_values, W1, b1, h, xbm, DWpad, ctrl);
+                     x_indices, x_values, W1, b1, h, xbm, TWF, ctrl);
   return hipGetLastError();
 }
 
@@ -83,16 +87,15 @@ hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_
 // are not read a second time.  Partial states are merged per sample by combine_kernel.
 // ---------------------------------------------------------------------------------------------
 template <int LPR, int CH>
-__global__ __launch_bounds__(256) void forward_kernel(ActiveDev ad, int H, const float* __restrict__ h,
-                                                      const float* __restrict__ W2, const float* __restrict__ b2,
-                                                      float* __restrict__ z, float* __restrict__ partials,
-                                                      const Ctrl* __restrict__ ctrl) {
+__device__ void forward_items(const ActiveDev& ad, int H, const float* __restrict__ h, const float* __restrict__ W2,
+                              const float* __restrict__ b2, float* __restrict__ z, float* __restrict__ partials,
+                              const Ctrl* __restrict__ ctrl, int block, int nblocks) {
   constexpr int RPW = 64 / LPR;
   const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
-  const int nwaves = gridDim.x * 4;
+  const int nwaves = nblocks * 4;
   const int nitems = (int)ctrl->total_chunks;
   const int PS = H + 4;
-  for (int item = blockIdx.x * 4 + (threadIdx.x >> 6); item < nitems; item += nwaves) {
+  for (int item = block * 4 + (threadIdx.x >> 6); item < nitems; item += nwaves) {
     const int i = ad.chunk_sample[item];
     const int done = (item - ad.chunk_ptr[i]) * kChunk;
     const int first = ad.as_base[i] + done;
@@ -165,21 +168,30 @@ __global__ __launch_bounds__(256) void forward_kernel(ActiveDev ad, int H, const
   }
 }
 
+constexpr int kForwardBlocks = 2048;
+
 template <int LPR, int CH>
-static hipError_t launch_forward_t(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2,
-                                   float* z, float* partials, const Ctrl* ctrl, hipStream_t s) {
-  hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(2048), dim3(256), 0, s, ad, H, h, W2, b2, z, partials, ctrl);
+__global__ __launch_bounds__(256) void forward_kernel(ActiveDev ad, int H, const float* __restrict__ h,
+                                                      const float* __restrict__ W2, const float* __restrict__ b2,
+                                                      float* __restrict__ z, float* __restrict__ partials,
+                                                      const Ctrl* __restrict__ ctrl) {
+  forward_items<LPR, CH>(ad, H, h, W2, b2, z, partials, ctrl, blockIdx.x, kForwardBlocks);
+}
+
+template <int LPR, int CH>
+static hipError_t launch_fwd(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
+                             float* partials, const Ctrl* ctrl, hipStream_t s) {
+  hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(kForwardBlocks), dim3(256), 0, s, ad, H, h, W2, b2, z, partials,
+                     ctrl);
   return hipGetLastError();
 }
 
-hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2,
-                          float* z, float* partials, const Ctrl* ctrl, hipStream_t s) {
-#define SLIDE_FWD(L_, C_) return launch_forward_t<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, s)
+hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
+                          float* partials, const Ctrl* ctrl, hipStream_t s) {
+#define SLIDE_FWD(L_, C_) return launch_fwd<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, s)
   if (H <= 32) SLIDE_FWD(8, 1);
   if (H <= 64) SLIDE_FWD(8, 2);
-  if (H <= 128) {
-    SLIDE_FWD(8, 4);
-  }
+  if (H <= 128) SLIDE_FWD(8, 4);
   if (H <= 256) SLIDE_FWD(16, 4);
   if (H <= 512) SLIDE_FWD(32, 4);
   if (H <= 1024) SLIDE_FWD(64, 4);
@@ -202,7 +214,11 @@ __global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const
                                                       const int32_t* __restrict__ ylist,
                                                       float* __restrict__ delta, float* __restrict__ dh,
                                                       float* __restrict__ dh_copy, float* __restrict__ loss_i,
-                                                      float* __restrict__ msum) {
+                                                      float* __restrict__ msum, TransposeArgs t2) {
+  // workgroups past the batch transpose the active bit matrix (needed only by the update that
+  // follows; this launch is latency-bound and leaves most of the machine idle)
+  extern __shared__ uint32_t dyn_lds[];
+  if ((int)blockIdx.x >= ad.B) { transpose_tile<false>(t2, blockIdx.x - ad.B, dyn_lds); return; }
   __shared__ float red[4];
   const int i = blockIdx.x, tid = threadIdx.x;
   const int c0 = ad.chunk_ptr[i], nch = ad.chunk_ptr[i + 1] - c0;
@@ -259,10 +275,16 @@ __global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const
 
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
-                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3(ad.B), dim3(256), 0, s, ad, H, h, z, partials, W2, y_indptr, ylist,
-                     delta, dh, dh_copy, loss_i, msum);
+                          float* dh, float* dh_copy, float* loss_i, float* msum, const TransposeArgs& t2,
+                          hipStream_t s) {
+  hipLaunchKernelGGL(combine_kernel, dim3(ad.B + t2.ntiles), dim3(256), t2.ntiles ? transpose_lds(t2.TS, t2.Bpad) : 0,
+                     s, ad, H, h, z, partials, W2, y_indptr, ylist, delta, dh, dh_copy, loss_i, msum, t2);
   return hipGetLastError();
+}
+
+hipError_t forward_setup_attributes(size_t lds_limit) {
+  const int lim = (int)(lds_limit < 72 * 1024 ? lds_limit : 72 * 1024);
+  return hipFuncSetAttribute((const void*)combine_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
 }
 
 // ---------------------------------------------------------------------------------------------

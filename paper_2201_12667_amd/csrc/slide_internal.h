@@ -78,8 +78,9 @@ struct ActiveDev {
   int NWpad, NT;                   // bitmap words per sample (multiple of TW), tiles per sample
   int PS;                          // slots reserved per sample for candidates: min(L*C, N)
   int num_labels;                  // label entries in the batch
-  uint32_t* act;                   // [B][NWpad] active-set bit matrix
-  uint32_t* rankT;                 // [B][NT] tile counts, then exclusive prefix
+  uint32_t* act;                   // [NT][B][TW] active-set bit matrix, tile-major
+  uint32_t* rankS;                 // [B][NT] per-sample scratch: tile counts, then exclusive prefix
+  uint32_t* rankT;                 // [NT][B] rank of the tile's first active neuron inside the sample
   int32_t* cnt;                    // [B] |AS_i|
   int32_t* ny;                     // [B] distinct labels
   int32_t* as_base;                // [B] first slot of sample i = i*PS + (label entries before sample i)
@@ -89,12 +90,6 @@ struct ActiveDev {
   uint8_t* as_lab;                 // [slots]
   int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
 };
-hipError_t active_setup_attributes(size_t* lds_limit_out);
-hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
-                               uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
-                               int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
-hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, hipStream_t s);
-
 // Transposition of a [B][words] bit matrix into per-row pair lists.  Row slots are grouped by tile:
 // tile t owns slots [t*rows_per_tile, t*rows_per_tile + tile_nu[t]).
 struct PairsDev {
@@ -108,34 +103,67 @@ struct PairsDev {
   int long_cap;
   uint32_t* max_nu; // largest tile_nu (bounds the work items of the row kernel)
 };
-hipError_t launch_transpose_active(const ActiveDev& ad, const PairsDev& pd, hipStream_t s);
-hipError_t launch_transpose_features(int B, int TW, int DWpad, uint32_t* xbm, const int32_t* x_indptr,
-                                     const int32_t* x_indices, const PairsDev& pd, hipStream_t s);
+
+struct TransposeArgs {
+  int B, Bpad, TW, TS, ntiles;   // TW words per record, TS words per tile; ntiles = 0: nothing to do
+  uint32_t* bits;                // [records][B][TW]
+  const uint32_t* rankT;         // [records][B]  (active matrix only)
+  const int32_t* as_base;        // [B]           (active matrix only)
+  const int32_t* x_indptr;       // feature matrix only
+  const int32_t* x_indices;
+  PairsDev pd;
+};
+
+hipError_t active_setup_attributes(size_t* lds_limit_out);
+hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
+                               uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
+                               int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
+hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, const TransposeArgs& t1,
+                               hipStream_t s);
+
 
 // ---- output.hip -----------------------------------------------------------------------
 hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
                             const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, uint32_t* xbm, int DWpad, Ctrl* ctrl, hipStream_t s);
-hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2,
-                          float* z, float* partials, const Ctrl* ctrl, hipStream_t s);
+                            float* h, uint32_t* xbm, int TWF, Ctrl* ctrl, hipStream_t s);
+hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
+                          float* partials, const Ctrl* ctrl, hipStream_t s);
+hipError_t forward_setup_attributes(size_t lds_limit);
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
-                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s);
+                          float* dh, float* dh_copy, float* loss_i, float* msum, const TransposeArgs& t2,
+                          hipStream_t s);
 hipError_t launch_topk(const ActiveDev& ad, const float* z, int topk, int32_t* out_ids,
                        float* out_scores, hipStream_t s);
 hipError_t launch_dense_topk(int B, int64_t N, int H, const float* h, const float* W2, const float* b2,
                              int topk, int32_t* out_ids, float* out_scores, hipStream_t s);
 
 // ---- update.hip -----------------------------------------------------------------------
-// For every listed row r: g = sum over its pairs of coef[psrc] * V[psample][:], then Adam on
-// W[r][:] (and on bias[r] with the sum of the coefficients when bias != nullptr).
-hipError_t launch_rowgrad_adam(int H, const PairsDev& pd, const float* coef, const float* V,
-                               float* W, float* M, float* Vv, float* bias, float* mbias, float* vbias,
-                               const AdamDev& ad, hipStream_t s);
-// loss = mean(loss_i); with b1 != nullptr also gb1 = column sums of dh and Adam on b1.
-hipError_t launch_finish(int B, int H, const float* loss_i, float* d_loss, const float* dh, float* b1,
-                         float* mb1, float* vb1, const AdamDev& ad, Ctrl* ctrl, const int32_t* tile_nu2,
-                         int ntiles2, const int32_t* tile_nu1, int ntiles1, hipStream_t s);
+// Rows of one weight matrix to update: for every listed row r, g = sum over its pairs of
+// coef[src] * V[sample][:], then Adam on W[r][:] (and on bias[r] with the sum of the coefficients
+// when bias != nullptr).
+struct RowUpdate {
+  PairsDev pd;
+  const float* coef;
+  const float* V;
+  float *W, *M, *Vv, *bias, *mbias, *vbias;
+  int nblocks;                   // workgroups given to this matrix; 0 = absent
+};
+struct FinishArgs {
+  int B;
+  const float* loss_i;
+  float* d_loss;
+  const float* dh;
+  float *b1, *mb1, *vb1;         // nullptr in dense-hidden mode
+  Ctrl* ctrl;
+  const int32_t* tile_nu2; int ntiles2;
+  const int32_t* tile_nu1; int ntiles1;
+  int nblocks;
+};
+// One launch, three roles by workgroup index: loss mean + hidden bias + statistics, the rows of W1,
+// the rows of W2 (+ b2).
+hipError_t launch_update(int H, const RowUpdate& out, const RowUpdate& in, const FinishArgs& fin, const AdamDev& ad,
+                         hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 

@@ -55,15 +55,20 @@ __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd,
 // CH float4 per lane).  Rows with more than kLongRow pairs are skipped here and taken afterwards by
 // a whole wave each: its RPW lane groups accumulate interleaved shares of the pair list and the
 // shares are added in a fixed butterfly order.
-template <int LPR, int CH, int UNR, bool OUTPUT_LAYER>
-__global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, const float* __restrict__ coef,
-                                                           const float* __restrict__ V, float* __restrict__ W,
-                                                           float* __restrict__ M, float* __restrict__ Vv,
-                                                           float* __restrict__ bias, float* __restrict__ mbias,
-                                                           float* __restrict__ vbias, AdamDev ad) {
+template <int LPR, int CH, int UNR>
+__device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int block, int nblocks) {
+  const PairsDev& pd = ru.pd;
+  const float* __restrict__ coef = ru.coef;
+  const float* __restrict__ V = ru.V;
+  float* __restrict__ W = ru.W;
+  float* __restrict__ M = ru.M;
+  float* __restrict__ Vv = ru.Vv;
+  float* __restrict__ bias = ru.bias;
+  float* __restrict__ mbias = ru.mbias;
+  float* __restrict__ vbias = ru.vbias;
   constexpr int RPW = 64 / LPR;
   const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
-  const int wave_global = blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = gridDim.x * 4;
+  const int wave_global = block * 4 + (threadIdx.x >> 6), nwaves = nblocks * 4;
   const int cpt = ((int)*pd.max_nu + RPW - 1) / RPW;       // items per tile that can hold rows
   const int nitems = pd.ntiles * cpt;
   for (int item = wave_global; item < nitems; item += nwaves) {
@@ -162,48 +167,25 @@ __global__ __launch_bounds__(256) void rowgrad_adam_kernel(int H, PairsDev pd, c
   }
 }
 
-template <int LPR, int CH, int UNR = (CH <= 4 ? 4 : 2)>
-static hipError_t launch_rg(int H, const PairsDev& pd, const float* coef, const float* V, float* W, float* M,
-                            float* Vv, float* bias, float* mbias, float* vbias, const AdamDev& ad, hipStream_t s) {
-  // OUTPUT_LAYER only gives the two uses distinct kernel names in profiles (bias present = output layer)
-  if (bias)
-    hipLaunchKernelGGL((rowgrad_adam_kernel<LPR, CH, UNR, true>), dim3(2048), dim3(256), 0, s, H, pd, coef, V, W, M,
-                       Vv, bias, mbias, vbias, ad);
-  else
-    hipLaunchKernelGGL((rowgrad_adam_kernel<LPR, CH, UNR, false>), dim3(2048), dim3(256), 0, s, H, pd, coef, V, W, M,
-                       Vv, bias, mbias, vbias, ad);
-  return hipGetLastError();
-}
-
-hipError_t launch_rowgrad_adam(int H, const PairsDev& pd, const float* coef, const float* V, float* W, float* M,
-                               float* Vv, float* bias, float* mbias, float* vbias, const AdamDev& ad,
-                               hipStream_t s) {
-#define SLIDE_RG(L_, C_) return launch_rg<L_, C_>(H, pd, coef, V, W, M, Vv, bias, mbias, vbias, ad, s)
-  if (H <= 32) SLIDE_RG(8, 1);
-  if (H <= 64) SLIDE_RG(8, 2);
-  if (H <= 128) {
-    return launch_rg<8, 4, 2>(H, pd, coef, V, W, M, Vv, bias, mbias, vbias, ad, s);
-  }
-  if (H <= 256) SLIDE_RG(16, 4);
-  if (H <= 512) SLIDE_RG(32, 4);
-  if (H <= 1024) SLIDE_RG(64, 4);
-  SLIDE_RG(64, 8);
-#undef SLIDE_RG
-}
-
 // Block 0: loss = mean_i loss_i (fixed-shape reduction) and the step statistics.  With b1: every
 // block takes 32 columns of gb1[u] = sum_i dh[i][u]; 8 partial sums per column over interleaved
 // samples, added in a fixed order, then Adam on the dense hidden bias.
-__global__ __launch_bounds__(256) void finish_kernel(int B, int H, const float* __restrict__ loss_i,
-                                                     float* __restrict__ d_loss, const float* __restrict__ dh,
-                                                     float* __restrict__ b1, float* __restrict__ mb1,
-                                                     float* __restrict__ vb1, AdamDev ad, Ctrl* ctrl,
-                                                     const int32_t* __restrict__ tile_nu2, int ntiles2,
-                                                     const int32_t* __restrict__ tile_nu1, int ntiles1) {
+__device__ void finish_role(int H, const FinishArgs& f, const AdamDev& ad, int block) {
+  const int B = f.B;
+  const float* __restrict__ loss_i = f.loss_i;
+  float* __restrict__ d_loss = f.d_loss;
+  const float* __restrict__ dh = f.dh;
+  float* __restrict__ b1 = f.b1;
+  float* __restrict__ mb1 = f.mb1;
+  float* __restrict__ vb1 = f.vb1;
+  Ctrl* ctrl = f.ctrl;
+  const int32_t* __restrict__ tile_nu2 = f.tile_nu2;
+  const int32_t* __restrict__ tile_nu1 = f.tile_nu1;
+  const int ntiles2 = f.ntiles2, ntiles1 = f.ntiles1;
   __shared__ float red[256];
   __shared__ uint32_t ured[2][256];
   const int tid = threadIdx.x;
-  if (blockIdx.x == 0) {
+  if (block == 0) {
     float acc = 0.f;
     for (int i = tid; i < B; i += 256) acc += loss_i[i];
     uint32_t u2 = 0, u1 = 0;
@@ -228,7 +210,7 @@ __global__ __launch_bounds__(256) void finish_kernel(int B, int H, const float* 
   }
   if (!b1) return;
   const int col = tid & 31, part = tid >> 5;
-  const int u = blockIdx.x * 32 + col;
+  const int u = block * 32 + col;
   float g = 0.f;
   if (u < H)
     for (int i = part; i < B; i += 8) g += dh[(size_t)i * H + u];
@@ -243,13 +225,42 @@ __global__ __launch_bounds__(256) void finish_kernel(int B, int H, const float* 
   }
 }
 
-hipError_t launch_finish(int B, int H, const float* loss_i, float* d_loss, const float* dh, float* b1,
-                         float* mb1, float* vb1, const AdamDev& ad, Ctrl* ctrl, const int32_t* tile_nu2,
-                         int ntiles2, const int32_t* tile_nu1, int ntiles1, hipStream_t s) {
-  const int blocks = b1 ? ceil_div(H, 32) : 1;
-  hipLaunchKernelGGL(finish_kernel, dim3(blocks), dim3(256), 0, s, B, H, loss_i, d_loss, dh, b1, mb1, vb1, ad,
-                     ctrl, tile_nu2, ntiles2, tile_nu1, ntiles1);
+constexpr int kUpdateBlocksOut = 2048;
+
+template <int LPR, int CH, int UNR>
+__global__ __launch_bounds__(256) void update_kernel(int H, RowUpdate out, RowUpdate in, FinishArgs fin, AdamDev ad) {
+  int blk = blockIdx.x;
+  if (blk < fin.nblocks) { finish_role(H, fin, ad, blk); return; }
+  blk -= fin.nblocks;
+  if (blk < in.nblocks) { rowgrad_adam<LPR, CH, UNR>(H, in, ad, blk, in.nblocks); return; }
+  blk -= in.nblocks;
+  rowgrad_adam<LPR, CH, UNR>(H, out, ad, blk, out.nblocks);
+}
+
+template <int LPR, int CH, int UNR>
+static hipError_t launch_up(int H, const RowUpdate& out, const RowUpdate& in, const FinishArgs& fin,
+                            const AdamDev& ad, hipStream_t s) {
+  hipLaunchKernelGGL((update_kernel<LPR, CH, UNR>), dim3(fin.nblocks + in.nblocks + out.nblocks), dim3(256), 0, s, H,
+                     out, in, fin, ad);
   return hipGetLastError();
+}
+
+hipError_t launch_update(int H, const RowUpdate& out_, const RowUpdate& in_, const FinishArgs& fin_,
+                         const AdamDev& ad, hipStream_t s) {
+  RowUpdate out = out_, in = in_;
+  FinishArgs fin = fin_;
+  out.nblocks = kUpdateBlocksOut;
+  in.nblocks = in.W ? 256 : 0;
+  fin.nblocks = fin.b1 ? ceil_div(H, 32) : 1;
+#define SLIDE_UP(L_, C_, U_) return launch_up<L_, C_, U_>(H, out, in, fin, ad, s)
+  if (H <= 32) SLIDE_UP(8, 1, 4);
+  if (H <= 64) SLIDE_UP(8, 2, 4);
+  if (H <= 128) SLIDE_UP(8, 4, 2);
+  if (H <= 256) SLIDE_UP(16, 4, 2);
+  if (H <= 512) SLIDE_UP(32, 4, 2);
+  if (H <= 1024) SLIDE_UP(64, 4, 2);
+  SLIDE_UP(64, 8, 2);
+#undef SLIDE_UP
 }
 
 }  // namespace slide
