@@ -206,7 +206,9 @@ hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const floa
 // (the first sum is acc/s from the forward pass; the label rows are read here, in label order).
 // A sample without labels contributes nothing.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const float* __restrict__ h,
+constexpr int kCombineThreads = 512;
+
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, int H, const float* __restrict__ h,
                                                       const float* __restrict__ z,
                                                       const float* __restrict__ partials,
                                                       const float* __restrict__ W2,
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const
   // follows; this launch is latency-bound and leaves most of the machine idle)
   extern __shared__ uint32_t dyn_lds[];
   if ((int)blockIdx.x >= ad.B) { transpose_tile<false>(t2, blockIdx.x - ad.B, dyn_lds); return; }
-  __shared__ float red[4];
+  __shared__ float red[kCombineThreads / 64];
   const int i = blockIdx.x, tid = threadIdx.x;
   const int c0 = ad.chunk_ptr[i], nch = ad.chunk_ptr[i + 1] - c0;
   const int first = ad.as_base[i], n = ad.cnt[i];
@@ -235,7 +237,7 @@ __global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const
   }
   if (tid == 0) { msum[2 * i] = Mi; msum[2 * i + 1] = s; }
   const bool live = n > 0 && ny > 0;
-  for (int u = tid; u < H; u += 256) {
+  for (int u = tid; u < H; u += kCombineThreads) {
     float g = 0.f;
     if (live && h[(size_t)i * H + u] > 0.f) {
       float acc = 0.f;
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const
   float lacc = 0.f;
   const float logs = live ? __logf(s) : 0.f;
   const float yv = ny > 0 ? 1.0f / (float)ny : 0.f;
-  for (int q = tid; q < n; q += 256) {
+  for (int q = tid; q < n; q += kCombineThreads) {
     const int slot = first + q;
     float d = 0.f;
     if (live) {
@@ -270,14 +272,18 @@ __global__ __launch_bounds__(256) void combine_kernel(ActiveDev ad, int H, const
   for (int d = 32; d > 0; d >>= 1) lacc += __shfl_xor(lacc, d);
   if ((tid & 63) == 0) red[tid >> 6] = lacc;
   __syncthreads();
-  if (tid == 0) loss_i[i] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (tid == 0) {                     // fixed order
+    float t = 0.f;
+    for (int w = 0; w < kCombineThreads / 64; ++w) t += red[w];
+    loss_i[i] = t;
+  }
 }
 
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
                           float* dh, float* dh_copy, float* loss_i, float* msum, const TransposeArgs& t2,
                           hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3(ad.B + t2.ntiles), dim3(256), t2.ntiles ? transpose_lds(t2.TS, t2.Bpad) : 0,
+  hipLaunchKernelGGL(combine_kernel, dim3(ad.B + t2.ntiles), dim3(kCombineThreads), t2.ntiles ? transpose_lds(t2.TS, t2.Bpad) : 0,
                      s, ad, H, h, z, partials, W2, y_indptr, ylist, delta, dh, dh_copy, loss_i, msum, t2);
   return hipGetLastError();
 }

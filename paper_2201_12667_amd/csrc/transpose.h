@@ -2,6 +2,7 @@
 // can run as one role of a larger launch.
 #pragma once
 #include "slide_internal.h"
+#include "wave_ops.h"
 
 namespace slide {
 
@@ -26,15 +27,17 @@ __device__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* ld
   const int32_t* __restrict__ x_indices = ta.x_indices;
   const PairsDev& pd = ta.pd;
   const int nwaves = blockDim.x >> 6;
+  const int groups = Bpad >> 6;                          // 64-sample groups
   uint32_t* tile = lds;                                  // [TS][Bpad]
   uint32_t* sb = tile + (size_t)TS * Bpad;                // [Bpad] slot of the sample's first pair in this tile
-  uint32_t* wu = sb + Bpad;                              // [32] union word
-  uint32_t* wnp = wu + 32;                               // [32] pairs per word, then exclusive prefix
-  uint32_t* wou = wnp + 32;                              // [32] rows before the word
-  uint32_t* blk = wou + 32;                              // [2] pair base of the tile, sum of ranks
+  uint32_t* wug = sb + Bpad;                             // [TS][groups] union of the word over a sample group
+  uint32_t* wu = wug + (size_t)TS * groups;              // [TS] union over all samples
+  uint32_t* wnp = wu + TS;                               // [TS] pairs per word, then exclusive prefix
+  uint32_t* wou = wnp + TS;                              // [TS] rows before the word
+  uint32_t* blk = wou + TS;                              // [2] pair base of the tile, sum of ranks
   uint16_t* rk = (uint16_t*)(blk + 2);                   // [TS][Bpad] rank inside this tile before the word
-  const int tid = threadIdx.x;
-  if (tid == 0) { blk[0] = 0; blk[1] = 0; }
+  const int tid = threadIdx.x, lane = tid & 63;
+  for (int q = tid; q < TS * groups + 3 * TS + 2; q += blockDim.x) wug[q] = 0;   // wug, wu, wnp, wou, blk
   __syncthreads();
   uint32_t ranksum = 0;
   for (int i = tid; i < Bpad; i += blockDim.x) {
@@ -59,6 +62,16 @@ __device__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* ld
       } else if (w < w0 + TS) {
         tile[(w - w0) * Bpad + i] = x[w];
         rk[(w - w0) * Bpad + i] = (uint16_t)run;
+        // union and pair count of the word over this wave's 64 samples: LDS atomics from the few
+        // lanes that hold anything, or one register reduction when many do
+        const int holders = __popcll(__ballot(x[w] != 0u));
+        if (holders > 8) {
+          const uint32_t o = wave_or(x[w]), c = wave_sum((uint32_t)__popc(x[w]));
+          if (lane == 0) { wug[(w - w0) * groups + (i >> 6)] = o; atomicAdd(&wnp[w - w0], c); }
+        } else if (x[w]) {
+          atomicOr(&wug[(w - w0) * groups + (i >> 6)], x[w]);
+          atomicAdd(&wnp[w - w0], (uint32_t)__popc(x[w]));
+        }
         run += __popc(x[w]);
         any |= x[w];
       }
@@ -82,24 +95,20 @@ __device__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* ld
       sb[i] = a;
     }
   }
-  if (!FEAT) atomicAdd(&blk[1], ranksum);                // integer sum: order does not matter
+  if (!FEAT && ranksum) atomicAdd(&blk[1], ranksum);     // integer sum: order does not matter
   __syncthreads();
-  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int groups = Bpad >> 6;
-  for (int w = wave; w < TS; w += nwaves) {
-    uint32_t u = 0, np = 0;
-    for (int k = 0; k < groups; ++k) { const uint32_t x = tile[w * Bpad + k * 64 + lane]; u |= x; np += __popc(x); }
-    for (int d = 32; d > 0; d >>= 1) { u |= __shfl_xor(u, d); np += __shfl_xor(np, d); }
-    if (lane == 0) { wu[w] = u; wnp[w] = np; }
-  }
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t nu = 0, np = 0;
-    for (int w = 0; w < TS; ++w) { wou[w] = nu; nu += __popc(wu[w]); const uint32_t c = wnp[w]; wnp[w] = np; np += c; }
-    pd.tile_nu[tileno] = (int32_t)nu;
-    if (nu > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, nu);   // few workgroups ever get here
-    blk[0] = FEAT ? (np ? atomicAdd(pd.pcount, np) : 0u) : blk[1];
+  if (wave == 0) {                                       // per word: union, rows and pairs before it
+    uint32_t u = 0;
+    if (lane < TS) for (int k = 0; k < groups; ++k) u |= wug[lane * groups + k];
+    const uint32_t c = __popc(u), np = lane < TS ? wnp[lane] : 0u;
+    const uint32_t cin = wave_incl_scan_add(c), pin = wave_incl_scan_add(np);
+    if (lane < TS) { wu[lane] = u; wou[lane] = cin - c; wnp[lane] = pin - np; }
+    if (lane == 63) {
+      pd.tile_nu[tileno] = (int32_t)cin;
+      if (cin > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, cin);   // few workgroups ever get here
+      blk[0] = FEAT ? (pin ? atomicAdd(pd.pcount, pin) : 0u) : blk[1];
+    }
   }
   __syncthreads();
   const uint32_t slot0 = (uint32_t)tileno * (uint32_t)(TS * 32);
@@ -109,12 +118,13 @@ __device__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* ld
     if (u == 0) continue;
     uint32_t us = slot0 + __builtin_amdgcn_readfirstlane(wou[w]);
     uint32_t po = __builtin_amdgcn_readfirstlane(blk[0] + wnp[w]);
-    uint32_t xr[KG], sr[KG];
+    uint32_t xr[KG], sr[KG], ug[KG];                     // ug: union of the word over the 64 samples
 #pragma unroll
     for (int k = 0; k < KG; ++k) {
       const int i = k * 64 + lane;
       xr[k] = k < groups ? tile[w * Bpad + i] : 0u;
       sr[k] = k < groups ? sb[i] + rk[w * Bpad + i] : 0u;
+      ug[k] = k < groups ? __builtin_amdgcn_readfirstlane(wug[w * groups + k]) : 0u;
     }
     while (u) {
       const int b = __ffs(u) - 1;
@@ -133,7 +143,7 @@ __device__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* ld
       };
 #pragma unroll
       for (int k = 0; k < KG; ++k)
-        if (k < groups) take(k, xr[k], sr[k]);
+        if ((ug[k] >> b) & 1u) take(k, xr[k], sr[k]);     // skip sample groups without this row
       for (int k = KG; k < groups; ++k) {
         const int i = k * 64 + lane;
         take(k, tile[w * Bpad + i], sb[i] + rk[w * Bpad + i]);
@@ -151,6 +161,8 @@ __device__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* ld
   }
 }
 
-inline size_t transpose_lds(int TS, int Bpad) { return (size_t)TS * Bpad * 6 + (size_t)Bpad * 4 + 98 * 4; }
+inline size_t transpose_lds(int TS, int Bpad) {
+  return (size_t)TS * Bpad * 6 + (size_t)Bpad * 4 + ((size_t)TS * (Bpad >> 6) + 3 * TS + 2) * 4;
+}
 
 }  // namespace slide
