@@ -14,7 +14,11 @@
 #include "slide_internal.h"
 #include "transpose.h"
 
+#include <algorithm>
+
 namespace slide {
+
+constexpr int kScanThreads = 1024;
 
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
   const int lane = threadIdx.x & 63;
@@ -27,7 +31,7 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
 }
 
 // Exclusive scan over a workgroup of up to 1024 threads; sm: 17 words of LDS.
-__device__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t* total) {
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t& total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const uint32_t inc = wave_incl_scan_u32(v);
   __syncthreads();
@@ -35,7 +39,7 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t* total) {
   __syncthreads();
   uint32_t base = 0, tot = 0;
   for (int w = 0; w < nw; ++w) { const uint32_t x = sm[w]; if (w < wave) base += x; tot += x; }
-  *total = tot;
+  total = tot;
   return base + inc - v;
 }
 
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       o0s[t] = a;
     }
     uint32_t total;
-    const uint32_t ex = block_excl_scan(len, sm, &total);
+    const uint32_t ex = block_excl_scan(len, sm, total);
     if (t < ad.L) pos[t] = carry + ex;
     carry += total;
     __syncthreads();
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
     const int t = base + tid;
     const uint32_t v = t < ad.NT ? rk[t] : 0u;
     uint32_t total;
-    const uint32_t ex = block_excl_scan(v, sm, &total);
+    const uint32_t ex = block_excl_scan(v, sm, total);
     if (t < ad.NT) { rk[t] = carry + ex; ad.rankT[(size_t)t * ad.B + i] = carry + ex; }
     carry += total;
     __syncthreads();
@@ -252,14 +256,19 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   }
 }
 
-// Forward work items (chunks of kChunk active neurons) over the samples, totals for the statistics,
-// and the reset of the per-step device counters.
-// Workgroup 0 of the launch does this; the other workgroups transpose the feature bit matrix of the
-// batch (it only needs the batch, and this launch is otherwise a single workgroup).
-__global__ __launch_bounds__(256) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
-                                                           Ctrl* ctrl, TransposeArgs t1) {
+// Forward work items (chunks of kChunk active neurons) over the samples and totals for the statistics.
+// Workgroup 0 of the launch does this; the other workgroups transpose the two bit matrices of the
+// batch (active sets, then features): they need nothing that this launch computes, and the launch
+// is otherwise a single workgroup.
+__global__ __launch_bounds__(kScanThreads) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
+                                                                    Ctrl* ctrl, TransposeArgs t1, TransposeArgs t2) {
   extern __shared__ uint32_t dyn_lds[];
-  if (blockIdx.x > 0) { transpose_tile<true>(t1, blockIdx.x - 1, dyn_lds); return; }
+  if (blockIdx.x > 0) {
+    const int k = blockIdx.x - 1;
+    if (k < t2.ntiles) transpose_tile<false>(t2, k, dyn_lds);
+    else transpose_tile<true>(t1, k - t2.ntiles, dyn_lds);
+    return;
+  }
   __shared__ uint32_t sm[20];
   __shared__ unsigned long long cs[16], as[16];   // (at most 16 waves)
   uint32_t carry_c = 0;
@@ -269,7 +278,7 @@ __global__ __launch_bounds__(256) void scan_samples_kernel(ActiveDev ad, const i
     const uint32_t n = i < ad.B ? (uint32_t)ad.cnt[i] : 0u;
     const uint32_t ch = (n + kChunk - 1) / kChunk;
     uint32_t tc;
-    const uint32_t ec = block_excl_scan(ch, sm, &tc);
+    const uint32_t ec = block_excl_scan(ch, sm, tc);
     if (i < ad.B) {
       ad.chunk_ptr[i] = (int32_t)(carry_c + ec);
       for (uint32_t k = 0; k < ch; ++k) ad.chunk_sample[carry_c + ec + k] = i;
@@ -302,6 +311,9 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
   if (lim > 160 * 1024) lim = 160 * 1024;
   e = hipFuncSetAttribute((const void*)lookup_union_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
   if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)scan_samples_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          lim < 72 * 1024 ? lim : 72 * 1024);
+  if (e != hipSuccess) return e;
   *lds_limit_out = (size_t)lim;
   return hipSuccess;
 }
@@ -320,9 +332,12 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const flo
 }
 
 hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, const TransposeArgs& t1,
-                               hipStream_t s) {
-  hipLaunchKernelGGL(scan_samples_kernel, dim3(1 + t1.ntiles), dim3(256),
-                     t1.ntiles ? transpose_lds(t1.TS, t1.Bpad) : 0, s, ad, ncand, ctrl, t1);
+                               const TransposeArgs& t2, hipStream_t s) {
+  size_t lds = 0;
+  if (t1.ntiles) lds = transpose_lds(t1.TW, t1.Bpad);
+  if (t2.ntiles) lds = std::max(lds, transpose_lds(t2.TW, t2.Bpad));
+  hipLaunchKernelGGL(scan_samples_kernel, dim3(1 + t1.ntiles + t2.ntiles), dim3(kScanThreads), lds, s, ad, ncand,
+                     ctrl, t1, t2);
   return hipGetLastError();
 }
 

@@ -20,12 +20,12 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   // derived sizes
-  int Bmax, Bpad, H, L, K, C, TW, TS, TWF, NWpad, NT, NT2, NT1, DWpad, bits, PS;
+  int Bmax, Bpad, H, L, K, C, TW, TWF, NWpad, NT, NT2, NT1, DWpad, bits, PS;
   int64_t N, D, Amax, max_chunks, U2max, U1max, P1max, long2, long1;
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, xbm, h, dh, codes, act, rankS, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, xbm, xfirst, h, dh, codes, act, rankS, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -83,11 +83,10 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   int tw = 32;
   while (tw > 1 && tw * lo->Bpad > 8192) tw >>= 1;
   lo->TW = tw;
-  lo->TWF = std::min(tw, 8);
-  lo->TS = tw;
+  lo->TWF = tw;
   lo->NWpad = (int)(((lo->N + 31) / 32 + 31) / 32 * 32);
   lo->NT = lo->NWpad / tw;
-  lo->NT2 = lo->NWpad / lo->TS;
+  lo->NT2 = lo->NWpad / tw;
   lo->DWpad = (int)(((lo->D + 31) / 32 + 31) / 32 * 32);
   lo->NT1 = lo->DWpad / lo->TWF;
   const int64_t per_sample = std::min<int64_t>((int64_t)c->L * c->bucket_cap, lo->N);
@@ -111,6 +110,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->ctrl = take(sizeof(Ctrl));
   lo->hashw = take(lo->hash_words * 4);
   lo->xbm = take(lo->D ? B * lo->DWpad * 4 : 0);
+  lo->xfirst = take(lo->D ? B * lo->NT1 * 4 : 0);
   lo->h = take(lo->D ? B * H * 4 : 0);
   lo->dh = take(B * H * 4);
   lo->codes = take(B * lo->L * 4);
@@ -237,10 +237,11 @@ int check_batch(slide_ctx* ctx, const slide_batch* b, bool need_labels) {
   return SLIDE_OK;
 }
 
-// Hidden activations, hash codes + active sets, and the logits pass; t1 (training only) is the
-// feature transposition that rides in the scan launch.
+// Hidden activations, hash codes + active sets, and the logits pass; t1 and t2 (training only) are
+// the transpositions of the feature and the active bit matrix that ride in the scan launch (the
+// bit-matrix pointers of t2 are filled in here).
 int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out,
-                   const TransposeArgs& t1) {
+                   const TransposeArgs& t1, TransposeArgs t2) {
   const Layout& lo = ctx->lo;
   const int B = b->batch;
   const float* h = b->hidden;
@@ -248,7 +249,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
     float* hw = ctx->at<float>(lo.h);
     HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] {
       return launch_spmm_relu(B, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
-                              ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), lo.TWF, ctx->ctrl(), s); }));
+                              ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), ctx->at<int32_t>(lo.xfirst), lo.TWF, ctx->ctrl(), s); }));
     h = hw;
   }
   ctx->last_h = h;
@@ -260,7 +261,8 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
     return launch_lookup_union(ad, ctx->hd, h, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0,
                                ncand, ctx->ctrl(), ctx->lds_limit, s); }));
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), t1, s); }));
+  t2.bits = ad.act; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), t1, t2, s); }));
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
                           ctx->at<float>(lo.partials), ctx->ctrl(), s); }));
@@ -361,7 +363,6 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   if (e == hipSuccess) { what = "hipFuncSetAttribute(hash kernels)"; e = hash_setup_attributes(H); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(table kernels)"; e = tables_setup_attributes(); }
-  if (e == hipSuccess) { what = "hipFuncSetAttribute(forward kernels)"; e = forward_setup_attributes(ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipDeviceSynchronize"; e = hipDeviceSynchronize(); }
   if (e != hipSuccess) {
     set_err(nullptr, SLIDE_EHIP, "slide_init: %s failed: %s", what, hipGetErrorString(e));
@@ -405,7 +406,7 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   const Layout& lo = ctx->lo;
   const slide_config& c = ctx->cfg;
   PairsDev p2, p1;
-  p2.rows_per_tile = lo.TS * 32; p2.ntiles = lo.NT2; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
+  p2.rows_per_tile = lo.TW * 32; p2.ntiles = lo.NT2; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
   p2.umeta = ctx->at<int4>(lo.umeta2); p2.pairs = ctx->at<int2>(lo.pairs2);
   p2.pcount = nullptr; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
   p2.long_cap = (int)lo.long2; p2.max_nu = &ctx->ctrl()->max_nu2;
@@ -415,20 +416,19 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   p1.long_cap = (int)lo.long1; p1.max_nu = &ctx->ctrl()->max_nu1;
   const int Bpad = (b->batch + 63) & ~63;
   TransposeArgs t2{}, t1{};
-  t2.B = b->batch; t2.Bpad = Bpad; t2.TW = lo.TW; t2.TS = lo.TS; t2.ntiles = lo.NT2; t2.pd = p2;
+  t2.B = b->batch; t2.Bpad = Bpad; t2.TW = lo.TW; t2.ntiles = lo.NT2; t2.pd = p2;
   if (lo.D > 0) {
-    t1.B = b->batch; t1.Bpad = Bpad; t1.TW = lo.TWF; t1.TS = lo.TWF; t1.ntiles = lo.NT1; t1.pd = p1;
-    t1.bits = ctx->at<uint32_t>(lo.xbm); t1.x_indptr = b->x_indptr; t1.x_indices = b->x_indices;
+    t1.B = b->batch; t1.Bpad = Bpad; t1.TW = lo.TWF; t1.ntiles = lo.NT1; t1.pd = p1;
+    t1.bits = ctx->at<uint32_t>(lo.xbm); t1.xfirst = ctx->at<int32_t>(lo.xfirst); t1.x_nnz = b->nnz;
   }
   ActiveDev ad;
-  if ((rc = forward_common(ctx, b, true, s, &ad, t1)) != SLIDE_OK) return rc;
-  t2.bits = ad.act; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
+  if ((rc = forward_common(ctx, b, true, s, &ad, t1, t2)) != SLIDE_OK) return rc;
   float* dh = ctx->at<float>(lo.dh);
   float* delta = ctx->at<float>(lo.delta);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_COMBINE, s, [&] {
     return launch_combine(ad, lo.H, ctx->last_h, ctx->at<float>(lo.z), ctx->at<float>(lo.partials), ctx->buf.W2,
                           b->y_indptr, ad.ylist, delta, dh, b->dhidden_out, ctx->at<float>(lo.loss_i),
-                          ctx->at<float>(lo.msum), t2, s); }));
+                          ctx->at<float>(lo.msum), s); }));
   ctx->last_dh = dh;
   const int64_t t = ctx->t + 1;
   AdamDev a;
@@ -469,7 +469,7 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
   if (rc != SLIDE_OK) return rc;
   hipStream_t s = (hipStream_t)hip_stream;
   ActiveDev ad;
-  if ((rc = forward_common(ctx, b, false, s, &ad, TransposeArgs{})) != SLIDE_OK) return rc;
+  if ((rc = forward_common(ctx, b, false, s, &ad, TransposeArgs{}, TransposeArgs{})) != SLIDE_OK) return rc;
   if (ctx->lo.D > 0)   // the feature bit matrix is only consumed by training: clear it again
     HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(ctx->lo.xbm), (size_t)b->batch * ctx->lo.DWpad, 0u, s));
   HIPCHK(ctx, launch_topk(ad, ctx->at<float>(ctx->lo.z), topk, d_out_ids, d_out_scores, s));

@@ -3,7 +3,6 @@
 // (paper Section 2.1: activations are computed for the retrieved neurons only; Section 3.6: the
 // first layer is fed by index/value arrays, the second by the first layer's activations).
 #include "slide_internal.h"
-#include "transpose.h"
 
 namespace slide {
 
@@ -18,7 +17,8 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
                                                        const int32_t* __restrict__ x_indices,
                                                        const float* __restrict__ x_values,
                                                        const float* __restrict__ W1, const float* __restrict__ b1,
-                                                       float* __restrict__ h, uint32_t* xbm, int TWF, Ctrl* ctrl) {
+                                                       float* __restrict__ h, uint32_t* xbm, int32_t* __restrict__ xfirst, int TWF,
+                                                       Ctrl* ctrl) {
   const int i = blockIdx.x, lane = threadIdx.x, B = gridDim.x;
   if (i == 0 && blockIdx.y == 0 && lane == 0) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }  // used after this kernel
   const int c0 = (blockIdx.y * 64 + lane) * 2;
@@ -27,7 +27,7 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
   p0 = max(p0, 0);
   p1 = min(p1, nnz_total);
   float2 acc = col_ok ? *(const float2*)(b1 + c0) : make_float2(0.f, 0.f);
-  int prev = -1;
+  int prev = -1, last = -1;                              // last: feature of the pair before this batch of 64
   uint32_t flags = 0;
   constexpr int UN = 16;
   for (int pb = p0; pb < p1; pb += 64) {
@@ -37,9 +37,15 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
     const bool bad = pb + lane < p1 && (mine < 0 || mine >= D);
     if (__any(bad)) flags |= SLIDE_FLAG_BAD_FEATURE;
     const int kk = bad ? -1 : mine;
-    if (blockIdx.y == 0 && kk >= 0) {     // feature bit matrix, tile-major: [tile][sample][TWF words]
-      const int w = kk >> 5;
-      atomicOr(&xbm[((size_t)(w / TWF) * B + i) * TWF + (w % TWF)], 1u << (kk & 31));
+    if (blockIdx.y == 0) {                // feature bit matrix, tile-major: [tile][sample][TWF words]
+      int before = __shfl_up(kk, 1);      // and, per tile, where the sample's features of the tile start
+      if (lane == 0) before = last;
+      last = __shfl(kk, 63);
+      if (kk >= 0) {
+        const int w = kk >> 5, tile = w / TWF;
+        atomicOr(&xbm[((size_t)tile * B + i) * TWF + (w % TWF)], 1u << (kk & 31));
+        if (before < 0 || (before >> 5) / TWF != tile) xfirst[(size_t)tile * B + i] = pb + lane;
+      }
     }
     const int cnt = min(64, p1 - pb);
     for (int q0 = 0; q0 < cnt; q0 += UN) {
@@ -71,9 +77,9 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
 
 hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
                             const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, uint32_t* xbm, int TWF, Ctrl* ctrl, hipStream_t s) {
+                            float* h, uint32_t* xbm, int32_t* xfirst, int TWF, Ctrl* ctrl, hipStream_t s) {
   hipLaunchKernelGGL(spmm_relu_kernel, dim3(B, ceil_div(H, 128)), dim3(64), 0, s, D, H, nnz_total, x_indptr,
-                     x_indices, x_values, W1, b1, h, xbm, TWF, ctrl);
+                     x_indices, x_values, W1, b1, h, xbm, xfirst, TWF, ctrl);
   return hipGetLastError();
 }
 
@@ -216,11 +222,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
                                                       const int32_t* __restrict__ ylist,
                                                       float* __restrict__ delta, float* __restrict__ dh,
                                                       float* __restrict__ dh_copy, float* __restrict__ loss_i,
-                                                      float* __restrict__ msum, TransposeArgs t2) {
-  // workgroups past the batch transpose the active bit matrix (needed only by the update that
-  // follows; this launch is latency-bound and leaves most of the machine idle)
-  extern __shared__ uint32_t dyn_lds[];
-  if ((int)blockIdx.x >= ad.B) { transpose_tile<false>(t2, blockIdx.x - ad.B, dyn_lds); return; }
+                                                      float* __restrict__ msum) {
   __shared__ float red[kCombineThreads / 64];
   const int i = blockIdx.x, tid = threadIdx.x;
   const int c0 = ad.chunk_ptr[i], nch = ad.chunk_ptr[i + 1] - c0;
@@ -281,16 +283,10 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
 
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
-                          float* dh, float* dh_copy, float* loss_i, float* msum, const TransposeArgs& t2,
-                          hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3(ad.B + t2.ntiles), dim3(kCombineThreads), t2.ntiles ? transpose_lds(t2.TS, t2.Bpad) : 0,
-                     s, ad, H, h, z, partials, W2, y_indptr, ylist, delta, dh, dh_copy, loss_i, msum, t2);
+                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s) {
+  hipLaunchKernelGGL(combine_kernel, dim3(ad.B), dim3(kCombineThreads), 0, s, ad, H, h, z, partials, W2, y_indptr,
+                     ylist, delta, dh, dh_copy, loss_i, msum);
   return hipGetLastError();
-}
-
-hipError_t forward_setup_attributes(size_t lds_limit) {
-  const int lim = (int)(lds_limit < 72 * 1024 ? lds_limit : 72 * 1024);
-  return hipFuncSetAttribute((const void*)combine_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
 }
 
 // ---------------------------------------------------------------------------------------------

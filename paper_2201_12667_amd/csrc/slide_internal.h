@@ -105,12 +105,13 @@ struct PairsDev {
 };
 
 struct TransposeArgs {
-  int B, Bpad, TW, TS, ntiles;   // TW words per record, TS words per tile; ntiles = 0: nothing to do
-  uint32_t* bits;                // [records][B][TW]
-  const uint32_t* rankT;         // [records][B]  (active matrix only)
+  int B, Bpad, TW, ntiles;       // TW words per record = per tile; ntiles = 0: nothing to do
+  uint32_t* bits;                // [ntiles][B][TW]
+  const uint32_t* rankT;         // [ntiles][B]  (active matrix only)
   const int32_t* as_base;        // [B]           (active matrix only)
-  const int32_t* x_indptr;       // feature matrix only
-  const int32_t* x_indices;
+  const int32_t* xfirst;         // [ntiles][B]  (feature matrix only) CSR position of the sample's first
+                                 // feature inside the tile, valid where the record is non-empty
+  int x_nnz;                     // feature matrix only: entries in the batch's CSR arrays
   PairsDev pd;
 };
 
@@ -119,20 +120,18 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const flo
                                uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
                                int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
 hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, const TransposeArgs& t1,
-                               hipStream_t s);
+                               const TransposeArgs& t2, hipStream_t s);
 
 
 // ---- output.hip -----------------------------------------------------------------------
 hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
                             const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, uint32_t* xbm, int TWF, Ctrl* ctrl, hipStream_t s);
+                            float* h, uint32_t* xbm, int32_t* xfirst, int TWF, Ctrl* ctrl, hipStream_t s);
 hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
                           float* partials, const Ctrl* ctrl, hipStream_t s);
-hipError_t forward_setup_attributes(size_t lds_limit);
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
-                          float* dh, float* dh_copy, float* loss_i, float* msum, const TransposeArgs& t2,
-                          hipStream_t s);
+                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s);
 hipError_t launch_topk(const ActiveDev& ad, const float* z, int topk, int32_t* out_ids,
                        float* out_scores, hipStream_t s);
 hipError_t launch_dense_topk(int B, int64_t N, int H, const float* h, const float* W2, const float* b2,

@@ -6,163 +6,216 @@
 
 namespace slide {
 
-// One workgroup per call and tile of TS bitmap words, all samples: the tile's touched rows, in row order,
-// each with the ascending list of the samples that touch it.  Row slots of tile t are
-// [t*TS*32, t*TS*32 + tile_nu[t]).  FEAT = false: the active bit matrix; a pair's coefficient
-// index is its slot in the sample-major arrays, and the tile's first pair position is the sum over
-// the samples of their in-sample ranks at the tile start (no atomics: the layout is a pure function
-// of the bit matrix).  FEAT = true: the feature bit matrix of the batch; the coefficient index is the
-// position in the CSR value array (the features of a sample are ascending, so it is the position of
-// the tile's first feature plus the rank inside the tile), pair space is handed out per workgroup, and the matrix is cleared
-// behind the read so that it is all-zero again for the next batch.
-template <bool FEAT>
-__device__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* lds) {
-  // TW = words per record of the bit matrix (the unit ranks are kept for), TS = words handled here
-  const int B = ta.B, Bpad = ta.Bpad, TW = ta.TW, TS = ta.TS;
-  const int per = TW / TS, rec = tileno / per, w0 = (tileno - rec * per) * TS;
-  uint32_t* bits = ta.bits;
-  const uint32_t* __restrict__ rankT = ta.rankT;
-  const int32_t* __restrict__ as_base = ta.as_base;
-  const int32_t* __restrict__ x_indptr = ta.x_indptr;
-  const int32_t* __restrict__ x_indices = ta.x_indices;
+// One workgroup per call and tile (TW bitmap words = TW*32 rows, all samples): the tile's touched
+// rows, in row order, each with the ascending list of the samples that touch it.  Row slots of tile
+// t are [t*TW*32, t*TW*32 + tile_nu[t]).
+//   FEAT = false: the active bit matrix; a pair's coefficient index is its slot in the sample-major
+//     arrays, and the tile's first pair position is the sum over the samples of their in-sample
+//     ranks at the tile start (the layout is a pure function of the bit matrix).
+//   FEAT = true: the feature bit matrix of the batch; the coefficient index is the position in the
+//     CSR value array (the features of a sample are ascending, so it is the position of the
+//     sample's first feature inside the tile, recorded by the hidden-layer kernel, plus the rank
+//     inside the tile); pair space is handed out per workgroup, and the matrix is cleared behind
+//     the read so that it is all-zero again for the next batch.
+// WT = min(TW, 8) words of a record per thread, TW/WT adjacent threads per sample.  Pass 1 builds
+// the transposed tile in LDS: one bit per (row, sample), set with LDS atomics from the (few)
+// non-zero bits of the records.  Lane = row then gives every row's pair count, the touched rows,
+// every row's position in the pair space and, inside it, where each group of 64 samples starts.
+// Pass 2 reads the records again (from cache); for each of its bits a thread finds the pair's place
+// in the row's list as the number of lower samples in the row's LDS mask, so every pair is written
+// straight to its final position -- ascending samples per row, no sort -- and a store instruction
+// carries one pair for every lane that still has a bit in its word, not one row.
+template <bool FEAT, int TW>
+__device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int tileno, uint32_t* lds) {
+  constexpr int ROWS = TW * 32;
+  constexpr int WT = TW < 8 ? TW : 8;                    // words per thread
+  constexpr int SUB = TW / WT;                           // threads per sample (1, 2 or 4)
+  const int B = ta.B, Bpad = ta.Bpad;
   const PairsDev& pd = ta.pd;
-  const int nwaves = blockDim.x >> 6;
-  const int groups = Bpad >> 6;                          // 64-sample groups
-  uint32_t* tile = lds;                                  // [TS][Bpad]
-  uint32_t* sb = tile + (size_t)TS * Bpad;                // [Bpad] slot of the sample's first pair in this tile
-  uint32_t* wug = sb + Bpad;                             // [TS][groups] union of the word over a sample group
-  uint32_t* wu = wug + (size_t)TS * groups;              // [TS] union over all samples
-  uint32_t* wnp = wu + TS;                               // [TS] pairs per word, then exclusive prefix
-  uint32_t* wou = wnp + TS;                              // [TS] rows before the word
-  uint32_t* blk = wou + TS;                              // [2] pair base of the tile, sum of ranks
-  uint16_t* rk = (uint16_t*)(blk + 2);                   // [TS][Bpad] rank inside this tile before the word
-  const int tid = threadIdx.x, lane = tid & 63;
-  for (int q = tid; q < TS * groups + 3 * TS + 2; q += blockDim.x) wug[q] = 0;   // wug, wu, wnp, wou, blk
+  const int groups = Bpad >> 6, GW = Bpad >> 5;
+  uint32_t* T = lds;                                     // [GW][ROWS] bit (i & 31) of word i >> 5: sample i holds the row
+  uint32_t* rowoff = T + (size_t)GW * ROWS;              // [ROWS] pairs of the word's lower rows
+  uint32_t* wu = rowoff + ROWS;                          // [TW] touched rows of the word (bit mask)
+  uint32_t* wnp = wu + TW;                               // [TW] pairs of the word, then pairs before it
+  uint32_t* wou = wnp + TW;                              // [TW] rows before the word
+  uint32_t* blk = wou + TW;                              // [2] pair base of the tile, sum of ranks
+  uint16_t* rowcnt = (uint16_t*)(blk + 2);               // [ROWS] pairs of the row
+  uint16_t* rowgrp = rowcnt + ROWS;                      // [groups][ROWS] pairs of the row in lower sample groups
+  const int tid = threadIdx.x, lane = tid & 63, b31 = tid & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t below = (1u << b31) - 1u;
+  const int nwork = Bpad * SUB;
+
+  for (int q = tid; q < GW * ROWS; q += blockDim.x) T[q] = 0;
+  if (tid == 0) blk[1] = 0;
   __syncthreads();
-  uint32_t ranksum = 0;
-  for (int i = tid; i < Bpad; i += blockDim.x) {
-    uint32_t* src = bits + ((size_t)rec * B + i) * TW;
-    // the whole record in a few vector loads (a scalar load per word would wait for each in turn)
-    uint32_t x[32];
-    if (TW >= 4) {
+
+  // The loaded words (and `extra`, a value loaded beside them) are forced to arrive before the
+  // call returns: left to the first use inside the branching word loops, the compiler's wait would
+  // be a wait for every outstanding memory operation, the loop's own stores included.
+  auto load_words = [&](int i, int sub, uint32_t* x, bool clear, uint32_t& extra) {
+    uint32_t* src = ta.bits + ((size_t)tileno * B + i) * TW + sub * WT;
+    uint32_t any = 0;
+    if (WT >= 4) {
 #pragma unroll
-      for (int v = 0; v < 8; ++v) {
-        const uint4 q = (i < B && v * 4 < TW) ? ((const uint4*)src)[v] : make_uint4(0u, 0u, 0u, 0u);
+      for (int v = 0; v < WT / 4; ++v) {
+        const uint4 q = i < B ? ((const uint4*)src)[v] : make_uint4(0u, 0u, 0u, 0u);
         x[4 * v] = q.x; x[4 * v + 1] = q.y; x[4 * v + 2] = q.z; x[4 * v + 3] = q.w;
+        any |= q.x | q.y | q.z | q.w;
+      }
+      asm volatile("" : "+v"(any), "+v"(extra));
+      if (clear && any) {
+#pragma unroll
+        for (int v = 0; v < WT / 4; ++v) ((uint4*)src)[v] = make_uint4(0u, 0u, 0u, 0u);
       }
     } else {
 #pragma unroll
-      for (int w = 0; w < 32; ++w) x[w] = (i < B && w < TW) ? src[w] : 0u;
-    }
-    uint32_t before = 0, run = 0, any = 0;             // before: active neurons of the record before this tile
+      for (int w = 0; w < WT; ++w) { x[w] = i < B ? src[w] : 0u; any |= x[w]; }
+      asm volatile("" : "+v"(any), "+v"(extra));
+      if (clear && any) {
 #pragma unroll
-    for (int w = 0; w < 32; ++w) {
-      if (w < w0) {
-        before += __popc(x[w]);
-      } else if (w < w0 + TS) {
-        tile[(w - w0) * Bpad + i] = x[w];
-        rk[(w - w0) * Bpad + i] = (uint16_t)run;
-        // union and pair count of the word over this wave's 64 samples: LDS atomics from the few
-        // lanes that hold anything, or one register reduction when many do
-        const int holders = __popcll(__ballot(x[w] != 0u));
-        if (holders > 8) {
-          const uint32_t o = wave_or(x[w]), c = wave_sum((uint32_t)__popc(x[w]));
-          if (lane == 0) { wug[(w - w0) * groups + (i >> 6)] = o; atomicAdd(&wnp[w - w0], c); }
-        } else if (x[w]) {
-          atomicOr(&wug[(w - w0) * groups + (i >> 6)], x[w]);
-          atomicAdd(&wnp[w - w0], (uint32_t)__popc(x[w]));
-        }
-        run += __popc(x[w]);
-        any |= x[w];
+        for (int w = 0; w < WT; ++w) src[w] = 0u;
       }
     }
-    if (FEAT && any)                                   // leave the feature matrix all-zero behind
-      for (int w = 0; w < TS; ++w) src[w0 + w] = 0u;
+  };
+
+  // ---- pass 1: transposed tile -------------------------------------------------------------------
+  for (int t = tid; t < nwork; t += blockDim.x) {
+    const int i = t / SUB, sub = t % SUB;
+    uint32_t x[WT];
+    uint32_t rank0 = (!FEAT && sub == 0 && i < B) ? ta.rankT[(size_t)tileno * B + i] : 0u;
+    load_words(i, sub, x, false, rank0);
+    uint32_t* tc = T + (size_t)(i >> 5) * ROWS + sub * WT * 32;
+    const uint32_t ibit = 1u << (i & 31);
+#pragma unroll
+    for (int w = 0; w < WT; ++w) {
+      uint32_t y = x[w];
+      while (y) {
+        const int b = __ffs(y) - 1;
+        y &= y - 1u;
+        atomicOr(&tc[w * 32 + b], ibit);
+      }
+    }
     if (!FEAT) {
-      const uint32_t r0 = i < B ? rankT[(size_t)rec * B + i] + before : 0u;
-      sb[i] = i < B ? (uint32_t)as_base[i] + r0 : 0u;
-      ranksum += r0;
-    } else {
-      // position in the CSR arrays of the sample's first feature inside this tile (one search per
-      // sample and tile, all samples at once; indices are ascending)
-      uint32_t a = 0;
-      if (any) {
-        const int first = (rec * TW + w0) * 32;
-        int lo_ = x_indptr[i], hi_ = x_indptr[i + 1];
-        while (lo_ < hi_) { const int mid = (lo_ + hi_) >> 1; if (x_indices[mid] < first) lo_ = mid + 1; else hi_ = mid; }
-        a = (uint32_t)lo_;
-      }
-      sb[i] = a;
+      const uint32_t s = wave_sum(rank0);
+      if (lane == 0 && s) atomicAdd(&blk[1], s);         // integer sum: order does not matter
     }
   }
-  if (!FEAT && ranksum) atomicAdd(&blk[1], ranksum);     // integer sum: order does not matter
   __syncthreads();
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  if (wave == 0) {                                       // per word: union, rows and pairs before it
-    uint32_t u = 0;
-    if (lane < TS) for (int k = 0; k < groups; ++k) u |= wug[lane * groups + k];
-    const uint32_t c = __popc(u), np = lane < TS ? wnp[lane] : 0u;
+
+  // ---- rows: pairs per row and per sample group, prefix inside the word (lane = bit of the word) ---
+  for (int r0 = 0; r0 < ROWS; r0 += blockDim.x) {
+    const int r = r0 + tid;
+    const bool ok = r < ROWS;
+    uint32_t c = 0;
+    if (ok) {
+      for (int g = 0; g < groups; ++g) {
+        rowgrp[(size_t)g * ROWS + r] = (uint16_t)c;
+        c += __popc(T[(size_t)(2 * g) * ROWS + r]) + __popc(T[(size_t)(2 * g + 1) * ROWS + r]);
+      }
+    }
+    const unsigned long long touched = __ballot(c != 0u);
+    const uint32_t incl = half_incl_scan_add(c);
+    if (ok) {
+      rowoff[r] = incl - c;
+      rowcnt[r] = (uint16_t)c;
+      if (b31 == 31) { wu[r >> 5] = (uint32_t)(touched >> (lane & 32)); wnp[r >> 5] = incl; }
+    }
+  }
+  __syncthreads();
+
+  // ---- rows and pairs before each word -----------------------------------------------------------
+  uint32_t nu_tile = 0;
+  if (wave == 0) {
+    const uint32_t u = lane < TW ? wu[lane] : 0u, np = lane < TW ? wnp[lane] : 0u;
+    const uint32_t c = __popc(u);
     const uint32_t cin = wave_incl_scan_add(c), pin = wave_incl_scan_add(np);
-    if (lane < TS) { wu[lane] = u; wou[lane] = cin - c; wnp[lane] = pin - np; }
+    if (lane < TW) { wou[lane] = cin - c; wnp[lane] = pin - np; }
     if (lane == 63) {
+      nu_tile = cin;
       pd.tile_nu[tileno] = (int32_t)cin;
-      if (cin > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, cin);   // few workgroups ever get here
       blk[0] = FEAT ? (pin ? atomicAdd(pd.pcount, pin) : 0u) : blk[1];
     }
   }
   __syncthreads();
-  const uint32_t slot0 = (uint32_t)tileno * (uint32_t)(TS * 32);
-  constexpr int KG = 4;                                  // sample groups held in registers
-  for (int w = wave; w < TS; w += nwaves) {
-    uint32_t u = __builtin_amdgcn_readfirstlane(wu[w]);
-    if (u == 0) continue;
-    uint32_t us = slot0 + __builtin_amdgcn_readfirstlane(wou[w]);
-    uint32_t po = __builtin_amdgcn_readfirstlane(blk[0] + wnp[w]);
-    uint32_t xr[KG], sr[KG], ug[KG];                     // ug: union of the word over the 64 samples
-#pragma unroll
-    for (int k = 0; k < KG; ++k) {
-      const int i = k * 64 + lane;
-      xr[k] = k < groups ? tile[w * Bpad + i] : 0u;
-      sr[k] = k < groups ? sb[i] + rk[w * Bpad + i] : 0u;
-      ug[k] = k < groups ? __builtin_amdgcn_readfirstlane(wug[w * groups + k]) : 0u;
-    }
-    while (u) {
-      const int b = __ffs(u) - 1;
-      u &= u - 1;
-      const int row = (rec * TW + w0 + w) * 32 + b;
-      uint32_t cntj = 0;
-      auto take = [&](int k, uint32_t x, uint32_t sbase) {
-        const int i = k * 64 + lane;
-        const bool has = (x >> b) & 1u;
-        const unsigned long long mk = __ballot(has);
-        if (has) {
-          const uint32_t p = po + cntj + __popcll(mk & ((1ull << lane) - 1ull));
-          pd.pairs[p] = make_int2(i, (int)(sbase + __popc(x & ((1u << b) - 1u))));
-        }
-        cntj += (uint32_t)__popcll(mk);
-      };
-#pragma unroll
-      for (int k = 0; k < KG; ++k)
-        if ((ug[k] >> b) & 1u) take(k, xr[k], sr[k]);     // skip sample groups without this row
-      for (int k = KG; k < groups; ++k) {
-        const int i = k * 64 + lane;
-        take(k, tile[w * Bpad + i], sb[i] + rk[w * Bpad + i]);
+  const uint32_t blk0 = blk[0];
+  const uint32_t slot0 = (uint32_t)tileno * (uint32_t)ROWS;
+
+  // ---- row headers ---------------------------------------------------------------------------------
+  for (int r = tid; r < ROWS; r += blockDim.x) {
+    const uint32_t c = rowcnt[r];
+    if (c) {
+      const int w = r >> 5;
+      const uint32_t us = slot0 + wou[w] + __popc(wu[w] & below);
+      pd.umeta[us] = make_int4(tileno * ROWS + r, (int)(blk0 + wnp[w] + rowoff[r]), (int)c, 0);
+      if ((int)c > kLongRow) {
+        const uint32_t l = atomicAdd(pd.nlong, 1u);
+        if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
       }
-      if (lane == 0) {
-        pd.umeta[us] = make_int4(row, (int)po, (int)cntj, 0);
-        if ((int)cntj > kLongRow) {
-          const uint32_t l = atomicAdd(pd.nlong, 1u);
-          if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
-        }
-      }
-      ++us;
-      po += cntj;
     }
+  }
+
+  // ---- pass 2: emit ----------------------------------------------------------------------------------
+  const uint32_t cmax = FEAT ? (uint32_t)(ta.x_nnz > 0 ? ta.x_nnz - 1 : 0) : 0xffffffffu;
+  for (int t = tid; t < nwork; t += blockDim.x) {
+    const int i = t / SUB, sub = t % SUB;
+    uint32_t x[WT];
+    uint32_t cbase = 0;                                  // coefficient index of the sample's first pair here
+    if (i < B) cbase = FEAT ? (uint32_t)ta.xfirst[(size_t)tileno * B + i]
+                            : (uint32_t)ta.as_base[i] + ta.rankT[(size_t)tileno * B + i];
+    load_words(i, sub, x, FEAT, cbase);
+    uint32_t mine = 0;
+#pragma unroll
+    for (int w = 0; w < WT; ++w) mine += __popc(x[w]);
+    uint32_t run = 0;                                    // bits of the sample in the words of its lower threads
+    if (SUB > 1) {
+      const uint32_t p0 = dpp_u32<0x00>(0u, mine), p1 = dpp_u32<0x55>(0u, mine), p2 = dpp_u32<0xAA>(0u, mine);
+      run = (sub > 0 ? p0 : 0u) + (sub > 1 ? p1 : 0u) + (sub > 2 ? p2 : 0u);
+      if (SUB == 2) run = (sub & 1) ? ((lane & 2) ? p2 : p0) : 0u;
+    }
+    if (!mine) continue;
+    const int g = i >> 6;
+    const uint32_t lo_mask = (i & 32) ? 0xffffffffu : ((1u << (i & 31)) - 1u);
+    const uint32_t hi_mask = (i & 32) ? ((1u << (i & 31)) - 1u) : 0u;
+    const uint32_t* t_lo = T + (size_t)(2 * g) * ROWS;
+    const uint32_t* t_hi = t_lo + ROWS;
+    const uint16_t* grp = rowgrp + (size_t)g * ROWS;
+#pragma unroll
+    for (int w = 0; w < WT; ++w) {
+      uint32_t y = x[w];
+      if (!y) continue;
+      const int W = sub * WT + w;
+      const uint32_t wbase = blk0 + wnp[W];
+      while (y) {
+        const int b = __ffs(y) - 1;
+        y &= y - 1u;
+        const int row = W * 32 + b;
+        const uint32_t place = wbase + rowoff[row] + grp[row] + __popc(t_lo[row] & lo_mask) + __popc(t_hi[row] & hi_mask);
+        const uint32_t ci = cbase + run + __popc(x[w] & ((1u << b) - 1u));
+        pd.pairs[place] = make_int2(i, (int)min(ci, cmax));
+      }
+      run += __popc(x[w]);
+    }
+  }
+  // few workgroups ever raise the maximum; the read is off the critical path here
+  if (wave == 0 && lane == 63 && nu_tile > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, nu_tile);
+}
+
+template <bool FEAT>
+__device__ __forceinline__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* lds) {
+  switch (ta.TW) {
+    case 32: transpose_tile_t<FEAT, 32>(ta, tileno, lds); break;
+    case 16: transpose_tile_t<FEAT, 16>(ta, tileno, lds); break;
+    case 8: transpose_tile_t<FEAT, 8>(ta, tileno, lds); break;
+    case 4: transpose_tile_t<FEAT, 4>(ta, tileno, lds); break;
+    case 2: transpose_tile_t<FEAT, 2>(ta, tileno, lds); break;
+    default: transpose_tile_t<FEAT, 1>(ta, tileno, lds); break;
   }
 }
 
-inline size_t transpose_lds(int TS, int Bpad) {
-  return (size_t)TS * Bpad * 6 + (size_t)Bpad * 4 + ((size_t)TS * (Bpad >> 6) + 3 * TS + 2) * 4;
+inline size_t transpose_lds(int TW, int Bpad) {
+  const size_t rows = (size_t)TW * 32, GW = (size_t)Bpad >> 5, groups = (size_t)Bpad >> 6;
+  return (rows * GW + rows + (size_t)TW * 3 + 2) * 4 + rows * 2 + groups * rows * 2;
 }
 
 }  // namespace slide
