@@ -169,15 +169,13 @@ int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out);
 /* Launches of a step, in order, for slide_profile. */
 enum slide_stage {
   SLIDE_STAGE_HIDDEN = 0,   /* sparse-input hidden layer                                              */
-  SLIDE_STAGE_LOOKUP = 1,   /* hash codes, bucket reads, union, sorted id lists                       */
-  SLIDE_STAGE_SCAN = 2,     /* forward work items over the samples; the same launch turns the feature  */
-                            /* bit matrix of the batch into per-row sample lists                       */
-  SLIDE_STAGE_FORWARD = 3,  /* logits + running soft-max over the gathered rows                        */
-  SLIDE_STAGE_COMBINE = 4,  /* normaliser, errors, loss, hidden gradient; the same launch turns the    */
-                            /* active bit matrix into per-row sample lists                             */
-  SLIDE_STAGE_UPDATE = 5,   /* gradient + Adam on the touched rows of W2, b2, W1; b1; loss mean        */
-  SLIDE_STAGE_REBUILD = 6,  /* table build / rebuild (all its kernels)                                */
-  SLIDE_NUM_STAGES = 7
+  SLIDE_STAGE_LOOKUP = 1,   /* hash codes, bucket reads, union, sorted id lists, forward work items   */
+  SLIDE_STAGE_FORWARD = 2,  /* logits + running soft-max over the gathered rows; the same launch turns */
+                            /* the feature and the active bit matrix into per-row sample lists         */
+  SLIDE_STAGE_COMBINE = 3,  /* normaliser, errors, loss, hidden gradient                               */
+  SLIDE_STAGE_UPDATE = 4,   /* gradient + Adam on the touched rows of W2, b2, W1; b1; loss mean        */
+  SLIDE_STAGE_REBUILD = 5,  /* table build / rebuild (all its kernels)                                */
+  SLIDE_NUM_STAGES = 6
 };
 
 /* Measurement aid: for every stage whose bit (1 << slide_stage) is set in stage_mask, later calls

@@ -3,22 +3,13 @@
 //
 //  lookup_union : one workgroup per sample.  Reads one bucket per table, sets one bit per candidate
 //                 and per label in an LDS bitmap over the neuron ids (deduplication and sorting
-//                 are free: the bitmap is swept in id order), writes the sample's row of the
-//                 [B][words] active bit matrix and per-tile population counts.
-//  scan_samples : exclusive scans over the B samples (offsets of the compact id lists, forward
-//                 work items).
-//  emit         : compact ascending id list per sample + label flags.
-//  transpose    : the bit matrix read tile-by-tile across all samples gives, for every touched row,
-//                 the ascending list of samples that touch it (wave ballots), i.e. the row-major
-//                 pair lists of the gradient/Adam kernel -- no sort, no atomics on data.
+//                 are free: the bitmap is swept in id order), writes per-tile population counts
+//                 (their prefix splits the sample's id list into one segment per tile of rows).
+//                 It also emits the compact ascending id list per sample + label flags and hands
+//                 the sample its forward work items (chunks of kChunk active neurons).
 #include "slide_internal.h"
-#include "transpose.h"
-
-#include <algorithm>
 
 namespace slide {
-
-constexpr int kScanThreads = 1024;
 
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
   const int lane = threadIdx.x & 63;
@@ -192,7 +183,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       const uint32_t word = w < sw ? bm[w] : 0u;
       uint32_t c = __popc(word);
       my_cnt += c;
-      if (w < sw) ad.act[act_index(ad, i, seg0 + w)] = word;
+      if (w < sw && segw < ad.NWpad) ad.act[act_index(ad, i, seg0 + w)] = word;   // spill: re-read by the id sweep
       for (int d = 1; d < ad.TW; d <<= 1) c += __shfl_xor(c, d);
       if (w < sw && (lane & (ad.TW - 1)) == 0) ad.rankS[(size_t)i * ad.NT + (seg0 + w) / ad.TW] = c;
     }
@@ -202,7 +193,15 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   if (lane == 0) atomicAdd(&sm[18], my_cnt);
   __syncthreads();
   const int n = (int)sm[18];
-  if (tid == 0) { ad.cnt[i] = n; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; ad.as_base[i] = base_i; }
+  const uint32_t nch = ((uint32_t)n + kChunk - 1) / kChunk;
+  uint32_t chunk0 = 0;
+  if (tid == 0) {
+    ad.cnt[i] = n; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; ad.as_base[i] = base_i;
+    // forward work items of this sample: a block of consecutive item numbers (which block does not
+    // matter: the partial results of a sample are merged in the sample's own chunk order)
+    chunk0 = nch ? atomicAdd(&ctrl->chunk_alloc[ad.par], nch) : 0u;   // (the answer is not needed before the end)
+    if (i == 0) ctrl->chunk_alloc[ad.par ^ 1] = 0;       // the previous call's counter: clear it for the next call
+  }
 
   // per-tile counts -> exclusive prefix inside the sample (rank of the tile's first active neuron)
   uint32_t* rk = ad.rankS + (size_t)i * ad.NT;
@@ -216,6 +215,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
     carry += total;
     __syncthreads();
   }
+  if (tid == 0) ad.rankT[(size_t)ad.NT * ad.B + i] = carry;   // closes the last tile's segment
   // compact ascending id list: sweep the bitmap (still in LDS if it fitted in one segment)
   const bool in_lds = segw >= ad.NWpad;
   for (int wb = 0; wb < ad.NWpad; wb += nthr) {
@@ -238,7 +238,9 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       }
     }
   }
+  if (tid == 0) { sm[19] = chunk0; ad.chunk_ptr[i] = (int32_t)chunk0; }
   __syncthreads();
+  for (uint32_t k = tid; k < nch; k += nthr) ad.chunk_sample[sm[19] + k] = i;
   // label flags, and for every label entry its slot (-1 for invalid or repeated entries)
   for (int q = tid; q < nlab; q += nthr) {
     const int y = y_indices[y0 + q];
@@ -256,52 +258,6 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   }
 }
 
-// Forward work items (chunks of kChunk active neurons) over the samples and totals for the statistics.
-// Workgroup 0 of the launch does this; the other workgroups transpose the two bit matrices of the
-// batch (active sets, then features): they need nothing that this launch computes, and the launch
-// is otherwise a single workgroup.
-__global__ __launch_bounds__(kScanThreads) void scan_samples_kernel(ActiveDev ad, const int32_t* __restrict__ ncand,
-                                                                    Ctrl* ctrl, TransposeArgs t1, TransposeArgs t2) {
-  extern __shared__ uint32_t dyn_lds[];
-  if (blockIdx.x > 0) {
-    const int k = blockIdx.x - 1;
-    if (k < t2.ntiles) transpose_tile<false>(t2, k, dyn_lds);
-    else transpose_tile<true>(t1, k - t2.ntiles, dyn_lds);
-    return;
-  }
-  __shared__ uint32_t sm[20];
-  __shared__ unsigned long long cs[16], as[16];   // (at most 16 waves)
-  uint32_t carry_c = 0;
-  unsigned long long cand = 0, pairs = 0;
-  for (int base = 0; base < ad.B; base += blockDim.x) {
-    const int i = base + threadIdx.x;
-    const uint32_t n = i < ad.B ? (uint32_t)ad.cnt[i] : 0u;
-    const uint32_t ch = (n + kChunk - 1) / kChunk;
-    uint32_t tc;
-    const uint32_t ec = block_excl_scan(ch, sm, tc);
-    if (i < ad.B) {
-      ad.chunk_ptr[i] = (int32_t)(carry_c + ec);
-      for (uint32_t k = 0; k < ch; ++k) ad.chunk_sample[carry_c + ec + k] = i;
-      cand += (unsigned long long)ncand[i];
-      pairs += n;
-    }
-    carry_c += tc;
-    __syncthreads();
-  }
-  for (int d = 32; d > 0; d >>= 1) { cand += __shfl_xor(cand, d); pairs += __shfl_xor(pairs, d); }
-  if ((threadIdx.x & 63) == 0) { cs[threadIdx.x >> 6] = cand; as[threadIdx.x >> 6] = pairs; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned long long c = 0, a = 0;
-    for (unsigned w = 0; w < blockDim.x / 64; ++w) { c += cs[w]; a += as[w]; }
-    ad.chunk_ptr[ad.B] = (int32_t)carry_c;
-    ctrl->total_pairs = (uint32_t)a;
-    ctrl->total_chunks = carry_c;
-    ctrl->candidates_lo = (uint32_t)c;
-    ctrl->candidates_hi = (uint32_t)(c >> 32);
-  }
-}
-
 hipError_t active_setup_attributes(size_t* lds_limit_out) {
   int dev = 0, lim = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -310,9 +266,6 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
   if (e != hipSuccess) return e;
   if (lim > 160 * 1024) lim = 160 * 1024;
   e = hipFuncSetAttribute((const void*)lookup_union_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)scan_samples_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                          lim < 72 * 1024 ? lim : 72 * 1024);
   if (e != hipSuccess) return e;
   *lds_limit_out = (size_t)lim;
   return hipSuccess;
@@ -328,16 +281,6 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const flo
   const size_t bytes = (size_t)segw * 4 + fixed;
   hipLaunchKernelGGL(lookup_union_kernel, dim3(ad.B), dim3(1024), bytes, s, ad, hd, h, td.off, td.ids, td.nb,
                      codes, y_indptr, y_indices, include_labels, ncand, ctrl, segw);
-  return hipGetLastError();
-}
-
-hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, const TransposeArgs& t1,
-                               const TransposeArgs& t2, hipStream_t s) {
-  size_t lds = 0;
-  if (t1.ntiles) lds = transpose_lds(t1.TW, t1.Bpad);
-  if (t2.ntiles) lds = std::max(lds, transpose_lds(t2.TW, t2.Bpad));
-  hipLaunchKernelGGL(scan_samples_kernel, dim3(1 + t1.ntiles + t2.ntiles), dim3(kScanThreads), lds, s, ad, ncand,
-                     ctrl, t1, t2);
   return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ struct Layout {
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, xbm, xfirst, h, dh, codes, act, rankS, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, xse, h, dh, codes, act, rankS, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -109,14 +109,13 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   const size_t B = lo->Bmax, H = lo->H, A = (size_t)lo->Amax;
   lo->ctrl = take(sizeof(Ctrl));
   lo->hashw = take(lo->hash_words * 4);
-  lo->xbm = take(lo->D ? B * lo->DWpad * 4 : 0);
-  lo->xfirst = take(lo->D ? B * lo->NT1 * 4 : 0);
+  lo->xse = take(lo->D ? B * lo->NT1 * 8 : 0);
   lo->h = take(lo->D ? B * H * 4 : 0);
   lo->dh = take(B * H * 4);
   lo->codes = take(B * lo->L * 4);
   lo->act = take(B * lo->NWpad * 4);
   lo->rankS = take(B * lo->NT * 4);
-  lo->rankT = take(B * lo->NT * 4);
+  lo->rankT = take(B * (lo->NT + 1) * 4);
   lo->cnt = take(B * 4); lo->ny = take(B * 4); lo->ncand = take(B * 4);
   lo->as_base = take(B * 4); lo->chunk_ptr = take((B + 1) * 4);
   lo->tile_nu2 = take((size_t)lo->NT2 * 4); lo->tile_nu1 = take((size_t)lo->NT1 * 4 + 4);
@@ -153,6 +152,7 @@ struct slide_ctx {
   int64_t t = 0, r = 0;
   bool built = false;
   int last_B = 0;
+  uint64_t calls = 0;            // forward passes launched (selects the set of per-call device accumulators)
   const float* last_h = nullptr;
   float* last_dh = nullptr;
   std::string err;
@@ -238,7 +238,7 @@ int check_batch(slide_ctx* ctx, const slide_batch* b, bool need_labels) {
 }
 
 // Hidden activations, hash codes + active sets, and the logits pass; t1 and t2 (training only) are
-// the transpositions of the feature and the active bit matrix that ride in the scan launch (the
+// the transpositions of the feature and the active bit matrix that ride in the logits launch (the
 // bit-matrix pointers of t2 are filled in here).
 int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out,
                    const TransposeArgs& t1, TransposeArgs t2) {
@@ -249,7 +249,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
     float* hw = ctx->at<float>(lo.h);
     HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] {
       return launch_spmm_relu(B, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
-                              ctx->buf.b1, hw, ctx->at<uint32_t>(lo.xbm), ctx->at<int32_t>(lo.xfirst), lo.TWF, ctx->ctrl(), s); }));
+                              ctx->buf.b1, hw, ctx->at<int2>(lo.xse), lo.TWF * 32, ctx->ctrl(), s); }));
     h = hw;
   }
   ctx->last_h = h;
@@ -257,15 +257,15 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   uint32_t* codes = ctx->at<uint32_t>(lo.codes);
   ActiveDev ad = make_active(ctx, B);
   ad.num_labels = with_labels ? b->num_labels : 0;
+  ad.par = (int)(ctx->calls++ & 1);
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
     return launch_lookup_union(ad, ctx->hd, h, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0,
                                ncand, ctx->ctrl(), ctx->lds_limit, s); }));
-  t2.bits = ad.act; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_SCAN, s, [&] { return launch_scan_samples(ad, ncand, ctx->ctrl(), t1, t2, s); }));
+  t2.ids = ad.as_ids; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
-                          ctx->at<float>(lo.partials), ctx->ctrl(), s); }));
+                          ctx->at<float>(lo.partials), ctx->ctrl(), t1, t2, s); }));
   *ad_out = ad;
   return SLIDE_OK;
 }
@@ -358,11 +358,12 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   ctx->prio_a = hp->prio_a; ctx->prio_b = hp->prio_b;
   const char* what = "hipMemset(ctrl)";
   hipError_t e = hipMemset(ctx->ws() + lo.ctrl, 0, sizeof(Ctrl));
-  if (e == hipSuccess && lo.D) { what = "hipMemset(feature bits)"; e = hipMemset(ctx->ws() + lo.xbm, 0, (size_t)lo.Bmax * lo.DWpad * 4); }
+  if (e == hipSuccess && lo.D) { what = "hipMemset(feature segments)"; e = hipMemset(ctx->ws() + lo.xse, 0, (size_t)lo.Bmax * lo.NT1 * 8); }
   if (e == hipSuccess && !words.empty()) { what = "hipMemcpy(hash parameters)"; e = hipMemcpy(ctx->ws() + lo.hashw, words.data(), words.size() * 4, hipMemcpyHostToDevice); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(hash kernels)"; e = hash_setup_attributes(H); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(table kernels)"; e = tables_setup_attributes(); }
+  if (e == hipSuccess) { what = "hipFuncSetAttribute(forward kernels)"; e = forward_setup_attributes(ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipDeviceSynchronize"; e = hipDeviceSynchronize(); }
   if (e != hipSuccess) {
     set_err(nullptr, SLIDE_EHIP, "slide_init: %s failed: %s", what, hipGetErrorString(e));
@@ -419,7 +420,7 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   t2.B = b->batch; t2.Bpad = Bpad; t2.TW = lo.TW; t2.ntiles = lo.NT2; t2.pd = p2;
   if (lo.D > 0) {
     t1.B = b->batch; t1.Bpad = Bpad; t1.TW = lo.TWF; t1.ntiles = lo.NT1; t1.pd = p1;
-    t1.bits = ctx->at<uint32_t>(lo.xbm); t1.xfirst = ctx->at<int32_t>(lo.xfirst); t1.x_nnz = b->nnz;
+    t1.ids = b->x_indices; t1.xse = ctx->at<int2>(lo.xse); t1.x_nnz = b->nnz;
   }
   ActiveDev ad;
   if ((rc = forward_common(ctx, b, true, s, &ad, t1, t2)) != SLIDE_OK) return rc;
@@ -443,7 +444,7 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   out.bias = ctx->buf.b2; out.mbias = ctx->buf.mb2; out.vbias = ctx->buf.vb2;
   FinishArgs fin{};
   fin.B = b->batch; fin.loss_i = ctx->at<float>(lo.loss_i); fin.d_loss = d_loss; fin.dh = dh; fin.ctrl = ctx->ctrl();
-  fin.tile_nu2 = p2.tile_nu; fin.ntiles2 = p2.ntiles;
+  fin.tile_nu2 = p2.tile_nu; fin.ntiles2 = p2.ntiles; fin.cnt = ad.cnt; fin.ncand = ctx->at<int32_t>(lo.ncand);
   if (lo.D > 0) {
     in.pd = p1; in.coef = b->x_values; in.V = dh;
     in.W = ctx->buf.W1; in.M = ctx->buf.mW1; in.Vv = ctx->buf.vW1;
@@ -470,8 +471,8 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
   hipStream_t s = (hipStream_t)hip_stream;
   ActiveDev ad;
   if ((rc = forward_common(ctx, b, false, s, &ad, TransposeArgs{}, TransposeArgs{})) != SLIDE_OK) return rc;
-  if (ctx->lo.D > 0)   // the feature bit matrix is only consumed by training: clear it again
-    HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(ctx->lo.xbm), (size_t)b->batch * ctx->lo.DWpad, 0u, s));
+  if (ctx->lo.D > 0)   // the feature segments are only consumed by training: clear them again
+    HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(ctx->lo.xse), (size_t)b->batch * ctx->lo.NT1 * 2, 0u, s));
   HIPCHK(ctx, launch_topk(ad, ctx->at<float>(ctx->lo.z), topk, d_out_ids, d_out_scores, s));
   ctx->last_dh = nullptr;
   return SLIDE_OK;

@@ -3,6 +3,9 @@
 // (paper Section 2.1: activations are computed for the retrieved neurons only; Section 3.6: the
 // first layer is fed by index/value arrays, the second by the first layer's activations).
 #include "slide_internal.h"
+#include "transpose.h"
+
+#include <algorithm>
 
 namespace slide {
 
@@ -10,14 +13,16 @@ namespace slide {
 // h[i][:] = max(0, b1 + sum_k x_ik * W1[k][:]), one fused multiply-add per stored feature, in
 // storage order (so any other fp32 implementation using the same order gets the same bits).
 // One wave per (sample, 128 columns); each lane owns two columns and reads a float2 per W1 row.
-// The first column block also records the sample's features in the feature bit matrix.
+// The first column block also records, per tile of rows_per_tile features, where the sample's
+// features of the tile start and end in the CSR arrays (the row lists of the W1 update are built
+// from these segments).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz_total,
                                                        const int32_t* __restrict__ x_indptr,
                                                        const int32_t* __restrict__ x_indices,
                                                        const float* __restrict__ x_values,
                                                        const float* __restrict__ W1, const float* __restrict__ b1,
-                                                       float* __restrict__ h, uint32_t* xbm, int32_t* __restrict__ xfirst, int TWF,
+                                                       float* __restrict__ h, int2* __restrict__ xse, int rows_per_tile,
                                                        Ctrl* ctrl) {
   const int i = blockIdx.x, lane = threadIdx.x, B = gridDim.x;
   if (i == 0 && blockIdx.y == 0 && lane == 0) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }  // used after this kernel
@@ -37,14 +42,17 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
     const bool bad = pb + lane < p1 && (mine < 0 || mine >= D);
     if (__any(bad)) flags |= SLIDE_FLAG_BAD_FEATURE;
     const int kk = bad ? -1 : mine;
-    if (blockIdx.y == 0) {                // feature bit matrix, tile-major: [tile][sample][TWF words]
-      int before = __shfl_up(kk, 1);      // and, per tile, where the sample's features of the tile start
+    if (blockIdx.y == 0) {                // segment ends: a feature whose predecessor lies in another tile
+      int before = __shfl_up(kk, 1);      // starts its own tile's segment and ends the predecessor's
       if (lane == 0) before = last;
       last = __shfl(kk, 63);
       if (kk >= 0) {
-        const int w = kk >> 5, tile = w / TWF;
-        atomicOr(&xbm[((size_t)tile * B + i) * TWF + (w % TWF)], 1u << (kk & 31));
-        if (before < 0 || (before >> 5) / TWF != tile) xfirst[(size_t)tile * B + i] = pb + lane;
+        const int tile = kk / rows_per_tile, tb = before >= 0 ? before / rows_per_tile : -1;
+        if (tb != tile) {
+          xse[(size_t)tile * B + i].x = pb + lane;
+          if (tb >= 0) xse[(size_t)tb * B + i].y = pb + lane;
+        }
+        if (pb + lane == p1 - 1) xse[(size_t)tile * B + i].y = p1;
       }
     }
     const int cnt = min(64, p1 - pb);
@@ -77,9 +85,9 @@ __global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz
 
 hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
                             const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, uint32_t* xbm, int32_t* xfirst, int TWF, Ctrl* ctrl, hipStream_t s) {
+                            float* h, int2* xse, int rows_per_tile, Ctrl* ctrl, hipStream_t s) {
   hipLaunchKernelGGL(spmm_relu_kernel, dim3(B, ceil_div(H, 128)), dim3(64), 0, s, D, H, nnz_total, x_indptr,
-                     x_indices, x_values, W1, b1, h, xbm, xfirst, TWF, ctrl);
+                     x_indices, x_values, W1, b1, h, xse, rows_per_tile, ctrl);
   return hipGetLastError();
 }
 
@@ -91,17 +99,24 @@ hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_
 // exp(z - M), acc = sum of exp(z - M) * w) that is rescaled when the maximum moves.  acc/s is the
 // probability-weighted sum of the rows, which is all the hidden-layer gradient needs, so the rows
 // are not read a second time.  Partial states are merged per sample by combine_kernel.
+// The same launch transposes the two bit matrices of the batch (workgroups before the logit
+// workers): they depend on the lookup only, like the logits, and are latency-bound where the logit
+// workers are bandwidth-bound.
 // ---------------------------------------------------------------------------------------------
+constexpr int kForwardThreads = 512;
+constexpr int kForwardBlocks = 768;    // logit workers
+
 template <int LPR, int CH>
-__device__ void forward_items(const ActiveDev& ad, int H, const float* __restrict__ h, const float* __restrict__ W2,
+__device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const float* __restrict__ h, const float* __restrict__ W2,
                               const float* __restrict__ b2, float* __restrict__ z, float* __restrict__ partials,
                               const Ctrl* __restrict__ ctrl, int block, int nblocks) {
   constexpr int RPW = 64 / LPR;
   const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
-  const int nwaves = nblocks * 4;
-  const int nitems = (int)ctrl->total_chunks;
+  constexpr int WPB = kForwardThreads / 64;
+  const int nwaves = nblocks * WPB;
+  const int nitems = (int)ctrl->chunk_alloc[ad.par];
   const int PS = H + 4;
-  for (int item = block * 4 + (threadIdx.x >> 6); item < nitems; item += nwaves) {
+  for (int item = block * WPB + (threadIdx.x >> 6); item < nitems; item += nwaves) {
     const int i = ad.chunk_sample[item];
     const int done = (item - ad.chunk_ptr[i]) * kChunk;
     const int first = ad.as_base[i] + done;
@@ -174,27 +189,57 @@ __device__ void forward_items(const ActiveDev& ad, int H, const float* __restric
   }
 }
 
-constexpr int kForwardBlocks = 2048;
-
 template <int LPR, int CH>
-__global__ __launch_bounds__(256) void forward_kernel(ActiveDev ad, int H, const float* __restrict__ h,
-                                                      const float* __restrict__ W2, const float* __restrict__ b2,
-                                                      float* __restrict__ z, float* __restrict__ partials,
-                                                      const Ctrl* __restrict__ ctrl) {
-  forward_items<LPR, CH>(ad, H, h, W2, b2, z, partials, ctrl, blockIdx.x, kForwardBlocks);
+__global__ __launch_bounds__(kForwardThreads) void forward_kernel(ActiveDev ad, int H, const float* __restrict__ h,
+                                                                  const float* __restrict__ W2,
+                                                                  const float* __restrict__ b2, float* __restrict__ z,
+                                                                  float* __restrict__ partials,
+                                                                  const Ctrl* __restrict__ ctrl, TransposeArgs t1,
+                                                                  TransposeArgs t2) {
+  extern __shared__ uint32_t dyn_lds[];
+  // Workgroups start in index order and the machine holds a few hundred at a time.  The logit
+  // workers go first (they are what the memory system is busy with); the tiles fill in behind them
+  // as workers without an item leave, the feature tiles (fewer, and with a global counter on their
+  // critical path) before the active-set tiles.
+  const int k = blockIdx.x;
+  if (k < kForwardBlocks) forward_items<LPR, CH>(ad, H, h, W2, b2, z, partials, ctrl, k, kForwardBlocks);
+  else if (k < kForwardBlocks + t1.ntiles) transpose_tile<true>(t1, k - kForwardBlocks, dyn_lds);
+  else transpose_tile<false>(t2, k - kForwardBlocks - t1.ntiles, dyn_lds);
 }
 
 template <int LPR, int CH>
 static hipError_t launch_fwd(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
-                             float* partials, const Ctrl* ctrl, hipStream_t s) {
-  hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(kForwardBlocks), dim3(256), 0, s, ad, H, h, W2, b2, z, partials,
-                     ctrl);
+                             float* partials, const Ctrl* ctrl, const TransposeArgs& t1, const TransposeArgs& t2,
+                             hipStream_t s) {
+  size_t lds = 0;
+  if (t1.ntiles) lds = transpose_lds(t1.TW, t1.Bpad);
+  if (t2.ntiles) lds = std::max(lds, transpose_lds(t2.TW, t2.Bpad));
+  hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(t2.ntiles + t1.ntiles + kForwardBlocks), dim3(kForwardThreads),
+                     lds, s, ad, H, h, W2, b2, z, partials, ctrl, t1, t2);
   return hipGetLastError();
 }
 
+template <int LPR, int CH>
+static hipError_t fwd_attr(int lim) {
+  return hipFuncSetAttribute((const void*)forward_kernel<LPR, CH>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+}
+
+hipError_t forward_setup_attributes(size_t lds_limit) {
+  const int lim = (int)std::min<size_t>(lds_limit, 72 * 1024);
+  hipError_t e = fwd_attr<8, 1>(lim);
+  if (e == hipSuccess) e = fwd_attr<8, 2>(lim);
+  if (e == hipSuccess) e = fwd_attr<8, 4>(lim);
+  if (e == hipSuccess) e = fwd_attr<16, 4>(lim);
+  if (e == hipSuccess) e = fwd_attr<32, 4>(lim);
+  if (e == hipSuccess) e = fwd_attr<64, 4>(lim);
+  if (e == hipSuccess) e = fwd_attr<64, 8>(lim);
+  return e;
+}
+
 hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
-                          float* partials, const Ctrl* ctrl, hipStream_t s) {
-#define SLIDE_FWD(L_, C_) return launch_fwd<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, s)
+                          float* partials, const Ctrl* ctrl, const TransposeArgs& t1, const TransposeArgs& t2,
+                          hipStream_t s) {
+#define SLIDE_FWD(L_, C_) return launch_fwd<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, t1, t2, s)
   if (H <= 32) SLIDE_FWD(8, 1);
   if (H <= 64) SLIDE_FWD(8, 2);
   if (H <= 128) SLIDE_FWD(8, 4);
@@ -225,7 +270,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
                                                       float* __restrict__ msum) {
   __shared__ float red[kCombineThreads / 64];
   const int i = blockIdx.x, tid = threadIdx.x;
-  const int c0 = ad.chunk_ptr[i], nch = ad.chunk_ptr[i + 1] - c0;
+  const int c0 = ad.chunk_ptr[i], nch = (ad.cnt[i] + kChunk - 1) / kChunk;
   const int first = ad.as_base[i], n = ad.cnt[i];
   const int ny = ad.ny[i];
   const int PS = H + 4;

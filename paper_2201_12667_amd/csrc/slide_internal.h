@@ -26,6 +26,9 @@ struct Ctrl {
   uint32_t nlong2, nlong1; // long rows queued by the two transpositions
   uint32_t max_nu2, max_nu1; // most touched rows in any tile
   uint32_t pad[1];
+  // forward work items handed out by the lookup workgroups; a call uses counter (call number & 1)
+  // and clears the other
+  uint32_t chunk_alloc[2];
   // running totals since the last slide_reset_stats (updated once per training step)
   unsigned long long sum_pairs, sum_u2, sum_u1, sum_candidates, sum_steps;
 };
@@ -78,14 +81,15 @@ struct ActiveDev {
   int NWpad, NT;                   // bitmap words per sample (multiple of TW), tiles per sample
   int PS;                          // slots reserved per sample for candidates: min(L*C, N)
   int num_labels;                  // label entries in the batch
-  uint32_t* act;                   // [NT][B][TW] active-set bit matrix, tile-major
+  int par;                         // which work-item counter this call uses
+  uint32_t* act;                   // [NT][B][TW] bitmap spill, used only when a sample's bitmap exceeds LDS
   uint32_t* rankS;                 // [B][NT] per-sample scratch: tile counts, then exclusive prefix
-  uint32_t* rankT;                 // [NT][B] rank of the tile's first active neuron inside the sample
+  uint32_t* rankT;                 // [NT+1][B] active neurons of the sample below the tile (last row: |AS_i|)
   int32_t* cnt;                    // [B] |AS_i|
   int32_t* ny;                     // [B] distinct labels
   int32_t* as_base;                // [B] first slot of sample i = i*PS + (label entries before sample i)
-  int32_t* chunk_ptr;              // [B+1]
-  int32_t* chunk_sample;           // [max chunks]
+  int32_t* chunk_ptr;              // [B] first forward work item of the sample
+  int32_t* chunk_sample;           // [max chunks] sample of the work item
   int32_t* as_ids;                 // [slots] ascending ids of sample i at as_base[i] .. +cnt[i]
   uint8_t* as_lab;                 // [slots]
   int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
@@ -105,13 +109,13 @@ struct PairsDev {
 };
 
 struct TransposeArgs {
-  int B, Bpad, TW, ntiles;       // TW words per record = per tile; ntiles = 0: nothing to do
-  uint32_t* bits;                // [ntiles][B][TW]
-  const uint32_t* rankT;         // [ntiles][B]  (active matrix only)
-  const int32_t* as_base;        // [B]           (active matrix only)
-  const int32_t* xfirst;         // [ntiles][B]  (feature matrix only) CSR position of the sample's first
-                                 // feature inside the tile, valid where the record is non-empty
-  int x_nnz;                     // feature matrix only: entries in the batch's CSR arrays
+  int B, Bpad, TW, ntiles;       // a tile is TW*32 rows; ntiles = 0: nothing to do
+  const int32_t* ids;            // ascending id list per sample (active-set ids / CSR feature indices)
+  const uint32_t* rankT;         // [ntiles+1][B] (active sets only) ids of the sample below the tile
+  const int32_t* as_base;        // [B]           (active sets only) first slot of the sample
+  int2* xse;                     // [ntiles][B]   (features only) positions [start, end) of the sample's
+                                 // features inside the tile; (0, 0) = none
+  int x_nnz;                     // features only: entries in the batch's CSR arrays
   PairsDev pd;
 };
 
@@ -119,16 +123,18 @@ hipError_t active_setup_attributes(size_t* lds_limit_out);
 hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
                                uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
                                int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
-hipError_t launch_scan_samples(const ActiveDev& ad, const int32_t* ncand, Ctrl* ctrl, const TransposeArgs& t1,
-                               const TransposeArgs& t2, hipStream_t s);
 
 
 // ---- output.hip -----------------------------------------------------------------------
 hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
                             const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, uint32_t* xbm, int32_t* xfirst, int TWF, Ctrl* ctrl, hipStream_t s);
+                            float* h, int2* xse, int rows_per_tile, Ctrl* ctrl, hipStream_t s);
+// Logits over the active sets; the same launch transposes the two bit matrices (t1: features, t2:
+// active sets; ntiles = 0 leaves one out).
 hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
-                          float* partials, const Ctrl* ctrl, hipStream_t s);
+                          float* partials, const Ctrl* ctrl, const TransposeArgs& t1, const TransposeArgs& t2,
+                          hipStream_t s);
+hipError_t forward_setup_attributes(size_t lds_limit);
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
                           float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s);
@@ -157,6 +163,8 @@ struct FinishArgs {
   Ctrl* ctrl;
   const int32_t* tile_nu2; int ntiles2;
   const int32_t* tile_nu1; int ntiles1;
+  const int32_t* cnt;            // [B] |AS_i|
+  const int32_t* ncand;          // [B] bucket entries read for sample i
   int nblocks;
 };
 // One launch, three roles by workgroup index: loss mean + hidden bias + statistics, the rows of W1,

@@ -183,23 +183,30 @@ __device__ void finish_role(int H, const FinishArgs& f, const AdamDev& ad, int b
   const int32_t* __restrict__ tile_nu1 = f.tile_nu1;
   const int ntiles2 = f.ntiles2, ntiles1 = f.ntiles1;
   __shared__ float red[256];
-  __shared__ uint32_t ured[2][256];
+  __shared__ unsigned long long ured[4][256];
   const int tid = threadIdx.x;
   if (block == 0) {
     float acc = 0.f;
     for (int i = tid; i < B; i += 256) acc += loss_i[i];
-    uint32_t u2 = 0, u1 = 0;
-    for (int t = tid; t < ntiles2; t += 256) u2 += (uint32_t)tile_nu2[t];
-    for (int t = tid; t < ntiles1; t += 256) u1 += (uint32_t)tile_nu1[t];
-    red[tid] = acc; ured[0][tid] = u2; ured[1][tid] = u1;
+    unsigned long long u2 = 0, u1 = 0, pairs = 0, cand = 0;
+    for (int t = tid; t < ntiles2; t += 256) u2 += (unsigned long long)tile_nu2[t];
+    for (int t = tid; t < ntiles1; t += 256) u1 += (unsigned long long)tile_nu1[t];
+    for (int i = tid; i < B; i += 256) { pairs += (unsigned long long)f.cnt[i]; cand += (unsigned long long)f.ncand[i]; }
+    red[tid] = acc; ured[0][tid] = u2; ured[1][tid] = u1; ured[2][tid] = pairs; ured[3][tid] = cand;
     __syncthreads();
     for (int d = 128; d > 0; d >>= 1) {
-      if (tid < d) { red[tid] += red[tid + d]; ured[0][tid] += ured[0][tid + d]; ured[1][tid] += ured[1][tid + d]; }
+      if (tid < d) {
+        red[tid] += red[tid + d];
+        for (int q = 0; q < 4; ++q) ured[q][tid] += ured[q][tid + d];
+      }
       __syncthreads();
     }
     if (tid == 0) {
       if (d_loss) *d_loss = red[0] / (float)B;
       ctrl->u2 = ured[0][0]; ctrl->u1 = ured[1][0];
+      ctrl->total_pairs = (uint32_t)ured[2][0];
+      ctrl->candidates_lo = (uint32_t)ured[3][0];
+      ctrl->candidates_hi = (uint32_t)(ured[3][0] >> 32);
       ctrl->sum_pairs += ctrl->total_pairs;
       ctrl->sum_u2 += ured[0][0];
       ctrl->sum_u1 += ured[1][0];

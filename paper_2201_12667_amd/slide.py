@@ -17,7 +17,7 @@ HASH_SIMHASH, HASH_DWTA = 0, 1
 KEEP_LOWEST_ID, KEEP_PRIORITY = 0, 1
 FLAG_BAD_FEATURE, FLAG_UNSORTED, FLAG_BAD_LABEL = 1, 2, 4
 ABI_VERSION = 1
-STAGES = ["hidden", "lookup", "scan", "forward", "combine", "update", "rebuild"]
+STAGES = ["hidden", "lookup", "forward", "combine", "update", "rebuild"]
 NUM_STAGES = len(STAGES)
 
 EXPORTS = ["slide_query_memory", "slide_init", "slide_build_tables", "slide_train_step", "slide_predict",
