@@ -11,6 +11,9 @@
 
 namespace slide {
 
+constexpr int kUpdateThreads = 256;
+constexpr int kUpdateBlocksOut = 2048;
+
 __device__ __forceinline__ void adam1(float& w, float& m, float& v, float g, const AdamDev& a) {
   m = a.beta1 * m + a.omb1 * g;
   v = a.beta2 * v + a.omb2 * g * g;
@@ -52,9 +55,11 @@ __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd,
 }
 
 // Work item = RPW consecutive row slots of one tile (RPW = 64/LPR rows per wave, LPR lanes per row,
-// CH float4 per lane).  Rows with more than kLongRow pairs are skipped here and taken afterwards by
-// a whole wave each: its RPW lane groups accumulate interleaved shares of the pair list and the
-// shares are added in a fixed butterfly order.
+// CH float4 per lane).  Rows with more than kLongRow pairs are skipped here and taken afterwards,
+// with more lanes on the pair list: by a whole wave each when a row needs only part of a wave (its
+// RPW lane groups accumulate interleaved shares of the list, added in a fixed butterfly order), by
+// a whole workgroup each when a row fills a wave (the waves accumulate interleaved shares, added in
+// wave order through LDS).
 template <int LPR, int CH, int UNR>
 __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int block, int nblocks) {
   const PairsDev& pd = ru.pd;
@@ -81,7 +86,7 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
     const int slot = t * pd.rows_per_tile + r;
     const int4 meta = r < nu ? pd.umeta[slot] : make_int4(0, 0, 0, 0);
     int cn = meta.z;
-    const bool valid = r < nu && (RPW == 1 || cn <= kLongRow);
+    const bool valid = r < nu && cn <= kLongRow;
     if (!valid) cn = 0;
     const int j = valid ? meta.x : 0;
     const size_t ro = (size_t)j * H;
@@ -117,8 +122,67 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
       bias[j] = bw; mbias[j] = bm; vbias[j] = bv;
     }
   }
-  if (RPW == 1) return;
   const int nlong = min((int)*pd.nlong, pd.long_cap);
+  if constexpr (RPW == 1) {
+    constexpr int NW = kUpdateThreads / 64;              // waves of the workgroup
+    __shared__ float4 part[NW - 1][CH][64];
+    __shared__ float partb[NW - 1];
+    const int wv = threadIdx.x >> 6;
+    for (int l = block; l < nlong; l += nblocks) {       // (the same trip count for every wave of the workgroup)
+      const int slot = pd.longlist[l];
+      const int4 meta = pd.umeta[slot];
+      const int j = meta.x, cn = meta.z;
+      const size_t ro = (size_t)j * H;
+      const uint32_t st = (uint32_t)meta.y;
+      float4 w[CH], m[CH], v[CH], g[CH];
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int col = (c * LPR + sub) * 4;
+        g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (wv == 0 && col < H) {
+          w[c] = *(const float4*)(W + ro + col);
+          m[c] = *(const float4*)(M + ro + col);
+          v[c] = *(const float4*)(Vv + ro + col);
+        }
+      }
+      float gb = 0.f;
+      row_gradient<LPR, CH, 2 * UNR>(H, sub, pd, coef, V, st, cn, wv, NW, g, gb);
+      if (wv > 0) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) part[wv - 1][c][lane] = g[c];
+        if (lane == 0) partb[wv - 1] = gb;
+      }
+      __syncthreads();
+      if (wv == 0) {
+        for (int k = 0; k < NW - 1; ++k) {
+          gb += partb[k];
+#pragma unroll
+          for (int c = 0; c < CH; ++c) {
+            const float4 p = part[k][c][lane];
+            g[c].x += p.x; g[c].y += p.y; g[c].z += p.z; g[c].w += p.w;
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const int col = (c * LPR + sub) * 4;
+          if (col < H) {
+            adam1(w[c].x, m[c].x, v[c].x, g[c].x, ad); adam1(w[c].y, m[c].y, v[c].y, g[c].y, ad);
+            adam1(w[c].z, m[c].z, v[c].z, g[c].z, ad); adam1(w[c].w, m[c].w, v[c].w, g[c].w, ad);
+            *(float4*)(W + ro + col) = w[c];
+            *(float4*)(M + ro + col) = m[c];
+            *(float4*)(Vv + ro + col) = v[c];
+          }
+        }
+        if (bias && sub == 0) {
+          float bw = bias[j], bm = mbias[j], bv = vbias[j];
+          adam1(bw, bm, bv, gb, ad);
+          bias[j] = bw; mbias[j] = bm; vbias[j] = bv;
+        }
+      }
+      __syncthreads();
+    }
+    return;
+  }
   for (int l = wave_global; l < nlong; l += nwaves) {
     const int slot = pd.longlist[l];
     const int4 meta = pd.umeta[slot];
@@ -232,22 +296,21 @@ __device__ void finish_role(int H, const FinishArgs& f, const AdamDev& ad, int b
   }
 }
 
-constexpr int kUpdateBlocksOut = 2048;
 
 template <int LPR, int CH, int UNR>
-__global__ __launch_bounds__(256) void update_kernel(int H, RowUpdate out, RowUpdate in, FinishArgs fin, AdamDev ad) {
+__global__ __launch_bounds__(kUpdateThreads) void update_kernel(int H, RowUpdate out, RowUpdate in, FinishArgs fin, AdamDev ad) {
   int blk = blockIdx.x;
   if (blk < fin.nblocks) { finish_role(H, fin, ad, blk); return; }
   blk -= fin.nblocks;
-  if (blk < in.nblocks) { rowgrad_adam<LPR, CH, UNR>(H, in, ad, blk, in.nblocks); return; }
-  blk -= in.nblocks;
+  // every other workgroup takes its share of both row lists (their sizes are known on the device only)
+  if (in.nblocks) rowgrad_adam<LPR, CH, UNR>(H, in, ad, blk, out.nblocks);
   rowgrad_adam<LPR, CH, UNR>(H, out, ad, blk, out.nblocks);
 }
 
 template <int LPR, int CH, int UNR>
 static hipError_t launch_up(int H, const RowUpdate& out, const RowUpdate& in, const FinishArgs& fin,
                             const AdamDev& ad, hipStream_t s) {
-  hipLaunchKernelGGL((update_kernel<LPR, CH, UNR>), dim3(fin.nblocks + in.nblocks + out.nblocks), dim3(256), 0, s, H,
+  hipLaunchKernelGGL((update_kernel<LPR, CH, UNR>), dim3(fin.nblocks + out.nblocks), dim3(kUpdateThreads), 0, s, H,
                      out, in, fin, ad);
   return hipGetLastError();
 }
@@ -257,7 +320,7 @@ hipError_t launch_update(int H, const RowUpdate& out_, const RowUpdate& in_, con
   RowUpdate out = out_, in = in_;
   FinishArgs fin = fin_;
   out.nblocks = kUpdateBlocksOut;
-  in.nblocks = in.W ? 256 : 0;
+  in.nblocks = in.W ? 1 : 0;          // present / absent
   fin.nblocks = fin.b1 ? ceil_div(H, 32) : 1;
 #define SLIDE_UP(L_, C_, U_) return launch_up<L_, C_, U_>(H, out, in, fin, ad, s)
   if (H <= 32) SLIDE_UP(8, 1, 4);
