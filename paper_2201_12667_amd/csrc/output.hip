@@ -268,34 +268,60 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
                                                       float* __restrict__ delta, float* __restrict__ dh,
                                                       float* __restrict__ dh_copy, float* __restrict__ loss_i,
                                                       float* __restrict__ msum) {
+  constexpr int kMaxCh = 1024, kMaxLab = 256;            // LDS-staged chunk scales / label rows; more fall back to global reads
   __shared__ float red[kCombineThreads / 64];
-  const int i = blockIdx.x, tid = threadIdx.x;
+  __shared__ float scale[kMaxCh];                        // exp(M_c - M) per forward work item of the sample
+  __shared__ int ylab[kMaxLab];                          // neuron of each label entry, -1 = not counted
+  __shared__ float ms[2];
+  const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int c0 = ad.chunk_ptr[i], nch = (ad.cnt[i] + kChunk - 1) / kChunk;
   const int first = ad.as_base[i], n = ad.cnt[i];
   const int ny = ad.ny[i];
   const int PS = H + 4;
   const float invB = 1.0f / (float)ad.B;
-  float Mi = -INFINITY;
-  for (int c = 0; c < nch; ++c) Mi = fmaxf(Mi, partials[(size_t)(c0 + c) * PS]);
-  float s = 0.f;
-  for (int c = 0; c < nch; ++c) {
-    const float* pp = partials + (size_t)(c0 + c) * PS;
-    s += pp[1] * __expf(pp[0] - Mi);
+  const int y0 = min(max(y_indptr[i], 0), ad.num_labels);               // (clamped like the lookup does)
+  const int nlab = min(max(y_indptr[i + 1], y0), ad.num_labels) - y0;
+  // label rows: both lookups for all labels at once (a chain of dependent reads per label otherwise)
+  for (int q = tid; q < min(nlab, kMaxLab); q += kCombineThreads) {
+    const int slot = ylist[y0 + q];
+    ylab[q] = slot >= 0 ? ad.as_ids[slot] : -1;
   }
-  if (tid == 0) { msum[2 * i] = Mi; msum[2 * i + 1] = s; }
+  // soft-max normaliser from the partial states: wave 0, one lane per work item, fixed butterfly order
+  if (tid < 64) {
+    float Mi = -INFINITY;
+    for (int c = lane; c < nch; c += 64) Mi = fmaxf(Mi, partials[(size_t)(c0 + c) * PS]);
+    for (int d = 32; d > 0; d >>= 1) Mi = fmaxf(Mi, __shfl_xor(Mi, d));
+    float s = 0.f;
+    for (int c = lane; c < nch; c += 64) {
+      const float* pp = partials + (size_t)(c0 + c) * PS;
+      const float sc = __expf(pp[0] - Mi);
+      if (c < kMaxCh) scale[c] = sc;
+      s += pp[1] * sc;
+    }
+    for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d);
+    if (lane == 0) { ms[0] = Mi; ms[1] = s; msum[2 * i] = Mi; msum[2 * i + 1] = s; }
+  }
+  __syncthreads();
+  const float Mi = ms[0], s = ms[1];
   const bool live = n > 0 && ny > 0;
   for (int u = tid; u < H; u += kCombineThreads) {
     float g = 0.f;
     if (live && h[(size_t)i * H + u] > 0.f) {
       float acc = 0.f;
-      for (int c = 0; c < nch; ++c) {
-        const float* pp = partials + (size_t)(c0 + c) * PS;
-        acc += pp[4 + u] * __expf(pp[0] - Mi);
+      const float* pu = partials + (size_t)c0 * PS + 4 + u;
+      int c = 0;
+      for (; c + 4 <= min(nch, kMaxCh); c += 4) {         // four reads in flight, added in chunk order
+        const float a0 = pu[(size_t)c * PS], a1 = pu[(size_t)(c + 1) * PS], a2 = pu[(size_t)(c + 2) * PS],
+                    a3 = pu[(size_t)(c + 3) * PS];
+        acc += a0 * scale[c]; acc += a1 * scale[c + 1]; acc += a2 * scale[c + 2]; acc += a3 * scale[c + 3];
       }
+      for (; c < nch; ++c) acc += pu[(size_t)c * PS] * (c < kMaxCh ? scale[c] : __expf(pu[(size_t)c * PS - 4 - u] - Mi));
       float accy = 0.f;
-      for (int q = y_indptr[i]; q < y_indptr[i + 1]; ++q) {
-        const int slot = ylist[q];
-        if (slot >= 0) accy += W2[(size_t)ad.as_ids[slot] * H + u];
+      for (int q = 0; q < nlab; ++q) {
+        int j;
+        if (q < kMaxLab) j = ylab[q];
+        else { const int slot = ylist[y0 + q]; j = slot >= 0 ? ad.as_ids[slot] : -1; }
+        if (j >= 0) accy += W2[(size_t)j * H + u];
       }
       g = (acc / s - accy / (float)ny) * invB;
     }
