@@ -8,6 +8,7 @@
 //                 It also emits the compact ascending id list per sample + label flags and hands
 //                 the sample its forward work items (chunks of kChunk active neurons).
 #include "slide_internal.h"
+#include "wave_ops.h"
 
 namespace slide {
 
@@ -116,7 +117,8 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   uint32_t* pos = o0s + ad.L;            // [L+1] exclusive prefix of the bucket lengths
   uint32_t* sm = pos + ad.L + 1;         // [20] scan scratch + counters
   float* hvec = (float*)(sm + 20);       // [H] the sample's hidden activations
-  int8_t* raw = (int8_t*)(hvec + hd.H);  // [NH] elementary hash values
+  uint32_t* tcnt = (uint32_t*)(hvec + hd.H);   // [NT] active neurons per tile, then their exclusive prefix
+  int8_t* raw = (int8_t*)(tcnt + ad.NT); // [NH] elementary hash values
   const int i = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
   const int lane = tid & 63;
   if (tid == 0) { sm[17] = 0; sm[18] = 0; }
@@ -184,8 +186,8 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       uint32_t c = __popc(word);
       my_cnt += c;
       if (w < sw && segw < ad.NWpad) ad.act[act_index(ad, i, seg0 + w)] = word;   // spill: re-read by the id sweep
-      for (int d = 1; d < ad.TW; d <<= 1) c += __shfl_xor(c, d);
-      if (w < sw && (lane & (ad.TW - 1)) == 0) ad.rankS[(size_t)i * ad.NT + (seg0 + w) / ad.TW] = c;
+      c = group_incl_scan_add(c, ad.TW);                // the last lane of a tile holds the tile's count
+      if (w < sw && (lane & (ad.TW - 1)) == ad.TW - 1) tcnt[(seg0 + w) / ad.TW] = c;
     }
     __syncthreads();
   }
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   }
 
   // per-tile counts -> exclusive prefix inside the sample (rank of the tile's first active neuron)
-  uint32_t* rk = ad.rankS + (size_t)i * ad.NT;
+  uint32_t* rk = tcnt;
   carry = 0;
   for (int base = 0; base < ad.NT; base += nthr) {
     const int t = base + tid;
@@ -222,11 +224,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
     const int w = wb + tid;
     uint32_t word = w < ad.NWpad ? (in_lds ? bm[w] : ad.act[act_index(ad, i, w)]) : 0u;
     const uint32_t c = __popc(word);
-    uint32_t inc = c;
-    for (int d = 1; d < ad.TW; d <<= 1) {
-      const uint32_t t = __shfl_up(inc, d, ad.TW);
-      if ((lane & (ad.TW - 1)) >= d) inc += t;
-    }
+    const uint32_t inc = group_incl_scan_add(c, ad.TW);
     if (word) {
       int slot = base_i + (int)(rk[w / ad.TW] + inc - c);
       while (word) {
@@ -246,9 +244,19 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
     const int y = y_indices[y0 + q];
     int slot = -1;
     if (y >= 0 && y < ad.N) {
-      int a = 0, b = n;
-      while (a < b) { const int mid = (a + b) >> 1; if (ad.as_ids[base_i + mid] < y) a = mid + 1; else b = mid; }
-      if (a < n && ad.as_ids[base_i + a] == y) {
+      int a = 0;
+      bool found;
+      if (in_lds) {                                      // rank of the label in the bitmap = its slot
+        const int w = y >> 5, w0 = w & ~(ad.TW - 1);
+        a = (int)rk[w / ad.TW] + __popc(bm[w] & ((1u << (y & 31)) - 1u));
+        for (int q = w0; q < w; ++q) a += __popc(bm[q]);
+        found = (bm[w] >> (y & 31)) & 1u;
+      } else {
+        int b = n;
+        while (a < b) { const int mid = (a + b) >> 1; if (ad.as_ids[base_i + mid] < y) a = mid + 1; else b = mid; }
+        found = a < n && ad.as_ids[base_i + a] == y;
+      }
+      if (found) {
         ad.as_lab[base_i + a] = 1;
         slot = base_i + a;
         for (int q2 = 0; q2 < q; ++q2) if (y_indices[y0 + q2] == y) { slot = -1; break; }
@@ -274,7 +282,7 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
 hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
                                uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
                                int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s) {
-  const size_t fixed = ((size_t)2 * ad.L + 1 + 20 + hd.H) * 4 + (((size_t)hd.NH + 3) & ~(size_t)3);
+  const size_t fixed = ((size_t)2 * ad.L + 1 + 20 + hd.H + ad.NT) * 4 + (((size_t)hd.NH + 3) & ~(size_t)3);
   size_t avail = (lds_limit - fixed) / 4;
   int segw = (int)(avail / 32 * 32);
   if (segw > ad.NWpad) segw = ad.NWpad;

@@ -25,7 +25,7 @@ struct Layout {
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, xse, h, dh, codes, act, rankS, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, xse, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -114,7 +114,6 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->dh = take(B * H * 4);
   lo->codes = take(B * lo->L * 4);
   lo->act = take(B * lo->NWpad * 4);
-  lo->rankS = take(B * lo->NT * 4);
   lo->rankT = take(B * (lo->NT + 1) * 4);
   lo->cnt = take(B * 4); lo->ny = take(B * 4); lo->ncand = take(B * 4);
   lo->as_base = take(B * 4); lo->chunk_ptr = take((B + 1) * 4);
@@ -211,7 +210,7 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ActiveDev ad;
   const Layout& lo = c->lo;
   ad.B = B; ad.L = lo.L; ad.C = lo.C; ad.TW = lo.TW; ad.N = lo.N; ad.NWpad = lo.NWpad; ad.NT = lo.NT;
-  ad.act = c->at<uint32_t>(lo.act); ad.rankS = c->at<uint32_t>(lo.rankS); ad.rankT = c->at<uint32_t>(lo.rankT);
+  ad.act = c->at<uint32_t>(lo.act); ad.rankT = c->at<uint32_t>(lo.rankT);
   ad.cnt = c->at<int32_t>(lo.cnt); ad.ny = c->at<int32_t>(lo.ny);
   ad.PS = lo.PS; ad.num_labels = 0;
   ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);

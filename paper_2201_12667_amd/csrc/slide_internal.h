@@ -83,7 +83,6 @@ struct ActiveDev {
   int num_labels;                  // label entries in the batch
   int par;                         // which work-item counter this call uses
   uint32_t* act;                   // [NT][B][TW] bitmap spill, used only when a sample's bitmap exceeds LDS
-  uint32_t* rankS;                 // [B][NT] per-sample scratch: tile counts, then exclusive prefix
   uint32_t* rankT;                 // [NT+1][B] active neurons of the sample below the tile (last row: |AS_i|)
   int32_t* cnt;                    // [B] |AS_i|
   int32_t* ny;                     // [B] distinct labels
