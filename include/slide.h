@@ -61,7 +61,7 @@ typedef struct {
   int64_t input_dim;         /* D; 0 = dense-hidden mode: the batch carries hidden[B][H]         */
   int64_t num_classes;       /* N, output neurons held by this GPU                               */
   int32_t hidden_dim;        /* H, multiple of 4, <= 2048                                        */
-  int32_t max_batch;         /* largest batch any call will pass                                 */
+  int32_t max_batch;         /* largest batch any call will pass, <= 2048                        */
   int32_t max_nnz_per_batch; /* largest total number of stored features in a batch              */
   int32_t max_labels_per_batch; /* largest total number of label entries in a batch             */
   int32_t hash_kind;         /* slide_hash_kind                                                  */

@@ -12,20 +12,10 @@
 
 namespace slide {
 
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t t = __shfl_up(v, d);
-    if (lane >= d) v += t;
-  }
-  return v;
-}
-
 // Exclusive scan over a workgroup of up to 1024 threads; sm: 17 words of LDS.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t& total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  const uint32_t inc = wave_incl_scan_u32(v);
+  const uint32_t inc = wave_incl_scan_add(v);
   __syncthreads();
   if (lane == 63) sm[wave] = inc;
   __syncthreads();
@@ -39,7 +29,8 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, ui
 // words], so that the transposition reads one contiguous block per tile; the per-sample writer
 // pays the stride instead (full 4*TW-byte records).
 __device__ __forceinline__ size_t act_index(const ActiveDev& ad, int i, int w) {
-  return ((size_t)(w / ad.TW) * ad.B + i) * ad.TW + (w & (ad.TW - 1));
+  const int tws = __ffs(ad.TW) - 1;
+  return ((size_t)(w >> tws) * ad.B + i) * ad.TW + (w & (ad.TW - 1));
 }
 
 // Hash codes of one vector held in LDS, one thread per elementary hash (same arithmetic, in the
@@ -124,9 +115,38 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   if (tid == 0) { sm[17] = 0; sm[18] = 0; }
   if (i == 0 && tid == 0) { ctrl->nlong2 = 0; ctrl->max_nu2 = 0; }   // consumed after this kernel
 
-  // a2: hash codes of this sample's hidden activations
+  // the sample's slice of the sample-major arrays: room for every candidate plus its labels
+  int y0 = 0, nlab = 0;
+  if (include_labels) {
+    y0 = min(max(y_indptr[i], 0), ad.num_labels);
+    nlab = min(max(y_indptr[i + 1], y0), ad.num_labels) - y0;
+  }
+  const int base_i = i * ad.PS + y0;
+  const int tws = __ffs(ad.TW) - 1;                      // TW is a power of two >= 4
+  const int LT = ad.TW >> 2;                             // lanes per tile in the sweeps (four words per lane)
+
+  // Bitmap segment [seg0, seg0 + sw) words: cleared, then the labels (their "new bit" test counts the
+  // distinct labels, so they go in before any candidate).
+  auto start_segment = [&](int seg0, int sw) {
+    for (int q = tid; q < sw / 4; q += nthr) ((uint4*)bm)[q] = make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+    const int64_t lo = (int64_t)seg0 * 32, hi = lo + (int64_t)sw * 32;
+    for (int q = tid; q < nlab; q += nthr) {
+      const int y = y_indices[y0 + q];
+      if (y < 0 || y >= ad.N) { if (seg0 == 0) atomicOr(&ctrl->status, SLIDE_FLAG_BAD_LABEL); continue; }
+      if (y >= lo && y < hi) {
+        const uint32_t bit = 1u << (y & 31);
+        const uint32_t old = atomicOr(&bm[(y - lo) >> 5], bit);
+        if (!(old & bit)) atomicAdd(&sm[17], 1u);       // distinct labels
+      }
+    }
+  };
+
+  // a2: hash codes of this sample's hidden activations (the first bitmap segment is prepared while
+  // the activations arrive)
   for (int c = tid; c < hd.H; c += nthr) hvec[c] = h[(size_t)i * hd.H + c];
-  __syncthreads();
+  __syncthreads();                                       // (also orders the counters' reset before the labels)
+  start_segment(0, min(segw, ad.NWpad));
   sample_hash_codes(hd, hvec, raw, o0s, codes + (size_t)i * ad.L);
 
   uint32_t carry = 0;
@@ -149,45 +169,31 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   if (tid == 0) pos[ad.L] = carry;
   __syncthreads();
   const uint32_t T = pos[ad.L];
-  // the sample's slice of the sample-major arrays: room for every candidate plus its labels
-  int y0 = 0, nlab = 0;
-  if (include_labels) {
-    y0 = min(max(y_indptr[i], 0), ad.num_labels);
-    nlab = min(max(y_indptr[i + 1], y0), ad.num_labels) - y0;
-  }
-  const int base_i = i * ad.PS + y0;
 
   uint32_t my_cnt = 0;
   for (int seg0 = 0; seg0 < ad.NWpad; seg0 += segw) {
     const int sw = min(segw, ad.NWpad - seg0);
     const int64_t lo = (int64_t)seg0 * 32, hi = lo + (int64_t)sw * 32;
-    for (int w = tid; w < sw; w += nthr) bm[w] = 0;
-    __syncthreads();
-    for (int q = tid; q < nlab; q += nthr) {
-      const int y = y_indices[y0 + q];
-      if (y < 0 || y >= ad.N) { if (seg0 == 0) atomicOr(&ctrl->status, SLIDE_FLAG_BAD_LABEL); continue; }
-      if (y >= lo && y < hi) {
-        const uint32_t bit = 1u << (y & 31);
-        const uint32_t old = atomicOr(&bm[(y - lo) >> 5], bit);
-        if (!(old & bit)) atomicAdd(&sm[17], 1u);       // distinct labels
-      }
-    }
-    __syncthreads();                                    // labels first: their "new bit" test must not
-    for (uint32_t c = tid; c < T; c += nthr) {          // see candidate bits
+    if (seg0 > 0) { start_segment(seg0, sw); __syncthreads(); }
+    for (uint32_t c = tid; c < T; c += nthr) {
       int a = 0, b = ad.L;                              // last t with pos[t] <= c
       while (b - a > 1) { const int mid = (a + b) >> 1; if (pos[mid] <= c) a = mid; else b = mid; }
       const int j = ids[(size_t)a * ad.N + o0s[a] + (c - pos[a])];
       if (j >= lo && j < hi) atomicOr(&bm[(j - lo) >> 5], 1u << (j & 31));
     }
     __syncthreads();
-    for (int wb = 0; wb < sw; wb += nthr) {
-      const int w = wb + tid;
-      const uint32_t word = w < sw ? bm[w] : 0u;
-      uint32_t c = __popc(word);
+    // sweep, four words per lane: population per tile (the last lane of a tile holds its count)
+    for (int qb = 0; qb < sw / 4; qb += nthr) {
+      const int q = qb + tid;
+      const uint4 wd = q < sw / 4 ? ((const uint4*)bm)[q] : make_uint4(0u, 0u, 0u, 0u);
+      uint32_t c = __popc(wd.x) + __popc(wd.y) + __popc(wd.z) + __popc(wd.w);
       my_cnt += c;
-      if (w < sw && segw < ad.NWpad) ad.act[act_index(ad, i, seg0 + w)] = word;   // spill: re-read by the id sweep
-      c = group_incl_scan_add(c, ad.TW);                // the last lane of a tile holds the tile's count
-      if (w < sw && (lane & (ad.TW - 1)) == ad.TW - 1) tcnt[(seg0 + w) / ad.TW] = c;
+      if (q < sw / 4 && segw < ad.NWpad) {               // spill: re-read by the id sweep
+        uint32_t* dst = &ad.act[act_index(ad, i, seg0 + 4 * q)];
+        *(uint4*)dst = wd;
+      }
+      c = small_group_incl_scan_add(c, LT);
+      if (q < sw / 4 && (lane & (LT - 1)) == LT - 1) tcnt[(seg0 + 4 * q) >> tws] = c;
     }
     __syncthreads();
   }
@@ -220,19 +226,25 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   if (tid == 0) ad.rankT[(size_t)ad.NT * ad.B + i] = carry;   // closes the last tile's segment
   // compact ascending id list: sweep the bitmap (still in LDS if it fitted in one segment)
   const bool in_lds = segw >= ad.NWpad;
-  for (int wb = 0; wb < ad.NWpad; wb += nthr) {
-    const int w = wb + tid;
-    uint32_t word = w < ad.NWpad ? (in_lds ? bm[w] : ad.act[act_index(ad, i, w)]) : 0u;
-    const uint32_t c = __popc(word);
-    const uint32_t inc = group_incl_scan_add(c, ad.TW);
-    if (word) {
-      int slot = base_i + (int)(rk[w / ad.TW] + inc - c);
-      while (word) {
-        const int b = __ffs(word) - 1;
-        ad.as_ids[slot] = w * 32 + b;
-        ad.as_lab[slot] = 0;
-        ++slot;
-        word &= word - 1;
+  for (int qb = 0; qb < ad.NWpad / 4; qb += nthr) {
+    const int q = qb + tid;
+    uint4 wd = make_uint4(0u, 0u, 0u, 0u);
+    if (q < ad.NWpad / 4) wd = in_lds ? ((const uint4*)bm)[q] : *(const uint4*)&ad.act[act_index(ad, i, 4 * q)];
+    const uint32_t c = __popc(wd.x) + __popc(wd.y) + __popc(wd.z) + __popc(wd.w);
+    const uint32_t inc = small_group_incl_scan_add(c, LT);
+    if (c) {
+      int slot = base_i + (int)(rk[(4 * q) >> tws] + inc - c);
+      const uint32_t ww[4] = {wd.x, wd.y, wd.z, wd.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        uint32_t word = ww[k];
+        while (word) {
+          const int b = __ffs(word) - 1;
+          ad.as_ids[slot] = (4 * q + k) * 32 + b;
+          ad.as_lab[slot] = 0;
+          ++slot;
+          word &= word - 1;
+        }
       }
     }
   }
@@ -248,7 +260,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       bool found;
       if (in_lds) {                                      // rank of the label in the bitmap = its slot
         const int w = y >> 5, w0 = w & ~(ad.TW - 1);
-        a = (int)rk[w / ad.TW] + __popc(bm[w] & ((1u << (y & 31)) - 1u));
+        a = (int)rk[w >> tws] + __popc(bm[w] & ((1u << (y & 31)) - 1u));
         for (int q = w0; q < w; ++q) a += __popc(bm[q]);
         found = (bm[w] >> (y & 31)) & 1u;
       } else {

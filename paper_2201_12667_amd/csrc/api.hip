@@ -53,7 +53,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   if (c->hidden_dim < 4 || c->hidden_dim > 2048 || c->hidden_dim % 4) FAIL(SLIDE_EINVAL, "hidden_dim must be a multiple of 4 in [4, 2048]");
   if (c->num_classes < 1 || c->num_classes > (int64_t)1 << 30) FAIL(SLIDE_EINVAL, "num_classes out of range");
   if (c->input_dim < 0 || c->input_dim > (int64_t)1 << 30) FAIL(SLIDE_EINVAL, "input_dim out of range");
-  if (c->max_batch < 1 || c->max_batch > 4096) FAIL(SLIDE_EINVAL, "max_batch must be in [1, 4096]");
+  if (c->max_batch < 1 || c->max_batch > 2048) FAIL(SLIDE_EINVAL, "max_batch must be in [1, 2048]");
   if (c->K < 1 || c->L < 1 || c->L > 65535) FAIL(SLIDE_EINVAL, "K and L must be positive (L <= 65535)");
   if (c->bucket_cap < 1 || c->bucket_cap > 1024) FAIL(SLIDE_EINVAL, "bucket_cap must be in [1, 1024]");
   if (c->max_labels_per_batch < 0 || c->max_nnz_per_batch < 0) FAIL(SLIDE_EINVAL, "negative batch capacity");
@@ -81,7 +81,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->Bmax = c->max_batch;
   lo->Bpad = (c->max_batch + 63) & ~63;
   int tw = 32;
-  while (tw > 1 && tw * lo->Bpad > 8192) tw >>= 1;
+  while (tw > 4 && tw * lo->Bpad > 8192) tw >>= 1;
   lo->TW = tw;
   lo->TWF = tw;
   lo->NWpad = (int)(((lo->N + 31) / 32 + 31) / 32 * 32);

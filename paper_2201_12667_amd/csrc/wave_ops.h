@@ -71,6 +71,17 @@ __device__ __forceinline__ uint32_t group_incl_scan_add(uint32_t v, int G) {
   }
   return v;
 }
+// The same for G <= 8 (1, 2, 4 or 8), in register moves only.
+__device__ __forceinline__ uint32_t small_group_incl_scan_add(uint32_t v, int G) {
+  const int p = threadIdx.x & (G - 1);
+  uint32_t t = dpp_u32<kDppRowShr + 1>(0u, v);
+  if (p >= 1) v += t;
+  t = dpp_u32<kDppRowShr + 2>(0u, v);
+  if (p >= 2) v += t;
+  t = dpp_u32<kDppRowShr + 4>(0u, v);
+  if (p >= 4) v += t;
+  return v;
+}
 // Sum over aligned groups of G lanes, valid in the LAST lane of each group.
 __device__ __forceinline__ uint32_t group_sum_last(uint32_t v, int G) { return group_incl_scan_add(v, G); }
 
