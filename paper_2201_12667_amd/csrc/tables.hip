@@ -11,6 +11,7 @@
 // bits in LDS, writes that partition's offsets, places the ids, and sorts the small buckets in
 // place; (4) buckets that are long or over capacity are queued and handled by one workgroup each.
 #include "slide_internal.h"
+#include "wave_ops.h"
 
 namespace slide {
 
@@ -127,75 +128,133 @@ __global__ __launch_bounds__(1024) void part_scan_kernel(uint32_t* bh, int nslab
   if (t == 0 && tid == 0) { ctrl->wl_count = 0; ctrl->overflowed = 0; }
 }
 
+// One workgroup per (slab, table): the slab's (code, row) entries are first grouped by partition in
+// LDS (a local counting sort), then written out, so that every partition receives one contiguous
+// run per slab instead of single 8-byte entries.
 __global__ __launch_bounds__(1024) void part_scatter_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,
                                                             int nbins, const uint32_t* __restrict__ bh, int nslab,
                                                             const uint32_t* __restrict__ pbase,
                                                             uint2* __restrict__ entries) {
-  extern __shared__ uint32_t cur[];
+  extern __shared__ uint32_t lds[];
+  uint2* stage = (uint2*)lds;                      // [kSlab] entries grouped by partition
+  uint32_t* lstart = lds + 2 * kSlab;              // [nbins] first staged entry of the partition
+  uint32_t* cur = lstart + nbins;                  // [nbins] counters, then cursors
+  uint32_t* gbase = cur + nbins;                   // [nbins] where the partition's run goes in the table's entries
+  uint32_t* sm = gbase + nbins;                    // [20]
   const int slab = blockIdx.x, tid = threadIdx.x;
   const size_t t = blockIdx.y;
-  for (int b = tid; b < nbins; b += 1024) cur[b] = pbase[t * (nbins + 1) + b] + bh[(t * nslab + slab) * nbins + b];
+  for (int b = tid; b < nbins; b += 1024) {
+    cur[b] = 0;
+    gbase[b] = pbase[t * (nbins + 1) + b] + bh[(t * nslab + slab) * nbins + b];
+  }
   __syncthreads();
   const int64_t j0 = (int64_t)slab * kSlab;
+  const int nvalid = (int)(N - j0 < kSlab ? N - j0 : kSlab);
+  uint32_t code[kSlab / 1024];
+#pragma unroll
   for (int k = 0; k < kSlab / 1024; ++k) {
-    const int64_t j = j0 + k * 1024 + tid;
-    if (j < N) {
-      const uint32_t code = codes_t[t * N + j];
-      const uint32_t pos = atomicAdd(&cur[code >> lb], 1u);
-      entries[t * N + pos] = make_uint2(code, (uint32_t)j);
-    }
+    const int r = k * 1024 + tid;
+    code[k] = r < nvalid ? codes_t[t * N + j0 + r] : 0u;
+    if (r < nvalid) atomicAdd(&cur[code[k] >> lb], 1u);
+  }
+  __syncthreads();
+  uint32_t carry = 0;
+  for (int base = 0; base < nbins; base += 1024) {
+    const int b = base + tid;
+    const uint32_t v = b < nbins ? cur[b] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_excl_scan1024(v, sm, &total);
+    if (b < nbins) lstart[b] = carry + ex;
+    carry += total;
+    __syncthreads();
+  }
+  for (int b = tid; b < nbins; b += 1024) cur[b] = lstart[b];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kSlab / 1024; ++k) {
+    const int r = k * 1024 + tid;
+    if (r < nvalid) stage[atomicAdd(&cur[code[k] >> lb], 1u)] = make_uint2(code[k], (uint32_t)(j0 + r));
+  }
+  __syncthreads();
+  uint2* out = entries + t * N;
+  for (int k = tid; k < nvalid; k += 1024) {
+    const uint2 e = stage[k];
+    const uint32_t p = e.x >> lb;
+    out[gbase[p] + ((uint32_t)k - lstart[p])] = e;
   }
 }
 
-// One workgroup per (partition d, table t): buckets (d << lb) .. (d << lb) + 2^lb - 1.
+constexpr int kStageIds = 4096;    // ids of a partition staged in LDS by part_buckets (larger partitions go through memory)
+constexpr int kLdsSort = 32;       // buckets up to this size are sorted by one thread while staged in LDS
+
+// One workgroup per (partition d, table t): buckets (d << lb) .. (d << lb) + 2^lb - 1.  Counts the
+// low digit, writes the partition's offsets, groups the ids by bucket -- in LDS when the partition
+// fits, so that the table receives whole lines -- and sorts the small buckets; long and
+// over-capacity buckets are queued.
 __global__ __launch_bounds__(256) void part_buckets_kernel(const uint2* __restrict__ entries,
                                                            const uint32_t* __restrict__ pbase, int nbins, int lb,
                                                            uint32_t nb, int64_t N, int C, uint32_t* __restrict__ off,
                                                            int32_t* ids, uint64_t* worklist, uint32_t wl_cap,
                                                            Ctrl* ctrl) {
   extern __shared__ uint32_t lds[];
-  const int nlo = 1 << lb, tid = threadIdx.x;
-  uint32_t* start = lds;                 // [nlo + 1] first position of each bucket inside the partition
-  uint32_t* cur = lds + nlo + 1;         // [nlo] counters, then cursors
-  uint32_t* sm = cur + nlo;              // [8]
+  const int nlo = 1 << lb, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nchunk = (nlo + 63) >> 6;    // 64 buckets per scan chunk
+  uint32_t* cur = lds;                   // [nlo] counters, then bucket starts, then (after placing) bucket ends
+  uint32_t* csum = cur + nlo;            // [nchunk] ids in the chunk, then in the chunks before it
+  int32_t* idl = (int32_t*)(csum + nchunk);   // [kStageIds] the partition's ids grouped by bucket
   const uint32_t d = blockIdx.x;
   const size_t t = blockIdx.y;
   const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
   const uint32_t mask = (uint32_t)nlo - 1u;
   const uint2* ent = entries + t * N;
+  const bool staged = s1 - s0 <= (uint32_t)kStageIds;
   for (int b = tid; b < nlo; b += 256) cur[b] = 0;
   __syncthreads();
   for (uint32_t e = s0 + tid; e < s1; e += 256) atomicAdd(&cur[ent[e].x & mask], 1u);
   __syncthreads();
-  uint32_t carry = 0;
-  for (int base = 0; base < nlo; base += 256) {
-    const int b = base + tid;
+  // exclusive scan of the counters: every wave scans chunks of 64 in registers, wave 0 the chunk sums
+  for (int c = wave; c < nchunk; c += 4) {
+    const int b = c * 64 + lane;
     const uint32_t v = b < nlo ? cur[b] : 0u;
-    uint32_t total;
-    const uint32_t ex = block_excl_scan256(v, sm, &total);
-    if (b < nlo) start[b] = carry + ex;
-    carry += total;
-    __syncthreads();
+    const uint32_t inc = wave_incl_scan_add(v);
+    if (b < nlo) cur[b] = inc - v;
+    if (lane == 63) csum[c] = inc;
   }
-  if (tid == 0) start[nlo] = carry;
+  __syncthreads();
+  if (wave == 0) {
+    uint32_t carry = 0;
+    for (int c0 = 0; c0 < nchunk; c0 += 64) {
+      const int c = c0 + lane;
+      const uint32_t v = c < nchunk ? csum[c] : 0u;
+      const uint32_t inc = wave_incl_scan_add(v);
+      if (c < nchunk) csum[c] = carry + inc - v;
+      carry += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+    }
+  }
   __syncthreads();
   uint32_t* orow = off + t * (nb + 1) + ((size_t)d << lb);
-  for (int b = tid; b < nlo; b += 256) { orow[b] = s0 + start[b]; cur[b] = start[b]; }
+  for (int b = tid; b < nlo; b += 256) {
+    const uint32_t st = cur[b] + csum[b >> 6];
+    cur[b] = st;
+    orow[b] = s0 + st;
+  }
   if (d == (uint32_t)nbins - 1 && tid == 0) off[t * (nb + 1) + nb] = (uint32_t)N;
   __syncthreads();
   int32_t* seg = ids + t * N + s0;
+  int32_t* place = staged ? idl : seg;
   for (uint32_t e = s0 + tid; e < s1; e += 256) {
     const uint2 x = ent[e];
-    seg[atomicAdd(&cur[x.x & mask], 1u)] = (int32_t)x.y;
+    place[atomicAdd(&cur[x.x & mask], 1u)] = (int32_t)x.y;
   }
-  __syncthreads();
+  __syncthreads();                                  // cur[b] is now the end of bucket b = the start of bucket b + 1
+  const uint32_t small = staged ? (uint32_t)kLdsSort : (uint32_t)kSmallBucket;
   uint32_t over = 0;
   for (int b = tid; b < nlo; b += 256) {
-    const uint32_t a = start[b], sz = start[b + 1] - a;
+    const uint32_t a = b ? cur[b - 1] : 0u, sz = cur[b] - a;
     if (sz > (uint32_t)C) ++over;
     if (sz < 2) continue;
-    if (sz <= (uint32_t)kSmallBucket && sz <= (uint32_t)C) {
-      int32_t* p = seg + a;                       // arrival order is arbitrary: restore ascending ids
+    if (sz <= small && sz <= (uint32_t)C) {
+      int32_t* p = place + a;                     // arrival order is arbitrary: restore ascending ids
       for (uint32_t i = 1; i < sz; ++i) {
         const int32_t key = p[i];
         int q = (int)i - 1;
@@ -208,6 +267,10 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint2* __restri
     }
   }
   if (over) atomicAdd(&ctrl->overflowed, over);
+  if (staged) {
+    __syncthreads();
+    for (uint32_t k = tid; k < s1 - s0; k += 256) seg[k] = idl[k];
+  }
 }
 
 __device__ void bitonic_sort_u64(uint64_t* keys, int n) {
@@ -307,9 +370,18 @@ size_t tables_pbase_words(int bits, int64_t N, int L) {
   return (size_t)L * (((size_t)1 << hb) + 1);
 }
 
+static size_t part_buckets_lds(int lb) {
+  const size_t nlo = (size_t)1 << lb;
+  return (nlo + ((nlo + 63) >> 6) + kStageIds) * 4;
+}
+static size_t part_scatter_lds(int nbins) { return ((size_t)2 * kSlab + 3 * (size_t)nbins + 20) * 4; }
+
 hipError_t tables_setup_attributes() {
-  return hipFuncSetAttribute((const void*)part_buckets_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (2 * 8192 + 16) * 4);
+  hipError_t e = hipFuncSetAttribute((const void*)part_buckets_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)part_buckets_lds(13));
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)part_scatter_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)part_scatter_lds(2048));
 }
 
 hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
@@ -326,9 +398,9 @@ hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const flo
   hipLaunchKernelGGL(part_hist_kernel, dim3(nslab, td.L), dim3(1024), (size_t)nbins * 4, s, codes_t, td.N, lb, nbins,
                      bh, nslab);
   hipLaunchKernelGGL(part_scan_kernel, dim3(td.L), dim3(1024), 0, s, bh, nslab, nbins, pbase, ctrl);
-  hipLaunchKernelGGL(part_scatter_kernel, dim3(nslab, td.L), dim3(1024), (size_t)nbins * 4, s, codes_t, td.N, lb,
+  hipLaunchKernelGGL(part_scatter_kernel, dim3(nslab, td.L), dim3(1024), part_scatter_lds(nbins), s, codes_t, td.N, lb,
                      nbins, bh, nslab, pbase, entries);
-  hipLaunchKernelGGL(part_buckets_kernel, dim3(nbins, td.L), dim3(256), (size_t)(2 * (1 << lb) + 16) * 4, s, entries,
+  hipLaunchKernelGGL(part_buckets_kernel, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb), s, entries,
                      pbase, nbins, lb, td.nb, td.N, td.C, td.off, td.ids, worklist, wl_cap, ctrl);
   hipLaunchKernelGGL(big_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, td.C, policy,
                      r, prio_a, prio_b, worklist, wl_cap, ctrl);
