@@ -89,6 +89,15 @@ def test_degenerate_tables_all_rows_identical():
                                 input_dim=400, nnz_mean=6.0, feat_zipf_s=None, lab_zipf_s=None)),
     ("h200", synth.small(synth.HASH_DWTA, hidden_dim=200, K=3, L=13, batch=33, num_classes=4099,
                          input_dim=1200)),
+    # larger batches: tiles of 512, 256 and 128 rows in the row-list construction
+    ("b300-tile512", synth.small(synth.HASH_DWTA, hidden_dim=64, K=3, L=9, batch=300, num_classes=6007,
+                                 input_dim=2900, nnz_mean=8.0, bucket_cap=8)),
+    ("b600-tile256", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=6, L=7, batch=600, num_classes=5003,
+                                 input_dim=1900, nnz_mean=6.0, bucket_cap=8)),
+    ("b1100-tile128", synth.small(synth.HASH_DWTA, hidden_dim=32, K=3, L=5, batch=1100, num_classes=4001,
+                                  input_dim=700, nnz_mean=5.0, bucket_cap=8)),
+    ("b2048-tile128", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=5, L=4, batch=2048, num_classes=3001,
+                                  input_dim=0, bucket_cap=8)),
 ])
 def test_single_step_from_identical_state(name, wl):
     _say("step", name)
