@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslide_hip.so")
-SOURCES = ["api.hip", "hash.hip", "tables.hip", "active.hip", "output.hip", "update.hip"]
+SOURCES = ["api.hip", "hash.hip", "tables.hip", "active.hip", "output.hip", "update.hip", "predict.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -21,11 +21,12 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   // derived sizes
   int Bmax, Bpad, H, L, K, C, TW, TWF, NWpad, NT, NT2, NT1, DWpad, bits, PS;
+  int64_t dense_chunk;   // neurons per chunk of the dense prediction pass
   int64_t N, D, Amax, max_chunks, U2max, U1max, P1max, long2, long1;
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, xse, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, xse, zc, best, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -110,6 +111,9 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->ctrl = take(sizeof(Ctrl));
   lo->hashw = take(lo->hash_words * 4);
   lo->xse = take(lo->D ? B * lo->NT1 * 8 : 0);
+  lo->dense_chunk = dense_chunk_neurons(lo->N, lo->Bmax);
+  lo->zc = take(B * (size_t)lo->dense_chunk * 4);
+  lo->best = take(B * 64 * 8);
   lo->h = take(lo->D ? B * H * 4 : 0);
   lo->dh = take(B * H * 4);
   lo->codes = take(B * lo->L * 4);
@@ -464,10 +468,28 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
   if (!ctx) return SLIDE_EINVAL;
   if (!ctx->built) return set_err(ctx, SLIDE_ESTATE, "slide_build_tables must run before slide_predict");
   if (topk < 1 || topk > 64 || !d_out_ids || !d_out_scores) return set_err(ctx, SLIDE_EINVAL, "topk must be in [1, 64] and outputs non-NULL");
-  if (mode != 0) return set_err(ctx, SLIDE_EINVAL, "only mode 0 (scores over the retrieved neurons) is available");
+  if (mode != 0 && mode != 1) return set_err(ctx, SLIDE_EINVAL, "mode must be 0 (retrieved neurons) or 1 (all neurons)");
   int rc = check_batch(ctx, b, false);
   if (rc != SLIDE_OK) return rc;
   hipStream_t s = (hipStream_t)hip_stream;
+  if (mode == 1) {
+    const Layout& lo = ctx->lo;
+    const float* h = b->hidden;
+    if (lo.D > 0) {
+      float* hw = ctx->at<float>(lo.h);
+      HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] {
+        return launch_spmm_relu(b->batch, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
+                                ctx->buf.b1, hw, ctx->at<int2>(lo.xse), lo.TWF * 32, ctx->ctrl(), s); }));
+      HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(lo.xse), (size_t)b->batch * lo.NT1 * 2, 0u, s));
+      h = hw;
+    }
+    ctx->last_h = h;
+    ctx->last_B = b->batch;
+    ctx->last_dh = nullptr;
+    HIPCHK(ctx, launch_dense_topk(b->batch, lo.N, lo.H, h, ctx->buf.W2, ctx->buf.b2, topk, ctx->at<float>(lo.zc),
+                                  lo.dense_chunk, ctx->at<uint64_t>(lo.best), d_out_ids, d_out_scores, s));
+    return SLIDE_OK;
+  }
   ActiveDev ad;
   if ((rc = forward_common(ctx, b, false, s, &ad, TransposeArgs{}, TransposeArgs{})) != SLIDE_OK) return rc;
   if (ctx->lo.D > 0)   // the feature segments are only consumed by training: clear them again

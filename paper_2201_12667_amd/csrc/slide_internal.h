@@ -139,8 +139,14 @@ hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const floa
                           float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s);
 hipError_t launch_topk(const ActiveDev& ad, const float* z, int topk, int32_t* out_ids,
                        float* out_scores, hipStream_t s);
-hipError_t launch_dense_topk(int B, int64_t N, int H, const float* h, const float* W2, const float* b2,
-                             int topk, int32_t* out_ids, float* out_scores, hipStream_t s);
+
+// ---- predict.hip ----------------------------------------------------------------------
+// Scores over all N neurons in chunks of `chunk` neurons (zc: [B][chunk] scratch) and the topk best
+// per sample (best: [B][64] scratch keys).
+int64_t dense_chunk_neurons(int64_t N, int Bmax);
+hipError_t launch_dense_topk(int B, int64_t N, int H, const float* h, const float* W2, const float* b2, int topk,
+                             float* zc, int64_t chunk, uint64_t* best, int32_t* out_ids, float* out_scores,
+                             hipStream_t s);
 
 // ---- update.hip -----------------------------------------------------------------------
 // Rows of one weight matrix to update: for every listed row r, g = sum over its pairs of

@@ -107,3 +107,35 @@ def compare_step(model, orc, batch, check_state=True):
 def assert_ok(res):
     bad = {k: v for k, v in res.items() if not k.startswith("_") and not (v <= 1.0)}
     assert not bad, bad
+
+
+# ---- a synthetic task with planted structure (prediction-quality tests) -----------------------
+def planted_workload(num_classes=500, lr=5e-3):
+    """Small DWTA model for the planted task below: 64 buckets per table, rebuilt every 20 steps."""
+    return synth.small(synth.HASH_DWTA, num_classes=num_classes, input_dim=800, hidden_dim=64, K=2, L=16,
+                       bucket_cap=64, batch=128, rebuild_every=20, lr=lr, nnz_mean=8.0)
+
+
+def planted_prototypes(wl, per_class=6):
+    """Every class owns a fixed set of features; a sample of the class shows them plus noise."""
+    return np.stack([np.random.default_rng([1, c]).choice(wl.input_dim, size=per_class, replace=False)
+                     for c in range(wl.num_classes)])
+
+
+def planted_batch(wl, protos, step, noise=2, seed=0):
+    """One batch: a uniformly drawn class per sample (its single label), the class's features plus
+    `noise` random ones, equal values with unit norm.  Returns (batch dict, labels)."""
+    rng = np.random.default_rng([seed, 77, step])
+    labels = rng.integers(0, wl.num_classes, size=wl.batch)
+    xp, xi, xv = [0], [], []
+    for c in labels:
+        f = set(protos[c].tolist())
+        f.update(rng.integers(0, wl.input_dim, size=noise).tolist())
+        f = np.array(sorted(f), dtype=np.int32)
+        xi.append(f)
+        xv.append(np.full(f.size, 1.0 / np.sqrt(f.size), dtype=np.float32))
+        xp.append(xp[-1] + f.size)
+    batch = dict(batch=wl.batch, x_indptr=np.array(xp, np.int32), x_indices=np.concatenate(xi),
+                 x_values=np.concatenate(xv), y_indptr=np.arange(wl.batch + 1, dtype=np.int32),
+                 y_indices=labels.astype(np.int32))
+    return batch, labels

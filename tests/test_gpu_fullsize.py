@@ -45,3 +45,37 @@ def test_full_size_step(i):
          {k: round(v, 3) for k, v in res.items() if not k.startswith("_")}, res["_loss"], model.stats())
     assert_ok(res)
     model.destroy()
+
+
+@pytest.mark.timeout(600)
+def test_full_size_prediction_over_all_neurons():
+    """cfg2 (670K-class): top-5 over all neurons for the whole batch; sampled samples are checked
+    against the oracle's double-precision scores, every sample against the properties that hold at
+    any size (distinct valid ids, scores descending)."""
+    from helpers import FLOOR, REL
+    wl = synth.config(2)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    b = gen.batch(0)
+    db = model.to_device(b)
+    ids, sc = model.predict(db, 5, mode=1)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for _ in range(3):
+        ids, sc = model.predict(db, 5, mode=1)
+    torch.cuda.synchronize()
+    _say("  dense prediction over", wl.num_classes, "neurons x", wl.batch, "samples:",
+         round((time.time() - t0) / 3 * 1e3, 2), "ms")
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    assert ids.min() >= 0 and ids.max() < wl.num_classes
+    assert all(len(set(r.tolist())) == 5 for r in ids)
+    assert np.all(np.diff(sc, axis=1) <= 0)
+    h = orc.forward_hidden(b).astype(np.float64)
+    W2, b2 = orc.p["W2"].astype(np.float64), orc.p["b2"].astype(np.float64)
+    for i in np.random.default_rng(3).choice(wl.batch, size=6, replace=False):
+        z = W2 @ h[i] + b2
+        order = np.lexsort((np.arange(z.size), -z))[:5]
+        tol = REL * np.abs(z[order]) + FLOOR * np.abs(z).max()
+        assert np.all(np.abs(sc[i] - z[order]) <= tol), (i, sc[i], z[order])
+        assert np.all(np.abs(z[ids[i]] - z[order]) <= 2 * tol)
+    model.destroy()
