@@ -21,7 +21,10 @@ __device__ __forceinline__ void adam1(float& w, float& m, float& v, float g, con
 }
 
 // Gradient of one row from its pair list, pairs first, first + stride, ... (this lane group's share).
-template <int LPR, int CH, int UNR>
+// Every load is unconditional (lanes past the end of their list read pair 0 of the list, sample 0,
+// and select zero afterwards), so that all of a step's loads are in flight together.  FULL: the
+// lane groups cover the vector exactly (H == LPR*CH*4), no column test.
+template <int LPR, int CH, int UNR, bool FULL>
 __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd, const float* __restrict__ coef,
                                              const float* __restrict__ V, uint32_t st, int cn, int first,
                                              int stride, float4 (&g)[CH], float& gb) {
@@ -31,24 +34,25 @@ __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd,
 #pragma unroll
     for (int a = 0; a < UNR; ++a) {
       const bool ok = q + a * stride < cn;
-      const int2 pr = ok ? pd.pairs[st + q + a * stride] : make_int2(0, 0);
-      const int si = pr.x;
-      d[a] = ok ? coef[pr.y] : 0.f;
+      const int2 pr = pd.pairs[st + (ok ? q + a * stride : 0)];
+      const int si = ok ? pr.x : 0;
+      const float dv = coef[ok ? pr.y : 0];
+      d[a] = ok ? dv : 0.f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col = (c * LPR + sub) * 4;
-        hv[a][c] = (ok && col < H) ? *(const float4*)(V + (size_t)si * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const bool cok = FULL || col < H;
+        const float4 x = *(const float4*)(V + (size_t)si * H + (cok ? col : 0));
+        hv[a][c] = cok ? x : make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
 #pragma unroll
     for (int a = 0; a < UNR; ++a) {
-      if (q + a * stride < cn) {
-        gb += d[a];
+      gb += d[a];
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-          g[c].x += d[a] * hv[a][c].x; g[c].y += d[a] * hv[a][c].y;
-          g[c].z += d[a] * hv[a][c].z; g[c].w += d[a] * hv[a][c].w;
-        }
+      for (int c = 0; c < CH; ++c) {
+        g[c].x += d[a] * hv[a][c].x; g[c].y += d[a] * hv[a][c].y;
+        g[c].z += d[a] * hv[a][c].z; g[c].w += d[a] * hv[a][c].w;
       }
     }
   }
@@ -60,7 +64,7 @@ __device__ __forceinline__ void row_gradient(int H, int sub, const PairsDev& pd,
 // RPW lane groups accumulate interleaved shares of the list, added in a fixed butterfly order), by
 // a whole workgroup each when a row fills a wave (the waves accumulate interleaved shares, added in
 // wave order through LDS).
-template <int LPR, int CH, int UNR>
+template <int LPR, int CH, int UNR, bool FULL>
 __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int block, int nblocks) {
   const PairsDev& pd = ru.pd;
   const float* __restrict__ coef = ru.coef;
@@ -91,24 +95,29 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
     const int j = valid ? meta.x : 0;
     const size_t ro = (size_t)j * H;
     const uint32_t st = (uint32_t)meta.y;
-    float4 w[CH], m[CH], v[CH], g[CH];
+    // the gradient first (few registers live, so that many waves fit and cover its chain of
+    // dependent reads: header -> pairs -> coefficients and vectors), then the row itself
+    float4 g[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    float gb = 0.f;
+    row_gradient<LPR, CH, UNR, FULL>(H, sub, pd, coef, V, st, cn, 0, 1, g, gb);
+    if (!valid) continue;
+    asm volatile("" ::: "memory");                       // keep the row's loads behind the gradient loop
+    float4 w[CH], m[CH], v[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       const int col = (c * LPR + sub) * 4;
-      g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (valid && col < H) {
+      if (FULL || col < H) {
         w[c] = *(const float4*)(W + ro + col);
         m[c] = *(const float4*)(M + ro + col);
         v[c] = *(const float4*)(Vv + ro + col);
       }
     }
-    float gb = 0.f;
-    row_gradient<LPR, CH, UNR>(H, sub, pd, coef, V, st, cn, 0, 1, g, gb);
-    if (!valid) continue;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       const int col = (c * LPR + sub) * 4;
-      if (col < H) {
+      if (FULL || col < H) {
         adam1(w[c].x, m[c].x, v[c].x, g[c].x, ad); adam1(w[c].y, m[c].y, v[c].y, g[c].y, ad);
         adam1(w[c].z, m[c].z, v[c].z, g[c].z, ad); adam1(w[c].w, m[c].w, v[c].w, g[c].w, ad);
         *(float4*)(W + ro + col) = w[c];
@@ -134,19 +143,11 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
       const int j = meta.x, cn = meta.z;
       const size_t ro = (size_t)j * H;
       const uint32_t st = (uint32_t)meta.y;
-      float4 w[CH], m[CH], v[CH], g[CH];
+      float4 g[CH];
 #pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        const int col = (c * LPR + sub) * 4;
-        g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (wv == 0 && col < H) {
-          w[c] = *(const float4*)(W + ro + col);
-          m[c] = *(const float4*)(M + ro + col);
-          v[c] = *(const float4*)(Vv + ro + col);
-        }
-      }
+      for (int c = 0; c < CH; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
       float gb = 0.f;
-      row_gradient<LPR, CH, 2 * UNR>(H, sub, pd, coef, V, st, cn, wv, NW, g, gb);
+      row_gradient<LPR, CH, 2 * UNR, FULL>(H, sub, pd, coef, V, st, cn, wv, NW, g, gb);
       if (wv > 0) {
 #pragma unroll
         for (int c = 0; c < CH; ++c) part[wv - 1][c][lane] = g[c];
@@ -154,6 +155,16 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
       }
       __syncthreads();
       if (wv == 0) {
+        float4 w[CH], m[CH], v[CH];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const int col = (c * LPR + sub) * 4;
+          if (FULL || col < H) {
+            w[c] = *(const float4*)(W + ro + col);
+            m[c] = *(const float4*)(M + ro + col);
+            v[c] = *(const float4*)(Vv + ro + col);
+          }
+        }
         for (int k = 0; k < NW - 1; ++k) {
           gb += partb[k];
 #pragma unroll
@@ -165,7 +176,7 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
           const int col = (c * LPR + sub) * 4;
-          if (col < H) {
+          if (FULL || col < H) {
             adam1(w[c].x, m[c].x, v[c].x, g[c].x, ad); adam1(w[c].y, m[c].y, v[c].y, g[c].y, ad);
             adam1(w[c].z, m[c].z, v[c].z, g[c].z, ad); adam1(w[c].w, m[c].w, v[c].w, g[c].w, ad);
             *(float4*)(W + ro + col) = w[c];
@@ -189,19 +200,11 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
     const int j = meta.x, cn = meta.z;
     const size_t ro = (size_t)j * H;
     const uint32_t st = (uint32_t)meta.y;
-    float4 w[CH], m[CH], v[CH], g[CH];
+    float4 g[CH];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int col = (c * LPR + sub) * 4;
-      g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (grp == 0 && col < H) {
-        w[c] = *(const float4*)(W + ro + col);
-        m[c] = *(const float4*)(M + ro + col);
-        v[c] = *(const float4*)(Vv + ro + col);
-      }
-    }
+    for (int c = 0; c < CH; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     float gb = 0.f;
-    row_gradient<LPR, CH, UNR>(H, sub, pd, coef, V, st, cn, grp, RPW, g, gb);
+    row_gradient<LPR, CH, UNR, FULL>(H, sub, pd, coef, V, st, cn, grp, RPW, g, gb);
 #pragma unroll
     for (int d = LPR; d < 64; d <<= 1) {
       gb += __shfl_xor(gb, d);
@@ -212,10 +215,20 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
       }
     }
     if (grp != 0) continue;
+    float4 w[CH], m[CH], v[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       const int col = (c * LPR + sub) * 4;
-      if (col < H) {
+      if (FULL || col < H) {
+        w[c] = *(const float4*)(W + ro + col);
+        m[c] = *(const float4*)(M + ro + col);
+        v[c] = *(const float4*)(Vv + ro + col);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int col = (c * LPR + sub) * 4;
+      if (FULL || col < H) {
         adam1(w[c].x, m[c].x, v[c].x, g[c].x, ad); adam1(w[c].y, m[c].y, v[c].y, g[c].y, ad);
         adam1(w[c].z, m[c].z, v[c].z, g[c].z, ad); adam1(w[c].w, m[c].w, v[c].w, g[c].w, ad);
         *(float4*)(W + ro + col) = w[c];
@@ -303,8 +316,13 @@ __global__ __launch_bounds__(kUpdateThreads) void update_kernel(int H, RowUpdate
   if (blk < fin.nblocks) { finish_role(H, fin, ad, blk); return; }
   blk -= fin.nblocks;
   // every other workgroup takes its share of both row lists (their sizes are known on the device only)
-  if (in.nblocks) rowgrad_adam<LPR, CH, UNR>(H, in, ad, blk, out.nblocks);
-  rowgrad_adam<LPR, CH, UNR>(H, out, ad, blk, out.nblocks);
+  if (H == LPR * CH * 4) {                               // the lane groups cover the vector exactly
+    if (in.nblocks) rowgrad_adam<LPR, CH, UNR, true>(H, in, ad, blk, out.nblocks);
+    rowgrad_adam<LPR, CH, UNR, true>(H, out, ad, blk, out.nblocks);
+  } else {
+    if (in.nblocks) rowgrad_adam<LPR, CH, UNR, false>(H, in, ad, blk, out.nblocks);
+    rowgrad_adam<LPR, CH, UNR, false>(H, out, ad, blk, out.nblocks);
+  }
 }
 
 template <int LPR, int CH, int UNR>
