@@ -106,7 +106,7 @@ hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_
 constexpr int kForwardThreads = 512;
 constexpr int kForwardBlocks = 768;    // logit workers
 
-template <int LPR, int CH>
+template <int LPR, int CH, bool FULL>
 __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const float* __restrict__ h, const float* __restrict__ W2,
                               const float* __restrict__ b2, float* __restrict__ z, float* __restrict__ partials,
                               const Ctrl* __restrict__ ctrl, int block, int nblocks) {
@@ -125,7 +125,7 @@ __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const 
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       const int col = (c * LPR + sub) * 4;
-      hv[c] = col < H ? *(const float4*)(h + (size_t)i * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+      hv[c] = (FULL || col < H) ? *(const float4*)(h + (size_t)i * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
       acc[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float M = -INFINITY, s = 0.f;
@@ -140,11 +140,10 @@ __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const 
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col = (c * LPR + sub) * 4;
-        row[c] = col < H ? *(const float4*)(wr + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+        row[c] = (FULL || col < H) ? *(const float4*)(wr + col) : make_float4(0.f, 0.f, 0.f, 0.f);
         dot += row[c].x * hv[c].x + row[c].y * hv[c].y + row[c].z * hv[c].z + row[c].w * hv[c].w;
       }
-#pragma unroll
-      for (int d = 1; d < LPR; d <<= 1) dot += __shfl_xor(dot, d);
+      dot = group_sum<LPR>(dot);
       const float zz = dot + b2[j];
       if (valid) {
         if (sub == 0) z[slot] = zz;
@@ -183,7 +182,7 @@ __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const 
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col = (c * LPR + sub) * 4;
-        if (col < H) *(float4*)(pp + 4 + col) = acc[c];
+        if (FULL || col < H) *(float4*)(pp + 4 + col) = acc[c];
       }
     }
   }
@@ -202,7 +201,10 @@ __global__ __launch_bounds__(kForwardThreads) void forward_kernel(ActiveDev ad, 
   // as workers without an item leave, the feature tiles (fewer, and with a global counter on their
   // critical path) before the active-set tiles.
   const int k = blockIdx.x;
-  if (k < kForwardBlocks) forward_items<LPR, CH>(ad, H, h, W2, b2, z, partials, ctrl, k, kForwardBlocks);
+  if (k < kForwardBlocks) {
+    if (H == LPR * CH * 4) forward_items<LPR, CH, true>(ad, H, h, W2, b2, z, partials, ctrl, k, kForwardBlocks);
+    else forward_items<LPR, CH, false>(ad, H, h, W2, b2, z, partials, ctrl, k, kForwardBlocks);
+  }
   else if (k < kForwardBlocks + t1.ntiles) transpose_tile<true>(t1, k - kForwardBlocks, dyn_lds);
   else transpose_tile<false>(t2, k - kForwardBlocks - t1.ntiles, dyn_lds);
 }

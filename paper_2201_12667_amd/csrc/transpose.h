@@ -19,7 +19,8 @@ namespace slide {
 //     sample) by the hidden-layer kernel and cleared here behind the read (all-zero = empty, ready
 //     for the next batch); pair space is handed out per workgroup.  The coefficient index is the
 //     position in the CSR arrays.
-// A thread owns a sample.  Pass 1 builds the transposed tile in LDS: one bit per (row, sample), set
+// A thread owns a sample (or, when the workgroup has more threads than samples, an interleaved
+// share of a sample's segment).  Pass 1 builds the transposed tile in LDS: one bit per (row, sample), set
 // with LDS atomics.  Lane = row then gives every row's pair count, the touched rows, every row's
 // position in the pair space and, inside it, where each group of 64 samples starts.  Pass 2 walks
 // the segments again; a pair's place in the row's list is the number of lower samples in the row's
@@ -50,14 +51,12 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
   __syncthreads();
 
   // segment of sample i inside this tile; rank0 = the sample's rank at the tile start (active sets)
-  auto segment = [&](int i, int& lo, int& hi, uint32_t& rank0, bool clear) {
+  auto segment = [&](int i, int& lo, int& hi, uint32_t& rank0) {
     lo = 0; hi = 0; rank0 = 0;
     if (i >= B) return;
     if (FEAT) {
-      int2* se = ta.xse + (size_t)tileno * B + i;
-      const int2 v = *se;
+      const int2 v = ta.xse[(size_t)tileno * B + i];
       lo = max(v.x, 0); hi = min(v.y, ta.x_nnz);
-      if (clear && (v.x | v.y)) *se = make_int2(0, 0);
     } else {
       const int base = ta.as_base[i];
       rank0 = ta.rankT[(size_t)tileno * B + i];
@@ -66,13 +65,16 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
   };
 
   // ---- pass 1: transposed tile -------------------------------------------------------------------
-  for (int i = tid; i < Bpad; i += blockDim.x) {
+  const int shares = max(1, (int)blockDim.x / Bpad);     // threads per sample
+  for (int idx = tid; idx < Bpad * shares; idx += blockDim.x) {
+    const int i = idx % Bpad, share = idx / Bpad;
     int lo, hi;
     uint32_t rank0;
-    segment(i, lo, hi, rank0, false);
+    segment(i, lo, hi, rank0);
+    if (share) rank0 = 0;
     uint32_t* tc = T + (size_t)(i >> 5) * ROWS;
     const uint32_t ibit = 1u << (i & 31);
-    for (int p = lo; p < hi; p += 4) {                   // four ids in flight
+    for (int p = lo + 4 * share; p < hi; p += 4 * shares) {   // four ids in flight
       int r[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
@@ -140,17 +142,18 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
   }
 
   // ---- pass 2: emit ----------------------------------------------------------------------------------
-  for (int i = tid; i < Bpad; i += blockDim.x) {
+  for (int idx = tid; idx < Bpad * shares; idx += blockDim.x) {
+    const int i = idx % Bpad, share = idx / Bpad;
     int lo, hi;
     uint32_t rank0;
-    segment(i, lo, hi, rank0, true);
+    segment(i, lo, hi, rank0);
     const int g = i >> 6;
     const uint32_t lo_mask = (i & 32) ? 0xffffffffu : ((1u << (i & 31)) - 1u);
     const uint32_t hi_mask = (i & 32) ? ((1u << (i & 31)) - 1u) : 0u;
     const uint32_t* t_lo = T + (size_t)(2 * g) * ROWS;
     const uint32_t* t_hi = t_lo + ROWS;
     const uint16_t* grp = rowgrp + (size_t)g * ROWS;
-    for (int p = lo; p < hi; p += 4) {
+    for (int p = lo + 4 * share; p < hi; p += 4 * shares) {
       int r[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
@@ -162,6 +165,14 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
                                __popc(t_hi[row] & hi_mask);
         pd.pairs[place] = make_int2(i, p + k);
       }
+    }
+  }
+  if (FEAT) {                                            // leave the segments all-zero for the next batch
+    __syncthreads();
+    for (int i = tid; i < B; i += blockDim.x) {
+      int2* se = ta.xse + (size_t)tileno * B + i;
+      const int2 v = *se;
+      if (v.x | v.y) *se = make_int2(0, 0);
     }
   }
   // few workgroups ever raise the maximum; the read is off the critical path here
