@@ -43,7 +43,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="0..4; 2 = the 670K-class model the metric is quoted on")
+    ap.add_argument("--config", type=int, default=2, help="0..7; 2 = the 670K-class model the metric is quoted on")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-steps", type=int, default=3, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--breakdown", action="store_true", help="also time every stage on extra steps")

@@ -82,7 +82,8 @@ class Workload:
 
 
 def config(i: int) -> Workload:
-    """The five benchmark configurations (0 = tiny plumbing run ... 4 = near-billion parameters)."""
+    """The five benchmark configurations (0 = tiny plumbing run ... 4 = near-billion parameters),
+    then shapes of the paper's other settings (5: second workload at batch 1024, 6-7: batch 2048)."""
     if i == 0:
         return Workload("cfg0-tiny", 1000, 32, 2000, 32, HASH_SIMHASH, 4, 8, 16, 5, lr=1e-3,
                         nnz_mode="exact", nnz_mean=20, feat_zipf_s=None, value_mode="uniform",
@@ -97,7 +98,17 @@ def config(i: int) -> Workload:
                         nnz_mean=42.0, lab_mean=3.0)
     if i == 4:
         return Workload("cfg4-825m", 135909, 1024, 670091, 512, HASH_DWTA, 8, 200, 256, 0)
-    raise ValueError("config index must be 0..4")
+    if i == 5:   # the paper's second workload (Section 4.1, Table 1): a word-embedding model, one
+        # input index per sample, 253,855 -> 200 -> 253,855; its K, L and C are not stated (taken
+        # from the sparse-random-projection setting above), word frequencies Zipfian
+        return Workload("cfg5-text8-shape", 253855, 200, 253855, 1024, HASH_SIMHASH, 9, 50, 128, 50,
+                        nnz_mode="exact", nnz_mean=1, feat_zipf_s=1.0, value_mode="uniform",
+                        lab_mode="exact", lab_mean=1, lab_zipf_s=1.0)
+    if i == 6:   # 670K-class shape at the paper's low-bandwidth cluster setting: hidden 256, batch 2048
+        return Workload("cfg6-670k-b2048-h256", 135909, 256, 670091, 2048, HASH_DWTA, 6, 400, 128, 50)
+    if i == 7:   # and at its large-batch setting: hidden 1024, batch 2048
+        return Workload("cfg7-670k-b2048-h1024", 135909, 1024, 670091, 2048, HASH_DWTA, 8, 200, 128, 0)
+    raise ValueError("config index must be 0..7")
 
 
 def small(kind: int = HASH_DWTA, **over) -> Workload:

@@ -22,7 +22,7 @@ def _say(*a):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("i", [1, 2, 3, 4])
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 5, 6])
 def test_full_size_step(i):
     wl = synth.config(i)
     t0 = time.time()
