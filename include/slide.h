@@ -146,6 +146,13 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
  * later explicit calls count as rebuilds. */
 int slide_build_tables(slide_ctx* ctx, void* hip_stream);
 
+/* Replaces the hash functions (Algorithm 1 rebuilds "hash tables and hash functions" on its
+ * schedule; the library draws no random numbers, so the caller supplies the new functions).
+ * Synchronises the stream, uploads the parameters, and marks the tables stale: slide_build_tables
+ * must run before the next slide_train_step / slide_predict; it counts as a rebuild.  Same
+ * validation and ownership as in slide_init (host arrays, copied). */
+int slide_set_hash_params(slide_ctx* ctx, const slide_hash_params* params, void* hip_stream);
+
 /* One training step on one batch, Algorithm 1's loop body: retrieve active neurons (hash the
  * hidden activations, read one bucket per table, union with the labels), feed forward over the
  * active set only, softmax errors, sparse backpropagation, Adam on the touched rows only, then

@@ -214,10 +214,8 @@ class SlideOracle:
         self.D, self.H, self.N = int(input_dim), int(hidden_dim), int(num_classes)
         self.C, self.R, self.policy = int(bucket_cap), int(rebuild_every), int(overflow_policy)
         self.lr, self.beta1, self.beta2, self.eps = float(lr), float(beta1), float(beta2), float(eps)
-        self.hp = dict(hash_params)
-        self.hash = HashFn(hash_kind, self.H, K, L, dwta_bin, self.hp.get("dwta_perm"),
-                           self.hp.get("srp_idx"), self.hp.get("srp_sign"),
-                           self.hp["dens_a"], self.hp["dens_b"])
+        self._hash_shape = (hash_kind, K, L, dwta_bin)
+        self.set_hash_params(hash_params)
         self.p = {k: np.array(v, dtype=np.float32, copy=True) for k, v in weights.items()}
         self.m = {k: np.zeros_like(v) for k, v in self.p.items()}
         self.v = {k: np.zeros_like(v) for k, v in self.p.items()}
@@ -228,6 +226,15 @@ class SlideOracle:
     @property
     def dense_hidden(self):
         return self.D == 0
+
+    def set_hash_params(self, hash_params):
+        """New hash functions (Algorithm 1 redraws them when it rebuilds the tables); the tables
+        must be rebuilt before the next step."""
+        kind, K, L, m = self._hash_shape
+        self.hp = dict(hash_params)
+        self.hash = HashFn(kind, self.H, K, L, m, self.hp.get("dwta_perm"), self.hp.get("srp_idx"),
+                           self.hp.get("srp_sign"), self.hp["dens_a"], self.hp["dens_b"])
+        self.tables = None
 
     def build_tables(self, first=True):
         """Tables over the rows of the current W2 (biases are not hashed)."""

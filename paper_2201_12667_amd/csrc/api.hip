@@ -154,6 +154,7 @@ struct slide_ctx {
   size_t lds_limit;
   int64_t t = 0, r = 0;
   bool built = false;
+  bool ever_built = false;       // a build has happened (later ones count as rebuilds)
   int last_B = 0;
   uint64_t calls = 0;            // forward passes launched (selects the set of per-call device accumulators)
   const float* last_h = nullptr;
@@ -298,29 +299,11 @@ int slide_query_memory(const slide_config* cfg, slide_mem_req* out) {
   return SLIDE_OK;
 }
 
-int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_hash_params* hp, slide_ctx** out) {
-  if (!out) return set_err(nullptr, SLIDE_EINVAL, "out is NULL");
-  *out = nullptr;
-  Layout lo;
-  std::string err;
-  int rc = make_layout(cfg, &lo, err);
-  if (rc != SLIDE_OK) { g_last_error = err; return rc; }
-  if (!buf || !hp) return set_err(nullptr, SLIDE_EINVAL, "buffers / hash params are NULL");
-  if (!buf->W2 || !buf->b2 || !buf->mW2 || !buf->vW2 || !buf->mb2 || !buf->vb2)
-    return set_err(nullptr, SLIDE_EINVAL, "output-layer parameter / Adam-state pointer is NULL");
-  if (cfg->input_dim > 0 && (!buf->W1 || !buf->b1 || !buf->mW1 || !buf->vW1 || !buf->mb1 || !buf->vb1))
-    return set_err(nullptr, SLIDE_EINVAL, "hidden-layer parameter / Adam-state pointer is NULL");
-  const void* al[] = {buf->W1, buf->W2, buf->mW1, buf->vW1, buf->mW2, buf->vW2, buf->b1, buf->workspace, buf->tables};
-  for (const void* p : al)
-    if (((uintptr_t)p) & 15) return set_err(nullptr, SLIDE_EINVAL, "device buffers must be 16-byte aligned");
-  if (!buf->tables || buf->tables_bytes < lo.tables_total)
-    return set_err(nullptr, SLIDE_ENOMEM, "tables buffer too small: %zu < %zu", buf->tables_bytes, lo.tables_total);
-  if (!buf->workspace || buf->workspace_bytes < lo.ws_total)
-    return set_err(nullptr, SLIDE_ENOMEM, "workspace too small: %zu < %zu", buf->workspace_bytes, lo.ws_total);
-
-  // hash-function parameters -> packed 16-bit coordinate words
+// Hash-function parameters -> packed 16-bit coordinate words (validated).
+static int pack_hash_params(const slide_config* cfg, const Layout& lo, const slide_hash_params* hp,
+                            std::vector<uint32_t>& words) {
   const int H = cfg->hidden_dim, NH = cfg->K * cfg->L;
-  std::vector<uint32_t> words(lo.hash_words, 0u);
+  words.assign(lo.hash_words, 0u);
   if (cfg->hash_kind == SLIDE_HASH_DWTA) {
     if (!hp->dwta_perm) return set_err(nullptr, SLIDE_EINVAL, "dwta_perm is NULL");
     const int m = cfg->dwta_bin, P = H / m;
@@ -355,6 +338,33 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   }
   if (!(hp->dens_a & 1u) || !(hp->dens_b & 1u) || !(hp->prio_a & 1u) || !(hp->prio_b & 1u))
     return set_err(nullptr, SLIDE_EINVAL, "dens_a, dens_b, prio_a, prio_b must be odd");
+
+  return SLIDE_OK;
+}
+
+int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_hash_params* hp, slide_ctx** out) {
+  if (!out) return set_err(nullptr, SLIDE_EINVAL, "out is NULL");
+  *out = nullptr;
+  Layout lo;
+  std::string err;
+  int rc = make_layout(cfg, &lo, err);
+  if (rc != SLIDE_OK) { g_last_error = err; return rc; }
+  if (!buf || !hp) return set_err(nullptr, SLIDE_EINVAL, "buffers / hash params are NULL");
+  if (!buf->W2 || !buf->b2 || !buf->mW2 || !buf->vW2 || !buf->mb2 || !buf->vb2)
+    return set_err(nullptr, SLIDE_EINVAL, "output-layer parameter / Adam-state pointer is NULL");
+  if (cfg->input_dim > 0 && (!buf->W1 || !buf->b1 || !buf->mW1 || !buf->vW1 || !buf->mb1 || !buf->vb1))
+    return set_err(nullptr, SLIDE_EINVAL, "hidden-layer parameter / Adam-state pointer is NULL");
+  const void* al[] = {buf->W1, buf->W2, buf->mW1, buf->vW1, buf->mW2, buf->vW2, buf->b1, buf->workspace, buf->tables};
+  for (const void* p : al)
+    if (((uintptr_t)p) & 15) return set_err(nullptr, SLIDE_EINVAL, "device buffers must be 16-byte aligned");
+  if (!buf->tables || buf->tables_bytes < lo.tables_total)
+    return set_err(nullptr, SLIDE_ENOMEM, "tables buffer too small: %zu < %zu", buf->tables_bytes, lo.tables_total);
+  if (!buf->workspace || buf->workspace_bytes < lo.ws_total)
+    return set_err(nullptr, SLIDE_ENOMEM, "workspace too small: %zu < %zu", buf->workspace_bytes, lo.ws_total);
+
+  std::vector<uint32_t> words;
+  if ((rc = pack_hash_params(cfg, lo, hp, words)) != SLIDE_OK) return rc;
+  const int H = cfg->hidden_dim, NH = cfg->K * cfg->L;
 
   slide_ctx* ctx = new slide_ctx();
   ctx->cfg = *cfg; ctx->buf = *buf; ctx->lo = lo;
@@ -394,10 +404,25 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
 
 int slide_build_tables(slide_ctx* ctx, void* hip_stream) {
   if (!ctx) return SLIDE_EINVAL;
-  if (ctx->built) ctx->r += 1;
+  if (ctx->ever_built) ctx->r += 1;
   const int rc = do_build(ctx, (hipStream_t)hip_stream);
-  if (rc == SLIDE_OK) ctx->built = true;
+  if (rc == SLIDE_OK) { ctx->built = true; ctx->ever_built = true; }
   return rc;
+}
+
+int slide_set_hash_params(slide_ctx* ctx, const slide_hash_params* hp, void* hip_stream) {
+  if (!ctx) return SLIDE_EINVAL;
+  if (!hp) return set_err(ctx, SLIDE_EINVAL, "hash params are NULL");
+  std::vector<uint32_t> words;
+  const int rc = pack_hash_params(&ctx->cfg, ctx->lo, hp, words);
+  if (rc != SLIDE_OK) { ctx->err = g_last_error; return rc; }
+  HIPCHK(ctx, hipStreamSynchronize((hipStream_t)hip_stream));   // nothing in flight may still read the old functions
+  if (!words.empty())
+    HIPCHK(ctx, hipMemcpy(ctx->ws() + ctx->lo.hashw, words.data(), words.size() * 4, hipMemcpyHostToDevice));
+  ctx->hd.dens_a = hp->dens_a; ctx->hd.dens_b = hp->dens_b;
+  ctx->prio_a = hp->prio_a; ctx->prio_b = hp->prio_b;
+  ctx->built = false;                                           // the tables belong to the old functions
+  return SLIDE_OK;
 }
 
 int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* hip_stream) {

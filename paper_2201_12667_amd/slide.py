@@ -20,7 +20,8 @@ ABI_VERSION = 1
 STAGES = ["hidden", "lookup", "forward", "combine", "update", "rebuild"]
 NUM_STAGES = len(STAGES)
 
-EXPORTS = ["slide_query_memory", "slide_init", "slide_build_tables", "slide_train_step", "slide_predict",
+EXPORTS = ["slide_query_memory", "slide_init", "slide_build_tables", "slide_set_hash_params", "slide_train_step",
+           "slide_predict",
            "slide_status", "slide_get_stats", "slide_profile", "slide_profile_read", "slide_reset_stats", "slide_destroy", "slide_last_error", "slide_debug_copy", "slide_debug_hash",
            "slide_debug_get_bucket", "slide_debug_get_active", "slide_debug_get_hidden"]
 
@@ -86,6 +87,7 @@ def load_library(path: str = LIB_PATH):
     L.slide_init.argtypes = [C.POINTER(slide_config), C.POINTER(slide_buffers), C.POINTER(slide_hash_params),
                              C.POINTER(vp)]
     L.slide_build_tables.argtypes = [vp, vp]
+    L.slide_set_hash_params.argtypes = [vp, vp, vp]
     L.slide_train_step.argtypes = [vp, C.POINTER(slide_batch), vp, vp]
     L.slide_predict.argtypes = [vp, C.POINTER(slide_batch), i32, i32, vp, vp, vp]
     L.slide_status.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
@@ -175,6 +177,15 @@ class Slide:
             setattr(b, "v" + n, self.v[n].data_ptr())
         b.tables, b.tables_bytes = self.tables.data_ptr(), req.tables_bytes
         b.workspace, b.workspace_bytes = self.workspace.data_ptr(), req.workspace_bytes
+        hp = self._hash_struct(hash_params)
+        self.ctx = C.c_void_p()
+        rc = self.L.slide_init(C.byref(cfg), C.byref(b), C.byref(hp), C.byref(self.ctx))
+        if rc:
+            raise SlideError(rc, self.L.slide_last_error(None).decode())
+        self._batch_keep = None
+
+    # ---- helpers ---------------------------------------------------------------------------
+    def _hash_struct(self, hash_params: dict):
         hp = slide_hash_params()
         self._keep = []
         for key, dt in (("dwta_perm", np.int32), ("srp_idx", np.int32), ("srp_sign", np.int8)):
@@ -184,13 +195,8 @@ class Slide:
                 setattr(hp, key, a.ctypes.data)
         hp.dens_a, hp.dens_b = hash_params["dens_a"], hash_params["dens_b"]
         hp.prio_a, hp.prio_b = hash_params["prio_a"], hash_params["prio_b"]
-        self.ctx = C.c_void_p()
-        rc = self.L.slide_init(C.byref(cfg), C.byref(b), C.byref(hp), C.byref(self.ctx))
-        if rc:
-            raise SlideError(rc, self.L.slide_last_error(None).decode())
-        self._batch_keep = None
+        return hp
 
-    # ---- helpers ---------------------------------------------------------------------------
     def _check(self, rc):
         if rc:
             raise SlideError(rc, self.L.slide_last_error(self.ctx).decode())
@@ -224,6 +230,10 @@ class Slide:
     # ---- the C ABI ---------------------------------------------------------------------------
     def build_tables(self):
         self._check(self.L.slide_build_tables(self.ctx, self._stream()))
+
+    def set_hash_params(self, hash_params: dict):
+        hp = self._hash_struct(hash_params)
+        self._check(self.L.slide_set_hash_params(self.ctx, C.byref(hp), self._stream()))
 
     def train_step(self, db: dict, dhidden_out=None):
         """Enqueues one step; returns the device tensor holding the loss (no synchronisation)."""

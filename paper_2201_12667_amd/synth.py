@@ -187,12 +187,12 @@ class Generator:
         out["b2"] = np.zeros(wl.num_classes, dtype=np.float32)
         return out
 
-    def hash_params(self) -> dict:
+    def hash_params(self, draw: int = 0) -> dict:
         """DWTA: ceil(NH / (H // m)) permutations of the H coordinates.
         SimHash: per bit, S distinct ascending coordinates and their signs.
         Plus the odd 32-bit multipliers of the densification probe and of the
-        bucket-overflow priority."""
-        wl, rng = self.wl, _rng(self.seed, _S_HASH)
+        bucket-overflow priority.  `draw` numbers the redraws (0 = the initial functions)."""
+        wl, rng = self.wl, _rng(self.seed, _S_HASH, draw)
         H, NH = wl.hidden_dim, wl.num_hashes
         out = {}
         if wl.hash_kind == HASH_DWTA:

@@ -247,3 +247,32 @@ def test_predict_mode0_matches_oracle(kind):
     res = compare_step(model, orc, gen.batch(1))
     assert_ok(res)
     model.destroy()
+
+
+@pytest.mark.parametrize("kind", [synth.HASH_DWTA, synth.HASH_SIMHASH])
+def test_redrawn_hash_functions_then_rebuild(kind):
+    """New hash functions at a rebuild (Algorithm 1): both sides get the same redraw; the tables
+    built from them are bit-identical, the rebuild is counted, and the next step matches."""
+    _say("redraw", kind)
+    from paper_2201_12667_amd import slide
+    wl = synth.small(kind, rebuild_every=0, bucket_cap=8)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    assert_ok(compare_step(model, orc, gen.batch(0)))
+    hp1 = gen.hash_params(draw=1)
+    model.set_hash_params(hp1)
+    with pytest.raises(slide.SlideError):                 # stale tables: a step must not run
+        model.train_step(model.to_device(gen.batch(1)))
+    orc.set_hash_params(hp1)
+    load_state(model, orc)
+    model.build_tables()
+    T = orc.build_tables(first=False)
+    assert model.stats()["rebuilds"] == orc.r == 1
+    for t in range(wl.L):
+        for c in range(wl.num_buckets):
+            assert np.array_equal(model.debug_bucket(t, c), T.bucket(t, c)), (t, c)
+    V = np.random.default_rng(2).standard_normal((50, wl.hidden_dim)).astype(np.float32)
+    assert np.array_equal(model.debug_hash(V), orc.hash.codes(V))
+    assert_ok(compare_step(model, orc, gen.batch(1)))
+    model.destroy()
