@@ -205,15 +205,80 @@ def adam_rows(W, M, V, ids, g, lr, beta1, beta2, eps, t):
 # --------------------------------------------------------------------------------------
 # the step
 # --------------------------------------------------------------------------------------
+# --------------------------------------------------------------------------------------
+# Sampling budget (Section 3.7: when the tables return more neurons than the budget, a uniform
+# random subset of the budget's size is kept -- the paper uses reservoir sampling; when they return
+# fewer, the rest of the budget may be filled with uniformly drawn neurons).  The labels are always
+# kept and do not count against the budget.  Random numbers come from a counter-based generator,
+# so the same (seed, step, sample, neuron / draw number) gives the same number anywhere:
+#   mix   = the 32-bit finaliser of MurmurHash3 (a bijection on 32-bit integers)
+#   base  = mix(seed + 0x9E3779B9 * step + 0x7F4A7C15 * sample)
+#   prio  = mix(base + 0x9E3779B1 * (neuron + 1))         distinct neurons -> distinct priorities
+#   draw  = floor(mix((base ^ 0xA5A5A5A5) + 0x632BE5AB * (d + 1)) * N / 2^32)
+# Kept subset = the `budget` retrieved non-label neurons of smallest priority.  Fill = draws
+# d = 0, 1, 2, ... in order, each accepted if not yet in the set, until the budget is reached or
+# 4 * budget + 64 draws are used.
+# --------------------------------------------------------------------------------------
+_M32 = np.uint64(0xFFFFFFFF)
+
+
+def sample_mix(x):
+    x = np.asarray(x, dtype=np.uint64) & _M32
+    x ^= x >> np.uint64(16)
+    x = (x * np.uint64(0x85EBCA6B)) & _M32
+    x ^= x >> np.uint64(13)
+    x = (x * np.uint64(0xC2B2AE35)) & _M32
+    x ^= x >> np.uint64(16)
+    return x
+
+
+def sample_base(seed, step, sample):
+    return sample_mix(np.uint64(seed) + np.uint64(0x9E3779B9) * np.uint64(step) + np.uint64(0x7F4A7C15) * np.uint64(sample))
+
+
+def sample_prio(base, neurons):
+    return sample_mix(np.uint64(base) + np.uint64(0x9E3779B1) * (np.asarray(neurons, dtype=np.uint64) + np.uint64(1)))
+
+
+def sample_draw(base, d, N):
+    x = sample_mix((np.uint64(base) ^ np.uint64(0xA5A5A5A5)) + np.uint64(0x632BE5AB) * (np.asarray(d, dtype=np.uint64) + np.uint64(1)))
+    return ((x * np.uint64(N)) >> np.uint64(32)).astype(np.int64)
+
+
+def apply_budget(cand, labels, N, budget, fill, seed, step, sample):
+    """cand: retrieved neurons (ascending, unique); labels: the sample's valid distinct labels.
+    Returns the non-label members of the active set after the budget rule, ascending."""
+    C_ = np.setdiff1d(np.asarray(cand, dtype=np.int64), np.asarray(labels, dtype=np.int64))
+    base = sample_base(seed, step, sample)
+    if C_.size > budget:
+        order = np.argsort(sample_prio(base, C_), kind="stable")
+        return np.sort(C_[order[:budget]])
+    if fill and C_.size < budget:
+        present = set(C_.tolist()) | set(int(y) for y in labels)
+        added, need, d, dmax = [], budget - C_.size, 0, 4 * budget + 64
+        while need > 0 and d < dmax:
+            j = int(sample_draw(base, d, N))
+            d += 1
+            if j not in present:
+                present.add(j)
+                added.append(j)
+                need -= 1
+        return np.sort(np.concatenate([C_, np.array(added, dtype=np.int64)]))
+    return C_
+
+
+
 class SlideOracle:
     """Model state + one training step.  `weights` arrays are copied; fp32 storage."""
 
     def __init__(self, *, input_dim, hidden_dim, num_classes, hash_kind, K, L, bucket_cap,
                  rebuild_every, lr, beta1=0.9, beta2=0.999, eps=1e-8, dwta_bin=8,
-                 overflow_policy=1, weights, hash_params):
+                 overflow_policy=1, weights, hash_params, sample_budget=0,
+                 sample_fill=False, sample_seed=1):
         self.D, self.H, self.N = int(input_dim), int(hidden_dim), int(num_classes)
         self.C, self.R, self.policy = int(bucket_cap), int(rebuild_every), int(overflow_policy)
         self.lr, self.beta1, self.beta2, self.eps = float(lr), float(beta1), float(beta2), float(eps)
+        self.budget, self.fill, self.sample_seed = int(sample_budget), bool(sample_fill), int(sample_seed)
         self._hash_shape = (hash_kind, K, L, dwta_bin)
         self.set_hash_params(hash_params)
         self.p = {k: np.array(v, dtype=np.float32, copy=True) for k, v in weights.items()}
@@ -256,7 +321,10 @@ class SlideOracle:
         out = {}
         h = self.forward_hidden(batch)
         codes = self.hash.codes(h)
-        as_ptr, as_ids, lab, ncand = self.tables.active_sets(codes, batch["y_indptr"], batch["y_indices"])
+        if self.budget > 0:
+            as_ptr, as_ids, lab, ncand = self._budgeted_active_sets(codes, batch)
+        else:
+            as_ptr, as_ids, lab, ncand = self.tables.active_sets(codes, batch["y_indptr"], batch["y_indices"])
         z, p, delta, loss_i, dh = output_forward_backward(h, as_ptr, as_ids, lab, self.p["W2"], self.p["b2"])
         uniq = np.unique(as_ids).astype(np.int32)
         gW2, gb2 = output_grads(h, as_ptr, as_ids, delta, uniq)
@@ -281,6 +349,24 @@ class SlideOracle:
             if out["rebuilt"]:
                 self.build_tables(first=False)
         return out
+
+    def _budgeted_active_sets(self, codes, batch):
+        """Active sets of the step about to run (number self.t + 1) under the sampling budget."""
+        yp, yi = _c(batch["y_indptr"], np.int32), _c(batch["y_indices"], np.int32)
+        c_ptr, c_ids, _, ncand = self.tables.active_sets(codes, yp, yi, include_labels=False)
+        B = codes.shape[0]
+        ptr, ids, lab = [0], [], []
+        for i in range(B):
+            y = yi[yp[i]:yp[i + 1]]
+            y = np.unique(y[(y >= 0) & (y < self.N)]).astype(np.int64)
+            kept = apply_budget(c_ids[c_ptr[i]:c_ptr[i + 1]], y, self.N, self.budget, self.fill, self.sample_seed,
+                                self.t + 1, i)
+            allv = np.union1d(kept, y)
+            ids.append(allv)
+            lab.append(np.isin(allv, y))
+            ptr.append(ptr[-1] + allv.size)
+        return (np.array(ptr, dtype=np.int64), np.concatenate(ids).astype(np.int32) if ids else np.empty(0, np.int32),
+                np.concatenate(lab).astype(np.uint8) if lab else np.empty(0, np.uint8), ncand)
 
     def predict(self, batch, topk, mode=0):
         """mode 0: scores over the LSH active set without labels; mode 1: over all N.

@@ -30,3 +30,28 @@ def test_lsh_prediction_finds_the_planted_class():
     codes = orc.hash.codes(orc.forward_hidden(b))
     as_ptr, _, _, _ = orc.tables.active_sets(codes, b["y_indptr"], b["y_indices"], include_labels=False)
     assert np.diff(as_ptr).mean() < 0.6 * wl.num_classes
+
+
+def test_training_under_a_sampling_budget_still_learns():
+    """Section 3.7's budget: at most `budget` retrieved neurons per sample (random fill when the
+    tables return fewer), labels always present; the planted task is still learnt."""
+    wl = planted_workload()
+    gen = synth.Generator(wl, 0)
+    from oracle import slide_oracle as so
+    orc = so.SlideOracle(input_dim=wl.input_dim, hidden_dim=wl.hidden_dim, num_classes=wl.num_classes,
+                         hash_kind=wl.hash_kind, K=wl.K, L=wl.L, bucket_cap=wl.bucket_cap,
+                         rebuild_every=wl.rebuild_every, lr=wl.lr, dwta_bin=wl.dwta_bin,
+                         overflow_policy=wl.overflow_policy, weights=gen.weights(), hash_params=gen.hash_params(),
+                         sample_budget=60, sample_fill=True, sample_seed=5)
+    protos = planted_prototypes(wl)
+    orc.build_tables()
+    for s in range(300):
+        b, labels = planted_batch(wl, protos, s)
+        r = orc.train_step(b)
+        sizes = np.diff(r["as_ptr"])
+        assert np.all(sizes == 61)                                 # budget (filled) + the one label
+        assert r["is_label"].sum() == wl.batch
+    assert r["loss"] < 0.2
+    b, labels = planted_batch(wl, protos, 10_000)
+    dense, _ = orc.predict(b, 1, 1)
+    assert float((dense[:, 0] == labels).mean()) >= 0.95
