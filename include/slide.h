@@ -32,7 +32,7 @@
 extern "C" {
 #endif
 
-#define SLIDE_ABI_VERSION 1u
+#define SLIDE_ABI_VERSION 2u
 
 typedef struct slide_ctx slide_ctx; /* opaque, host side */
 
@@ -73,6 +73,16 @@ typedef struct {
   int32_t overflow_policy;   /* slide_overflow_policy                                            */
   int32_t rebuild_every;     /* R: rebuild the tables after every R-th step; 0 = never           */
   double lr, beta1, beta2, eps; /* Adam (Section 4.1: 1e-4, 0.9, 0.999, 1e-8)                    */
+  /* Sampling budget of training steps (Section 3.7); 0 = none.  At most sample_budget retrieved
+   * neurons per sample enter the active set (labels are always added and do not count): a uniform
+   * random subset when the tables return more; when they return fewer and sample_fill != 0, uniformly
+   * drawn neurons make up the difference.  Random numbers come from a counter-based generator keyed by
+   * (sample_seed, step number, sample index), so a step is reproducible.  Needs the per-sample bitmap
+   * in LDS (num_classes up to about 1.2 million).  slide_predict ignores the budget. */
+  int32_t sample_budget;
+  int32_t sample_fill;
+  uint32_t sample_seed;
+  uint32_t reserved;         /* 0                                                                 */
 } slide_config;
 
 typedef struct {

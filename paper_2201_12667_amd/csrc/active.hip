@@ -12,6 +12,19 @@
 
 namespace slide {
 
+constexpr int kSelWords = 264;     // 256 histogram bins + counters of the sampling-budget selection
+
+// Counter-based random numbers of the sampling budget (Section 3.7): the 32-bit finaliser of
+// MurmurHash3, a bijection, keyed by (seed, step, sample) and then by neuron or draw number.
+__device__ __forceinline__ uint32_t sample_mix(uint32_t x) {
+  x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
+  return x;
+}
+__device__ __forceinline__ uint32_t sample_prio(uint32_t base, uint32_t j) { return sample_mix(base + 0x9E3779B1u * (j + 1u)); }
+__device__ __forceinline__ uint32_t sample_draw(uint32_t base, uint32_t d, uint32_t N) {
+  return __umulhi(sample_mix((base ^ 0xA5A5A5A5u) + 0x632BE5ABu * (d + 1u)), N);
+}
+
 // Exclusive scan over a workgroup of up to 1024 threads; sm: 17 words of LDS.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t& total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -109,7 +122,8 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   uint32_t* sm = pos + ad.L + 1;         // [20] scan scratch + counters
   float* hvec = (float*)(sm + 20);       // [H] the sample's hidden activations
   uint32_t* tcnt = (uint32_t*)(hvec + hd.H);   // [NT] active neurons per tile, then their exclusive prefix
-  int8_t* raw = (int8_t*)(tcnt + ad.NT); // [NH] elementary hash values
+  uint32_t* sel = tcnt + ad.NT;          // [kSelWords] sampling budget: digit histogram + counters
+  int8_t* raw = (int8_t*)(sel + kSelWords);    // [NH] elementary hash values
   const int i = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
   const int lane = tid & 63;
   if (tid == 0) { sm[17] = 0; sm[18] = 0; }
@@ -127,9 +141,11 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
 
   // Bitmap segment [seg0, seg0 + sw) words: cleared, then the labels (their "new bit" test counts the
   // distinct labels, so they go in before any candidate).
+  const bool budgeted = ad.budget > 0 && include_labels;  // (then the whole bitmap is one segment)
   auto start_segment = [&](int seg0, int sw) {
     for (int q = tid; q < sw / 4; q += nthr) ((uint4*)bm)[q] = make_uint4(0u, 0u, 0u, 0u);
     __syncthreads();
+    if (budgeted) return;                                // the labels go in after the sampling
     const int64_t lo = (int64_t)seg0 * 32, hi = lo + (int64_t)sw * 32;
     for (int q = tid; q < nlab; q += nthr) {
       const int y = y_indices[y0 + q];
@@ -170,6 +186,101 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   __syncthreads();
   const uint32_t T = pos[ad.L];
 
+  // Sampling budget: the bitmap holds the retrieved neurons.  The labels do not count (their bits are
+  // taken out first and put back at the end); more than `budget` left: keep the `budget` of smallest
+  // priority (a radix selection over the 32-bit priorities, which are distinct); fewer, with the fill
+  // option: draws d = 0, 1, 2, ... accepted when new, in rounds that cannot overshoot.
+  auto apply_budget = [&]() {
+    uint32_t* hist = sel;                                // [256]
+    uint32_t* misc = sel + 256;                          // [0] count, [1] prefix, [2] still to take, [3] new bits
+    const uint32_t base = sample_mix(ad.sample_seed + 0x9E3779B9u * ad.step + 0x7F4A7C15u * (uint32_t)i);
+    const int nq = ad.NWpad / 4;
+    for (int q = tid; q < nlab; q += nthr) {
+      const int y = y_indices[y0 + q];
+      if (y >= 0 && y < ad.N) atomicAnd(&bm[y >> 5], ~(1u << (y & 31)));
+    }
+    if (tid == 0) { misc[0] = 0; misc[1] = 0; misc[2] = (uint32_t)ad.budget; }
+    __syncthreads();
+    uint32_t c = 0;
+    for (int q = tid; q < nq; q += nthr) {
+      const uint4 wd = ((const uint4*)bm)[q];
+      c += __popc(wd.x) + __popc(wd.y) + __popc(wd.z) + __popc(wd.w);
+    }
+    c = wave_sum(c);
+    if (lane == 0 && c) atomicAdd(&misc[0], c);
+    __syncthreads();
+    const uint32_t have = misc[0];
+    if (have > (uint32_t)ad.budget) {
+      for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int b = tid; b < 256; b += nthr) hist[b] = 0;
+        __syncthreads();
+        const uint32_t prefix = misc[1];
+        for (int w = tid; w < ad.NWpad; w += nthr) {
+          uint32_t word = bm[w];
+          while (word) {
+            const int b = __ffs(word) - 1;
+            word &= word - 1;
+            const uint32_t p = sample_prio(base, (uint32_t)(w * 32 + b));
+            const uint32_t upper = pass == 0 ? 0u : p >> ((shift + 8) & 31);   // the digits fixed so far
+            if (upper == prefix) atomicAdd(&hist[(p >> shift) & 255u], 1u);
+          }
+        }
+        __syncthreads();
+        if (tid == 0) {                                  // the digit that holds the misc[2]-th smallest
+          uint32_t cum = 0, take = misc[2];
+          int bin = 255;
+          for (int b = 0; b < 256; ++b) {
+            if (cum + hist[b] >= take) { bin = b; break; }
+            cum += hist[b];
+          }
+          misc[1] = (prefix << 8) | (uint32_t)bin;
+          misc[2] = take - cum;
+        }
+        __syncthreads();
+      }
+      const uint32_t last = misc[1];                     // the largest priority that stays
+      for (int w = tid; w < ad.NWpad; w += nthr) {
+        uint32_t word = bm[w], keep = word;
+        while (word) {
+          const int b = __ffs(word) - 1;
+          word &= word - 1;
+          if (sample_prio(base, (uint32_t)(w * 32 + b)) > last) keep &= ~(1u << b);
+        }
+        bm[w] = keep;
+      }
+    } else if (ad.fill && have < (uint32_t)ad.budget) {
+      uint32_t need = (uint32_t)ad.budget - have, drawn = 0;
+      const uint32_t dmax = 4u * (uint32_t)ad.budget + 64u;
+      while (need > 0 && drawn < dmax) {                 // (uniform: both come from LDS values read after barriers)
+        const uint32_t n = min(need, dmax - drawn);
+        if (tid == 0) misc[3] = 0;
+        __syncthreads();
+        for (uint32_t d = tid; d < n; d += nthr) {
+          const uint32_t j = sample_draw(base, drawn + d, (uint32_t)ad.N);
+          bool is_label = false;
+          for (int q = 0; q < nlab; ++q) is_label |= y_indices[y0 + q] == (int)j;
+          if (!is_label) {
+            const uint32_t bit = 1u << (j & 31);
+            if (!(atomicOr(&bm[j >> 5], bit) & bit)) atomicAdd(&misc[3], 1u);
+          }
+        }
+        __syncthreads();
+        need -= misc[3];
+        drawn += n;
+        __syncthreads();
+      }
+    }
+    __syncthreads();
+    for (int q = tid; q < nlab; q += nthr) {             // the labels, counted once each
+      const int y = y_indices[y0 + q];
+      if (y < 0 || y >= ad.N) { atomicOr(&ctrl->status, SLIDE_FLAG_BAD_LABEL); continue; }
+      const uint32_t bit = 1u << (y & 31);
+      if (!(atomicOr(&bm[y >> 5], bit) & bit)) atomicAdd(&sm[17], 1u);
+    }
+    __syncthreads();
+  };
+
   uint32_t my_cnt = 0;
   for (int seg0 = 0; seg0 < ad.NWpad; seg0 += segw) {
     const int sw = min(segw, ad.NWpad - seg0);
@@ -182,6 +293,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       if (j >= lo && j < hi) atomicOr(&bm[(j - lo) >> 5], 1u << (j & 31));
     }
     __syncthreads();
+    if (budgeted) apply_budget();
     // sweep, four words per lane: population per tile (the last lane of a tile holds its count)
     for (int qb = 0; qb < sw / 4; qb += nthr) {
       const int q = qb + tid;
@@ -278,6 +390,14 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   }
 }
 
+static size_t lookup_fixed_lds(int L, int H, int NT, int NH) {
+  return ((size_t)2 * L + 1 + 20 + H + NT + kSelWords) * 4 + (((size_t)NH + 3) & ~(size_t)3);
+}
+
+bool lookup_bitmap_fits(int NWpad, int NT, int L, int H, int NH, size_t lds_limit) {
+  return lookup_fixed_lds(L, H, NT, NH) + (size_t)NWpad * 4 <= lds_limit;
+}
+
 hipError_t active_setup_attributes(size_t* lds_limit_out) {
   int dev = 0, lim = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -294,7 +414,7 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
 hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
                                uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
                                int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s) {
-  const size_t fixed = ((size_t)2 * ad.L + 1 + 20 + hd.H + ad.NT) * 4 + (((size_t)hd.NH + 3) & ~(size_t)3);
+  const size_t fixed = lookup_fixed_lds(ad.L, hd.H, ad.NT, hd.NH);
   size_t avail = (lds_limit - fixed) / 4;
   int segw = (int)(avail / 32 * 32);
   if (segw > ad.NWpad) segw = ad.NWpad;

@@ -90,7 +90,8 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->NT2 = lo->NWpad / tw;
   lo->DWpad = (int)(((lo->D + 31) / 32 + 31) / 32 * 32);
   lo->NT1 = lo->DWpad / lo->TWF;
-  const int64_t per_sample = std::min<int64_t>((int64_t)c->L * c->bucket_cap, lo->N);
+  if (c->sample_budget < 0 || c->reserved != 0) FAIL(SLIDE_EINVAL, "sample_budget must be >= 0 and reserved 0");
+  const int64_t per_sample = std::min<int64_t>(std::max<int64_t>((int64_t)c->L * c->bucket_cap, c->sample_budget), lo->N);
   lo->PS = (int)per_sample;
   lo->Amax = (int64_t)c->max_batch * per_sample + c->max_labels_per_batch;
   if (lo->Amax >= ((int64_t)1 << 31) - 64) FAIL(SLIDE_EINVAL, "max_batch * L * bucket_cap does not fit 31 bits");
@@ -218,6 +219,7 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ad.act = c->at<uint32_t>(lo.act); ad.rankT = c->at<uint32_t>(lo.rankT);
   ad.cnt = c->at<int32_t>(lo.cnt); ad.ny = c->at<int32_t>(lo.ny);
   ad.PS = lo.PS; ad.num_labels = 0;
+  ad.budget = 0; ad.fill = 0; ad.sample_seed = c->cfg.sample_seed; ad.step = 0;
   ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
   ad.chunk_sample = c->at<int32_t>(lo.chunk_sample);
   ad.as_ids = c->at<int32_t>(lo.as_ids); ad.as_lab = c->at<uint8_t>(lo.as_lab); ad.ylist = c->at<int32_t>(lo.ylist);
@@ -262,6 +264,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   ActiveDev ad = make_active(ctx, B);
   ad.num_labels = with_labels ? b->num_labels : 0;
   ad.par = (int)(ctx->calls++ & 1);
+  if (with_labels) { ad.budget = ctx->cfg.sample_budget; ad.fill = ctx->cfg.sample_fill; ad.step = (uint32_t)(ctx->t + 1); }
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
     return launch_lookup_union(ad, ctx->hd, h, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0,
@@ -382,6 +385,11 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
     set_err(nullptr, SLIDE_EHIP, "slide_init: %s failed: %s", what, hipGetErrorString(e));
     slide_destroy(ctx);
     return SLIDE_EHIP;
+  }
+  if (cfg->sample_budget > 0 && !lookup_bitmap_fits(lo.NWpad, lo.NT, lo.L, H, NH, ctx->lds_limit)) {
+    set_err(nullptr, SLIDE_EINVAL, "sample_budget needs the per-sample bitmap in LDS: num_classes is too large");
+    slide_destroy(ctx);
+    return SLIDE_EINVAL;
   }
   if (hash_lds_bytes(H) > ctx->lds_limit) {
     set_err(nullptr, SLIDE_EINVAL, "hidden_dim %d needs %zu bytes of LDS, device offers %zu", H, hash_lds_bytes(H), ctx->lds_limit);

@@ -82,6 +82,8 @@ struct ActiveDev {
   int PS;                          // slots reserved per sample for candidates: min(L*C, N)
   int num_labels;                  // label entries in the batch
   int par;                         // which work-item counter this call uses
+  int budget, fill;                // sampling budget of this call (0 = none) and its fill option
+  uint32_t sample_seed, step;      // keys of the counter-based generator: seed, number of the step being run
   uint32_t* act;                   // [NT][B][TW] bitmap spill, used only when a sample's bitmap exceeds LDS
   uint32_t* rankT;                 // [NT+1][B] active neurons of the sample below the tile (last row: |AS_i|)
   int32_t* cnt;                    // [B] |AS_i|
@@ -119,6 +121,7 @@ struct TransposeArgs {
 };
 
 hipError_t active_setup_attributes(size_t* lds_limit_out);
+bool lookup_bitmap_fits(int NWpad, int NT, int L, int H, int NH, size_t lds_limit);
 hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
                                uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
                                int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);

@@ -16,7 +16,7 @@ SLIDE_OK, SLIDE_EINVAL, SLIDE_ENOMEM, SLIDE_EHIP, SLIDE_ESTATE, SLIDE_EDATA = 0,
 HASH_SIMHASH, HASH_DWTA = 0, 1
 KEEP_LOWEST_ID, KEEP_PRIORITY = 0, 1
 FLAG_BAD_FEATURE, FLAG_UNSORTED, FLAG_BAD_LABEL = 1, 2, 4
-ABI_VERSION = 1
+ABI_VERSION = 2
 STAGES = ["hidden", "lookup", "forward", "combine", "update", "rebuild"]
 NUM_STAGES = len(STAGES)
 
@@ -34,7 +34,9 @@ class slide_config(C.Structure):
                 ("hash_kind", C.c_int32), ("K", C.c_int32), ("L", C.c_int32), ("dwta_bin", C.c_int32),
                 ("srp_nnz", C.c_int32), ("bucket_cap", C.c_int32), ("overflow_policy", C.c_int32),
                 ("rebuild_every", C.c_int32),
-                ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double)]
+                ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("sample_budget", C.c_int32), ("sample_fill", C.c_int32), ("sample_seed", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 class slide_mem_req(C.Structure):
@@ -118,7 +120,8 @@ class SlideError(RuntimeError):
 
 def make_config(*, input_dim, hidden_dim, num_classes, max_batch, max_nnz_per_batch, max_labels_per_batch,
                 hash_kind, K, L, bucket_cap, rebuild_every, lr, beta1=0.9, beta2=0.999, eps=1e-8, dwta_bin=8,
-                srp_nnz=0, overflow_policy=KEEP_PRIORITY) -> slide_config:
+                srp_nnz=0, overflow_policy=KEEP_PRIORITY, sample_budget=0, sample_fill=False,
+                sample_seed=1) -> slide_config:
     c = slide_config()
     c.struct_size, c.abi_version = C.sizeof(slide_config), ABI_VERSION
     c.input_dim, c.num_classes, c.hidden_dim, c.max_batch = input_dim, num_classes, hidden_dim, max_batch
@@ -126,6 +129,7 @@ def make_config(*, input_dim, hidden_dim, num_classes, max_batch, max_nnz_per_ba
     c.hash_kind, c.K, c.L, c.dwta_bin, c.srp_nnz, c.bucket_cap = hash_kind, K, L, dwta_bin, srp_nnz, bucket_cap
     c.overflow_policy, c.rebuild_every = overflow_policy, rebuild_every
     c.lr, c.beta1, c.beta2, c.eps = lr, beta1, beta2, eps
+    c.sample_budget, c.sample_fill, c.sample_seed = sample_budget, int(bool(sample_fill)), sample_seed
     return c
 
 
@@ -328,4 +332,5 @@ def config_from_workload(wl, max_nnz_per_batch=None, max_labels_per_batch=None) 
                        bucket_cap=wl.bucket_cap, rebuild_every=wl.rebuild_every, lr=wl.lr, beta1=wl.beta1,
                        beta2=wl.beta2, eps=wl.eps, dwta_bin=wl.dwta_bin,
                        srp_nnz=wl.srp_nnz if wl.hash_kind == HASH_SIMHASH else 0,
-                       overflow_policy=wl.overflow_policy)
+                       overflow_policy=wl.overflow_policy, sample_budget=wl.sample_budget,
+                       sample_fill=wl.sample_fill, sample_seed=wl.sample_seed)

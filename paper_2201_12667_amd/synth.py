@@ -48,6 +48,9 @@ class Workload:
     eps: float = 1e-8
     dwta_bin: int = 8       # m
     overflow_policy: int = 1
+    sample_budget: int = 0           # retrieved neurons per sample kept in training (0 = all)
+    sample_fill: bool = False        # fill an unmet budget with uniformly drawn neurons
+    sample_seed: int = 1
     # input recipe
     nnz_mode: str = "poisson"        # "exact" | "poisson"
     nnz_mean: float = 75.0

@@ -52,7 +52,8 @@ def make_oracle(wl, weights, hp):
                           hash_kind=wl.hash_kind, K=wl.K, L=wl.L, bucket_cap=wl.bucket_cap,
                           rebuild_every=wl.rebuild_every, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
                           dwta_bin=wl.dwta_bin, overflow_policy=wl.overflow_policy, weights=weights,
-                          hash_params=hp)
+                          hash_params=hp, sample_budget=wl.sample_budget, sample_fill=wl.sample_fill,
+                          sample_seed=wl.sample_seed)
 
 
 def make_pair(wl, seed=0, **cfg_over):

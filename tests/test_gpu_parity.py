@@ -276,3 +276,38 @@ def test_redrawn_hash_functions_then_rebuild(kind):
     assert np.array_equal(model.debug_hash(V), orc.hash.codes(V))
     assert_ok(compare_step(model, orc, gen.batch(1)))
     model.destroy()
+
+
+@pytest.mark.parametrize("name,wl", [
+    ("over-budget", synth.small(synth.HASH_DWTA, sample_budget=20, sample_seed=9)),
+    ("over-budget-simhash", synth.small(synth.HASH_SIMHASH, sample_budget=7, sample_seed=3, batch=130)),
+    ("fill", synth.small(synth.HASH_DWTA, sample_budget=900, sample_fill=True, sample_seed=5)),
+    ("no-fill-under-budget", synth.small(synth.HASH_DWTA, sample_budget=900, sample_fill=False)),
+    ("fill-small-layer", synth.small(synth.HASH_SIMHASH, num_classes=600, sample_budget=550, sample_fill=True,
+                                     K=4, L=5, batch=20)),
+    ("budget-of-one", synth.small(synth.HASH_DWTA, sample_budget=1, sample_fill=True, input_dim=0, batch=70,
+                                  num_classes=9973)),
+])
+def test_sampling_budget_steps_match_oracle(name, wl):
+    """Section 3.7's budget: the kept / filled neurons are decided by a counter-based generator that
+    both sides implement, so the active sets stay bit-exact; three steps so that the step number
+    enters the generator, each from the oracle's state."""
+    _say("budget", name)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    sizes = []
+    for s in range(3):
+        load_state(model, orc)
+        res = compare_step(model, orc, gen.batch(s))
+        assert_ok(res)
+        ref = res["_ref"]
+        non_label = np.diff(ref["as_ptr"]) - np.add.reduceat(ref["is_label"], ref["as_ptr"][:-1])
+        assert non_label.max() <= wl.sample_budget
+        sizes.append(int(non_label.mean()))
+    _say("   mean non-label active neurons per sample:", sizes)
+    # prediction ignores the budget
+    b = gen.batch(7)
+    ids, _ = model.predict(model.to_device(b), 5)
+    assert np.array_equal(ids.cpu().numpy(), orc.predict(b, 5)[0])
+    model.destroy()
