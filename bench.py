@@ -45,8 +45,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="0..7; 2 = the 670K-class model the metric is quoted on")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--cpu-steps", type=int, default=3, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=20, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--breakdown", action="store_true", help="also time every stage on extra steps")
+    ap.add_argument("--sample-budget", type=int, default=0,
+                    help="retrieved neurons kept per sample (0 = all, the configuration the metric is quoted on)")
+    ap.add_argument("--sample-fill", action="store_true", help="fill an unmet budget with uniformly drawn neurons")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run the library's plain copy kernel on MIB mebibytes (10 launches) and print "
                          "its bandwidth: the yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
@@ -79,6 +82,9 @@ def main() -> int:
         return 0
 
     wl = synth.config(args.config)
+    if args.sample_budget:
+        import dataclasses
+        wl = dataclasses.replace(wl, sample_budget=args.sample_budget, sample_fill=args.sample_fill)
     gen = synth.Generator(wl, args.seed)
     weights, hp = gen.weights(), gen.hash_params()
     model = slide.Slide(slide.config_from_workload(wl), weights, hp)
@@ -130,7 +136,8 @@ def main() -> int:
                    "input_dim": wl.input_dim, "hidden_dim": wl.hidden_dim, "num_classes": wl.num_classes,
                    "hash": "dwta" if wl.hash_kind == synth.HASH_DWTA else "simhash", "K": wl.K, "L": wl.L,
                    "bucket_cap": wl.bucket_cap, "rebuild_every": wl.rebuild_every,
-                   "rebuilds_in_timed_region": rebuilds_in_region, "seed": args.seed},
+                   "rebuilds_in_timed_region": rebuilds_in_region, "seed": args.seed,
+                   "sample_budget": wl.sample_budget, "sample_fill": bool(wl.sample_fill)},
         "roofline": {"bound": "hbm", "kernel": "update_kernel (gradient + Adam on the touched rows of W2 and W1)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "algorithmic_bytes_per_launch": dom_bytes,
@@ -159,7 +166,8 @@ def main() -> int:
         orc = so.SlideOracle(input_dim=wl.input_dim, hidden_dim=wl.hidden_dim, num_classes=wl.num_classes,
                              hash_kind=wl.hash_kind, K=wl.K, L=wl.L, bucket_cap=wl.bucket_cap, rebuild_every=0,
                              lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, dwta_bin=wl.dwta_bin,
-                             overflow_policy=wl.overflow_policy, weights=weights, hash_params=hp)
+                             overflow_policy=wl.overflow_policy, weights=weights, hash_params=hp,
+                             sample_budget=wl.sample_budget, sample_fill=wl.sample_fill, sample_seed=wl.sample_seed)
         tb0 = time.perf_counter()
         orc.build_tables()
         tb1 = time.perf_counter()

@@ -216,38 +216,55 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
         for (int b = tid; b < 256; b += nthr) hist[b] = 0;
         __syncthreads();
         const uint32_t prefix = misc[1];
-        for (int w = tid; w < ad.NWpad; w += nthr) {
-          uint32_t word = bm[w];
-          while (word) {
-            const int b = __ffs(word) - 1;
-            word &= word - 1;
-            const uint32_t p = sample_prio(base, (uint32_t)(w * 32 + b));
-            const uint32_t upper = pass == 0 ? 0u : p >> ((shift + 8) & 31);   // the digits fixed so far
-            if (upper == prefix) atomicAdd(&hist[(p >> shift) & 255u], 1u);
+        for (int q = tid; q < nq; q += nthr) {
+          const uint4 wd = ((const uint4*)bm)[q];
+          const uint32_t ww[4] = {wd.x, wd.y, wd.z, wd.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            uint32_t word = ww[k];
+            while (word) {
+              const int b = __ffs(word) - 1;
+              word &= word - 1;
+              const uint32_t p = sample_prio(base, (uint32_t)((4 * q + k) * 32 + b));
+              const uint32_t upper = pass == 0 ? 0u : p >> ((shift + 8) & 31);   // the digits fixed so far
+              if (upper == prefix) atomicAdd(&hist[(p >> shift) & 255u], 1u);
+            }
           }
         }
         __syncthreads();
-        if (tid == 0) {                                  // the digit that holds the misc[2]-th smallest
-          uint32_t cum = 0, take = misc[2];
-          int bin = 255;
-          for (int b = 0; b < 256; ++b) {
-            if (cum + hist[b] >= take) { bin = b; break; }
-            cum += hist[b];
+        if (tid < 64) {                                  // the digit that holds the misc[2]-th smallest: wave 0,
+          const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+          const uint32_t four = h0 + h1 + h2 + h3;       // four bins per lane
+          const uint32_t inc = wave_incl_scan_add(four);
+          const uint32_t take = misc[2];
+          const unsigned long long reached = __ballot(inc >= take);
+          if (reached && lane == __ffsll(reached) - 1) {
+            uint32_t cum = inc - four;
+            int bin = 4 * lane;
+            if (cum + h0 < take) { cum += h0; ++bin;
+              if (cum + h1 < take) { cum += h1; ++bin;
+                if (cum + h2 < take) { cum += h2; ++bin; } } }
+            misc[1] = (prefix << 8) | (uint32_t)bin;
+            misc[2] = take - cum;
           }
-          misc[1] = (prefix << 8) | (uint32_t)bin;
-          misc[2] = take - cum;
         }
         __syncthreads();
       }
       const uint32_t last = misc[1];                     // the largest priority that stays
-      for (int w = tid; w < ad.NWpad; w += nthr) {
-        uint32_t word = bm[w], keep = word;
-        while (word) {
-          const int b = __ffs(word) - 1;
-          word &= word - 1;
-          if (sample_prio(base, (uint32_t)(w * 32 + b)) > last) keep &= ~(1u << b);
+      for (int q = tid; q < nq; q += nthr) {
+        const uint4 wd = ((const uint4*)bm)[q];
+        if (!(wd.x | wd.y | wd.z | wd.w)) continue;
+        uint32_t ww[4] = {wd.x, wd.y, wd.z, wd.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          uint32_t word = ww[k];
+          while (word) {
+            const int b = __ffs(word) - 1;
+            word &= word - 1;
+            if (sample_prio(base, (uint32_t)((4 * q + k) * 32 + b)) > last) ww[k] &= ~(1u << b);
+          }
         }
-        bm[w] = keep;
+        ((uint4*)bm)[q] = make_uint4(ww[0], ww[1], ww[2], ww[3]);
       }
     } else if (ad.fill && have < (uint32_t)ad.budget) {
       uint32_t need = (uint32_t)ad.budget - have, drawn = 0;
