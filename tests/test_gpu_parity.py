@@ -89,6 +89,7 @@ def test_degenerate_tables_all_rows_identical():
                                 input_dim=400, nnz_mean=6.0, feat_zipf_s=None, lab_zipf_s=None)),
     ("h200", synth.small(synth.HASH_DWTA, hidden_dim=200, K=3, L=13, batch=33, num_classes=4099,
                          input_dim=1200)),
+    ("single-sample", synth.small(synth.HASH_DWTA, batch=1)),
     # larger batches: tiles of 512, 256 and 128 rows in the row-list construction
     ("b300-tile512", synth.small(synth.HASH_DWTA, hidden_dim=64, K=3, L=9, batch=300, num_classes=6007,
                                  input_dim=2900, nnz_mean=8.0, bucket_cap=8)),
@@ -310,4 +311,43 @@ def test_sampling_budget_steps_match_oracle(name, wl):
     b = gen.batch(7)
     ids, _ = model.predict(model.to_device(b), 5)
     assert np.array_equal(ids.cpu().numpy(), orc.predict(b, 5)[0])
+    model.destroy()
+
+
+def _random_workloads():
+    rng = np.random.default_rng(2024)
+    out = []
+    Hs = [4, 8, 20, 36, 64, 100, 132, 260, 516, 1028, 2048]
+    Bs = [1, 2, 3, 31, 63, 64, 65, 127, 129, 255, 257, 333]
+    for k in range(14):
+        kind = synth.HASH_DWTA if k % 2 == 0 else synth.HASH_SIMHASH
+        H = int(Hs[k % len(Hs)])
+        if kind == synth.HASH_DWTA and H % 8:
+            H += 8 - H % 8                                  # DWTA bins of 8 coordinates
+        B = int(Bs[(3 * k + 1) % len(Bs)])
+        N = int(rng.integers(33, 5000))
+        D = 0 if k % 5 == 4 else int(rng.integers(5, 3000))
+        K = int(rng.integers(1, 4)) if kind == synth.HASH_DWTA else int(rng.integers(1, 9))
+        L = int(rng.integers(1, 12))
+        Ccap = int(rng.choice([1, 2, 5, 16, 64]))
+        nnz = float(min(max(D // 3, 1), rng.integers(1, 40))) if D else 1.0
+        wl = synth.small(kind, hidden_dim=H, batch=B, num_classes=N, input_dim=D, K=K, L=L, bucket_cap=Ccap,
+                         nnz_mean=nnz, lab_mean=float(rng.integers(1, 6)), rebuild_every=2,
+                         overflow_policy=int(k % 3 == 0))
+        out.append(("r%02d-H%d-B%d-N%d-D%d-K%dL%dC%d" % (k, H, B, N, D, K, L, Ccap), wl))
+    return out
+
+
+@pytest.mark.parametrize("name,wl", _random_workloads())
+def test_randomly_shaped_workloads_two_steps(name, wl):
+    """Odd shapes: vectors that do not fill the lane groups, single-sample batches, layers smaller
+    than a tile, one table, buckets of one -- two steps each (the second after a rebuild)."""
+    _say("random shape", name)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    for s in range(2):
+        load_state(model, orc)
+        res = compare_step(model, orc, gen.batch(s))
+        assert_ok(res)
     model.destroy()
