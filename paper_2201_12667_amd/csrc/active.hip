@@ -8,6 +8,7 @@
 //                 It also emits the compact ascending id list per sample + label flags and hands
 //                 the sample its forward work items (chunks of kChunk active neurons).
 #include "slide_internal.h"
+#include "spmm.h"
 #include "wave_ops.h"
 
 namespace slide {
@@ -111,7 +112,7 @@ __device__ void sample_hash_codes(const HashDev& hd, const float* hvec, int8_t* 
 }
 
 __global__ __launch_bounds__(1024) void lookup_union_kernel(
-    ActiveDev ad, HashDev hd, const float* __restrict__ h, const uint32_t* __restrict__ off,
+    ActiveDev ad, HashDev hd, const float* __restrict__ h, SpmmArgs sp, const uint32_t* __restrict__ off,
     const int32_t* __restrict__ ids, uint32_t nb, uint32_t* __restrict__ codes,
     const int32_t* __restrict__ y_indptr, const int32_t* __restrict__ y_indices, int include_labels,
     int32_t* __restrict__ ncand, Ctrl* ctrl, int segw) {
@@ -127,7 +128,10 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   const int i = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
   const int lane = tid & 63;
   if (tid == 0) { sm[17] = 0; sm[18] = 0; }
-  if (i == 0 && tid == 0) { ctrl->nlong2 = 0; ctrl->max_nu2 = 0; }   // consumed after this kernel
+  if (i == 0 && tid == 0) {                              // consumed after this kernel
+    ctrl->nlong2 = 0; ctrl->max_nu2 = 0;
+    if (sp.W1) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }
+  }
 
   // the sample's slice of the sample-major arrays: room for every candidate plus its labels
   int y0 = 0, nlab = 0;
@@ -139,13 +143,11 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   const int tws = __ffs(ad.TW) - 1;                      // TW is a power of two >= 4
   const int LT = ad.TW >> 2;                             // lanes per tile in the sweeps (four words per lane)
 
-  // Bitmap segment [seg0, seg0 + sw) words: cleared, then the labels (their "new bit" test counts the
-  // distinct labels, so they go in before any candidate).
   const bool budgeted = ad.budget > 0 && include_labels;  // (then the whole bitmap is one segment)
-  auto start_segment = [&](int seg0, int sw) {
-    for (int q = tid; q < sw / 4; q += nthr) ((uint4*)bm)[q] = make_uint4(0u, 0u, 0u, 0u);
-    __syncthreads();
-    if (budgeted) return;                                // the labels go in after the sampling
+  // The labels of bitmap segment [seg0, seg0 + sw) words (their "new bit" test counts the distinct
+  // labels, so they go in before any candidate; under a sampling budget they go in after it).
+  auto segment_labels = [&](int seg0, int sw) {
+    if (budgeted) return;
     const int64_t lo = (int64_t)seg0 * 32, hi = lo + (int64_t)sw * 32;
     for (int q = tid; q < nlab; q += nthr) {
       const int y = y_indices[y0 + q];
@@ -157,12 +159,22 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       }
     }
   };
+  auto clear_segment = [&](int sw) {
+    for (int q = tid; q < sw / 4; q += nthr) ((uint4*)bm)[q] = make_uint4(0u, 0u, 0u, 0u);
+  };
 
-  // a2: hash codes of this sample's hidden activations (the first bitmap segment is prepared while
-  // the activations arrive)
-  for (int c = tid; c < hd.H; c += nthr) hvec[c] = h[(size_t)i * hd.H + c];
+  // a1 (sparse-input mode): the sample's hidden activations, by the first waves of the workgroup;
+  // the first bitmap segment is cleared meanwhile.  Dense-hidden mode: the activations are read.
+  clear_segment(min(segw, ad.NWpad));
+  if (sp.W1) {
+    const int wave = tid >> 6;
+    if (wave * 128 < hd.H) spmm_sample(sp, i, ad.B, wave, lane, hvec, ctrl);
+  } else {
+    for (int c = tid; c < hd.H; c += nthr) hvec[c] = h[(size_t)i * hd.H + c];
+  }
   __syncthreads();                                       // (also orders the counters' reset before the labels)
-  start_segment(0, min(segw, ad.NWpad));
+  segment_labels(0, min(segw, ad.NWpad));
+  // a2: hash codes of the hidden activations
   sample_hash_codes(hd, hvec, raw, o0s, codes + (size_t)i * ad.L);
 
   uint32_t carry = 0;
@@ -302,7 +314,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   for (int seg0 = 0; seg0 < ad.NWpad; seg0 += segw) {
     const int sw = min(segw, ad.NWpad - seg0);
     const int64_t lo = (int64_t)seg0 * 32, hi = lo + (int64_t)sw * 32;
-    if (seg0 > 0) { start_segment(seg0, sw); __syncthreads(); }
+    if (seg0 > 0) { clear_segment(sw); __syncthreads(); segment_labels(seg0, sw); __syncthreads(); }
     for (uint32_t c = tid; c < T; c += nthr) {
       int a = 0, b = ad.L;                              // last t with pos[t] <= c
       while (b - a > 1) { const int mid = (a + b) >> 1; if (pos[mid] <= c) a = mid; else b = mid; }
@@ -428,15 +440,16 @@ hipError_t active_setup_attributes(size_t* lds_limit_out) {
   return hipSuccess;
 }
 
-hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
-                               uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
-                               int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s) {
+hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const SpmmArgs& sp,
+                               const TablesDev& td, uint32_t* codes, const int32_t* y_indptr,
+                               const int32_t* y_indices, int include_labels, int32_t* ncand, Ctrl* ctrl,
+                               size_t lds_limit, hipStream_t s) {
   const size_t fixed = lookup_fixed_lds(ad.L, hd.H, ad.NT, hd.NH);
   size_t avail = (lds_limit - fixed) / 4;
   int segw = (int)(avail / 32 * 32);
   if (segw > ad.NWpad) segw = ad.NWpad;
   const size_t bytes = (size_t)segw * 4 + fixed;
-  hipLaunchKernelGGL(lookup_union_kernel, dim3(ad.B), dim3(1024), bytes, s, ad, hd, h, td.off, td.ids, td.nb,
+  hipLaunchKernelGGL(lookup_union_kernel, dim3(ad.B), dim3(1024), bytes, s, ad, hd, h, sp, td.off, td.ids, td.nb,
                      codes, y_indptr, y_indices, include_labels, ncand, ctrl, segw);
   return hipGetLastError();
 }

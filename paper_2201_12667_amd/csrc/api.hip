@@ -212,6 +212,16 @@ hipError_t stage(slide_ctx* ctx, int id, hipStream_t s, F&& launch) {
   return e;
 }
 
+SpmmArgs make_spmm(slide_ctx* ctx, const slide_batch* b) {
+  const Layout& lo = ctx->lo;
+  SpmmArgs a{};
+  a.D = lo.D; a.H = lo.H; a.nnz_total = b->nnz; a.rows_per_tile = lo.TWF * 32;
+  a.x_indptr = b->x_indptr; a.x_indices = b->x_indices; a.x_values = b->x_values;
+  a.W1 = ctx->buf.W1; a.b1 = ctx->buf.b1;
+  a.h = ctx->at<float>(lo.h); a.xse = ctx->at<int2>(lo.xse);
+  return a;
+}
+
 ActiveDev make_active(const slide_ctx* c, int B) {
   ActiveDev ad;
   const Layout& lo = c->lo;
@@ -251,12 +261,10 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   const Layout& lo = ctx->lo;
   const int B = b->batch;
   const float* h = b->hidden;
+  SpmmArgs sp{};                                         // the hidden layer rides in the lookup launch
   if (lo.D > 0) {
-    float* hw = ctx->at<float>(lo.h);
-    HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] {
-      return launch_spmm_relu(B, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
-                              ctx->buf.b1, hw, ctx->at<int2>(lo.xse), lo.TWF * 32, ctx->ctrl(), s); }));
-    h = hw;
+    sp = make_spmm(ctx, b);
+    h = sp.h;
   }
   ctx->last_h = h;
   ctx->last_B = B;
@@ -267,7 +275,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   if (with_labels) { ad.budget = ctx->cfg.sample_budget; ad.fill = ctx->cfg.sample_fill; ad.step = (uint32_t)(ctx->t + 1); }
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
-    return launch_lookup_union(ad, ctx->hd, h, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0,
+    return launch_lookup_union(ad, ctx->hd, h, sp, ctx->td, codes, b->y_indptr, b->y_indices, with_labels ? 1 : 0,
                                ncand, ctx->ctrl(), ctx->lds_limit, s); }));
   t2.ids = ad.as_ids; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
@@ -509,12 +517,10 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
     const Layout& lo = ctx->lo;
     const float* h = b->hidden;
     if (lo.D > 0) {
-      float* hw = ctx->at<float>(lo.h);
-      HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] {
-        return launch_spmm_relu(b->batch, lo.D, lo.H, b->nnz, b->x_indptr, b->x_indices, b->x_values, ctx->buf.W1,
-                                ctx->buf.b1, hw, ctx->at<int2>(lo.xse), lo.TWF * 32, ctx->ctrl(), s); }));
+      const SpmmArgs sp = make_spmm(ctx, b);
+      HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] { return launch_spmm_relu(b->batch, sp, ctx->ctrl(), s); }));
       HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(lo.xse), (size_t)b->batch * lo.NT1 * 2, 0u, s));
-      h = hw;
+      h = sp.h;
     }
     ctx->last_h = h;
     ctx->last_B = b->batch;

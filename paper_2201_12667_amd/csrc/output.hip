@@ -3,91 +3,22 @@
 // (paper Section 2.1: activations are computed for the retrieved neurons only; Section 3.6: the
 // first layer is fed by index/value arrays, the second by the first layer's activations).
 #include "slide_internal.h"
+#include "spmm.h"
 #include "transpose.h"
 
 #include <algorithm>
 
 namespace slide {
 
-// ---------------------------------------------------------------------------------------------
-// h[i][:] = max(0, b1 + sum_k x_ik * W1[k][:]), one fused multiply-add per stored feature, in
-// storage order (so any other fp32 implementation using the same order gets the same bits).
-// One wave per (sample, 128 columns); each lane owns two columns and reads a float2 per W1 row.
-// The first column block also records, per tile of rows_per_tile features, where the sample's
-// features of the tile start and end in the CSR arrays (the row lists of the W1 update are built
-// from these segments).
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void spmm_relu_kernel(int64_t D, int H, int nnz_total,
-                                                       const int32_t* __restrict__ x_indptr,
-                                                       const int32_t* __restrict__ x_indices,
-                                                       const float* __restrict__ x_values,
-                                                       const float* __restrict__ W1, const float* __restrict__ b1,
-                                                       float* __restrict__ h, int2* __restrict__ xse, int rows_per_tile,
-                                                       Ctrl* ctrl) {
-  const int i = blockIdx.x, lane = threadIdx.x, B = gridDim.x;
-  if (i == 0 && blockIdx.y == 0 && lane == 0) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }  // used after this kernel
-  const int c0 = (blockIdx.y * 64 + lane) * 2;
-  const bool col_ok = c0 < H;
-  int p0 = x_indptr[i], p1 = x_indptr[i + 1];
-  p0 = max(p0, 0);
-  p1 = min(p1, nnz_total);
-  float2 acc = col_ok ? *(const float2*)(b1 + c0) : make_float2(0.f, 0.f);
-  int prev = -1, last = -1;                              // last: feature of the pair before this batch of 64
-  uint32_t flags = 0;
-  constexpr int UN = 16;
-  for (int pb = p0; pb < p1; pb += 64) {
-    // one coalesced read of the next 64 (index, value) pairs; lane q holds pair pb + q
-    const int mine = pb + lane < p1 ? x_indices[pb + lane] : -1;
-    const float myv = pb + lane < p1 ? x_values[pb + lane] : 0.f;
-    const bool bad = pb + lane < p1 && (mine < 0 || mine >= D);
-    if (__any(bad)) flags |= SLIDE_FLAG_BAD_FEATURE;
-    const int kk = bad ? -1 : mine;
-    if (blockIdx.y == 0) {                // segment ends: a feature whose predecessor lies in another tile
-      int before = __shfl_up(kk, 1);      // starts its own tile's segment and ends the predecessor's
-      if (lane == 0) before = last;
-      last = __shfl(kk, 63);
-      if (kk >= 0) {
-        const int tile = kk / rows_per_tile, tb = before >= 0 ? before / rows_per_tile : -1;
-        if (tb != tile) {
-          xse[(size_t)tile * B + i].x = pb + lane;
-          if (tb >= 0) xse[(size_t)tb * B + i].y = pb + lane;
-        }
-        if (pb + lane == p1 - 1) xse[(size_t)tile * B + i].y = p1;
-      }
-    }
-    const int cnt = min(64, p1 - pb);
-    for (int q0 = 0; q0 < cnt; q0 += UN) {
-      int k[UN];
-      float v[UN];
-      float2 w[UN];
-#pragma unroll
-      for (int q = 0; q < UN; ++q) {                       // broadcast pair q0 + q to the whole wave
-        k[q] = __shfl(kk, q0 + q);
-        v[q] = __shfl(myv, q0 + q);
-      }
-#pragma unroll
-      for (int q = 0; q < UN; ++q)
-        w[q] = (q0 + q < cnt && k[q] >= 0 && col_ok) ? *(const float2*)(W1 + (size_t)k[q] * H + c0)
-                                                    : make_float2(0.f, 0.f);
-#pragma unroll
-      for (int q = 0; q < UN; ++q) {
-        if (q0 + q >= cnt || k[q] < 0) continue;
-        if (k[q] <= prev) flags |= SLIDE_FLAG_UNSORTED;
-        prev = k[q];
-        acc.x = fmaf(v[q], w[q].x, acc.x);
-        acc.y = fmaf(v[q], w[q].y, acc.y);
-      }
-    }
-  }
-  if (col_ok) *(float2*)(h + (size_t)i * H + c0) = make_float2(acc.x > 0.f ? acc.x : 0.f, acc.y > 0.f ? acc.y : 0.f);
-  if (flags && lane == 0 && blockIdx.y == 0) atomicOr(&ctrl->status, flags);
+// The hidden layer as a launch of its own (prediction over all neurons; the training step runs it
+// inside the lookup workgroups).
+__global__ __launch_bounds__(64) void spmm_relu_kernel(SpmmArgs a, Ctrl* ctrl) {
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }
+  spmm_sample(a, blockIdx.x, gridDim.x, blockIdx.y, threadIdx.x, nullptr, ctrl);
 }
 
-hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
-                            const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, int2* xse, int rows_per_tile, Ctrl* ctrl, hipStream_t s) {
-  hipLaunchKernelGGL(spmm_relu_kernel, dim3(B, ceil_div(H, 128)), dim3(64), 0, s, D, H, nnz_total, x_indptr,
-                     x_indices, x_values, W1, b1, h, xse, rows_per_tile, ctrl);
+hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s) {
+  hipLaunchKernelGGL(spmm_relu_kernel, dim3(B, ceil_div(a.H, 128)), dim3(64), 0, s, a, ctrl);
   return hipGetLastError();
 }
 

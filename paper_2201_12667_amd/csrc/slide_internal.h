@@ -120,17 +120,28 @@ struct TransposeArgs {
   PairsDev pd;
 };
 
+// Sparse-input hidden layer: CSR batch, parameters, outputs (W1 == nullptr: absent).
+struct SpmmArgs {
+  int64_t D;
+  int H, nnz_total, rows_per_tile;
+  const int32_t *x_indptr, *x_indices;
+  const float *x_values, *W1, *b1;
+  float* h;                      // [B][H] activations (output)
+  int2* xse;                     // [tiles][B] feature segments per tile (output)
+};
+
 hipError_t active_setup_attributes(size_t* lds_limit_out);
 bool lookup_bitmap_fits(int NWpad, int NT, int L, int H, int NH, size_t lds_limit);
-hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const TablesDev& td,
-                               uint32_t* codes, const int32_t* y_indptr, const int32_t* y_indices,
-                               int include_labels, int32_t* ncand, Ctrl* ctrl, size_t lds_limit, hipStream_t s);
+// sp.W1 != nullptr: the workgroup of a sample first computes the sample's hidden activations (h is
+// then sp.h, written here); else h holds them already.
+hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const float* h, const SpmmArgs& sp,
+                               const TablesDev& td, uint32_t* codes, const int32_t* y_indptr,
+                               const int32_t* y_indices, int include_labels, int32_t* ncand, Ctrl* ctrl,
+                               size_t lds_limit, hipStream_t s);
 
 
 // ---- output.hip -----------------------------------------------------------------------
-hipError_t launch_spmm_relu(int B, int64_t D, int H, int nnz_total, const int32_t* x_indptr,
-                            const int32_t* x_indices, const float* x_values, const float* W1, const float* b1,
-                            float* h, int2* xse, int rows_per_tile, Ctrl* ctrl, hipStream_t s);
+hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s);
 // Logits over the active sets; the same launch transposes the two bit matrices (t1: features, t2:
 // active sets; ntiles = 0 leaves one out).
 hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
