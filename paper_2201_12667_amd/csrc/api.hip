@@ -26,7 +26,7 @@ struct Layout {
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, xse, zc, best, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, hashoff, xse, zc, best, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -111,6 +111,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   const size_t B = lo->Bmax, H = lo->H, A = (size_t)lo->Amax;
   lo->ctrl = take(sizeof(Ctrl));
   lo->hashw = take(lo->hash_words * 4);
+  lo->hashoff = take(lo->hash_words * 8);
   lo->xse = take(lo->D ? B * lo->NT1 * 8 : 0);
   lo->dense_chunk = dense_chunk_neurons(lo->N, lo->Bmax);
   lo->zc = take(B * (size_t)lo->dense_chunk * 4);
@@ -310,6 +311,28 @@ int slide_query_memory(const slide_config* cfg, slide_mem_req* out) {
   return SLIDE_OK;
 }
 
+// The packed coordinate words as byte offsets into the LDS tile of the row-tile hash kernel.
+static std::vector<uint32_t> hash_offsets(const slide_config* cfg, const std::vector<uint32_t>& words) {
+  const uint32_t pitch = (uint32_t)hash_tile_pitch(cfg->hidden_dim) * 4u;
+  std::vector<uint32_t> offs(words.size() * 2);
+  if (cfg->hash_kind == SLIDE_HASH_DWTA) {
+    for (size_t w = 0; w < words.size(); ++w) {
+      offs[2 * w] = (words[w] & 0xffffu) * pitch;
+      offs[2 * w + 1] = (words[w] >> 16) * pitch;
+    }
+  } else {
+    const int S = cfg->srp_nnz, Spad = (S + 1) / 2 * 2;
+    const uint32_t zero_cell = (uint32_t)cfg->hidden_dim * pitch;
+    for (size_t w = 0; w < words.size(); ++w)
+      for (int q = 0; q < 2; ++q) {
+        const uint32_t v = (words[w] >> (16 * q)) & 0xffffu;
+        const bool pad = (int)((2 * w + q) % Spad) >= S;
+        offs[2 * w + q] = pad ? zero_cell : (((v & 0x7fffu) * pitch) | ((v & 0x8000u) << 16));
+      }
+  }
+  return offs;
+}
+
 // Hash-function parameters -> packed 16-bit coordinate words (validated).
 static int pack_hash_params(const slide_config* cfg, const Layout& lo, const slide_hash_params* hp,
                             std::vector<uint32_t>& words) {
@@ -384,6 +407,11 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   hipError_t e = hipMemset(ctx->ws() + lo.ctrl, 0, sizeof(Ctrl));
   if (e == hipSuccess && lo.D) { what = "hipMemset(feature segments)"; e = hipMemset(ctx->ws() + lo.xse, 0, (size_t)lo.Bmax * lo.NT1 * 8); }
   if (e == hipSuccess && !words.empty()) { what = "hipMemcpy(hash parameters)"; e = hipMemcpy(ctx->ws() + lo.hashw, words.data(), words.size() * 4, hipMemcpyHostToDevice); }
+  if (e == hipSuccess && !words.empty()) {
+    const std::vector<uint32_t> offs = hash_offsets(cfg, words);
+    what = "hipMemcpy(hash offsets)";
+    e = hipMemcpy(ctx->ws() + lo.hashoff, offs.data(), offs.size() * 4, hipMemcpyHostToDevice);
+  }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(hash kernels)"; e = hash_setup_attributes(H); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(table kernels)"; e = tables_setup_attributes(); }
@@ -409,6 +437,7 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   hd.m = cfg->dwta_bin; hd.lgm = cfg->hash_kind == SLIDE_HASH_DWTA ? ilog2_exact(cfg->dwta_bin) : 0;
   hd.S = cfg->srp_nnz; hd.Spad = (cfg->srp_nnz + 1) / 2 * 2;
   hd.words = ctx->at<uint32_t>(lo.hashw);
+  hd.offs = ctx->at<uint32_t>(lo.hashoff);
   hd.dens_a = hp->dens_a; hd.dens_b = hp->dens_b;
   TablesDev& td = ctx->td;
   td.off = (uint32_t*)((char*)buf->tables + lo.t_off);
@@ -433,8 +462,11 @@ int slide_set_hash_params(slide_ctx* ctx, const slide_hash_params* hp, void* hip
   const int rc = pack_hash_params(&ctx->cfg, ctx->lo, hp, words);
   if (rc != SLIDE_OK) { ctx->err = g_last_error; return rc; }
   HIPCHK(ctx, hipStreamSynchronize((hipStream_t)hip_stream));   // nothing in flight may still read the old functions
-  if (!words.empty())
+  if (!words.empty()) {
+    const std::vector<uint32_t> offs = hash_offsets(&ctx->cfg, words);
     HIPCHK(ctx, hipMemcpy(ctx->ws() + ctx->lo.hashw, words.data(), words.size() * 4, hipMemcpyHostToDevice));
+    HIPCHK(ctx, hipMemcpy(ctx->ws() + ctx->lo.hashoff, offs.data(), offs.size() * 4, hipMemcpyHostToDevice));
+  }
   ctx->hd.dens_a = hp->dens_a; ctx->hd.dens_b = hp->dens_b;
   ctx->prio_a = hp->prio_a; ctx->prio_b = hp->prio_b;
   ctx->built = false;                                           // the tables belong to the old functions

@@ -14,7 +14,8 @@
 namespace slide {
 
 static int rows_per_tile(int H) { return H <= 512 ? 64 : (H <= 1024 ? 32 : 16); }
-size_t hash_lds_bytes(int H) { return (size_t)H * (rows_per_tile(H) + 1) * sizeof(float); }
+size_t hash_lds_bytes(int H) { return ((size_t)H + 1) * (rows_per_tile(H) + 1) * sizeof(float); }
+int hash_tile_pitch(int H) { return rows_per_tile(H) + 1; }
 
 // Key of a coordinate: 0 if it cannot win (zero of either sign, NaN), else an unsigned integer that
 // orders like the float (equal floats <-> equal keys), at least 1.
@@ -24,40 +25,44 @@ __device__ __forceinline__ uint32_t dwta_key(float x) {
   return (x != 0.0f && x == x) ? k : 0u;
 }
 
-// Winner position of elementary hash e for the vector whose keys start at col0 (pitch `stride`);
-// -1 when the bin has no entry.  Strictly greater wins, so ties keep the lowest position.
+// The row-tile kernel reads its coordinates from a second parameter table, offs: one 32-bit entry
+// per coordinate = its byte offset in the transposed tile (coordinate * pitch * 4), so that an LDS
+// address is one add (the 16-bit coordinate table would cost a mask, a multiply and a shift per
+// element); SimHash entries carry the sign in bit 31, and the padding entry of an odd S points at
+// a row of zeros behind the tile.
+//
+// Winner position of elementary hash e for the vector whose keys start at byte address col0 of the
+// tile; -1 when the bin has no entry.  Strictly greater wins, so ties keep the lowest position.
 template <int M>
-__device__ __forceinline__ int dwta_raw(const uint32_t* col0, int stride, const uint32_t* __restrict__ words, int e) {
+__device__ __forceinline__ int dwta_raw(const char* col0, const uint32_t* __restrict__ offs, int e) {
   int best_p = -1;
   uint32_t best = 0u;
+  const uint32_t* o = offs + (size_t)e * M;
 #pragma unroll
-  for (int p2 = 0; p2 < M / 2; ++p2) {
-    const uint32_t w = words[(size_t)e * (M / 2) + p2];
-    const uint32_t k0 = col0[(w & 0xffffu) * stride];
-    const uint32_t k1 = col0[(w >> 16) * stride];
-    if (k0 > best) { best_p = 2 * p2; best = k0; }
-    if (k1 > best) { best_p = 2 * p2 + 1; best = k1; }
+  for (int p = 0; p < M; ++p) {
+    const uint32_t k = *(const uint32_t*)(col0 + o[p]);
+    if (k > best) { best_p = p; best = k; }
   }
   return best_p;
 }
 
 template <int M>
-__device__ uint32_t dwta_code(const HashDev& hd, const uint32_t* col0, int stride, int t, int& rowstate) {
+__device__ uint32_t dwta_code(const HashDev& hd, const char* col0, int pitch_bytes, int t, int& rowstate) {
   uint32_t code = 0;
   for (int k = 0; k < hd.K; ++k) {
     const int e = t * hd.K + k;                      // uniform over the lanes of a table
-    int val = dwta_raw<M>(col0, stride, hd.words, e);
+    int val = dwta_raw<M>(col0, hd.offs, e);
     if (val < 0) {                                   // empty bin: borrow (rare, per lane)
       if (rowstate < 0) {
         rowstate = 0;
-        for (int c = 0; c < hd.H; ++c) if (col0[c * stride] != 0u) { rowstate = 1; break; }
+        for (int c = 0; c < hd.H; ++c) if (*(const uint32_t*)(col0 + (size_t)c * pitch_bytes) != 0u) { rowstate = 1; break; }
       }
       val = 0;
       if (rowstate == 1) {
         for (uint32_t tr = 1; tr <= 100; ++tr) {
           const uint32_t u = hd.dens_a * (uint32_t)(e + 1) + hd.dens_b * tr;
           const int e2 = (int)((u >> 8) % (uint32_t)hd.NH);
-          const int r2 = dwta_raw<M>(col0, stride, hd.words, e2);
+          const int r2 = dwta_raw<M>(col0, hd.offs, e2);
           if (r2 >= 0) { val = r2; break; }
         }
       }
@@ -67,21 +72,18 @@ __device__ uint32_t dwta_code(const HashDev& hd, const uint32_t* col0, int strid
   return code;
 }
 
-__device__ uint32_t simhash_code(const HashDev& hd, const float* col0, int stride, int t) {
+__device__ uint32_t simhash_code(const HashDev& hd, const char* col0, int t) {
   uint32_t code = 0;
-  const int half = hd.Spad / 2;
   for (int k = 0; k < hd.K; ++k) {
     const int e = t * hd.K + k;
-    const uint32_t* __restrict__ sw = hd.words + (size_t)e * half;
+    const uint2* __restrict__ o = (const uint2*)(hd.offs + (size_t)e * hd.Spad);   // Spad is even
     float acc = 0.0f;
-    for (int s2 = 0; s2 < half; ++s2) {
-      const uint32_t w = sw[s2];
-      const float x0 = col0[(w & 0x7fffu) * stride];
-      acc = (w & 0x8000u) ? acc - x0 : acc + x0;
-      if (2 * s2 + 1 < hd.S) {
-        const float x1 = col0[((w >> 16) & 0x7fffu) * stride];
-        acc = (w & 0x80000000u) ? acc - x1 : acc + x1;
-      }
+    for (int q = 0; q < hd.Spad / 2; ++q) {          // sequential sum: a - x is a + (-x) bit for bit
+      const uint2 w = o[q];
+      const uint32_t x0 = *(const uint32_t*)(col0 + (w.x & 0x7fffffffu));
+      const uint32_t x1 = *(const uint32_t*)(col0 + (w.y & 0x7fffffffu));
+      acc += __uint_as_float(x0 ^ (w.x & 0x80000000u));
+      acc += __uint_as_float(x1 ^ (w.y & 0x80000000u));
     }
     code |= (acc > 0.0f ? 1u : 0u) << k;
   }
@@ -95,8 +97,9 @@ __global__ __launch_bounds__(THREADS) void hash_rows_kernel(HashDev hd, const fl
                                                         int64_t row_stride, int64_t tab_stride,
                                                         uint32_t* hist, uint32_t* __restrict__ rank,
                                                         uint32_t nbp1, int tpb) {
-  extern __shared__ float tile[];                    // [H][RPT + 1]
+  extern __shared__ float tile[];                    // [H + 1][RPT + 1]; the last row is zero
   const int stride = RPT + 1, H = hd.H;
+  if ((int)threadIdx.x < stride) tile[H * stride + threadIdx.x] = 0.0f;
   const int64_t row0 = (int64_t)blockIdx.x * RPT;
   for (int idx = threadIdx.x; idx < RPT * H; idx += blockDim.x) {   // coalesced read, conflict-free store
     const int r = idx / H, c = idx - r * H;
@@ -109,15 +112,15 @@ __global__ __launch_bounds__(THREADS) void hash_rows_kernel(HashDev hd, const fl
   const int tps = 64 / RPT;                          // tables per wave and step (RPT is 16, 32 or 64)
   const int r = lane & (RPT - 1), sub = lane / RPT;
   const bool active = row0 + r < rows;
-  const float* col0 = tile + r;
+  const char* col0 = (const char*)(tile + r);
   const int t_end = min((int)(blockIdx.y + 1) * tpb, hd.L);
   int rowstate = -1;
   for (int t0 = blockIdx.y * tpb + wave * tps; t0 < t_end; t0 += nw * tps) {
     const int t = t0 + sub;
     if (t >= t_end) continue;
     uint32_t code;
-    if (MODE == 0) code = simhash_code(hd, col0, stride, t);
-    else code = dwta_code<(MODE == 0 ? 2 : MODE)>(hd, (const uint32_t*)col0, stride, t, rowstate);
+    if (MODE == 0) code = simhash_code(hd, col0, t);
+    else code = dwta_code<(MODE == 0 ? 2 : MODE)>(hd, col0, stride * 4, t, rowstate);
     if (active) {
       const int64_t row = row0 + r;
       codes[row * row_stride + (int64_t)t * tab_stride] = code;

@@ -40,6 +40,8 @@ struct HashDev {
   int S, Spad;            // SimHash coordinates per bit, padded to even
   const uint32_t* words;  // DWTA: NH*m/2 words of two u16 coordinates; SimHash: NH*Spad/2 words of
                           // two u16 (bit 15 = subtract)
+  const uint32_t* offs;   // the same coordinates as byte offsets into the row-tile kernel's LDS tile, one
+                          // entry each (SimHash: bit 31 = subtract; padding entries point at a zero cell)
   uint32_t dens_a, dens_b;
 };
 
@@ -57,6 +59,7 @@ hipError_t launch_hash(const HashDev& hd, const float* V, int64_t rows, uint32_t
                        uint32_t nb, int tables_per_block, hipStream_t s);
 hipError_t hash_setup_attributes(int H);
 size_t hash_lds_bytes(int H);
+int hash_tile_pitch(int H);       // words between consecutive coordinates in the row-tile kernel's LDS tile
 
 // ---- tables.hip -----------------------------------------------------------------------
 struct TablesDev {
