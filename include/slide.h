@@ -185,7 +185,8 @@ int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out);
 
 /* Launches of a step, in order, for slide_profile. */
 enum slide_stage {
-  SLIDE_STAGE_HIDDEN = 0,   /* sparse-input hidden layer as a launch of its own (slide_predict mode 1) */
+  SLIDE_STAGE_HIDDEN = 0,   /* sparse-input hidden layer as a launch of its own (batches above 256,   */
+                            /* slide_predict mode 1)                                                   */
   SLIDE_STAGE_LOOKUP = 1,   /* hidden layer of the sample (sparse-input mode), hash codes, bucket     */
                             /* reads, union, sorted id lists, forward work items                      */
   SLIDE_STAGE_FORWARD = 2,  /* logits + running soft-max over the gathered rows; the same launch turns */

@@ -213,6 +213,8 @@ hipError_t stage(slide_ctx* ctx, int id, hipStream_t s, F&& launch) {
   return e;
 }
 
+constexpr int kFusedHiddenBatch = 256;   // compute units of the target machine
+
 SpmmArgs make_spmm(slide_ctx* ctx, const slide_batch* b) {
   const Layout& lo = ctx->lo;
   SpmmArgs a{};
@@ -262,10 +264,17 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   const Layout& lo = ctx->lo;
   const int B = b->batch;
   const float* h = b->hidden;
-  SpmmArgs sp{};                                         // the hidden layer rides in the lookup launch
+  SpmmArgs sp{};
   if (lo.D > 0) {
     sp = make_spmm(ctx, b);
     h = sp.h;
+    // One lookup workgroup per sample holds a compute unit (its bitmap fills the LDS): while the batch
+    // fits the machine in one round the hidden layer rides in it; a larger batch would pay the hidden
+    // layer's latency once per round, so it gets its own, fully parallel launch.
+    if (B > kFusedHiddenBatch) {
+      HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] { return launch_spmm_relu(B, sp, ctx->ctrl(), s); }));
+      sp = SpmmArgs{};
+    }
   }
   ctx->last_h = h;
   ctx->last_B = B;

@@ -36,6 +36,7 @@ hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s)
 // ---------------------------------------------------------------------------------------------
 constexpr int kForwardThreads = 512;
 constexpr int kForwardBlocks = 768;    // logit workers
+constexpr int kForwardBlocksLong = 640;   // ... of which this many stay when each has several items
 
 template <int LPR, int CH, bool FULL>
 __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const float* __restrict__ h, const float* __restrict__ W2,
@@ -133,8 +134,13 @@ __global__ __launch_bounds__(kForwardThreads) void forward_kernel(ActiveDev ad, 
   // critical path) before the active-set tiles.
   const int k = blockIdx.x;
   if (k < kForwardBlocks) {
-    if (H == LPR * CH * 4) forward_items<LPR, CH, true>(ad, H, h, W2, b2, z, partials, ctrl, k, kForwardBlocks);
-    else forward_items<LPR, CH, false>(ad, H, h, W2, b2, z, partials, ctrl, k, kForwardBlocks);
+    // With several items per wave the workers would hold every slot of the machine until the end and
+    // the tiles would run after them: then the last workers leave at once and make room.
+    const int items = (int)ctrl->chunk_alloc[ad.par];
+    const int workers = items > 2 * kForwardBlocks * (kForwardThreads / 64) ? kForwardBlocksLong : kForwardBlocks;
+    if (k >= workers) return;
+    if (H == LPR * CH * 4) forward_items<LPR, CH, true>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
+    else forward_items<LPR, CH, false>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
   }
   else if (k < kForwardBlocks + t1.ntiles) transpose_tile<true>(t1, k - kForwardBlocks, dyn_lds);
   else transpose_tile<false>(t2, k - kForwardBlocks - t1.ntiles, dyn_lds);
