@@ -24,8 +24,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
-# scaled by the same counters on a plain copy kernel); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2-670k": 810.4e6}   # profiles/cfg2-670k_step_kernels.md
+# scaled by the same counters on a plain copy kernel); see profiles/<workload>_step_kernels.md.
+MEASURED_TRAFFIC_BYTES = {"cfg1-shard167k": 214.8e6, "cfg2-670k": 810.4e6, "cfg3-wide325k": 749.1e6, "cfg4-825m": 626.2e6}   # profiles/cfg2-670k_step_kernels.md
 
 
 def algorithmic_bytes_update(U: float, A: float, U1: float, nnz: float, B: int, H: int) -> float:

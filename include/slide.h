@@ -190,7 +190,7 @@ enum slide_stage {
   SLIDE_STAGE_LOOKUP = 1,   /* hidden layer of the sample (sparse-input mode), hash codes, bucket     */
                             /* reads, union, sorted id lists, forward work items                      */
   SLIDE_STAGE_FORWARD = 2,  /* logits + running soft-max over the gathered rows; the same launch turns */
-                            /* the feature and the active bit matrix into per-row sample lists         */
+                            /* the batch's features and active sets into per-row sample lists         */
   SLIDE_STAGE_COMBINE = 3,  /* normaliser, errors, loss, hidden gradient                               */
   SLIDE_STAGE_UPDATE = 4,   /* gradient + Adam on the touched rows of W2, b2, W1; b1; loss mean        */
   SLIDE_STAGE_REBUILD = 5,  /* table build / rebuild (all its kernels)                                */

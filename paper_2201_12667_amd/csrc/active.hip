@@ -39,7 +39,8 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, ui
   return base + inc - v;
 }
 
-// Position of bitmap word w of sample i: the bit matrix is stored tile-major, [tile][sample][TW
+// Position of bitmap word w of sample i in the spill copy of the bitmaps (used only when a bitmap
+// does not fit the LDS in one piece): tile-major, [tile][sample][TW
 // words], so that the transposition reads one contiguous block per tile; the per-sample writer
 // pays the stride instead (full 4*TW-byte records).
 __device__ __forceinline__ size_t act_index(const ActiveDev& ad, int i, int w) {

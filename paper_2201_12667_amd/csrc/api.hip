@@ -257,7 +257,7 @@ int check_batch(slide_ctx* ctx, const slide_batch* b, bool need_labels) {
 }
 
 // Hidden activations, hash codes + active sets, and the logits pass; t1 and t2 (training only) are
-// the transpositions of the feature and the active bit matrix that ride in the logits launch (the
+// the row-list constructions for the features and the active sets that ride in the logits launch (the
 // bit-matrix pointers of t2 are filled in here).
 int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out,
                    const TransposeArgs& t1, TransposeArgs t2) {

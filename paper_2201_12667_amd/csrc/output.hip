@@ -30,7 +30,7 @@ hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s)
 // exp(z - M), acc = sum of exp(z - M) * w) that is rescaled when the maximum moves.  acc/s is the
 // probability-weighted sum of the rows, which is all the hidden-layer gradient needs, so the rows
 // are not read a second time.  Partial states are merged per sample by combine_kernel.
-// The same launch transposes the two bit matrices of the batch (workgroups before the logit
+// The same launch builds the row lists of the two weight matrices (tile workgroups behind the logit
 // workers): they depend on the lookup only, like the logits, and are latency-bound where the logit
 // workers are bandwidth-bound.
 // ---------------------------------------------------------------------------------------------

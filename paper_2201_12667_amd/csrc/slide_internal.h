@@ -21,7 +21,7 @@ struct Ctrl {
   uint32_t wl_count;      // big-bucket worklist length
   uint32_t overflowed;    // buckets with more than C members at the last build
   uint32_t total_pairs;   // A
-  uint32_t total_chunks;
+  uint32_t unused0;
   uint32_t candidates_lo, candidates_hi;
   uint32_t nlong2, nlong1; // long rows queued by the two transpositions
   uint32_t max_nu2, max_nu1; // most touched rows in any tile
@@ -98,7 +98,7 @@ struct ActiveDev {
   uint8_t* as_lab;                 // [slots]
   int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
 };
-// Transposition of a [B][words] bit matrix into per-row pair lists.  Row slots are grouped by tile:
+// Row lists: for every touched row the ascending samples that touch it.  Row slots are grouped by tile:
 // tile t owns slots [t*rows_per_tile, t*rows_per_tile + tile_nu[t]).
 struct PairsDev {
   int rows_per_tile, ntiles;
@@ -145,7 +145,7 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const flo
 
 // ---- output.hip -----------------------------------------------------------------------
 hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s);
-// Logits over the active sets; the same launch transposes the two bit matrices (t1: features, t2:
+// Logits over the active sets; the same launch builds the two sets of row lists (t1: features, t2:
 // active sets; ntiles = 0 leaves one out).
 hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
                           float* partials, const Ctrl* ctrl, const TransposeArgs& t1, const TransposeArgs& t2,

@@ -56,19 +56,6 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
   return v;
 }
 
-// Exclusive scan over the 256 threads of a workgroup; *total gets the sum.  sm: 8 words of LDS.
-__device__ uint32_t block_excl_scan256(uint32_t v, uint32_t* sm, uint32_t* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t inc = wave_incl_scan(v);
-  __syncthreads();
-  if (lane == 63) sm[wave] = inc;
-  __syncthreads();
-  uint32_t base = 0;
-  for (int w = 0; w < wave; ++w) base += sm[w];
-  *total = sm[0] + sm[1] + sm[2] + sm[3];
-  return base + inc - v;
-}
-
 constexpr int kSlab = 16384;       // rows per workgroup in the partition passes
 
 __global__ __launch_bounds__(1024) void part_hist_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,

@@ -1,4 +1,4 @@
-// Transposition of a tile-major bit matrix into per-row pair lists, as a device function so that it
+// Transposition of sample-major id lists into per-row pair lists, as a device function so that it
 // can run as one role of a larger launch.
 #pragma once
 #include "slide_internal.h"

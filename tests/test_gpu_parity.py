@@ -244,7 +244,7 @@ def test_predict_mode0_matches_oracle(kind):
     assert np.array_equal(ids, want_ids)
     fin = np.isfinite(want_sc)
     assert close(sc[fin], want_sc[fin]) and np.array_equal(np.isfinite(sc), fin)
-    # a training step afterwards still works (the feature bit matrix was left clean)
+    # a training step afterwards still works (the feature segments were left clean)
     res = compare_step(model, orc, gen.batch(1))
     assert_ok(res)
     model.destroy()
