@@ -18,6 +18,12 @@ thread_local std::string g_last_error;
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
+// Entries of the byte-offset copy of the hash parameters (see hash_offsets).
+static size_t hash_offset_count(const slide_config* c) {
+  if (c->hash_kind == SLIDE_HASH_DWTA) return (size_t)c->K * c->L * c->dwta_bin;
+  return (size_t)c->K * c->L * simhash_offset_stride(c->srp_nnz);
+}
+
 struct Layout {
   // derived sizes
   int Bmax, Bpad, H, L, K, C, TW, TWF, NWpad, NT, NT2, NT1, DWpad, bits, PS;
@@ -111,7 +117,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   const size_t B = lo->Bmax, H = lo->H, A = (size_t)lo->Amax;
   lo->ctrl = take(sizeof(Ctrl));
   lo->hashw = take(lo->hash_words * 4);
-  lo->hashoff = take(lo->hash_words * 8);
+  lo->hashoff = take(hash_offset_count(c) * 4);
   lo->xse = take(lo->D ? B * lo->NT1 * 8 : 0);
   lo->dense_chunk = dense_chunk_neurons(lo->N, lo->Bmax);
   lo->zc = take(B * (size_t)lo->dense_chunk * 4);
@@ -320,23 +326,24 @@ int slide_query_memory(const slide_config* cfg, slide_mem_req* out) {
   return SLIDE_OK;
 }
 
-// The packed coordinate words as byte offsets into the LDS tile of the row-tile hash kernel.
+// The packed coordinate words as byte offsets into the LDS tile of the row-tile hash kernel.  A
+// SimHash bit owns simhash_offset_stride(S) entries; the ones past S point at the row of zeros.
 static std::vector<uint32_t> hash_offsets(const slide_config* cfg, const std::vector<uint32_t>& words) {
   const uint32_t pitch = (uint32_t)hash_tile_pitch(cfg->hidden_dim) * 4u;
-  std::vector<uint32_t> offs(words.size() * 2);
+  std::vector<uint32_t> offs(hash_offset_count(cfg));
   if (cfg->hash_kind == SLIDE_HASH_DWTA) {
     for (size_t w = 0; w < words.size(); ++w) {
       offs[2 * w] = (words[w] & 0xffffu) * pitch;
       offs[2 * w + 1] = (words[w] >> 16) * pitch;
     }
   } else {
-    const int S = cfg->srp_nnz, Spad = (S + 1) / 2 * 2;
+    const int S = cfg->srp_nnz, half = (S + 1) / 2, So = simhash_offset_stride(S);
     const uint32_t zero_cell = (uint32_t)cfg->hidden_dim * pitch;
-    for (size_t w = 0; w < words.size(); ++w)
-      for (int q = 0; q < 2; ++q) {
-        const uint32_t v = (words[w] >> (16 * q)) & 0xffffu;
-        const bool pad = (int)((2 * w + q) % Spad) >= S;
-        offs[2 * w + q] = pad ? zero_cell : (((v & 0x7fffu) * pitch) | ((v & 0x8000u) << 16));
+    const size_t NH = (size_t)cfg->K * cfg->L;
+    for (size_t e = 0; e < NH; ++e)
+      for (int q = 0; q < So; ++q) {
+        const uint32_t v = q < S ? (words[e * half + q / 2] >> (16 * (q & 1))) & 0xffffu : 0u;
+        offs[e * So + q] = q < S ? (((v & 0x7fffu) * pitch) | ((v & 0x8000u) << 16)) : zero_cell;
       }
   }
   return offs;
@@ -444,7 +451,7 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   HashDev& hd = ctx->hd;
   hd.kind = cfg->hash_kind; hd.H = H; hd.K = cfg->K; hd.L = cfg->L; hd.NH = NH;
   hd.m = cfg->dwta_bin; hd.lgm = cfg->hash_kind == SLIDE_HASH_DWTA ? ilog2_exact(cfg->dwta_bin) : 0;
-  hd.S = cfg->srp_nnz; hd.Spad = (cfg->srp_nnz + 1) / 2 * 2;
+  hd.S = cfg->srp_nnz; hd.Spad = (cfg->srp_nnz + 1) / 2 * 2; hd.So = simhash_offset_stride(cfg->srp_nnz);
   hd.words = ctx->at<uint32_t>(lo.hashw);
   hd.offs = ctx->at<uint32_t>(lo.hashoff);
   hd.dens_a = hp->dens_a; hd.dens_b = hp->dens_b;

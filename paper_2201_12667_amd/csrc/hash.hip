@@ -28,62 +28,81 @@ __device__ __forceinline__ uint32_t dwta_key(float x) {
 // The row-tile kernel reads its coordinates from a second parameter table, offs: one 32-bit entry
 // per coordinate = its byte offset in the transposed tile (coordinate * pitch * 4), so that an LDS
 // address is one add (the 16-bit coordinate table would cost a mask, a multiply and a shift per
-// element); SimHash entries carry the sign in bit 31, and the padding entry of an odd S points at
-// a row of zeros behind the tile.
+// element); SimHash entries carry the sign in bit 31, and a bit's entries are padded to a multiple
+// of eight with pointers to a row of zeros behind the tile (adding +0 changes no sum).
 //
 // Winner position of elementary hash e for the vector whose keys start at byte address col0 of the
 // tile; -1 when the bin has no entry.  Strictly greater wins, so ties keep the lowest position.
-template <int M>
+template <int M, bool UNI>
 __device__ __forceinline__ int dwta_raw(const char* col0, const uint32_t* __restrict__ offs, int e) {
-  int best_p = -1;
-  uint32_t best = 0u;
-  const uint32_t* o = offs + (size_t)e * M;
+  const uint32_t* o = offs + (size_t)(UNI ? __builtin_amdgcn_readfirstlane(e) : e) * M;
+  uint32_t k[M];
 #pragma unroll
-  for (int p = 0; p < M; ++p) {
-    const uint32_t k = *(const uint32_t*)(col0 + o[p]);
-    if (k > best) { best_p = p; best = k; }
-  }
-  return best_p;
+  for (int p = 0; p < M; ++p) k[p] = *(const uint32_t*)(col0 + o[p]);
+  uint32_t best = k[0];                              // the largest key first (three-operand maxima) ...
+#pragma unroll
+  for (int p = 1; p < M; ++p) best = max(best, k[p]);
+  bool eq[M];                                        // ... then the lowest position that holds it
+#pragma unroll
+  for (int p = 0; p < M; ++p) eq[p] = k[p] == best;
+  int best_p = M - 1;
+#pragma unroll
+  for (int p = M - 2; p >= 0; --p) best_p = eq[p] ? p : best_p;
+  return best == 0u ? -1 : best_p;
 }
 
-template <int M>
-__device__ uint32_t dwta_code(const HashDev& hd, const char* col0, int pitch_bytes, int t, int& rowstate) {
-  uint32_t code = 0;
-  for (int k = 0; k < hd.K; ++k) {
-    const int e = t * hd.K + k;                      // uniform over the lanes of a table
-    int val = dwta_raw<M>(col0, hd.offs, e);
-    if (val < 0) {                                   // empty bin: borrow (rare, per lane)
-      if (rowstate < 0) {
-        rowstate = 0;
-        for (int c = 0; c < hd.H; ++c) if (*(const uint32_t*)(col0 + (size_t)c * pitch_bytes) != 0u) { rowstate = 1; break; }
-      }
-      val = 0;
-      if (rowstate == 1) {
-        for (uint32_t tr = 1; tr <= 100; ++tr) {
-          const uint32_t u = hd.dens_a * (uint32_t)(e + 1) + hd.dens_b * tr;
-          const int e2 = (int)((u >> 8) % (uint32_t)hd.NH);
-          const int r2 = dwta_raw<M>(col0, hd.offs, e2);
-          if (r2 >= 0) { val = r2; break; }
-        }
-      }
+template <int M, bool UNI>
+__device__ __forceinline__ uint32_t dwta_code(const HashDev& hd, const uint32_t* __restrict__ offs, const char* col0,
+                                              int pitch_bytes, int t, int& rowstate) {
+  // Empty bin: borrow the winner of another elementary hash (rare, per lane).
+  auto borrow = [&](int e) -> int {
+    if (rowstate < 0) {
+      rowstate = 0;
+      for (int c = 0; c < hd.H; ++c) if (*(const uint32_t*)(col0 + (size_t)c * pitch_bytes) != 0u) { rowstate = 1; break; }
     }
-    code |= (uint32_t)val << (k * hd.lgm);
+    if (rowstate == 1)
+      for (uint32_t tr = 1; tr <= 100; ++tr) {
+        const uint32_t u = hd.dens_a * (uint32_t)(e + 1) + hd.dens_b * tr;
+        const int e2 = (int)((u >> 8) % (uint32_t)hd.NH);
+        const int r2 = dwta_raw<M, false>(col0, offs, e2);
+        if (r2 >= 0) return r2;
+      }
+    return 0;
+  };
+  uint32_t code = 0;
+  const int e0 = t * hd.K;                           // uniform over the lanes of a table
+  int k = 0;
+  for (; k + 1 < hd.K; k += 2) {                     // two independent argmax chains in flight
+    int v0 = dwta_raw<M, UNI>(col0, offs, e0 + k);
+    int v1 = dwta_raw<M, UNI>(col0, offs, e0 + k + 1);
+    if (v0 < 0) v0 = borrow(e0 + k);
+    if (v1 < 0) v1 = borrow(e0 + k + 1);
+    code |= ((uint32_t)v0 << (k * hd.lgm)) | ((uint32_t)v1 << ((k + 1) * hd.lgm));
+  }
+  if (k < hd.K) {
+    int v0 = dwta_raw<M, UNI>(col0, offs, e0 + k);
+    if (v0 < 0) v0 = borrow(e0 + k);
+    code |= (uint32_t)v0 << (k * hd.lgm);
   }
   return code;
 }
 
-__device__ uint32_t simhash_code(const HashDev& hd, const char* col0, int t) {
+template <bool UNI>
+__device__ __forceinline__ uint32_t simhash_code(const HashDev& hd, const uint32_t* __restrict__ offs, const char* col0,
+                                                 int t) {
   uint32_t code = 0;
   for (int k = 0; k < hd.K; ++k) {
-    const int e = t * hd.K + k;
-    const uint2* __restrict__ o = (const uint2*)(hd.offs + (size_t)e * hd.Spad);   // Spad is even
+    const int e = UNI ? __builtin_amdgcn_readfirstlane(t * hd.K + k) : t * hd.K + k;
+    const uint32_t* __restrict__ o = offs + (size_t)e * hd.So;        // So is a multiple of 8
     float acc = 0.0f;
-    for (int q = 0; q < hd.Spad / 2; ++q) {          // sequential sum: a - x is a + (-x) bit for bit
-      const uint2 w = o[q];
-      const uint32_t x0 = *(const uint32_t*)(col0 + (w.x & 0x7fffffffu));
-      const uint32_t x1 = *(const uint32_t*)(col0 + (w.y & 0x7fffffffu));
-      acc += __uint_as_float(x0 ^ (w.x & 0x80000000u));
-      acc += __uint_as_float(x1 ^ (w.y & 0x80000000u));
+    for (int q = 0; q < hd.So; q += 8) {             // sequential sum: a - x is a + (-x) bit for bit
+      uint32_t w[8], x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) w[j] = o[q + j];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = *(const uint32_t*)(col0 + (w[j] & 0x7fffffffu));
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc += __uint_as_float(x[j] ^ (w[j] & 0x80000000u));
     }
     code |= (acc > 0.0f ? 1u : 0u) << k;
   }
@@ -91,8 +110,9 @@ __device__ uint32_t simhash_code(const HashDev& hd, const char* col0, int t) {
 }
 
 // MODE 0: SimHash; 2,4,8,16: DWTA with that bin size.
-template <int MODE, int THREADS>
-__global__ __launch_bounds__(THREADS) void hash_rows_kernel(HashDev hd, const float* __restrict__ V,
+template <int MODE, bool UNI>
+__global__ __launch_bounds__(1024) void hash_rows_kernel(HashDev hd, const uint32_t* __restrict__ offs,
+                                                        const float* __restrict__ V,
                                                         int64_t rows, int RPT, uint32_t* __restrict__ codes,
                                                         int64_t row_stride, int64_t tab_stride,
                                                         uint32_t* hist, uint32_t* __restrict__ rank,
@@ -119,8 +139,8 @@ __global__ __launch_bounds__(THREADS) void hash_rows_kernel(HashDev hd, const fl
     const int t = t0 + sub;
     if (t >= t_end) continue;
     uint32_t code;
-    if (MODE == 0) code = simhash_code(hd, col0, t);
-    else code = dwta_code<(MODE == 0 ? 2 : MODE)>(hd, col0, stride * 4, t, rowstate);
+    if (MODE == 0) code = simhash_code<UNI>(hd, offs, col0, t);
+    else code = dwta_code<(MODE == 0 ? 2 : MODE), UNI>(hd, offs, col0, stride * 4, t, rowstate);
     if (active) {
       const int64_t row = row0 + r;
       codes[row * row_stride + (int64_t)t * tab_stride] = code;
@@ -139,11 +159,11 @@ static hipError_t launch_mode(const HashDev& hd, const float* V, int64_t rows, u
   const int RPT = rows_per_tile(hd.H);
   dim3 grid((unsigned)ceil_div(rows, RPT), (unsigned)ceil_div(hd.L, tpb));
   if (RPT == 64)
-    hipLaunchKernelGGL((hash_rows_kernel<MODE, 256>), grid, dim3(256), hash_lds_bytes(hd.H), s, hd, V, rows, RPT, codes,
-                       row_stride, tab_stride, hist, rank, nb + 1, tpb);
+    hipLaunchKernelGGL((hash_rows_kernel<MODE, true>), grid, dim3(1024), hash_lds_bytes(hd.H), s, hd, hd.offs, V, rows,
+                       RPT, codes, row_stride, tab_stride, hist, rank, nb + 1, tpb);
   else
-    hipLaunchKernelGGL((hash_rows_kernel<MODE, 1024>), grid, dim3(1024), hash_lds_bytes(hd.H), s, hd, V, rows, RPT,
-                       codes, row_stride, tab_stride, hist, rank, nb + 1, tpb);
+    hipLaunchKernelGGL((hash_rows_kernel<MODE, false>), grid, dim3(1024), hash_lds_bytes(hd.H), s, hd, hd.offs, V, rows,
+                       RPT, codes, row_stride, tab_stride, hist, rank, nb + 1, tpb);
   return hipGetLastError();
 }
 
@@ -169,16 +189,16 @@ hipError_t hash_setup_attributes(int H) {
 #define SLIDE_SET(K) \
   e = hipFuncSetAttribute((const void*)&K, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); \
   if (e != hipSuccess) return e;
-  SLIDE_SET((hash_rows_kernel<0, 256>))
-  SLIDE_SET((hash_rows_kernel<2, 256>))
-  SLIDE_SET((hash_rows_kernel<4, 256>))
-  SLIDE_SET((hash_rows_kernel<8, 256>))
-  SLIDE_SET((hash_rows_kernel<16, 256>))
-  SLIDE_SET((hash_rows_kernel<0, 1024>))
-  SLIDE_SET((hash_rows_kernel<2, 1024>))
-  SLIDE_SET((hash_rows_kernel<4, 1024>))
-  SLIDE_SET((hash_rows_kernel<8, 1024>))
-  SLIDE_SET((hash_rows_kernel<16, 1024>))
+  SLIDE_SET((hash_rows_kernel<0, true>))
+  SLIDE_SET((hash_rows_kernel<2, true>))
+  SLIDE_SET((hash_rows_kernel<4, true>))
+  SLIDE_SET((hash_rows_kernel<8, true>))
+  SLIDE_SET((hash_rows_kernel<16, true>))
+  SLIDE_SET((hash_rows_kernel<0, false>))
+  SLIDE_SET((hash_rows_kernel<2, false>))
+  SLIDE_SET((hash_rows_kernel<4, false>))
+  SLIDE_SET((hash_rows_kernel<8, false>))
+  SLIDE_SET((hash_rows_kernel<16, false>))
 #undef SLIDE_SET
   return hipSuccess;
 }

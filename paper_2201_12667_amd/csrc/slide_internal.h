@@ -37,7 +37,7 @@ struct Ctrl {
 struct HashDev {
   int kind, H, K, L, NH;
   int m, lgm;             // DWTA bin size and its log2
-  int S, Spad;            // SimHash coordinates per bit, padded to even
+  int S, Spad, So;        // SimHash coordinates per bit, padded to even; entries per bit in offs
   const uint32_t* words;  // DWTA: NH*m/2 words of two u16 coordinates; SimHash: NH*Spad/2 words of
                           // two u16 (bit 15 = subtract)
   const uint32_t* offs;   // the same coordinates as byte offsets into the row-tile kernel's LDS tile, one
@@ -59,7 +59,8 @@ hipError_t launch_hash(const HashDev& hd, const float* V, int64_t rows, uint32_t
                        uint32_t nb, int tables_per_block, hipStream_t s);
 hipError_t hash_setup_attributes(int H);
 size_t hash_lds_bytes(int H);
-int hash_tile_pitch(int H);       // words between consecutive coordinates in the row-tile kernel's LDS tile
+int hash_tile_pitch(int H);
+inline int simhash_offset_stride(int S) { return (S + 7) / 8 * 8; }       // words between consecutive coordinates in the row-tile kernel's LDS tile
 
 // ---- tables.hip -----------------------------------------------------------------------
 struct TablesDev {
