@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--sample-budget", type=int, default=0,
                     help="retrieved neurons kept per sample (0 = all, the configuration the metric is quoted on)")
     ap.add_argument("--sample-fill", action="store_true", help="fill an unmet budget with uniformly drawn neurons")
+    ap.add_argument("--rebuild-every", type=int, default=None, help="override the workload's rebuild schedule")
+    ap.add_argument("--incremental-rebuild", action="store_true",
+                    help="scheduled rebuilds hash only the rows updated since the last build")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run the library's plain copy kernel on MIB mebibytes (10 launches) and print "
                          "its bandwidth: the yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
@@ -85,6 +88,10 @@ def main() -> int:
     if args.sample_budget:
         import dataclasses
         wl = dataclasses.replace(wl, sample_budget=args.sample_budget, sample_fill=args.sample_fill)
+    if args.rebuild_every is not None or args.incremental_rebuild:
+        import dataclasses
+        wl = dataclasses.replace(wl, incremental_rebuild=args.incremental_rebuild,
+                                 rebuild_every=wl.rebuild_every if args.rebuild_every is None else args.rebuild_every)
     gen = synth.Generator(wl, args.seed)
     weights, hp = gen.weights(), gen.hash_params()
     model = slide.Slide(slide.config_from_workload(wl), weights, hp)
@@ -105,7 +112,8 @@ def main() -> int:
     assert model.status() == 0, "device flagged bad batch data"
     model.reset_stats()
     dom = slide.STAGES.index("update")
-    model.profile(1 << dom)
+    reb = slide.STAGES.index("rebuild")
+    model.profile((1 << dom) | (1 << reb))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(W, W + K):
@@ -136,7 +144,8 @@ def main() -> int:
                    "input_dim": wl.input_dim, "hidden_dim": wl.hidden_dim, "num_classes": wl.num_classes,
                    "hash": "dwta" if wl.hash_kind == synth.HASH_DWTA else "simhash", "K": wl.K, "L": wl.L,
                    "bucket_cap": wl.bucket_cap, "rebuild_every": wl.rebuild_every,
-                   "rebuilds_in_timed_region": rebuilds_in_region, "seed": args.seed,
+                   "rebuilds_in_timed_region": rebuilds_in_region,
+                   "incremental_rebuild": bool(wl.incremental_rebuild), "seed": args.seed,
                    "sample_budget": wl.sample_budget, "sample_fill": bool(wl.sample_fill)},
         "roofline": {"bound": "hbm", "kernel": "update_kernel (gradient + Adam on the touched rows of W2 and W1)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -150,6 +159,10 @@ def main() -> int:
                        "compulsory_GBs": (7.0 * wl.hidden_dim * 4 * (U + U1) + 40.0 * A) / (step_ms * 1e-3) / 1e9},
         "table_build_ms": build_ms,
     }
+    if rebuilds_in_region and int(n[reb]):
+        out["rebuild_in_region"] = {"avg_ms": float(ms[reb]) / int(n[reb]), "count": int(n[reb]),
+                                    "incremental": bool(wl.incremental_rebuild),
+                                    "rows_hashed_by_last": st["rehashed_rows"]}
     if wl.rebuild_every:
         out["ms_per_step_amortised_rebuild"] = step_ms + (0 if rebuilds_in_region else build_ms / wl.rebuild_every)
 

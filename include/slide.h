@@ -32,7 +32,7 @@
 extern "C" {
 #endif
 
-#define SLIDE_ABI_VERSION 2u
+#define SLIDE_ABI_VERSION 3u
 
 typedef struct slide_ctx slide_ctx; /* opaque, host side */
 
@@ -82,7 +82,13 @@ typedef struct {
   int32_t sample_budget;
   int32_t sample_fill;
   uint32_t sample_seed;
-  uint32_t reserved;         /* 0                                                                 */
+  /* 1: a rebuild scheduled by rebuild_every hashes only the rows of W2 that the training steps since the
+   * last build have updated (Section 3.1: the tables are updated locally) and keeps the codes of the
+   * others (when more than three quarters of the rows were updated it hashes them all, which is then
+   * cheaper); the tables come out exactly as from a full rebuild.  The library then assumes that nobody
+   * else writes W2 between builds: after changing W2 yourself, call slide_build_tables, which always
+   * hashes every row.  Costs 5 bytes per output neuron of workspace. */
+  int32_t incremental_rebuild;
 } slide_config;
 
 typedef struct {
@@ -137,6 +143,7 @@ typedef struct {
   int64_t overflowed_buckets;/* buckets that held more than C neurons at last build */
   int64_t steps;             /* t, training steps done                              */
   int64_t rebuilds;          /* r, rebuilds done after the first build              */
+  int64_t rehashed_rows;     /* rows of W2 hashed by the last build                 */
   /* totals over the training steps since the last slide_reset_stats */
   int64_t sum_active_pairs, sum_unique_out_rows, sum_unique_in_rows, sum_candidates, sum_steps;
 } slide_stats;

@@ -33,7 +33,7 @@ struct Layout {
   size_t hash_words;
   // workspace offsets
   size_t ctrl, hashw, hashoff, xse, zc, best, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
-      as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, ws_total;
+      as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, touched, touched_rows, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
 };
@@ -96,7 +96,8 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->NT2 = lo->NWpad / tw;
   lo->DWpad = (int)(((lo->D + 31) / 32 + 31) / 32 * 32);
   lo->NT1 = lo->DWpad / lo->TWF;
-  if (c->sample_budget < 0 || c->reserved != 0) FAIL(SLIDE_EINVAL, "sample_budget must be >= 0 and reserved 0");
+  if (c->sample_budget < 0) FAIL(SLIDE_EINVAL, "sample_budget must be >= 0");
+  if (c->incremental_rebuild != 0 && c->incremental_rebuild != 1) FAIL(SLIDE_EINVAL, "incremental_rebuild must be 0 or 1");
   const int64_t per_sample = std::min<int64_t>(std::max<int64_t>((int64_t)c->L * c->bucket_cap, c->sample_budget), lo->N);
   lo->PS = (int)per_sample;
   lo->Amax = (int64_t)c->max_batch * per_sample + c->max_labels_per_batch;
@@ -142,6 +143,11 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->bh = take(tables_bh_words(lo->bits, lo->N, lo->L) * 4);
   lo->pbase = take(tables_pbase_words(lo->bits, lo->N, lo->L) * 4);
   lo->worklist = take((size_t)lo->wl_cap * 8);
+  lo->touched = lo->touched_rows = 0;
+  if (c->incremental_rebuild) {
+    lo->touched = take(((size_t)lo->N + 3) / 4 * 4);
+    lo->touched_rows = take((size_t)lo->N * 4);
+  }
   lo->ws_total = o;
   o = 0;
   lo->t_off = take((size_t)lo->L * (lo->nb + 1) * 4);
@@ -163,6 +169,7 @@ struct slide_ctx {
   int64_t t = 0, r = 0;
   bool built = false;
   bool ever_built = false;       // a build has happened (later ones count as rebuilds)
+  bool codes_current = false;    // codes_t holds the codes of W2 under the current hash functions, up to the marked rows
   int last_B = 0;
   uint64_t calls = 0;            // forward passes launched (selects the set of per-call device accumulators)
   const float* last_h = nullptr;
@@ -301,13 +308,20 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   return SLIDE_OK;
 }
 
-int do_build(slide_ctx* ctx, hipStream_t s) {
+// scheduled: the build is the training step's own, so the rows marked by the steps since the last
+// build are the only ones whose weights (hence codes) can differ from what codes_t holds.
+int do_build(slide_ctx* ctx, hipStream_t s, bool scheduled) {
   const Layout& lo = ctx->lo;
+  const bool inc = ctx->cfg.incremental_rebuild != 0;
+  const bool only_touched = inc && scheduled && ctx->codes_current;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_REBUILD, s, [&] {
     return launch_build_tables(ctx->hd, ctx->td, ctx->buf.W2, ctx->at<uint32_t>(lo.codes_t),
                                ctx->at<uint2>(lo.entries), ctx->at<uint32_t>(lo.bh), ctx->at<uint32_t>(lo.pbase),
                                ctx->at<uint64_t>(lo.worklist), lo.wl_cap, ctx->ctrl(), ctx->cfg.overflow_policy,
-                               (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b, s); }));
+                               (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b,
+                               inc ? ctx->at<uint8_t>(lo.touched) : nullptr,
+                               inc ? ctx->at<int32_t>(lo.touched_rows) : nullptr, only_touched, s); }));
+  ctx->codes_current = true;
   return SLIDE_OK;
 }
 
@@ -443,7 +457,7 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
     slide_destroy(ctx);
     return SLIDE_EINVAL;
   }
-  if (hash_lds_bytes(H) > ctx->lds_limit) {
+  if (hash_lds_bytes(H) + 1024 > ctx->lds_limit) {
     set_err(nullptr, SLIDE_EINVAL, "hidden_dim %d needs %zu bytes of LDS, device offers %zu", H, hash_lds_bytes(H), ctx->lds_limit);
     slide_destroy(ctx);
     return SLIDE_EINVAL;
@@ -466,7 +480,7 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
 int slide_build_tables(slide_ctx* ctx, void* hip_stream) {
   if (!ctx) return SLIDE_EINVAL;
   if (ctx->ever_built) ctx->r += 1;
-  const int rc = do_build(ctx, (hipStream_t)hip_stream);
+  const int rc = do_build(ctx, (hipStream_t)hip_stream, false);
   if (rc == SLIDE_OK) { ctx->built = true; ctx->ever_built = true; }
   return rc;
 }
@@ -484,6 +498,7 @@ int slide_set_hash_params(slide_ctx* ctx, const slide_hash_params* hp, void* hip
     HIPCHK(ctx, hipMemcpy(ctx->ws() + ctx->lo.hashoff, offs.data(), offs.size() * 4, hipMemcpyHostToDevice));
   }
   ctx->hd.dens_a = hp->dens_a; ctx->hd.dens_b = hp->dens_b;
+  ctx->codes_current = false;
   ctx->prio_a = hp->prio_a; ctx->prio_b = hp->prio_b;
   ctx->built = false;                                           // the tables belong to the old functions
   return SLIDE_OK;
@@ -510,6 +525,7 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   const int Bpad = (b->batch + 63) & ~63;
   TransposeArgs t2{}, t1{};
   t2.B = b->batch; t2.Bpad = Bpad; t2.TW = lo.TW; t2.ntiles = lo.NT2; t2.pd = p2;
+  t2.touched = c.incremental_rebuild ? ctx->at<uint8_t>(lo.touched) : nullptr;
   if (lo.D > 0) {
     t1.B = b->batch; t1.Bpad = Bpad; t1.TW = lo.TWF; t1.ntiles = lo.NT1; t1.pd = p1;
     t1.ids = b->x_indices; t1.xse = ctx->at<int2>(lo.xse); t1.x_nnz = b->nnz;
@@ -547,7 +563,7 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   ctx->t = t;
   if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
     ctx->r += 1;
-    if ((rc = do_build(ctx, s)) != SLIDE_OK) return rc;
+    if ((rc = do_build(ctx, s, true)) != SLIDE_OK) return rc;
   }
   return SLIDE_OK;
 }
@@ -609,6 +625,7 @@ int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out) {
   out->unique_in_rows = c.u1;
   out->candidates = ((int64_t)c.candidates_hi << 32) | c.candidates_lo;
   out->overflowed_buckets = c.overflowed;
+  out->rehashed_rows = c.rehashed;
   out->steps = ctx->t;
   out->rebuilds = ctx->r;
   out->sum_active_pairs = (int64_t)c.sum_pairs;
@@ -665,7 +682,7 @@ int slide_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_str
 
 int slide_debug_hash(slide_ctx* ctx, const float* d_vectors, int64_t rows, uint32_t* d_codes, void* hip_stream) {
   if (!ctx || !d_vectors || !d_codes || rows < 0) return SLIDE_EINVAL;
-  HIPCHK(ctx, launch_hash(ctx->hd, d_vectors, rows, d_codes, ctx->lo.L, 1, nullptr, nullptr, ctx->lo.nb, 4,
+  HIPCHK(ctx, launch_hash(ctx->hd, d_vectors, rows, d_codes, ctx->lo.L, 1, nullptr, nullptr, 4,
                           (hipStream_t)hip_stream));
   return SLIDE_OK;
 }

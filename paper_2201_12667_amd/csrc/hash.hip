@@ -109,21 +109,38 @@ __device__ __forceinline__ uint32_t simhash_code(const HashDev& hd, const uint32
   return code;
 }
 
-// MODE 0: SimHash; 2,4,8,16: DWTA with that bin size.
+// MODE 0: SimHash; 2,4,8,16: DWTA with that bin size.  UNI: a tile holds 64 vectors, so a wave works
+// on one table at a time and reads its coordinates through scalar loads.
+// rowlist == nullptr: vectors 0 .. rows-1 of V.  Otherwise the vectors rowlist[0 .. *nrows_dev) of V
+// (the grid covers rows; tiles past the device-side count leave at once; a count equal to rows means
+// all of them, and the list is not read).
 template <int MODE, bool UNI>
 __global__ __launch_bounds__(1024) void hash_rows_kernel(HashDev hd, const uint32_t* __restrict__ offs,
                                                         const float* __restrict__ V,
                                                         int64_t rows, int RPT, uint32_t* __restrict__ codes,
                                                         int64_t row_stride, int64_t tab_stride,
-                                                        uint32_t* hist, uint32_t* __restrict__ rank,
-                                                        uint32_t nbp1, int tpb) {
+                                                        const int32_t* __restrict__ rowlist,
+                                                        const uint32_t* __restrict__ nrows_dev, int tpb) {
   extern __shared__ float tile[];                    // [H + 1][RPT + 1]; the last row is zero
+  __shared__ int64_t rid[64];                        // vector held by tile column r, -1 = none
   const int stride = RPT + 1, H = hd.H;
-  if ((int)threadIdx.x < stride) tile[H * stride + threadIdx.x] = 0.0f;
   const int64_t row0 = (int64_t)blockIdx.x * RPT;
+  if (rowlist) {
+    const int64_t listed = (int64_t)*nrows_dev;
+    if (listed == rows) rowlist = nullptr;           // every vector: in place, without the list
+    rows = listed;
+  }
+  if (row0 >= rows) return;
+  if ((int)threadIdx.x < RPT) {
+    const int64_t q = row0 + threadIdx.x;
+    rid[threadIdx.x] = q < rows ? (rowlist ? (int64_t)rowlist[q] : q) : -1;
+  }
+  if ((int)threadIdx.x < stride) tile[H * stride + threadIdx.x] = 0.0f;
+  __syncthreads();
   for (int idx = threadIdx.x; idx < RPT * H; idx += blockDim.x) {   // coalesced read, conflict-free store
     const int r = idx / H, c = idx - r * H;
-    const float x = (row0 + r < rows) ? V[(row0 + r) * H + c] : 0.0f;
+    const int64_t row = rid[r];
+    const float x = row >= 0 ? V[row * H + c] : 0.0f;
     tile[c * stride + r] = MODE == 0 ? x : __uint_as_float(dwta_key(x));
   }
   __syncthreads();
@@ -131,7 +148,7 @@ __global__ __launch_bounds__(1024) void hash_rows_kernel(HashDev hd, const uint3
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
   const int tps = 64 / RPT;                          // tables per wave and step (RPT is 16, 32 or 64)
   const int r = lane & (RPT - 1), sub = lane / RPT;
-  const bool active = row0 + r < rows;
+  const int64_t row = rid[r];
   const char* col0 = (const char*)(tile + r);
   const int t_end = min((int)(blockIdx.y + 1) * tpb, hd.L);
   int rowstate = -1;
@@ -141,44 +158,37 @@ __global__ __launch_bounds__(1024) void hash_rows_kernel(HashDev hd, const uint3
     uint32_t code;
     if (MODE == 0) code = simhash_code<UNI>(hd, offs, col0, t);
     else code = dwta_code<(MODE == 0 ? 2 : MODE), UNI>(hd, offs, col0, stride * 4, t, rowstate);
-    if (active) {
-      const int64_t row = row0 + r;
-      codes[row * row_stride + (int64_t)t * tab_stride] = code;
-      if (hist) {
-        const uint32_t pos = atomicAdd(&hist[(size_t)t * nbp1 + code], 1u);
-        rank[(size_t)t * rows + row] = pos;
-      }
-    }
+    if (row >= 0) codes[row * row_stride + (int64_t)t * tab_stride] = code;
   }
 }
 
 template <int MODE>
 static hipError_t launch_mode(const HashDev& hd, const float* V, int64_t rows, uint32_t* codes,
-                              int64_t row_stride, int64_t tab_stride, uint32_t* hist, uint32_t* rank,
-                              uint32_t nb, int tpb, hipStream_t s) {
+                              int64_t row_stride, int64_t tab_stride, const int32_t* rowlist,
+                              const uint32_t* nrows_dev, int tpb, hipStream_t s) {
   const int RPT = rows_per_tile(hd.H);
   dim3 grid((unsigned)ceil_div(rows, RPT), (unsigned)ceil_div(hd.L, tpb));
   if (RPT == 64)
     hipLaunchKernelGGL((hash_rows_kernel<MODE, true>), grid, dim3(1024), hash_lds_bytes(hd.H), s, hd, hd.offs, V, rows,
-                       RPT, codes, row_stride, tab_stride, hist, rank, nb + 1, tpb);
+                       RPT, codes, row_stride, tab_stride, rowlist, nrows_dev, tpb);
   else
     hipLaunchKernelGGL((hash_rows_kernel<MODE, false>), grid, dim3(1024), hash_lds_bytes(hd.H), s, hd, hd.offs, V, rows,
-                       RPT, codes, row_stride, tab_stride, hist, rank, nb + 1, tpb);
+                       RPT, codes, row_stride, tab_stride, rowlist, nrows_dev, tpb);
   return hipGetLastError();
 }
 
 hipError_t launch_hash(const HashDev& hd, const float* V, int64_t rows, uint32_t* codes,
-                       int64_t row_stride, int64_t tab_stride, uint32_t* hist, uint32_t* rank,
-                       uint32_t nb, int tables_per_block, hipStream_t s) {
+                       int64_t row_stride, int64_t tab_stride, const int32_t* rowlist,
+                       const uint32_t* nrows_dev, int tables_per_block, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   const int tpb = tables_per_block < 1 ? 1 : tables_per_block;
   if (hd.kind == SLIDE_HASH_SIMHASH)
-    return launch_mode<0>(hd, V, rows, codes, row_stride, tab_stride, hist, rank, nb, tpb, s);
+    return launch_mode<0>(hd, V, rows, codes, row_stride, tab_stride, rowlist, nrows_dev, tpb, s);
   switch (hd.m) {
-    case 2: return launch_mode<2>(hd, V, rows, codes, row_stride, tab_stride, hist, rank, nb, tpb, s);
-    case 4: return launch_mode<4>(hd, V, rows, codes, row_stride, tab_stride, hist, rank, nb, tpb, s);
-    case 8: return launch_mode<8>(hd, V, rows, codes, row_stride, tab_stride, hist, rank, nb, tpb, s);
-    case 16: return launch_mode<16>(hd, V, rows, codes, row_stride, tab_stride, hist, rank, nb, tpb, s);
+    case 2: return launch_mode<2>(hd, V, rows, codes, row_stride, tab_stride, rowlist, nrows_dev, tpb, s);
+    case 4: return launch_mode<4>(hd, V, rows, codes, row_stride, tab_stride, rowlist, nrows_dev, tpb, s);
+    case 8: return launch_mode<8>(hd, V, rows, codes, row_stride, tab_stride, rowlist, nrows_dev, tpb, s);
+    case 16: return launch_mode<16>(hd, V, rows, codes, row_stride, tab_stride, rowlist, nrows_dev, tpb, s);
   }
   return hipErrorInvalidValue;
 }

@@ -21,7 +21,7 @@ struct Ctrl {
   uint32_t wl_count;      // big-bucket worklist length
   uint32_t overflowed;    // buckets with more than C members at the last build
   uint32_t total_pairs;   // A
-  uint32_t unused0;
+  uint32_t rehashed;      // rows of W2 hashed by the last build
   uint32_t candidates_lo, candidates_hi;
   uint32_t nlong2, nlong1; // long rows queued by the two transpositions
   uint32_t max_nu2, max_nu1; // most touched rows in any tile
@@ -54,9 +54,11 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 // ---- hash.hip -------------------------------------------------------------------------
 // codes[r*row_stride + t*tab_stride] for r < rows, t < L.  With hist != nullptr also
 // pos = atomicAdd(&hist[t*(nb+1) + code], 1) and rank[t*rows + r] = pos.
+// codes[row * row_stride + t * tab_stride] for the vectors 0 .. rows-1 of V, or, with a row list, for the
+// vectors rowlist[0 .. *nrows_dev) (count on the device, at most rows).
 hipError_t launch_hash(const HashDev& hd, const float* V, int64_t rows, uint32_t* codes,
-                       int64_t row_stride, int64_t tab_stride, uint32_t* hist, uint32_t* rank,
-                       uint32_t nb, int tables_per_block, hipStream_t s);
+                       int64_t row_stride, int64_t tab_stride, const int32_t* rowlist,
+                       const uint32_t* nrows_dev, int tables_per_block, hipStream_t s);
 hipError_t hash_setup_attributes(int H);
 size_t hash_lds_bytes(int H);
 int hash_tile_pitch(int H);
@@ -73,7 +75,8 @@ struct TablesDev {
 hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
                                uint2* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
                                uint32_t wl_cap, Ctrl* ctrl, int policy, uint32_t r, uint32_t prio_a,
-                               uint32_t prio_b, hipStream_t s);
+                               uint32_t prio_b, uint8_t* touched, int32_t* touched_rows, bool only_touched,
+                               hipStream_t s);
 size_t tables_bh_words(int bits, int64_t N, int L);      // per-slab histograms
 size_t tables_pbase_words(int bits, int64_t N, int L);   // partition starts
 hipError_t tables_setup_attributes();
@@ -121,6 +124,7 @@ struct TransposeArgs {
   int2* xse;                     // [ntiles][B]   (features only) positions [start, end) of the sample's
                                  // features inside the tile; (0, 0) = none
   int x_nnz;                     // features only: entries in the batch's CSR arrays
+  uint8_t* touched;              // optional [rows]: set to 1 for every row that gets a header
   PairsDev pd;
 };
 

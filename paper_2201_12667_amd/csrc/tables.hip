@@ -363,6 +363,37 @@ static size_t part_buckets_lds(int lb) {
 }
 static size_t part_scatter_lds(int nbins) { return ((size_t)2 * kSlab + 3 * (size_t)nbins + 20) * 4; }
 
+// Rows of W2 touched since the last build (one byte each, set by the training step) -> a list of
+// their ids and its length; the marks are cleared.  One thread per row, one counter update per
+// workgroup (ascending ids within a workgroup's stretch; stretches in arrival order).
+__global__ __launch_bounds__(1024) void collect_touched_kernel(uint8_t* __restrict__ touched, int64_t N,
+                                                               int32_t* __restrict__ rows, uint32_t* count) {
+  __shared__ uint32_t wsum[17];
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool hit = j < N && touched[j] != 0;
+  const uint64_t m = __ballot(hit);
+  if (lane == 0) wsum[wave] = (uint32_t)__popcll(m);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t run = 0;
+    for (int w = 0; w < 16; ++w) { const uint32_t c = wsum[w]; wsum[w] = run; run += c; }
+    wsum[16] = run ? atomicAdd(count, run) : 0u;
+  }
+  __syncthreads();
+  if (hit) {
+    rows[wsum[16] + wsum[wave] + __popcll(m & ((1ull << lane) - 1))] = (int32_t)j;
+    touched[j] = 0;
+  }
+}
+
+// When most rows were touched, hashing all of them in place is cheaper than hashing them through
+// the list (whole lines of codes instead of scattered words): the count becomes N, which the hash
+// kernel takes as "no list".
+__global__ void settle_touched_kernel(uint32_t* count, uint32_t N) {
+  if (threadIdx.x == 0 && blockIdx.x == 0 && (uint64_t)*count * 4 > (uint64_t)N * 3) *count = N;
+}
+
 hipError_t tables_setup_attributes() {
   hipError_t e = hipFuncSetAttribute((const void*)part_buckets_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)part_buckets_lds(13));
@@ -374,14 +405,28 @@ hipError_t tables_setup_attributes() {
 hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
                                uint2* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
                                uint32_t wl_cap, Ctrl* ctrl, int policy, uint32_t r, uint32_t prio_a,
-                               uint32_t prio_b, hipStream_t s) {
+                               uint32_t prio_b, uint8_t* touched, int32_t* touched_rows, bool only_touched,
+                               hipStream_t s) {
   hipError_t e;
   int bits = 0, hb, lb;
   while ((1u << bits) < td.nb) ++bits;
   tables_split(bits, td.N, &hb, &lb);
   const int nbins = 1 << hb;
   const int nslab = td.N > 0 ? (int)((td.N + kSlab - 1) / kSlab) : 1;
-  if ((e = launch_hash(hd, W2, td.N, codes_t, 1, td.N, nullptr, nullptr, td.nb, hd.L, s)) != hipSuccess) return e;
+  // (1) codes of every row, or -- when codes_t still holds the codes of the last build -- only of the
+  // rows whose weights changed since; the grouping below always runs in full, so the tables are the
+  // same either way.
+  if (only_touched) {
+    if ((e = launch_fill_u32(&ctrl->rehashed, 1, 0u, s)) != hipSuccess) return e;
+    hipLaunchKernelGGL(collect_touched_kernel, dim3((unsigned)ceil_div(td.N, 1024)), dim3(1024), 0, s, touched, td.N,
+                       touched_rows, &ctrl->rehashed);
+    hipLaunchKernelGGL(settle_touched_kernel, dim3(1), dim3(64), 0, s, &ctrl->rehashed, (uint32_t)td.N);
+    if ((e = launch_hash(hd, W2, td.N, codes_t, 1, td.N, touched_rows, &ctrl->rehashed, hd.L, s)) != hipSuccess) return e;
+  } else {
+    if ((e = launch_fill_u32(&ctrl->rehashed, 1, (uint32_t)td.N, s)) != hipSuccess) return e;
+    if (touched && (e = launch_fill_u32((uint32_t*)touched, (size_t)ceil_div(td.N, 4), 0u, s)) != hipSuccess) return e;
+    if ((e = launch_hash(hd, W2, td.N, codes_t, 1, td.N, nullptr, nullptr, hd.L, s)) != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(part_hist_kernel, dim3(nslab, td.L), dim3(1024), (size_t)nbins * 4, s, codes_t, td.N, lb, nbins,
                      bh, nslab);
   hipLaunchKernelGGL(part_scan_kernel, dim3(td.L), dim3(1024), 0, s, bh, nslab, nbins, pbase, ctrl);

@@ -134,6 +134,7 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
       const int w = r >> 5;
       const uint32_t us = slot0 + wou[w] + __popc(wu[w] & below);
       pd.umeta[us] = make_int4(row0 + r, (int)(blk0 + wnp[w] + rowoff[r]), (int)c, 0);
+      if (ta.touched) ta.touched[row0 + r] = 1;
       if ((int)c > kLongRow) {
         const uint32_t l = atomicAdd(pd.nlong, 1u);
         if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;

@@ -51,6 +51,7 @@ class Workload:
     sample_budget: int = 0           # retrieved neurons per sample kept in training (0 = all)
     sample_fill: bool = False        # fill an unmet budget with uniformly drawn neurons
     sample_seed: int = 1
+    incremental_rebuild: bool = False   # scheduled rebuilds rehash only the rows updated since the last build
     # input recipe
     nnz_mode: str = "poisson"        # "exact" | "poisson"
     nnz_mean: float = 75.0

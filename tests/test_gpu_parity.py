@@ -279,6 +279,66 @@ def test_redrawn_hash_functions_then_rebuild(kind):
     model.destroy()
 
 
+@pytest.mark.parametrize("kind,hidden,N", [(synth.HASH_DWTA, 128, 20011), (synth.HASH_SIMHASH, 128, 20011),
+                                           (synth.HASH_DWTA, 1024, 20011), (synth.HASH_DWTA, 128, 1500)])
+def test_incremental_rebuild_equals_full_rebuild(kind, hidden, N):
+    """Scheduled rebuilds that hash only the rows updated since the last build (Section 3.1: the
+    tables are updated locally).  A row that no step touched keeps its weights, hence its codes, so
+    the tables must be those of a full rebuild: checked bucket by bucket against a second model
+    that rebuilds in full, with the loss checked against the oracle (which always rebuilds in full),
+    and the number of rows hashed checked against the union of the active sets since the last build
+    (all N once that union exceeds three quarters of the rows: the small layer of the last case)."""
+    import dataclasses
+    _say("incremental rebuild", kind, hidden, N)
+    over = dict(hidden_dim=hidden, K=3, L=6) if hidden != 128 else {}
+    wl_full = synth.small(kind, rebuild_every=2, bucket_cap=8, num_classes=N, **over)
+
+    def hashed(touched):
+        return len(touched) if 4 * len(touched) <= 3 * N else N
+
+    wl_inc = dataclasses.replace(wl_full, incremental_rebuild=True)
+    gen, full, orc = make_pair(wl_full)
+    _, inc, _ = make_pair(wl_inc)
+    full.build_tables()
+    inc.build_tables()
+    orc.build_tables()
+    assert inc.stats()["rehashed_rows"] == N and full.stats()["rehashed_rows"] == N
+    hashed_all = 0
+    touched = set()
+    for s in range(6):
+        b = gen.batch(s)
+        loss_full = float(full.train_step(full.to_device(b)).item())
+        loss_inc = float(inc.train_step(inc.to_device(b)).item())
+        ref = orc.train_step(b)
+        assert loss_full == loss_inc
+        assert abs(loss_inc - ref["loss"]) < 1e-3
+        _, ids, _, _, _ = inc.debug_active()
+        touched |= set(ids.tolist())
+        if (s + 1) % 2 == 0:
+            assert ref["rebuilt"]
+            assert inc.stats()["rehashed_rows"] == hashed(touched)
+            hashed_all += hashed(touched) == N
+            assert full.stats()["rehashed_rows"] == N
+            touched.clear()
+            for t in range(wl_full.L):
+                for c in range(wl_full.num_buckets):
+                    assert np.array_equal(inc.debug_bucket(t, c), full.debug_bucket(t, c)), (s, t, c)
+    assert inc.stats()["rebuilds"] == full.stats()["rebuilds"] == orc.r == 3
+    assert hashed_all == (3 if N == 1500 else 0)
+    for n in inc.p:
+        assert torch.equal(inc.p[n], full.p[n]), n
+    # an explicit build trusts nothing: every row is hashed again, and the marks start afresh
+    inc.build_tables()
+    assert inc.stats()["rehashed_rows"] == N
+    inc.train_step(inc.to_device(gen.batch(6)))
+    _, ids, _, _, _ = inc.debug_active()
+    inc.train_step(inc.to_device(gen.batch(7)))
+    _, ids2, _, _, _ = inc.debug_active()
+    assert inc.stats()["rehashed_rows"] == hashed(set(ids.tolist()) | set(ids2.tolist()))
+    full.destroy()
+    inc.destroy()
+
+
 @pytest.mark.parametrize("name,wl", [
     ("over-budget", synth.small(synth.HASH_DWTA, sample_budget=20, sample_seed=9)),
     ("over-budget-simhash", synth.small(synth.HASH_SIMHASH, sample_budget=7, sample_seed=3, batch=130)),
