@@ -32,7 +32,7 @@ struct Layout {
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, hashoff, xse, zc, best, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, hashoff, xse, zc, best, cand, ccnt, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, touched, touched_rows, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -123,6 +123,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->dense_chunk = dense_chunk_neurons(lo->N, lo->Bmax);
   lo->zc = take(B * (size_t)lo->dense_chunk * 4);
   lo->best = take(B * 64 * 8);
+  lo->cand = take(B * dense_cand_keys() * 8); lo->ccnt = take(B * dense_counter_words() * 4);
   lo->h = take(lo->D ? B * H * 4 : 0);
   lo->dh = take(B * H * 4);
   lo->codes = take(B * lo->L * 4);
@@ -590,7 +591,8 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
     ctx->last_B = b->batch;
     ctx->last_dh = nullptr;
     HIPCHK(ctx, launch_dense_topk(b->batch, lo.N, lo.H, h, ctx->buf.W2, ctx->buf.b2, topk, ctx->at<float>(lo.zc),
-                                  lo.dense_chunk, ctx->at<uint64_t>(lo.best), d_out_ids, d_out_scores, s));
+                                  lo.dense_chunk, ctx->at<uint64_t>(lo.best), ctx->at<uint64_t>(lo.cand),
+                                  ctx->at<uint32_t>(lo.ccnt), d_out_ids, d_out_scores, s));
     return SLIDE_OK;
   }
   ActiveDev ad;

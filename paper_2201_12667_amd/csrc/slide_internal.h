@@ -167,8 +167,10 @@ hipError_t launch_topk(const ActiveDev& ad, const float* z, int topk, int32_t* o
 // per sample (best: [B][64] scratch keys).
 int64_t dense_chunk_neurons(int64_t N, int Bmax);
 hipError_t launch_dense_topk(int B, int64_t N, int H, const float* h, const float* W2, const float* b2, int topk,
-                             float* zc, int64_t chunk, uint64_t* best, int32_t* out_ids, float* out_scores,
-                             hipStream_t s);
+                             float* zc, int64_t chunk, uint64_t* best, uint64_t* cand, uint32_t* ccnt,
+                             int32_t* out_ids, float* out_scores, hipStream_t s);
+size_t dense_cand_keys();     // candidate keys per sample (cand is [B][dense_cand_keys()])
+size_t dense_counter_words(); // words per sample in ccnt
 
 // ---- update.hip -----------------------------------------------------------------------
 // Rows of one weight matrix to update: for every listed row r, g = sum over its pairs of

@@ -54,7 +54,7 @@ def _check_topk(ids, sc, z, topk):
                                input_dim=2500, bucket_cap=64), 10),
     ("fewer-neurons-than-k", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=3, L=3, batch=9, num_classes=50,
                                          input_dim=100, nnz_mean=5.0, lab_mean=1.0), 64),
-    # 2048 samples: the neurons are scored in three chunks of 8192
+    # 2048 samples: eight sample tiles per neuron tile, two chunks of neurons
     ("b2048-three-chunks", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=5, L=4, batch=2048, num_classes=20011,
                                        input_dim=0, bucket_cap=8), 7),
     ("h4", synth.small(synth.HASH_SIMHASH, hidden_dim=4, K=2, L=3, batch=3, num_classes=700,
@@ -72,6 +72,31 @@ def test_predict_over_all_neurons_matches_oracle(name, wl, topk):
     assert exact > 0.98
     want_ids, _ = orc.predict(b, topk, 1)
     assert float((ids == want_ids).mean()) > 0.98
+    assert model.status() == 0
+    model.destroy()
+
+
+@pytest.mark.parametrize("slope", [0.01, -0.01])
+def test_predict_when_every_or_no_later_neuron_beats_the_list(slope):
+    """The two extremes of the chunked top-k: biases that grow with the neuron id make every score of
+    every later chunk beat the running list (the candidate buffers overflow and the chunk's scores are
+    streamed instead); biases that fall with the id make none beat it (the list of the first chunk stands)."""
+    _say("dense predict, bias slope", slope)
+    wl = synth.small(synth.HASH_DWTA, num_classes=20011, batch=33)
+    gen, model, orc = make_pair(wl)
+    bias = (slope * np.arange(wl.num_classes)).astype(np.float32)
+    orc.p["b2"][:] = bias
+    model.p["b2"].copy_(torch.from_numpy(bias))
+    model.build_tables()
+    b = gen.batch(0)
+    for topk in (1, 64):
+        ids, sc = model.predict(model.to_device(b), topk, mode=1)
+        ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+        exact = _check_topk(ids, sc, _dense_scores(orc, b), topk)
+        _say("   topk", topk, "positions identical to the oracle's order:", round(exact, 4))
+        assert exact > 0.9
+        lo, hi = (wl.num_classes - 200, wl.num_classes) if slope > 0 else (0, 200)
+        assert ids.min() >= lo and ids.max() < hi
     assert model.status() == 0
     model.destroy()
 
