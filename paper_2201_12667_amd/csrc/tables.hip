@@ -115,15 +115,23 @@ __global__ __launch_bounds__(1024) void part_scan_kernel(uint32_t* bh, int nslab
   if (t == 0 && tid == 0) { ctrl->wl_count = 0; ctrl->overflowed = 0; }
 }
 
-// One workgroup per (slab, table): the slab's (code, row) entries are first grouped by partition in
+// An entry of the partitioned list: (code, row), or -- PACKED, when the low digit and the row index fit
+// 32 bits together -- (low digit << rowbits) | row, which halves what the two passes below move.
+template <bool PACKED> struct Entry { typedef uint2 type; };
+template <> struct Entry<true> { typedef uint32_t type; };
+
+// One workgroup per (slab, table): the slab's entries are first grouped by partition in
 // LDS (a local counting sort), then written out, so that every partition receives one contiguous
-// run per slab instead of single 8-byte entries.
+// run per slab instead of single entries.
+template <bool PACKED>
 __global__ __launch_bounds__(1024) void part_scatter_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,
-                                                            int nbins, const uint32_t* __restrict__ bh, int nslab,
-                                                            const uint32_t* __restrict__ pbase,
-                                                            uint2* __restrict__ entries) {
+                                                            int rowbits, int nbins, const uint32_t* __restrict__ bh,
+                                                            int nslab, const uint32_t* __restrict__ pbase,
+                                                            typename Entry<PACKED>::type* __restrict__ entries) {
+  typedef typename Entry<PACKED>::type E;
   extern __shared__ uint32_t lds[];
-  uint2* stage = (uint2*)lds;                      // [kSlab] entries grouped by partition
+  E* stage = (E*)lds;                              // [kSlab] entries grouped by partition
+  uint16_t* stage_p = (uint16_t*)(lds + kSlab);    // [kSlab] PACKED: their partitions (the entry no longer says)
   uint32_t* lstart = lds + 2 * kSlab;              // [nbins] first staged entry of the partition
   uint32_t* cur = lstart + nbins;                  // [nbins] counters, then cursors
   uint32_t* gbase = cur + nbins;                   // [nbins] where the partition's run goes in the table's entries
@@ -160,13 +168,22 @@ __global__ __launch_bounds__(1024) void part_scatter_kernel(const uint32_t* __re
 #pragma unroll
   for (int k = 0; k < kSlab / 1024; ++k) {
     const int r = k * 1024 + tid;
-    if (r < nvalid) stage[atomicAdd(&cur[code[k] >> lb], 1u)] = make_uint2(code[k], (uint32_t)(j0 + r));
+    if (r < nvalid) {
+      const uint32_t pos = atomicAdd(&cur[code[k] >> lb], 1u);
+      if constexpr (PACKED) {
+        stage[pos] = ((code[k] & ((1u << lb) - 1u)) << rowbits) | (uint32_t)(j0 + r);
+        stage_p[pos] = (uint16_t)(code[k] >> lb);
+      } else {
+        stage[pos] = make_uint2(code[k], (uint32_t)(j0 + r));
+      }
+    }
   }
   __syncthreads();
-  uint2* out = entries + t * N;
+  E* out = entries + t * N;
   for (int k = tid; k < nvalid; k += 1024) {
-    const uint2 e = stage[k];
-    const uint32_t p = e.x >> lb;
+    const E e = stage[k];
+    uint32_t p;
+    if constexpr (PACKED) p = stage_p[k]; else p = e.x >> lb;
     out[gbase[p] + ((uint32_t)k - lstart[p])] = e;
   }
 }
@@ -178,9 +195,11 @@ constexpr int kLdsSort = 32;       // buckets up to this size are sorted by one 
 // low digit, writes the partition's offsets, groups the ids by bucket -- in LDS when the partition
 // fits, so that the table receives whole lines -- and sorts the small buckets; long and
 // over-capacity buckets are queued.
-__global__ __launch_bounds__(256) void part_buckets_kernel(const uint2* __restrict__ entries,
+template <bool PACKED>
+__global__ __launch_bounds__(256) void part_buckets_kernel(const typename Entry<PACKED>::type* __restrict__ entries,
                                                            const uint32_t* __restrict__ pbase, int nbins, int lb,
-                                                           uint32_t nb, int64_t N, int C, uint32_t* __restrict__ off,
+                                                           int rowbits, uint32_t nb, int64_t N, int C,
+                                                           uint32_t* __restrict__ off,
                                                            int32_t* ids, uint64_t* worklist, uint32_t wl_cap,
                                                            Ctrl* ctrl) {
   extern __shared__ uint32_t lds[];
@@ -193,11 +212,17 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint2* __restri
   const size_t t = blockIdx.y;
   const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
   const uint32_t mask = (uint32_t)nlo - 1u;
-  const uint2* ent = entries + t * N;
+  const typename Entry<PACKED>::type* ent = entries + t * N;
+  auto low_digit = [&](typename Entry<PACKED>::type e) -> uint32_t {
+    if constexpr (PACKED) return e >> rowbits; else return e.x & mask;
+  };
+  auto row_of = [&](typename Entry<PACKED>::type e) -> int32_t {
+    if constexpr (PACKED) return (int32_t)(e & ((1u << rowbits) - 1u)); else return (int32_t)e.y;
+  };
   const bool staged = s1 - s0 <= (uint32_t)kStageIds;
   for (int b = tid; b < nlo; b += 256) cur[b] = 0;
   __syncthreads();
-  for (uint32_t e = s0 + tid; e < s1; e += 256) atomicAdd(&cur[ent[e].x & mask], 1u);
+  for (uint32_t e = s0 + tid; e < s1; e += 256) atomicAdd(&cur[low_digit(ent[e])], 1u);
   __syncthreads();
   // exclusive scan of the counters: every wave scans chunks of 64 in registers, wave 0 the chunk sums
   for (int c = wave; c < nchunk; c += 4) {
@@ -230,8 +255,8 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint2* __restri
   int32_t* seg = ids + t * N + s0;
   int32_t* place = staged ? idl : seg;
   for (uint32_t e = s0 + tid; e < s1; e += 256) {
-    const uint2 x = ent[e];
-    place[atomicAdd(&cur[x.x & mask], 1u)] = (int32_t)x.y;
+    const auto x = ent[e];
+    place[atomicAdd(&cur[low_digit(x)], 1u)] = row_of(x);
   }
   __syncthreads();                                  // cur[b] is now the end of bucket b = the start of bucket b + 1
   const uint32_t small = staged ? (uint32_t)kLdsSort : (uint32_t)kSmallBucket;
@@ -395,11 +420,16 @@ __global__ void settle_touched_kernel(uint32_t* count, uint32_t N) {
 }
 
 hipError_t tables_setup_attributes() {
-  hipError_t e = hipFuncSetAttribute((const void*)part_buckets_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)part_buckets_lds(13));
+  hipError_t e;
+#define SLIDE_SET(K, BYTES) \
+  e = hipFuncSetAttribute((const void*)&K, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(BYTES)); \
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void*)part_scatter_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)part_scatter_lds(2048));
+  SLIDE_SET(part_buckets_kernel<false>, part_buckets_lds(13))
+  SLIDE_SET(part_buckets_kernel<true>, part_buckets_lds(13))
+  SLIDE_SET(part_scatter_kernel<false>, part_scatter_lds(2048))
+  SLIDE_SET(part_scatter_kernel<true>, part_scatter_lds(2048))
+#undef SLIDE_SET
+  return hipSuccess;
 }
 
 hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
@@ -430,10 +460,21 @@ hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const flo
   hipLaunchKernelGGL(part_hist_kernel, dim3(nslab, td.L), dim3(1024), (size_t)nbins * 4, s, codes_t, td.N, lb, nbins,
                      bh, nslab);
   hipLaunchKernelGGL(part_scan_kernel, dim3(td.L), dim3(1024), 0, s, bh, nslab, nbins, pbase, ctrl);
-  hipLaunchKernelGGL(part_scatter_kernel, dim3(nslab, td.L), dim3(1024), part_scatter_lds(nbins), s, codes_t, td.N, lb,
-                     nbins, bh, nslab, pbase, entries);
-  hipLaunchKernelGGL(part_buckets_kernel, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb), s, entries,
-                     pbase, nbins, lb, td.nb, td.N, td.C, td.off, td.ids, worklist, wl_cap, ctrl);
+  int rowbits = 1;
+  while (((int64_t)1 << rowbits) < td.N) ++rowbits;
+  if (lb + rowbits <= 32) {
+    hipLaunchKernelGGL(part_scatter_kernel<true>, dim3(nslab, td.L), dim3(1024), part_scatter_lds(nbins), s, codes_t, td.N,
+                       lb, rowbits, nbins, bh, nslab, pbase, (uint32_t*)entries);
+    hipLaunchKernelGGL(part_buckets_kernel<true>, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb), s,
+                       (const uint32_t*)entries, pbase, nbins, lb, rowbits, td.nb, td.N, td.C, td.off, td.ids, worklist,
+                       wl_cap, ctrl);
+  } else {
+    hipLaunchKernelGGL(part_scatter_kernel<false>, dim3(nslab, td.L), dim3(1024), part_scatter_lds(nbins), s, codes_t, td.N,
+                       lb, rowbits, nbins, bh, nslab, pbase, entries);
+    hipLaunchKernelGGL(part_buckets_kernel<false>, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb), s,
+                       (const uint2*)entries, pbase, nbins, lb, rowbits, td.nb, td.N, td.C, td.off, td.ids, worklist,
+                       wl_cap, ctrl);
+  }
   hipLaunchKernelGGL(big_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, td.C, policy,
                      r, prio_a, prio_b, worklist, wl_cap, ctrl);
   return hipGetLastError();
