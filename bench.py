@@ -53,6 +53,9 @@ def main() -> int:
     ap.add_argument("--rebuild-every", type=int, default=None, help="override the workload's rebuild schedule")
     ap.add_argument("--incremental-rebuild", action="store_true",
                     help="scheduled rebuilds hash only the rows updated since the last build")
+    ap.add_argument("--predict-topk", type=int, default=0, metavar="K",
+                    help="only time slide_predict (retrieved neurons, then all neurons) on one batch of the "
+                         "workload and print its own JSON line")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run the library's plain copy kernel on MIB mebibytes (10 launches) and print "
                          "its bandwidth: the yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
@@ -95,6 +98,25 @@ def main() -> int:
     gen = synth.Generator(wl, args.seed)
     weights, hp = gen.weights(), gen.hash_params()
     model = slide.Slide(slide.config_from_workload(wl), weights, hp)
+    if args.predict_topk:
+        model.build_tables()
+        db = model.to_device(gen.batch(0))
+        res = {"kernel": "slide_predict", "workload": wl.name, "batch": wl.batch, "topk": args.predict_topk}
+        for mode, name in ((0, "retrieved_neurons_ms"), (1, "all_neurons_ms")):
+            for _ in range(2):
+                model.predict(db, args.predict_topk, mode)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                model.predict(db, args.predict_topk, mode)
+            torch.cuda.synchronize()
+            res[name] = (time.perf_counter() - t0) / 10 * 1e3
+        flop = 2.0 * wl.batch * wl.num_classes * wl.hidden_dim
+        res["all_neurons_TFLOPs"] = flop / (res["all_neurons_ms"] * 1e-3) / 1e12
+        res["fp32_matrix_peak_TFLOPs"] = 157.3
+        print(json.dumps(res))
+        return 0
+
     W, K = args.warmup, args.steps
     host_batches = [gen.batch(s) for s in range(W + K)]
     batches = [model.to_device(b) for b in host_batches]
