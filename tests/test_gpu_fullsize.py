@@ -14,7 +14,7 @@ torch = pytest.importorskip("torch")
 if not torch.cuda.is_available():
     pytest.skip("needs a GPU", allow_module_level=True)
 
-from helpers import assert_ok, compare_step, make_pair  # noqa: E402
+from helpers import assert_ok, compare_step, load_state, make_pair  # noqa: E402
 
 
 def _say(*a):
@@ -44,6 +44,32 @@ def test_full_size_step(i):
     _say("  step compared", round(time.time() - t0, 1), "s",
          {k: round(v, 3) for k, v in res.items() if not k.startswith("_")}, res["_loss"], model.stats())
     assert_ok(res)
+    model.destroy()
+
+
+@pytest.mark.timeout(600)
+def test_output_layer_larger_than_one_lds_bitmap():
+    """1.5 million output neurons: a sample's bitmap of candidates no longer fits the LDS in one piece,
+    so the lookup sweeps it in two segments and re-reads the spilled words for the id list.  Two steps
+    from identical state, compared with the oracle in full, and a prediction over the retrieved set."""
+    wl = synth.small(synth.HASH_DWTA, num_classes=1_500_007, hidden_dim=16, K=6, L=4, bucket_cap=16, batch=21,
+                     input_dim=500, nnz_mean=10.0, rebuild_every=0)
+    _say("large layer", wl.num_classes)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    T = orc.build_tables()
+    assert model.stats()["overflowed_buckets"] == T.overflowed
+    for step in range(2):
+        load_state(model, orc)                             # (weights agree to 1e-4 after a step, not to the bit)
+        res = compare_step(model, orc, gen.batch(step))
+        _say("  step", step, {k: round(v, 3) for k, v in res.items() if not k.startswith("_")}, res["_loss"])
+        assert_ok(res)
+    load_state(model, orc)
+    b = gen.batch(2)
+    ids, _ = model.predict(model.to_device(b), 5, mode=0)
+    want, _ = orc.predict(b, 5, 0)
+    assert float((ids.cpu().numpy() == want).mean()) > 0.98
+    assert model.status() == 0
     model.destroy()
 
 
