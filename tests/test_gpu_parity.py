@@ -43,7 +43,9 @@ def test_hash_codes_bit_exact(kind, H, K, L):
 
 @pytest.mark.parametrize("kind,policy,C,N", [(synth.HASH_SIMHASH, 1, 16, 2000), (synth.HASH_SIMHASH, 0, 5, 1500),
                                              (synth.HASH_DWTA, 1, 16, 20011), (synth.HASH_DWTA, 0, 3, 5000),
-                                             (synth.HASH_SIMHASH, 1, 128, 30000)])
+                                             (synth.HASH_SIMHASH, 1, 128, 30000),
+                                             # the largest capacity, buckets of about 3000 members
+                                             (synth.HASH_SIMHASH, 1, 1024, 200000), (synth.HASH_SIMHASH, 0, 1024, 100000)])
 def test_tables_bit_exact_first_build_and_rebuild(kind, policy, C, N):
     _say("tables", kind, policy, C, N)
     K = 3 if kind == synth.HASH_DWTA else 6
@@ -99,6 +101,8 @@ def test_degenerate_tables_all_rows_identical():
                                   input_dim=700, nnz_mean=5.0, bucket_cap=8)),
     ("b2048-tile128", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=5, L=4, batch=2048, num_classes=3001,
                                   input_dim=0, bucket_cap=8)),
+    # the largest bucket capacity: every bucket holds more than 1024 neurons, 5120 candidates per sample
+    ("cap1024", synth.small(synth.HASH_SIMHASH, K=4, L=5, bucket_cap=1024, num_classes=60000, batch=9)),
 ])
 def test_single_step_from_identical_state(name, wl):
     _say("step", name)
