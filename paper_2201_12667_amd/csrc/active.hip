@@ -344,13 +344,14 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   __syncthreads();
   const int n = (int)sm[18];
   const uint32_t nch = ((uint32_t)n + kChunk - 1) / kChunk;
-  uint32_t chunk0 = 0;
   if (tid == 0) {
     ad.cnt[i] = n; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; ad.as_base[i] = base_i;
-    // forward work items of this sample: a block of consecutive item numbers (which block does not
-    // matter: the partial results of a sample are merged in the sample's own chunk order)
-    chunk0 = nch ? atomicAdd(&ctrl->chunk_alloc[ad.par], nch) : 0u;   // (the answer is not needed before the end)
-    if (i == 0) ctrl->chunk_alloc[ad.par ^ 1] = 0;       // the previous call's counter: clear it for the next call
+    // forward work items of this sample: room for their partial results (which block of slots does not
+    // matter: a sample's partial results are merged in the sample's own chunk order), and the largest
+    // number of items of any sample, which bounds the forward launch's enumeration
+    ad.chunk_ptr[i] = nch ? (int32_t)atomicAdd(&ctrl->chunk_alloc[ad.par], nch) : 0;
+    if (nch) atomicMax(&ctrl->max_nch[ad.par], nch);
+    if (i == 0) { ctrl->chunk_alloc[ad.par ^ 1] = 0; ctrl->max_nch[ad.par ^ 1] = 0; }   // the previous call's: clear for the next call
   }
 
   // per-tile counts -> exclusive prefix inside the sample (rank of the tile's first active neuron)
@@ -390,9 +391,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       }
     }
   }
-  if (tid == 0) { sm[19] = chunk0; ad.chunk_ptr[i] = (int32_t)chunk0; }
-  __syncthreads();
-  for (uint32_t k = tid; k < nch; k += nthr) ad.chunk_sample[sm[19] + k] = i;
+  __syncthreads();                                   // the sweep's flag writes (0) come before the labels' (1)
   // label flags, and for every label entry its slot (-1 for invalid or repeated entries)
   for (int q = tid; q < nlab; q += nthr) {
     const int y = y_indices[y0 + q];

@@ -32,7 +32,7 @@ struct Layout {
   uint32_t nb, wl_cap;
   size_t hash_words;
   // workspace offsets
-  size_t ctrl, hashw, hashoff, xse, zc, best, cand, ccnt, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, chunk_sample, as_ids,
+  size_t ctrl, hashw, hashoff, xse, zc, best, cand, ccnt, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, as_ids,
       as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, touched, touched_rows, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
@@ -133,7 +133,6 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->as_base = take(B * 4); lo->chunk_ptr = take((B + 1) * 4);
   lo->tile_nu2 = take((size_t)lo->NT2 * 4); lo->tile_nu1 = take((size_t)lo->NT1 * 4 + 4);
   lo->longlist2 = take((size_t)lo->long2 * 4); lo->longlist1 = take((size_t)lo->long1 * 4);
-  lo->chunk_sample = take((size_t)lo->max_chunks * 4);
   lo->as_ids = take(A * 4); lo->as_lab = take(A); lo->ylist = take((size_t)c->max_labels_per_batch * 4 + 4);
   lo->z = take(A * 4); lo->delta = take(A * 4);
   lo->partials = take((size_t)lo->max_chunks * (H + 4) * 4);
@@ -248,7 +247,6 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ad.PS = lo.PS; ad.num_labels = 0;
   ad.budget = 0; ad.fill = 0; ad.sample_seed = c->cfg.sample_seed; ad.step = 0;
   ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
-  ad.chunk_sample = c->at<int32_t>(lo.chunk_sample);
   ad.as_ids = c->at<int32_t>(lo.as_ids); ad.as_lab = c->at<uint8_t>(lo.as_lab); ad.ylist = c->at<int32_t>(lo.ylist);
   return ad;
 }

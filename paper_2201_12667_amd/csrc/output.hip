@@ -45,14 +45,28 @@ __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const 
   constexpr int RPW = 64 / LPR;
   const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
   constexpr int WPB = kForwardThreads / 64;
-  const int nwaves = nblocks * WPB;
-  const int nitems = (int)ctrl->chunk_alloc[ad.par];
+  // Work item (i, c) = chunk c (kChunk active neurons) of sample i, enumerated as c * B + i: items that are
+  // neighbours in this order cover about the same stretch of neuron ids (the ids of a sample ascend),
+  // so when samples share rows (saturated buckets) a row is fetched once and then found in L2.  With
+  // many chunks per sample every XCD (workgroup k runs on XCD k % 8, each with its own L2) also takes
+  // its own eighth of the chunk indices, a contiguous one, so that the stretches it works on at the
+  // same time are neighbours and a row is fetched by one XCD only.
+  const int B = ad.B;
+  const int maxnch = (int)ctrl->max_nch[ad.par];
+  const bool affine = maxnch >= 64;                  // (otherwise the XCDs would get unequal shares)
+  const int xcd = block & 7;
+  const int c_lo = affine ? xcd * maxnch / 8 : 0, c_hi = affine ? (xcd + 1) * maxnch / 8 : maxnch;
+  const int lwave = (affine ? (block >> 3) : block) * WPB + (threadIdx.x >> 6);
+  const int lwaves = (affine ? (nblocks >> 3) : nblocks) * WPB;
+  const int T = (c_hi - c_lo) * B;
   const int PS = H + 4;
-  for (int item = block * WPB + (threadIdx.x >> 6); item < nitems; item += nwaves) {
-    const int i = ad.chunk_sample[item];
-    const int done = (item - ad.chunk_ptr[i]) * kChunk;
+  for (int t = lwave; t < T; t += lwaves) {
+    const int i = t % B, ch = c_lo + t / B;
+    const int done = ch * kChunk, cnt = ad.cnt[i];
+    if (done >= cnt) continue;
+    const int item = ad.chunk_ptr[i] + ch;             // slot of the partial result
     const int first = ad.as_base[i] + done;
-    const int n = min(kChunk, ad.cnt[i] - done);
+    const int n = min(kChunk, cnt - done);
     float4 hv[CH], acc[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
@@ -136,7 +150,7 @@ __global__ __launch_bounds__(kForwardThreads) void forward_kernel(ActiveDev ad, 
   if (k < kForwardBlocks) {
     // With several items per wave the workers would hold every slot of the machine until the end and
     // the tiles would run after them: then the last workers leave at once and make room.
-    const int items = (int)ctrl->chunk_alloc[ad.par];
+    const int items = (int)ctrl->max_nch[ad.par] * ad.B;   // (upper bound: samples differ in length)
     const int workers = items > 2 * kForwardBlocks * (kForwardThreads / 64) ? kForwardBlocksLong : kForwardBlocks;
     if (k >= workers) return;
     if (H == LPR * CH * 4) forward_items<LPR, CH, true>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
@@ -217,6 +231,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
   const int first = ad.as_base[i], n = ad.cnt[i];
   const int ny = ad.ny[i];
   const int PS = H + 4;
+  const float* pmine = partials + (size_t)c0 * PS;
   const float invB = 1.0f / (float)ad.B;
   const int y0 = min(max(y_indptr[i], 0), ad.num_labels);               // (clamped like the lookup does)
   const int nlab = min(max(y_indptr[i + 1], y0), ad.num_labels) - y0;
@@ -228,11 +243,11 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
   // soft-max normaliser from the partial states: wave 0, one lane per work item, fixed butterfly order
   if (tid < 64) {
     float Mi = -INFINITY;
-    for (int c = lane; c < nch; c += 64) Mi = fmaxf(Mi, partials[(size_t)(c0 + c) * PS]);
+    for (int c = lane; c < nch; c += 64) Mi = fmaxf(Mi, pmine[(size_t)c * PS]);
     for (int d = 32; d > 0; d >>= 1) Mi = fmaxf(Mi, __shfl_xor(Mi, d));
     float s = 0.f;
     for (int c = lane; c < nch; c += 64) {
-      const float* pp = partials + (size_t)(c0 + c) * PS;
+      const float* pp = pmine + (size_t)c * PS;
       const float sc = __expf(pp[0] - Mi);
       if (c < kMaxCh) scale[c] = sc;
       s += pp[1] * sc;
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
     float g = 0.f;
     if (live && h[(size_t)i * H + u] > 0.f) {
       float acc = 0.f;
-      const float* pu = partials + (size_t)c0 * PS + 4 + u;
+      const float* pu = pmine + 4 + u;
       int c = 0;
       for (; c + 4 <= min(nch, kMaxCh); c += 4) {         // four reads in flight, added in chunk order
         const float a0 = pu[(size_t)c * PS], a1 = pu[(size_t)(c + 1) * PS], a2 = pu[(size_t)(c + 2) * PS],

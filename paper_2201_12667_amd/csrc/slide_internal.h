@@ -26,11 +26,14 @@ struct Ctrl {
   uint32_t nlong2, nlong1; // long rows queued by the two transpositions
   uint32_t max_nu2, max_nu1; // most touched rows in any tile
   uint32_t pad[1];
-  // forward work items handed out by the lookup workgroups; a call uses counter (call number & 1)
-  // and clears the other
+  // forward work items (chunks of kChunk active neurons): room for their partial results is handed out
+  // by the lookup workgroups; a call uses counter (call number & 1) and clears the other
   uint32_t chunk_alloc[2];
   // running totals since the last slide_reset_stats (updated once per training step)
   unsigned long long sum_pairs, sum_u2, sum_u1, sum_candidates, sum_steps;
+  uint32_t pad2[16];
+  uint32_t max_nch[2];    // most work items of any sample, same parity scheme (a cache line of its own)
+  uint32_t pad3[14];
 };
 
 // Hash functions as the kernels read them.
@@ -95,9 +98,8 @@ struct ActiveDev {
   uint32_t* rankT;                 // [NT+1][B] active neurons of the sample below the tile (last row: |AS_i|)
   int32_t* cnt;                    // [B] |AS_i|
   int32_t* ny;                     // [B] distinct labels
+  int32_t* chunk_ptr;              // [B] where the partial results of the sample's work items start
   int32_t* as_base;                // [B] first slot of sample i = i*PS + (label entries before sample i)
-  int32_t* chunk_ptr;              // [B] first forward work item of the sample
-  int32_t* chunk_sample;           // [max chunks] sample of the work item
   int32_t* as_ids;                 // [slots] ascending ids of sample i at as_base[i] .. +cnt[i]
   uint8_t* as_lab;                 // [slots]
   int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
