@@ -37,6 +37,7 @@ hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s)
 constexpr int kForwardThreads = 512;
 constexpr int kForwardBlocks = 768;    // logit workers
 constexpr int kForwardBlocksLong = 640;   // ... of which this many stay when each has several items
+constexpr int kForwardBlocksLongTiles = 512;   // ... or this many, when the tiles are many as well
 
 template <int LPR, int CH, bool FULL>
 __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const float* __restrict__ h, const float* __restrict__ W2,
@@ -151,7 +152,10 @@ __global__ __launch_bounds__(kForwardThreads) void forward_kernel(ActiveDev ad, 
     // With several items per wave the workers would hold every slot of the machine until the end and
     // the tiles would run after them: then the last workers leave at once and make room.
     const int items = (int)ctrl->max_nch[ad.par] * ad.B;   // (upper bound: samples differ in length)
-    const int workers = items > 2 * kForwardBlocks * (kForwardThreads / 64) ? kForwardBlocksLong : kForwardBlocks;
+    // (more of them when the tiles are many for the amount of logit work)
+    const int ntiles = t1.ntiles + t2.ntiles;
+    const int workers = items <= 2 * kForwardBlocks * (kForwardThreads / 64) ? kForwardBlocks
+                        : (items < 20 * ntiles ? kForwardBlocksLongTiles : kForwardBlocksLong);
     if (k >= workers) return;
     if (H == LPR * CH * 4) forward_items<LPR, CH, true>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
     else forward_items<LPR, CH, false>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
