@@ -114,6 +114,28 @@ def main() -> int:
         flop = 2.0 * wl.batch * wl.num_classes * wl.hidden_dim
         res["all_neurons_TFLOPs"] = flop / (res["all_neurons_ms"] * 1e-3) / 1e12
         res["fp32_matrix_peak_TFLOPs"] = 157.3
+        if args.cpu_steps > 0:                       # the oracle beside it, on a bounded sample of the batch
+            from oracle import slide_oracle as so
+            orc = so.SlideOracle(input_dim=wl.input_dim, hidden_dim=wl.hidden_dim, num_classes=wl.num_classes,
+                                 hash_kind=wl.hash_kind, K=wl.K, L=wl.L, bucket_cap=wl.bucket_cap, rebuild_every=0,
+                                 lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, dwta_bin=wl.dwta_bin,
+                                 overflow_policy=wl.overflow_policy, weights=weights, hash_params=hp)
+            orc.build_tables()
+            hb = gen.batch(0)
+            ns = min(wl.batch, 32)
+            xe, ye = int(hb["x_indptr"][ns]) if wl.input_dim else 0, int(hb["y_indptr"][ns])
+            sub = {"x_indptr": hb["x_indptr"][:ns + 1], "x_indices": hb["x_indices"][:xe], "x_values": hb["x_values"][:xe],
+                   "y_indptr": hb["y_indptr"][:ns + 1], "y_indices": hb["y_indices"][:ye]} if wl.input_dim else \
+                  {"hidden": hb["hidden"][:ns], "y_indptr": hb["y_indptr"][:ns + 1], "y_indices": hb["y_indices"][:ye]}
+            cpu = {}
+            for mode, name in ((0, "retrieved_neurons"), (1, "all_neurons")):
+                c0 = time.perf_counter()
+                orc.predict(sub, args.predict_topk, mode)
+                cpu[name + "_samples_per_s"] = ns / (time.perf_counter() - c0)
+            res["cpu_baseline"] = dict(cpu, cores=so.num_threads(), kind="oracle",
+                                       sample="the first %d samples of the same batch" % ns)
+            res["retrieved_neurons_samples_per_s"] = wl.batch / (res["retrieved_neurons_ms"] * 1e-3)
+            res["all_neurons_samples_per_s"] = wl.batch / (res["all_neurons_ms"] * 1e-3)
         print(json.dumps(res))
         return 0
 
