@@ -362,7 +362,7 @@ __global__ __launch_bounds__(256) void big_buckets_kernel(const uint32_t* __rest
 // Split of the code into partition digit (high hb bits) and in-partition digit (low lb bits).
 void tables_split(int bits, int64_t N, int* hb, int* lb) {
   int want = 0;
-  while (want < 11 && ((int64_t)2048 << want) < N) ++want;     // about 2048 rows per partition
+  while (want < 11 && ((int64_t)4096 << want) < N) ++want;     // about 2048 to 4096 rows per partition
   int h = want < bits ? want : bits;
   if (bits - h > 13) h = bits - 13;                            // low digit counters must fit in LDS
   *hb = h;
