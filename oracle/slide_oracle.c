@@ -156,8 +156,8 @@ int orc_hash_codes(const orc_hash* hc, const float* V, int64_t rows, uint32_t* c
 }
 
 /* ------------------------------------------------------------------------------------
- * Hash tables (Section 2.1 phase 1 and Algorithm 1: "hash weights to hash tables";
- * rebuilt on a schedule, Section 3.1).  For table t and code c the bucket is the set
+ * Hash tables (Section 2.1 phase 1 and Algorithm 1, the table-construction step before the
+ * loop; rebuilt on a schedule, Section 3.1).  For table t and code c the bucket is the set
  * of neurons j with code_t(W2[j,:]) = c, stored ascending by id.  A bucket keeps at most
  * C members: the C smallest keys, key = j (policy 0) or key = (prio(j,t,r), j) (policy 1)
  * with   u = prio_a*(j+1) + prio_b*(t*65537 + r + 1); u ^= u >> 15; u *= prio_a; u ^= u >> 13
@@ -267,15 +267,18 @@ uint64_t orc_tables_fingerprint(const orc_tables* T) {
 }
 
 /* ------------------------------------------------------------------------------------
- * Active sets (Algorithm 1 "retrieve active neurons"; Figure 1: the union of the neurons
- * retrieved from every table).  AS_i = sorted(set(union_t bucket_t(code_t(h_i))) + set(Y_i));
+ * Active sets (Algorithm 1, the retrieval step of the loop body; Figure 1: the union of the
+ * neurons retrieved from every table).  AS_i = sorted(set(union_t bucket_t(code_t(h_i))) + set(Y_i));
  * is_label marks the members of Y_i.  With include_labels = 0 (prediction) Y_i is left out.
+ * A label entry outside [0, N) names no neuron of this layer: it is left out of Y_i (as if it were
+ * not in the batch) and counted in *n_bad_labels.
  * Pass as_ids = NULL to obtain only as_ptr (sizes); as_ptr has B+1 entries.
  * ------------------------------------------------------------------------------------ */
 int orc_active_sets(const orc_tables* T, const uint32_t* codes /*[B][L]*/, int32_t B,
                     const int32_t* y_indptr, const int32_t* y_idx, int32_t include_labels,
-                    int64_t* as_ptr, int32_t* as_ids, uint8_t* is_label, int64_t* n_candidates) {
-  int64_t cand_total = 0;
+                    int64_t* as_ptr, int32_t* as_ids, uint8_t* is_label, int64_t* n_candidates,
+                    int64_t* n_bad_labels) {
+  int64_t cand_total = 0, bad = 0;
   const int fill = as_ids != NULL;
   if (!fill) as_ptr[0] = 0;
   for (int32_t i = 0; i < B; ++i) {
@@ -287,7 +290,7 @@ int orc_active_sets(const orc_tables* T, const uint32_t* codes /*[B][L]*/, int32
     cand_total += n;
     for (int32_t q = 0; q < nl; ++q) {
       int32_t y = y_idx[y_indptr[i] + q];
-      if (y < 0 || y >= T->N) { free(buf); return -1; }
+      if (y < 0 || y >= T->N) { ++bad; continue; }
       buf[n++] = y;
     }
     qsort(buf, (size_t)n, sizeof(int32_t), cmp_i32);
@@ -301,6 +304,7 @@ int orc_active_sets(const orc_tables* T, const uint32_t* codes /*[B][L]*/, int32
       memset(is_label + as_ptr[i], 0, (size_t)u);
       for (int32_t q = 0; q < nl; ++q) {
         int32_t y = y_idx[y_indptr[i] + q];
+        if (y < 0 || y >= T->N) continue;
         int64_t lo = 0, hi = u;
         while (lo < hi) { int64_t mid = (lo + hi) / 2; if (buf[mid] < y) lo = mid + 1; else hi = mid; }
         is_label[as_ptr[i] + lo] = 1;
@@ -309,12 +313,13 @@ int orc_active_sets(const orc_tables* T, const uint32_t* codes /*[B][L]*/, int32
     free(buf);
   }
   if (n_candidates) *n_candidates = cand_total;
+  if (n_bad_labels) *n_bad_labels = bad;
   return 0;
 }
 
 /* ------------------------------------------------------------------------------------
  * Output layer on the active set (Section 2.1: activations of retrieved neurons only,
- * all others are exactly zero / untouched; Algorithm 1 "compute errors").
+ * all others are exactly zero / untouched; Algorithm 1, the error computation).
  *   z_ij = b2[j] + sum_u W2[j][u]*h[i][u]                  j in AS_i
  *   p_ij = softmax over AS_i only
  *   y_ij = 1/|Y_i| for labels (distinct), 0 otherwise
@@ -408,7 +413,7 @@ int orc_hidden_grads(int32_t B, int32_t H, const int32_t* indptr, const int32_t*
 }
 
 /* ------------------------------------------------------------------------------------
- * Row-sparse Adam (Algorithm 1 "update weights with Adam"; Section 3.5: every weight and
+ * Row-sparse Adam (Algorithm 1, the optimizer step after the batch; Section 3.5: every weight and
  * bias carries a momentum and a velocity value; constants of Section 4.1).  Only the
  * listed rows change; t is the global 1-based step:
  *   m = b1*m + (1-b1)*g;  v = b2*v + (1-b2)*g*g;

@@ -57,7 +57,7 @@ def lib():
         L.orc_tables_bucket.argtypes = [vp, i32, u32, vp, i32]
         L.orc_tables_fingerprint.argtypes = [vp]
         L.orc_tables_fingerprint.restype = C.c_uint64
-        L.orc_active_sets.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, vp]
+        L.orc_active_sets.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
         L.orc_output_forward_backward.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.orc_output_grads.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, vp]
         L.orc_hidden_grads.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, vp]
@@ -135,19 +135,21 @@ class Tables:
         return int(lib().orc_tables_fingerprint(self._h))
 
     def active_sets(self, codes, y_indptr, y_indices, include_labels=True):
+        """Returns (as_ptr, ids, is_label, candidates).  Label entries outside [0, N) are left out of
+        the sets; their number is kept in self.bad_labels."""
         codes = _c(codes, np.uint32)
         B = codes.shape[0]
         yp, yi = _c(y_indptr, np.int32), _c(y_indices, np.int32)
         as_ptr = np.zeros(B + 1, dtype=np.int64)
-        ncand = C.c_int64(0)
+        ncand, nbad = C.c_int64(0), C.c_int64(0)
         rc = lib().orc_active_sets(self._h, _p(codes), B, _p(yp), _p(yi), int(include_labels),
-                                   _p(as_ptr), None, None, C.byref(ncand))
-        if rc:
-            raise ValueError("orc_active_sets: label out of range")
+                                   _p(as_ptr), None, None, C.byref(ncand), C.byref(nbad))
+        assert rc == 0
+        self.bad_labels = int(nbad.value)
         ids = np.empty(max(int(as_ptr[-1]), 1), dtype=np.int32)
         lab = np.zeros(max(int(as_ptr[-1]), 1), dtype=np.uint8)
         rc = lib().orc_active_sets(self._h, _p(codes), B, _p(yp), _p(yi), int(include_labels),
-                                   _p(as_ptr), _p(ids), _p(lab), None)
+                                   _p(as_ptr), _p(ids), _p(lab), None, None)
         assert rc == 0
         A = int(as_ptr[-1])
         return as_ptr, ids[:A], lab[:A], int(ncand.value)
@@ -328,7 +330,9 @@ class SlideOracle:
         z, p, delta, loss_i, dh = output_forward_backward(h, as_ptr, as_ids, lab, self.p["W2"], self.p["b2"])
         uniq = np.unique(as_ids).astype(np.int32)
         gW2, gb2 = output_grads(h, as_ptr, as_ids, delta, uniq)
+        yi_all = _c(batch["y_indices"], np.int32)
         out.update(h=h, codes=codes, as_ptr=as_ptr, as_ids=as_ids, is_label=lab, candidates=ncand,
+                   bad_labels=int(np.count_nonzero((yi_all < 0) | (yi_all >= self.N))),
                    z=z, p=p, delta=delta, loss_i=loss_i, loss=float(np.mean(loss_i)), dh=dh,
                    uniq=uniq, gW2=gW2, gb2=gb2)
         if not self.dense_hidden:

@@ -87,7 +87,8 @@ class Workload:
 
 def config(i: int) -> Workload:
     """The five benchmark configurations (0 = tiny plumbing run ... 4 = near-billion parameters),
-    then shapes of the paper's other settings (5: second workload at batch 1024, 6-7: batch 2048)."""
+    then shapes of the paper's other settings (5: second workload at batch 1024, 6-7: batch 2048,
+    8: hidden 1024 at batch 1024)."""
     if i == 0:
         return Workload("cfg0-tiny", 1000, 32, 2000, 32, HASH_SIMHASH, 4, 8, 16, 5, lr=1e-3,
                         nnz_mode="exact", nnz_mean=20, feat_zipf_s=None, value_mode="uniform",
@@ -112,7 +113,9 @@ def config(i: int) -> Workload:
         return Workload("cfg6-670k-b2048-h256", 135909, 256, 670091, 2048, HASH_DWTA, 6, 400, 128, 50)
     if i == 7:   # and at its large-batch setting: hidden 1024, batch 2048
         return Workload("cfg7-670k-b2048-h1024", 135909, 1024, 670091, 2048, HASH_DWTA, 8, 200, 128, 0)
-    raise ValueError("config index must be 0..7")
+    if i == 8:   # the large-batch experiment's other row: hidden 1024, batch 1024
+        return Workload("cfg8-670k-b1024-h1024", 135909, 1024, 670091, 1024, HASH_DWTA, 8, 200, 128, 0)
+    raise ValueError("config index must be 0..8")
 
 
 def small(kind: int = HASH_DWTA, **over) -> Workload:

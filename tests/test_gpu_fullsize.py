@@ -22,7 +22,7 @@ def _say(*a):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("i", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_full_size_step(i):
     wl = synth.config(i)
     t0 = time.time()
@@ -43,6 +43,7 @@ def test_full_size_step(i):
     res = compare_step(model, orc, gen.batch(0))
     _say("  step compared", round(time.time() - t0, 1), "s",
          {k: round(v, 3) for k, v in res.items() if not k.startswith("_")}, res["_loss"], model.stats())
+    _say("  with a floor of 1e-7 * max|ref|:", {k: round(v, 3) for k, v in res["_floor1e-7"].items()})
     assert_ok(res)
     model.destroy()
 

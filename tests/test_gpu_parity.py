@@ -203,6 +203,60 @@ def test_edge_cases_labels_and_empty_samples():
     model.destroy()
 
 
+def test_hash_densification_probe_limit(golden_dir):
+    """The hand-worked case in which one empty bin finds its donor at the 100th probe and another would
+    find it only at the 101st: the library's two hash kernels (row tiles, and the per-sample one inside the
+    lookup) must stop where the definition stops."""
+    from test_oracle_hash import dwta_probe_limit_case
+    from paper_2201_12667_amd import slide
+    g, perm, v, want = dwta_probe_limit_case(golden_dir)
+    wl = synth.small(synth.HASH_DWTA, hidden_dim=g["H"], K=g["K"], L=g["L"], dwta_bin=g["m"], input_dim=0,
+                     num_classes=64, batch=3, bucket_cap=4, rebuild_every=0)
+    gen = synth.Generator(wl, 0)
+    hp = dict(gen.hash_params(), dwta_perm=perm, dens_a=g["dens_a"], dens_b=g["dens_b"])
+    w = gen.weights()
+    from helpers import make_oracle
+    model, orc = slide.Slide(slide.config_from_workload(wl), w, hp), make_oracle(wl, w, hp)
+    V = np.concatenate([v, np.zeros((1, g["H"]), np.float32), v * 3])
+    got = model.debug_hash(V)
+    assert np.array_equal(got[0], want) and np.array_equal(got[2], want) and not got[1].any()
+    # the same vectors as a batch of hidden activations: the lookup's own hashing
+    model.build_tables()
+    orc.build_tables()
+    b = gen.batch(0)
+    b["hidden"] = V
+    res = compare_step(model, orc, b)
+    assert np.array_equal(res["_ref"]["codes"][0], want)
+    assert_ok(res)
+    model.destroy()
+
+
+def test_step_with_label_entries_outside_the_layer_matches_oracle():
+    """Label entries outside [0, N) are left out (as if absent) and flagged: the whole step is compared."""
+    _say("bad labels, full compare")
+    wl = synth.small(synth.HASH_DWTA, batch=9, num_classes=3000, input_dim=500)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    b = gen.batch(0)
+    yp, yi = b["y_indptr"], b["y_indices"]
+    ys = [yi[yp[i]:yp[i + 1]].tolist() for i in range(wl.batch)]
+    ys[0] = [-1] + ys[0]
+    ys[2] = ys[2] + [3000]
+    ys[4] = [2 ** 31 - 1]                          # a sample whose only label is invalid: no labels at all
+    ys[5] = ys[5][:1] + [-(2 ** 31)] + ys[5][1:]
+    yp2 = np.zeros(wl.batch + 1, np.int32)
+    yp2[1:] = np.cumsum([len(y) for y in ys])
+    b2 = dict(b, y_indptr=yp2, y_indices=np.array(sum(ys, []), np.int64).astype(np.int32))
+    res = compare_step(model, orc, b2)             # (asserts the flag word: exactly "bad label")
+    assert res["_ref"]["bad_labels"] == 4
+    assert not res["_ref"]["dh"][4].any()
+    assert_ok(res)
+    res = compare_step(model, orc, gen.batch(1))   # and the flag does not stick
+    assert_ok(res)
+    model.destroy()
+
+
 def test_bad_batch_data_is_flagged_not_fatal():
     _say("bad data")
     from paper_2201_12667_amd import slide

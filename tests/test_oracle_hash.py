@@ -33,6 +33,23 @@ def test_dwta_hand_example(golden_dir):
     assert hf.codes(np.array([g["v"]], dtype=np.float32)).tolist() == [g["codes"]]
 
 
+def dwta_probe_limit_case(golden_dir):
+    """(hash function, vector, expected codes) of tests/golden/dwta_probe_limit.json."""
+    g = _load(golden_dir, "dwta_probe_limit.json")
+    NP = g["K"] * g["L"] // (g["H"] // g["m"])
+    perm = np.array([g["special_perms"].get(str(q), g["default_perm"]) for q in range(NP)], np.int32)
+    want = np.zeros(g["L"], np.uint32)
+    for t, c in g["nonzero_codes"].items():
+        want[int(t)] = c
+    return g, perm, np.array([g["v"]], dtype=np.float32), want
+
+
+def test_dwta_densification_gives_up_after_exactly_100_probes(golden_dir):
+    g, perm, v, want = dwta_probe_limit_case(golden_dir)
+    hf = so.HashFn(so.DWTA, g["H"], g["K"], g["L"], m=g["m"], dwta_perm=perm, dens_a=g["dens_a"], dens_b=g["dens_b"])
+    assert np.array_equal(hf.codes(v)[0], want)
+
+
 def _srp(rng, H, K, L):
     S = -(-H // 3)
     NH = K * L
