@@ -118,7 +118,9 @@ def compare_step(model, orc, batch, check_state=True):
     h, dh = model.debug_hidden()
     as_ptr, ids, lab, z, d = model.debug_active()
     if not orc.dense_hidden:
-        assert np.array_equal(h, ref["h"]), "hidden activations are not bit-identical"
+        bad = np.argwhere(h != ref["h"])
+        assert bad.size == 0, ("hidden activations are not bit-identical", len(bad), bad[:6].tolist(),
+                               [(float(h[i, j]), float(ref["h"][i, j])) for i, j in bad[:6]])
     assert np.array_equal(as_ptr, ref["as_ptr"]), "active-set sizes differ"
     assert np.array_equal(ids, ref["as_ids"]), "active-set ids differ"
     assert np.array_equal(lab, ref["is_label"]), "label flags differ"

@@ -252,6 +252,7 @@ def test_step_with_label_entries_outside_the_layer_matches_oracle():
     assert res["_ref"]["bad_labels"] == 4
     assert not res["_ref"]["dh"][4].any()
     assert_ok(res)
+    load_state(model, orc)                         # (weights agree to 1e-4 after a step, not to the bit)
     res = compare_step(model, orc, gen.batch(1))   # and the flag does not stick
     assert_ok(res)
     model.destroy()
