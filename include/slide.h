@@ -183,6 +183,22 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* batch, float* d_loss, vo
 int slide_predict(slide_ctx* ctx, const slide_batch* batch, int mode, int topk,
                   int32_t* d_out_ids, float* d_out_scores, void* hip_stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace at the call (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): slide_predict with mode 1 (scores
+ * of all N neurons, the topk best per sample), with every intermediate -- the hidden activations in
+ * sparse-input mode, one chunk of scores, the running best lists, the candidate buffers and their
+ * counters -- in a fixed array of SLIDE_STATIC_SCRATCH_MIB MiB inside the library's device image instead
+ * of the context's workspace.  Same arguments, results and ordering rules as slide_predict; allocates
+ * nothing on host paths that touch the device and calls no allocating routine.
+ * Limits: batch <= SLIDE_STATIC_MAX_BATCH (SLIDE_ENOMEM beyond); the context's device must be current
+ * (SLIDE_ESTATE otherwise).  Every call on a GPU shares that GPU's array, whatever the context or
+ * stream: calls that overlap on one GPU race; calls on one stream are ordered and safe.  The array
+ * keeps the previous call's contents; the call clears what it needs cleared itself. */
+#define SLIDE_STATIC_MAX_BATCH 64
+#define SLIDE_STATIC_SCRATCH_MIB 16
+int slide_predict_static(slide_ctx* ctx, const slide_batch* batch, int topk, int32_t* d_out_ids,
+                         float* d_out_scores, void* hip_stream);
+
 /* Synchronises the stream; returns SLIDE_OK, SLIDE_EHIP, or SLIDE_EDATA with the flag bits in
  * *flags (may be NULL).  The flags are then cleared. */
 int slide_status(slide_ctx* ctx, void* hip_stream, uint32_t* flags);

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -11,9 +12,39 @@
 
 using namespace slide;
 
+// Scratch memory of slide_predict_static, the one entry point that uses no caller-supplied workspace:
+// a fixed array in the library's device image (every GPU the library runs on holds its own copy until
+// the process ends).  Host code never uses the array's name as an address: each device's address is
+// looked up once, in slide_init, with that device current, and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = (size_t)SLIDE_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local std::string g_last_error;
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];      // per device: address of `scratch` on that device
+std::mutex g_scratch_mu;
+
+// Address of the static scratch array on the current device (looked up on first use per device).
+hipError_t static_scratch_of_current_device(int* dev_out, void** ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *dev_out = dev;
+  *ptr_out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -166,6 +197,8 @@ struct slide_ctx {
   TablesDev td;
   uint32_t prio_a, prio_b;
   size_t lds_limit;
+  int device = -1;               // device that was current at slide_init
+  char* static_scratch = nullptr;   // this device's copy of the static scratch array
   int64_t t = 0, r = 0;
   bool built = false;
   bool ever_built = false;       // a build has happened (later ones count as rebuilds)
@@ -445,6 +478,12 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(table kernels)"; e = tables_setup_attributes(); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(forward kernels)"; e = forward_setup_attributes(ctx->lds_limit); }
+  if (e == hipSuccess) {
+    what = "hipGetSymbolAddress(static scratch)";
+    void* p = nullptr;
+    e = static_scratch_of_current_device(&ctx->device, &p);
+    ctx->static_scratch = (char*)p;
+  }
   if (e == hipSuccess) { what = "hipDeviceSynchronize"; e = hipDeviceSynchronize(); }
   if (e != hipSuccess) {
     set_err(nullptr, SLIDE_EHIP, "slide_init: %s failed: %s", what, hipGetErrorString(e));
@@ -599,6 +638,50 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
     HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(ctx->lo.xse), (size_t)b->batch * ctx->lo.NT1 * 2, 0u, s));
   HIPCHK(ctx, launch_topk(ad, ctx->at<float>(ctx->lo.z), topk, d_out_ids, d_out_scores, s));
   ctx->last_dh = nullptr;
+  return SLIDE_OK;
+}
+
+int slide_predict_static(slide_ctx* ctx, const slide_batch* b, int topk, int32_t* d_out_ids, float* d_out_scores,
+                         void* hip_stream) {
+  if (!ctx) return SLIDE_EINVAL;
+  if (topk < 1 || topk > 64 || !d_out_ids || !d_out_scores) return set_err(ctx, SLIDE_EINVAL, "topk must be in [1, 64] and outputs non-NULL");
+  int rc = check_batch(ctx, b, false);
+  if (rc != SLIDE_OK) return rc;
+  if (b->batch > SLIDE_STATIC_MAX_BATCH)
+    return set_err(ctx, SLIDE_ENOMEM, "batch %d exceeds the static scratch's maximum of %d samples", b->batch, SLIDE_STATIC_MAX_BATCH);
+  int dev = -1;
+  HIPCHK(ctx, hipGetDevice(&dev));
+  if (dev != ctx->device || !ctx->static_scratch)
+    return set_err(ctx, SLIDE_ESTATE, "the current device (%d) is not the one this context was created on (%d)", dev, ctx->device);
+  hipStream_t s = (hipStream_t)hip_stream;
+  const Layout& lo = ctx->lo;
+  // the scratch array, carved up for the largest case (SLIDE_STATIC_MAX_BATCH samples, hidden_dim 2048);
+  // what is left holds the scores of one chunk of neurons
+  const size_t B = (size_t)b->batch, Bmax = SLIDE_STATIC_MAX_BATCH;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return ctx->static_scratch + at; };
+  float* hbuf = (float*)take(Bmax * 2048 * 4);
+  uint64_t* best = (uint64_t*)take(Bmax * 64 * 8);
+  uint64_t* cand = (uint64_t*)take(Bmax * dense_cand_keys() * 8);
+  uint32_t* ccnt = (uint32_t*)take(Bmax * dense_counter_words() * 4);
+  float* zc = (float*)take(0);
+  if (o + B * 128 * 4 > kStaticScratchBytes) return set_err(ctx, SLIDE_ENOMEM, "static scratch too small");
+  int64_t chunk = (int64_t)((kStaticScratchBytes - o) / (B * 4)) / 128 * 128;
+  const int64_t npad = (lo.N + 127) / 128 * 128;
+  if (chunk > npad) chunk = npad;
+  const float* h = b->hidden;
+  if (lo.D > 0) {
+    SpmmArgs sp = make_spmm(ctx, b);
+    sp.h = hbuf;
+    sp.xse = nullptr;                                   // (no training step follows on these activations)
+    HIPCHK(ctx, launch_spmm_relu(b->batch, sp, ctx->ctrl(), s));
+    h = hbuf;
+  }
+  ctx->last_h = h;
+  ctx->last_B = b->batch;
+  ctx->last_dh = nullptr;
+  HIPCHK(ctx, launch_dense_topk(b->batch, lo.N, lo.H, h, ctx->buf.W2, ctx->buf.b2, topk, zc, chunk, best, cand, ccnt,
+                                d_out_ids, d_out_scores, s));
   return SLIDE_OK;
 }
 

@@ -12,7 +12,8 @@ namespace slide {
 // One wave per (sample, 128 columns); each lane owns two columns and reads a float2 per W1 row.
 // The first column block also records, per tile of rows_per_tile features, where the sample's
 // features of the tile start and end in the CSR arrays (the row lists of the W1 update are built
-// from these segments).  hvec (optional, LDS): a second copy of the result for the caller.
+// from these segments; a.xse == nullptr: not recorded).  hvec (optional, LDS): a second copy of the
+// result for the caller.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void spmm_sample(const SpmmArgs& a, int i, int B, int cb, int lane, float* hvec,
                                             Ctrl* ctrl) {
@@ -41,7 +42,7 @@ __device__ __forceinline__ void spmm_sample(const SpmmArgs& a, int i, int B, int
     const bool bad = pb + lane < p1 && (mine < 0 || mine >= D);
     if (__any(bad)) flags |= SLIDE_FLAG_BAD_FEATURE;
     const int kk = bad ? -1 : mine;
-    if (cb == 0) {                // segment ends: a feature whose predecessor lies in another tile
+    if (cb == 0 && xse) {         // segment ends: a feature whose predecessor lies in another tile
       int before = __shfl_up(kk, 1);      // starts its own tile's segment and ends the predecessor's
       if (lane == 0) before = last;
       last = __shfl(kk, 63);

@@ -17,11 +17,12 @@ HASH_SIMHASH, HASH_DWTA = 0, 1
 KEEP_LOWEST_ID, KEEP_PRIORITY = 0, 1
 FLAG_BAD_FEATURE, FLAG_UNSORTED, FLAG_BAD_LABEL = 1, 2, 4
 ABI_VERSION = 3
+STATIC_MAX_BATCH = 64
 STAGES = ["hidden", "lookup", "forward", "combine", "update", "rebuild"]
 NUM_STAGES = len(STAGES)
 
 EXPORTS = ["slide_query_memory", "slide_init", "slide_build_tables", "slide_set_hash_params", "slide_train_step",
-           "slide_predict",
+           "slide_predict", "slide_predict_static",
            "slide_status", "slide_get_stats", "slide_profile", "slide_profile_read", "slide_reset_stats", "slide_destroy", "slide_last_error", "slide_debug_copy", "slide_debug_hash",
            "slide_debug_get_bucket", "slide_debug_get_active", "slide_debug_get_hidden"]
 
@@ -92,6 +93,7 @@ def load_library(path: str = LIB_PATH):
     L.slide_set_hash_params.argtypes = [vp, vp, vp]
     L.slide_train_step.argtypes = [vp, C.POINTER(slide_batch), vp, vp]
     L.slide_predict.argtypes = [vp, C.POINTER(slide_batch), i32, i32, vp, vp, vp]
+    L.slide_predict_static.argtypes = [vp, C.POINTER(slide_batch), i32, vp, vp, vp]
     L.slide_status.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
     L.slide_get_stats.argtypes = [vp, vp, C.POINTER(slide_stats)]
     L.slide_profile.argtypes = [vp, C.c_uint32]
@@ -253,6 +255,19 @@ class Slide:
         b = self._marshal(db)
         self._check(self.L.slide_predict(self.ctx, C.byref(b), mode, topk, C.c_void_p(ids.data_ptr()),
                                          C.c_void_p(sc.data_ptr()), self._stream()))
+        return ids, sc
+
+    def predict_static(self, db: dict, topk: int, out=None):
+        """slide_predict_static: scores over all neurons with the library's static scratch; the output
+        tensors may be passed in (then nothing is allocated on the way)."""
+        t = self.torch
+        if out is None:
+            out = (t.empty((db["batch"], topk), dtype=t.int32, device=self.dev),
+                   t.empty((db["batch"], topk), dtype=t.float32, device=self.dev))
+        ids, sc = out
+        b = self._marshal(db)
+        self._check(self.L.slide_predict_static(self.ctx, C.byref(b), topk, C.c_void_p(ids.data_ptr()),
+                                                C.c_void_p(sc.data_ptr()), self._stream()))
         return ids, sc
 
     def status(self) -> int:
