@@ -79,6 +79,12 @@ def num_threads() -> int:
     return int(lib().orc_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Number of OpenMP threads the oracle's loops use from now on (the OpenMP runtime's own call)."""
+    lib()
+    C.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
 # --------------------------------------------------------------------------------------
 # thin wrappers
 # --------------------------------------------------------------------------------------

@@ -170,7 +170,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->msum = take(B * 8); lo->loss_i = take(B * 4);
   lo->umeta2 = take((size_t)lo->U2max * 16); lo->pairs2 = take(A * 8);
   lo->umeta1 = take((size_t)lo->U1max * 16); lo->pairs1 = take((size_t)lo->P1max * 8);
-  lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->entries = take((size_t)lo->L * lo->N * 8);
+  lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->entries = take((size_t)lo->L * lo->N * 4);
   lo->bh = take(tables_bh_words(lo->bits, lo->N, lo->L) * 4);
   lo->pbase = take(tables_pbase_words(lo->bits, lo->N, lo->L) * 4);
   lo->worklist = take((size_t)lo->wl_cap * 8);
@@ -348,7 +348,7 @@ int do_build(slide_ctx* ctx, hipStream_t s, bool scheduled) {
   const bool only_touched = inc && scheduled && ctx->codes_current;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_REBUILD, s, [&] {
     return launch_build_tables(ctx->hd, ctx->td, ctx->buf.W2, ctx->at<uint32_t>(lo.codes_t),
-                               ctx->at<uint2>(lo.entries), ctx->at<uint32_t>(lo.bh), ctx->at<uint32_t>(lo.pbase),
+                               ctx->at<uint32_t>(lo.entries), ctx->at<uint32_t>(lo.bh), ctx->at<uint32_t>(lo.pbase),
                                ctx->at<uint64_t>(lo.worklist), lo.wl_cap, ctx->ctrl(), ctx->cfg.overflow_policy,
                                (uint32_t)ctx->r, ctx->prio_a, ctx->prio_b,
                                inc ? ctx->at<uint8_t>(lo.touched) : nullptr,

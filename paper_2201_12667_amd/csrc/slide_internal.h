@@ -16,7 +16,7 @@ constexpr int kLongRow = 32;       // rows touched by more samples than this are
 // Device-side counters, one block at the start of the workspace.
 struct Ctrl {
   uint32_t status;        // sticky SLIDE_FLAG_* bits
-  uint32_t u2, p2;        // touched rows of W2 (statistics) / unused
+  uint32_t u2, wl_short;  // touched rows of W2 (statistics) / short-bucket worklist length (filled from the back)
   uint32_t u1, p1;        // touched rows of W1 (statistics) / pair space handed out for the input layer
   uint32_t wl_count;      // big-bucket worklist length
   uint32_t overflowed;    // buckets with more than C members at the last build
@@ -76,11 +76,11 @@ struct TablesDev {
   int L, C;
 };
 hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
-                               uint2* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
+                               uint32_t* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
                                uint32_t wl_cap, Ctrl* ctrl, int policy, uint32_t r, uint32_t prio_a,
                                uint32_t prio_b, uint8_t* touched, int32_t* touched_rows, bool only_touched,
                                hipStream_t s);
-size_t tables_bh_words(int bits, int64_t N, int L);      // per-slab histograms
+size_t tables_bh_words(int bits, int64_t N, int L);      // per-slab run boundaries
 size_t tables_pbase_words(int bits, int64_t N, int L);   // partition starts
 hipError_t tables_setup_attributes();
 

@@ -5,11 +5,12 @@
 // (priority, id) keys.
 //
 // The build is a two-level counting sort with every counter in LDS (no global atomics on the
-// tables): (1) hash every row of W2, codes stored table-major; (2) split each table's rows by the
-// high bits of the code: per-slab LDS histograms, a scan over slabs and digits, and a scatter of
-// (code, id) entries into their partition; (3) one workgroup per (table, partition) counts the low
-// bits in LDS, writes that partition's offsets, places the ids, and sorts the small buckets in
-// place; (4) buckets that are long or over capacity are queued and handled by one workgroup each.
+// tables): (1) hash every row of W2, codes stored table-major; (2) every slab of 16,384 rows of a
+// table is grouped by the high bits of the code in LDS and written back in place, with the run
+// boundaries per (slab, digit); (3) a scan over slabs gives the partition starts; (4) one workgroup per
+// (table, partition) gathers the partition's runs from the slabs, counts the low bits in LDS, writes
+// that partition's offsets, places the ids and sorts the small buckets in place; (5) buckets that are
+// long or over capacity are queued and handled by one workgroup each.
 #include "slide_internal.h"
 #include "wave_ops.h"
 
@@ -46,38 +47,14 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s) {
   return hipGetLastError();
 }
 
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t t = __shfl_up(v, d);
-    if (lane >= d) v += t;
-  }
-  return v;
-}
-
-constexpr int kSlab = 16384;       // rows per workgroup in the partition passes
-
-__global__ __launch_bounds__(1024) void part_hist_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,
-                                                         int nbins, uint32_t* __restrict__ bh, int nslab) {
-  extern __shared__ uint32_t hst[];
-  const int slab = blockIdx.x, tid = threadIdx.x;
-  const size_t t = blockIdx.y;
-  for (int b = tid; b < nbins; b += 1024) hst[b] = 0;
-  __syncthreads();
-  const int64_t j0 = (int64_t)slab * kSlab;
-  for (int k = 0; k < kSlab / 1024; ++k) {
-    const int64_t j = j0 + k * 1024 + tid;
-    if (j < N) atomicAdd(&hst[codes_t[t * N + j] >> lb], 1u);
-  }
-  __syncthreads();
-  for (int b = tid; b < nbins; b += 1024) bh[(t * nslab + slab) * nbins + b] = hst[b];
-}
+constexpr int kSlabBits = 14;
+constexpr int kSlab = 1 << kSlabBits;   // rows per slab of the grouping pass
+constexpr int kRunBlock = 1024;         // slabs whose run boundaries a bucket workgroup holds in LDS at a time
 
 // Exclusive scan over a workgroup of 1024 threads; sm: 17 words of LDS.
 __device__ uint32_t block_excl_scan1024(uint32_t v, uint32_t* sm, uint32_t* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t inc = wave_incl_scan(v);
+  const uint32_t inc = wave_incl_scan_add(v);
   __syncthreads();
   if (lane == 63) sm[wave] = inc;
   __syncthreads();
@@ -87,10 +64,62 @@ __device__ uint32_t block_excl_scan1024(uint32_t v, uint32_t* sm, uint32_t* tota
   return base + inc - v;
 }
 
-// One workgroup per table: bh[t][slab][d] becomes the number of rows of digit d in earlier slabs,
-// pbase[t][d] the start of partition d.
-__global__ __launch_bounds__(1024) void part_scan_kernel(uint32_t* bh, int nslab, int nbins, uint32_t* pbase,
-                                                         Ctrl* ctrl) {
+// One workgroup per (slab, table): the slab's rows grouped by the high digit of their code, in place
+// -- the grouped entries of slab s stay in entries[t][s*kSlab ..), so no table-wide histogram has to
+// exist before this pass.  An entry is (low digit << kSlabBits) | row inside the slab (the reader
+// knows the slab).  runs[t][s][d] = first entry of digit d inside the slab's stretch,
+// runs[t][s][nbins] = rows of the slab.  The grouping happens in LDS and the slab is written out as
+// one coalesced stretch.
+__global__ __launch_bounds__(1024) void slab_group_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,
+                                                          int nbins, uint32_t* __restrict__ runs, int nslab,
+                                                          uint32_t* __restrict__ entries) {
+  extern __shared__ uint32_t lds[];
+  uint32_t* stage = lds;                           // [kSlab] entries grouped by digit
+  uint32_t* cur = lds + kSlab;                     // [nbins] counters, then cursors
+  uint32_t* sm = cur + nbins;                      // [20]
+  const int slab = blockIdx.x, tid = threadIdx.x;
+  const size_t t = blockIdx.y;
+  for (int b = tid; b < nbins; b += 1024) cur[b] = 0;
+  __syncthreads();
+  const int64_t j0 = (int64_t)slab * kSlab;
+  const int nvalid = (int)(N - j0 < kSlab ? N - j0 : kSlab);
+  uint32_t code[kSlab / 1024];
+#pragma unroll
+  for (int k = 0; k < kSlab / 1024; ++k) {
+    const int r = k * 1024 + tid;
+    code[k] = r < nvalid ? codes_t[t * N + j0 + r] : 0u;
+  }
+#pragma unroll
+  for (int k = 0; k < kSlab / 1024; ++k)
+    if (k * 1024 + tid < nvalid) atomicAdd(&cur[code[k] >> lb], 1u);
+  __syncthreads();
+  uint32_t* rrow = runs + (t * nslab + slab) * (size_t)(nbins + 1);
+  uint32_t carry = 0;
+  for (int base = 0; base < nbins; base += 1024) {
+    const int b = base + tid;
+    const uint32_t v = b < nbins ? cur[b] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_excl_scan1024(v, sm, &total);   // (its barriers separate the read of cur from the write)
+    if (b < nbins) { cur[b] = carry + ex; rrow[b] = carry + ex; }
+    carry += total;
+  }
+  if (tid == 0) rrow[nbins] = (uint32_t)nvalid;
+  __syncthreads();
+  const uint32_t lowmask = (1u << lb) - 1u;
+#pragma unroll
+  for (int k = 0; k < kSlab / 1024; ++k) {
+    const int r = k * 1024 + tid;
+    if (r < nvalid) stage[atomicAdd(&cur[code[k] >> lb], 1u)] = ((code[k] & lowmask) << kSlabBits) | (uint32_t)r;
+  }
+  __syncthreads();
+  uint32_t* out = entries + t * N + j0;
+  for (int k = tid; k < nvalid; k += 1024) out[k] = stage[k];
+}
+
+// One workgroup per table: pbase[t][d] = rows of the table whose digit is below d (the start of
+// partition d in the table's id array), from the per-slab run boundaries.
+__global__ __launch_bounds__(1024) void part_scan_kernel(const uint32_t* __restrict__ runs, int nslab, int nbins,
+                                                         uint32_t* __restrict__ pbase, Ctrl* ctrl) {
   __shared__ uint32_t sm[20];
   const size_t t = blockIdx.x;
   const int tid = threadIdx.x;
@@ -100,10 +129,8 @@ __global__ __launch_bounds__(1024) void part_scan_kernel(uint32_t* bh, int nslab
     uint32_t run = 0;
     if (d < nbins)
       for (int slab = 0; slab < nslab; ++slab) {
-        uint32_t* p = bh + (t * nslab + slab) * nbins + d;
-        const uint32_t v = *p;
-        *p = run;
-        run += v;
+        const uint32_t* p = runs + (t * nslab + slab) * (size_t)(nbins + 1) + d;
+        run += p[1] - p[0];
       }
     uint32_t total;
     const uint32_t ex = block_excl_scan1024(run, sm, &total);
@@ -112,118 +139,132 @@ __global__ __launch_bounds__(1024) void part_scan_kernel(uint32_t* bh, int nslab
     __syncthreads();
   }
   if (tid == 0) pbase[t * (nbins + 1) + nbins] = carry;
-  if (t == 0 && tid == 0) { ctrl->wl_count = 0; ctrl->overflowed = 0; }
-}
-
-// An entry of the partitioned list: (code, row), or -- PACKED, when the low digit and the row index fit
-// 32 bits together -- (low digit << rowbits) | row, which halves what the two passes below move.
-template <bool PACKED> struct Entry { typedef uint2 type; };
-template <> struct Entry<true> { typedef uint32_t type; };
-
-// One workgroup per (slab, table): the slab's entries are first grouped by partition in
-// LDS (a local counting sort), then written out, so that every partition receives one contiguous
-// run per slab instead of single entries.
-template <bool PACKED>
-__global__ __launch_bounds__(1024) void part_scatter_kernel(const uint32_t* __restrict__ codes_t, int64_t N, int lb,
-                                                            int rowbits, int nbins, const uint32_t* __restrict__ bh,
-                                                            int nslab, const uint32_t* __restrict__ pbase,
-                                                            typename Entry<PACKED>::type* __restrict__ entries) {
-  typedef typename Entry<PACKED>::type E;
-  extern __shared__ uint32_t lds[];
-  E* stage = (E*)lds;                              // [kSlab] entries grouped by partition
-  uint16_t* stage_p = (uint16_t*)(lds + kSlab);    // [kSlab] PACKED: their partitions (the entry no longer says)
-  uint32_t* lstart = lds + 2 * kSlab;              // [nbins] first staged entry of the partition
-  uint32_t* cur = lstart + nbins;                  // [nbins] counters, then cursors
-  uint32_t* gbase = cur + nbins;                   // [nbins] where the partition's run goes in the table's entries
-  uint32_t* sm = gbase + nbins;                    // [20]
-  const int slab = blockIdx.x, tid = threadIdx.x;
-  const size_t t = blockIdx.y;
-  for (int b = tid; b < nbins; b += 1024) {
-    cur[b] = 0;
-    gbase[b] = pbase[t * (nbins + 1) + b] + bh[(t * nslab + slab) * nbins + b];
-  }
-  __syncthreads();
-  const int64_t j0 = (int64_t)slab * kSlab;
-  const int nvalid = (int)(N - j0 < kSlab ? N - j0 : kSlab);
-  uint32_t code[kSlab / 1024];
-#pragma unroll
-  for (int k = 0; k < kSlab / 1024; ++k) {
-    const int r = k * 1024 + tid;
-    code[k] = r < nvalid ? codes_t[t * N + j0 + r] : 0u;
-    if (r < nvalid) atomicAdd(&cur[code[k] >> lb], 1u);
-  }
-  __syncthreads();
-  uint32_t carry = 0;
-  for (int base = 0; base < nbins; base += 1024) {
-    const int b = base + tid;
-    const uint32_t v = b < nbins ? cur[b] : 0u;
-    uint32_t total;
-    const uint32_t ex = block_excl_scan1024(v, sm, &total);
-    if (b < nbins) lstart[b] = carry + ex;
-    carry += total;
-    __syncthreads();
-  }
-  for (int b = tid; b < nbins; b += 1024) cur[b] = lstart[b];
-  __syncthreads();
-#pragma unroll
-  for (int k = 0; k < kSlab / 1024; ++k) {
-    const int r = k * 1024 + tid;
-    if (r < nvalid) {
-      const uint32_t pos = atomicAdd(&cur[code[k] >> lb], 1u);
-      if constexpr (PACKED) {
-        stage[pos] = ((code[k] & ((1u << lb) - 1u)) << rowbits) | (uint32_t)(j0 + r);
-        stage_p[pos] = (uint16_t)(code[k] >> lb);
-      } else {
-        stage[pos] = make_uint2(code[k], (uint32_t)(j0 + r));
-      }
-    }
-  }
-  __syncthreads();
-  E* out = entries + t * N;
-  for (int k = tid; k < nvalid; k += 1024) {
-    const E e = stage[k];
-    uint32_t p;
-    if constexpr (PACKED) p = stage_p[k]; else p = e.x >> lb;
-    out[gbase[p] + ((uint32_t)k - lstart[p])] = e;
-  }
+  if (t == 0 && tid == 0) { ctrl->wl_count = 0; ctrl->wl_short = 0; ctrl->overflowed = 0; }
 }
 
 constexpr int kStageIds = 4096;    // ids of a partition staged in LDS by part_buckets (larger partitions go through memory)
-constexpr int kLdsSort = 32;       // buckets up to this size are sorted by one thread while staged in LDS
+constexpr int kRankMax = 64;       // staged buckets up to this size are ordered by counting, in place
+constexpr int kWaveSort = 64;      // queued buckets up to this size (within capacity) are sorted by one wave
+constexpr int kSlotBatch = 16;     // 64-entry pieces of runs a wave keeps in flight
 
-// One workgroup per (partition d, table t): buckets (d << lb) .. (d << lb) + 2^lb - 1.  Counts the
-// low digit, writes the partition's offsets, groups the ids by bucket -- in LDS when the partition
-// fits, so that the table receives whole lines -- and sorts the small buckets; long and
-// over-capacity buckets are queued.
-template <bool PACKED>
-__global__ __launch_bounds__(256) void part_buckets_kernel(const typename Entry<PACKED>::type* __restrict__ entries,
+// One workgroup per (partition d, table t): buckets (d << lb) .. (d << lb) + 2^lb - 1.  The partition's
+// entries are the runs of digit d of every slab.  Counts the low digit, writes the partition's offsets,
+// groups the ids by bucket -- in LDS when the partition fits, so that the table receives whole lines --
+// and sorts the small buckets; long and over-capacity buckets are queued.
+__global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __restrict__ entries,
+                                                           const uint32_t* __restrict__ runs, int nslab,
                                                            const uint32_t* __restrict__ pbase, int nbins, int lb,
-                                                           int rowbits, uint32_t nb, int64_t N, int C,
+                                                           uint32_t nb, int64_t N, int C,
                                                            uint32_t* __restrict__ off,
                                                            int32_t* ids, uint64_t* worklist, uint32_t wl_cap,
-                                                           Ctrl* ctrl) {
+                                                           Ctrl* ctrl, int nsb /* min(nslab, kRunBlock) */) {
   extern __shared__ uint32_t lds[];
-  const int nlo = 1 << lb, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nlo = 1 << lb, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nchunk = (nlo + 63) >> 6;    // 64 buckets per scan chunk
   uint32_t* cur = lds;                   // [nlo] counters, then bucket starts, then (after placing) bucket ends
   uint32_t* csum = cur + nlo;            // [nchunk] ids in the chunk, then in the chunks before it
-  int32_t* idl = (int32_t*)(csum + nchunk);   // [kStageIds] the partition's ids grouped by bucket
+  uint32_t* ra = csum + nchunk;          // [nsb] start of the slab's run inside the slab's stretch
+  uint32_t* rn = ra + nsb;               // [nsb] its length
+  uint32_t* slots = rn + nsb;            // [nsb + kStageIds/64] 64-entry pieces of the runs: run | piece << 16
   const uint32_t d = blockIdx.x;
   const size_t t = blockIdx.y;
-  const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
-  const uint32_t mask = (uint32_t)nlo - 1u;
-  const typename Entry<PACKED>::type* ent = entries + t * N;
-  auto low_digit = [&](typename Entry<PACKED>::type e) -> uint32_t {
-    if constexpr (PACKED) return e >> rowbits; else return e.x & mask;
+  const int slot_cap = nsb + kStageIds / 64;
+  int32_t* idl = (int32_t*)(slots + slot_cap);                 // [kStageIds] the partition's ids grouped by bucket
+  uint32_t* nslots_p = (uint32_t*)(idl + kStageIds);           // [1]
+  const uint32_t* tent = entries + t * N;
+  const uint32_t* truns = runs + t * nslab * (size_t)(nbins + 1) + d;
+  // The partition's entries are visited twice (count, then place).  The slabs are taken in blocks of nsb:
+  // prepare() fetches the run boundaries of a block together and cuts the runs into pieces of 64
+  // entries; a wave takes a piece, a lane an entry, kSlotBatch pieces per wave in flight at once.
+  auto prepare = [&](int sb) -> int {
+    const int ns = min(nsb, nslab - sb);
+    __syncthreads();
+    for (int q = tid; q < ns; q += 256) {
+      const uint32_t* p = truns + (size_t)(sb + q) * (nbins + 1);
+      const uint32_t a = p[0];
+      ra[q] = a; rn[q] = p[1] - a;
+    }
+    __syncthreads();
+    if (wave == 0) {                               // pieces of every run, in run order
+      uint32_t carry = 0;
+      for (int q0 = 0; q0 < ns; q0 += 64) {
+        const int q = q0 + lane;
+        const uint32_t np = q < ns ? (rn[q] + 63u) >> 6 : 0u;
+        const uint32_t inc = wave_incl_scan_add(np);
+        uint32_t at = carry + inc - np;
+        for (uint32_t j = 0; j < np; ++j, ++at)
+          if (at < (uint32_t)slot_cap) slots[at] = (uint32_t)q | (j << 16);
+        carry += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+      }
+      if (lane == 0) *nslots_p = carry;
+    }
+    __syncthreads();
+    return ns;
   };
-  auto row_of = [&](typename Entry<PACKED>::type e) -> int32_t {
-    if constexpr (PACKED) return (int32_t)(e & ((1u << rowbits) - 1u)); else return (int32_t)e.y;
+  auto load_batch = [&](int sb, int base, int nslots, uint32_t (&x)[kSlotBatch], uint32_t (&rb)[kSlotBatch]) {
+#pragma unroll
+    for (int k = 0; k < kSlotBatch; ++k) {
+      const int sl = base + 4 * k + wave;            // (wave-uniform)
+      x[k] = 0xffffffffu; rb[k] = 0;                 // (no entry has all bits set: at most 27 are used)
+      if (sl < nslots) {
+        const uint32_t info = slots[sl];
+        const uint32_t q = info & 0xffffu, o = (info >> 16) * 64u + (uint32_t)lane;
+        rb[k] = (uint32_t)(sb + q) << kSlabBits;
+        if (o < rn[q]) x[k] = tent[(size_t)rb[k] + ra[q] + o];
+      }
+    }
   };
-  const bool staged = s1 - s0 <= (uint32_t)kStageIds;
+  auto visit_block = [&](int sb, int ns, auto&& f) {   // f(global row, low digit) for every entry of the block
+    const int nslots = (int)*nslots_p;
+    if (nslots <= slot_cap) {
+      for (int base = 0; base < nslots; base += 4 * kSlotBatch) {
+        uint32_t x[kSlotBatch], rb[kSlotBatch];
+        load_batch(sb, base, nslots, x, rb);
+#pragma unroll
+        for (int k = 0; k < kSlotBatch; ++k)
+          if (x[k] != 0xffffffffu) f(rb[k] + (x[k] & (uint32_t)(kSlab - 1)), x[k] >> kSlabBits);
+      }
+    } else {
+      // more pieces than the slot table holds (a partition far too large to stage): a wave per run
+      for (int q = wave; q < ns; q += 4) {
+        const uint32_t a = ra[q], n = rn[q], rowbase = (uint32_t)(sb + q) << kSlabBits;
+        for (uint32_t e = lane; e < n; e += 64) {
+          const uint32_t x = tent[(size_t)rowbase + a + e];
+          f(rowbase + (x & (uint32_t)(kSlab - 1)), x >> kSlabBits);
+        }
+      }
+    }
+  };
+  // Usual case: one block of slabs and at most 4*kSlotBatch pieces, so every entry of the partition sits
+  // in a register of some lane after one round of loads, and both visits use the registers.
+  const bool single = nslab <= nsb;
+  uint32_t x0[kSlotBatch], rb0[kSlotBatch];
+  bool cached = false;
+  int ns0 = 0;
   for (int b = tid; b < nlo; b += 256) cur[b] = 0;
-  __syncthreads();
-  for (uint32_t e = s0 + tid; e < s1; e += 256) atomicAdd(&cur[low_digit(ent[e])], 1u);
-  __syncthreads();
+  if (single) {
+    ns0 = prepare(0);
+    const int nslots = (int)*nslots_p;
+    cached = nslots <= 4 * kSlotBatch && nslots <= slot_cap;
+    if (cached) load_batch(0, 0, nslots, x0, rb0);
+  }
+  const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
+  const bool staged = s1 - s0 <= (uint32_t)kStageIds;
+  auto visit = [&](auto&& f) {
+    if (cached) {
+#pragma unroll
+      for (int k = 0; k < kSlotBatch; ++k)
+        if (x0[k] != 0xffffffffu) f(rb0[k] + (x0[k] & (uint32_t)(kSlab - 1)), x0[k] >> kSlabBits);
+    } else if (single) {
+      visit_block(0, ns0, f);
+    } else {
+      for (int sb = 0; sb < nslab; sb += nsb) { const int ns = prepare(sb); visit_block(sb, ns, f); }
+    }
+    __syncthreads();
+  };
+  if (!single) __syncthreads();                    // (the counters are cleared before the first visit)
+  visit([&](uint32_t, uint32_t low) { atomicAdd(&cur[low], 1u); });
   // exclusive scan of the counters: every wave scans chunks of 64 in registers, wave 0 the chunk sums
   for (int c = wave; c < nchunk; c += 4) {
     const int b = c * 64 + lane;
@@ -251,37 +292,116 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const typename Entry<
     orow[b] = s0 + st;
   }
   if (d == (uint32_t)nbins - 1 && tid == 0) off[t * (nb + 1) + nb] = (uint32_t)N;
-  __syncthreads();
   int32_t* seg = ids + t * N + s0;
   int32_t* place = staged ? idl : seg;
-  for (uint32_t e = s0 + tid; e < s1; e += 256) {
-    const auto x = ent[e];
-    place[atomicAdd(&cur[low_digit(x)], 1u)] = row_of(x);
-  }
-  __syncthreads();                                  // cur[b] is now the end of bucket b = the start of bucket b + 1
-  const uint32_t small = staged ? (uint32_t)kLdsSort : (uint32_t)kSmallBucket;
+  __syncthreads();
+  visit([&](uint32_t row, uint32_t low) { place[atomicAdd(&cur[low], 1u)] = (int32_t)row; });
+  // cur[b] is now the end of bucket b = the start of bucket b + 1
   uint32_t over = 0;
-  for (int b = tid; b < nlo; b += 256) {
-    const uint32_t a = b ? cur[b - 1] : 0u, sz = cur[b] - a;
-    if (sz > (uint32_t)C) ++over;
-    if (sz < 2) continue;
-    if (sz <= small && sz <= (uint32_t)C) {
-      int32_t* p = place + a;                     // arrival order is arbitrary: restore ascending ids
-      for (uint32_t i = 1; i < sz; ++i) {
-        const int32_t key = p[i];
-        int q = (int)i - 1;
-        while (q >= 0 && p[q] > key) { p[q + 1] = p[q]; --q; }
-        p[q + 1] = key;
-      }
+  auto enqueue = [&](int b, uint32_t sz) {           // short lists from the back of the worklist, long ones from the front
+    const uint64_t item = ((uint64_t)t << 32) | ((d << lb) + (uint32_t)b);
+    if (sz <= (uint32_t)kWaveSort && sz <= (uint32_t)C) {
+      const uint32_t slot = atomicAdd(&ctrl->wl_short, 1u);
+      if (slot < wl_cap) worklist[wl_cap - 1u - slot] = item;
     } else {
       const uint32_t slot = atomicAdd(&ctrl->wl_count, 1u);
-      if (slot < wl_cap) worklist[slot] = ((uint64_t)t << 32) | ((d << lb) + (uint32_t)b);
+      if (slot < wl_cap) worklist[slot] = item;
+    }
+  };
+  if (staged) {
+    // The ids sit in idl grouped by bucket, in arrival order; a thread takes a bucket.  Up to eight
+    // ids (nearly every bucket) are sorted in registers by a fixed network of comparators -- the same
+    // instructions in every lane, whatever the bucket's size -- and go straight to the table.  Longer
+    // buckets are sorted in LDS by their thread; those beyond kRankMax or over capacity are copied as
+    // they are and queued.
+    for (int b0 = 0; b0 < nlo; b0 += 256) {
+      const int b = b0 + tid;                        // (every lane runs the loop: the network is wave-wide)
+      const uint32_t a = (b && b < nlo) ? cur[b - 1] : 0u, sz = b < nlo ? cur[b] - a : 0u;
+      if (sz > (uint32_t)C) ++over;
+      const bool big = sz > (uint32_t)kRankMax || sz > (uint32_t)C;
+      if (big) {
+        for (uint32_t q = a; q < a + sz; ++q) seg[q] = idl[q];
+        enqueue(b, sz);
+      } else if (sz > 8u) {
+        int32_t* p = idl + a;
+        for (uint32_t i = 1; i < sz; ++i) {
+          const int32_t key = p[i];
+          int q = (int)i - 1;
+          while (q >= 0 && p[q] > key) { p[q + 1] = p[q]; --q; }
+          p[q + 1] = key;
+        }
+        for (uint32_t q = a; q < a + sz; ++q) seg[q] = idl[q];
+      }
+      const uint32_t n8 = (big || sz > 8u) ? 0u : sz;
+      int32_t v[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = (uint32_t)i < n8 ? idl[a + i] : 0x7fffffff;
+      if (__any(n8 > 4u)) {
+#pragma unroll
+        for (int i = 4; i < 8; ++i) v[i] = (uint32_t)i < n8 ? idl[a + i] : 0x7fffffff;
+      } else {
+#pragma unroll
+        for (int i = 4; i < 8; ++i) v[i] = 0x7fffffff;
+      }
+#define SLIDE_CE(i, j) { const int32_t lo_ = min(v[i], v[j]), hi_ = max(v[i], v[j]); v[i] = lo_; v[j] = hi_; }
+      SLIDE_CE(0, 1) SLIDE_CE(2, 3) SLIDE_CE(4, 5) SLIDE_CE(6, 7)         // odd-even merge sort of 8: 19 comparators
+      SLIDE_CE(0, 2) SLIDE_CE(1, 3) SLIDE_CE(4, 6) SLIDE_CE(5, 7)
+      SLIDE_CE(1, 2) SLIDE_CE(5, 6)
+      SLIDE_CE(0, 4) SLIDE_CE(1, 5) SLIDE_CE(2, 6) SLIDE_CE(3, 7)
+      SLIDE_CE(2, 4) SLIDE_CE(3, 5)
+      SLIDE_CE(1, 2) SLIDE_CE(3, 4) SLIDE_CE(5, 6)
+#undef SLIDE_CE
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if ((uint32_t)i < n8) seg[a + i] = v[i];
+    }
+  } else {
+    for (int b = tid; b < nlo; b += 256) {
+      const uint32_t a = b ? cur[b - 1] : 0u, sz = cur[b] - a;
+      if (sz > (uint32_t)C) ++over;
+      if (sz < 2) continue;
+      if (sz <= (uint32_t)kSmallBucket && sz <= (uint32_t)C) {
+        int32_t* p = seg + a;                       // arrival order is arbitrary: restore ascending ids
+        for (uint32_t i = 1; i < sz; ++i) {
+          const int32_t key = p[i];
+          int q = (int)i - 1;
+          while (q >= 0 && p[q] > key) { p[q + 1] = p[q]; --q; }
+          p[q + 1] = key;
+        }
+      } else {
+        enqueue(b, sz);
+      }
     }
   }
   if (over) atomicAdd(&ctrl->overflowed, over);
-  if (staged) {
-    __syncthreads();
-    for (uint32_t k = tid; k < s1 - s0; k += 256) seg[k] = idl[k];
+}
+
+// One wave per queued bucket of at most 64 ids (within capacity): a bitonic sort across the lanes.
+__global__ __launch_bounds__(256) void short_buckets_kernel(const uint32_t* __restrict__ off, int32_t* ids, uint32_t nb,
+                                                            int64_t N, const uint64_t* __restrict__ worklist,
+                                                            uint32_t wl_cap, const Ctrl* ctrl) {
+  uint32_t n_items = ctrl->wl_short;
+  if (n_items > wl_cap) n_items = wl_cap;
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = blockIdx.x * 4u + (threadIdx.x >> 6), nwaves = gridDim.x * 4u;
+  for (uint32_t item = wave; item < n_items; item += nwaves) {
+    const uint64_t w = worklist[wl_cap - 1u - item];
+    const uint64_t t = w >> 32;
+    const uint32_t c = (uint32_t)w;
+    const uint32_t o0 = off[t * (nb + 1) + c];
+    const uint32_t s = off[t * (nb + 1) + c + 1] - o0;          // <= 64
+    int32_t* p = ids + t * N + o0;
+    int32_t key = (uint32_t)lane < s ? p[lane] : 0x7fffffff;
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1)
+#pragma unroll
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        const int32_t other = __shfl_xor(key, j);
+        const bool up = (lane & k) == 0, lower = (lane & j) == 0;
+        const int32_t mn = key < other ? key : other, mx = key < other ? other : key;
+        key = (lower == up) ? mn : mx;
+      }
+    if ((uint32_t)lane < s) p[lane] = key;
   }
 }
 
@@ -334,9 +454,13 @@ __global__ __launch_bounds__(256) void big_buckets_kernel(const uint32_t* __rest
       const uint32_t chunk = kSortCap - capp;
       for (int i = threadIdx.x; i < capp; i += 256) keys[i] = ~0ull;
       for (uint32_t base = 0; base < s; base += chunk) {
-        for (uint32_t i = threadIdx.x; i < chunk; i += 256) {
+        // the survivors so far plus the next members, padded to a power of two (often well below kSortCap)
+        const uint32_t m = s - base < chunk ? s - base : chunk;
+        int nsort = 2 * capp;
+        while ((uint32_t)nsort < (uint32_t)capp + m) nsort <<= 1;
+        for (uint32_t i = threadIdx.x; i < (uint32_t)(nsort - capp); i += 256) {
           uint64_t k = ~0ull;
-          if (base + i < s) {
+          if (i < m) {
             const uint32_t j = (uint32_t)p[base + i];
             const uint32_t pr = policy == SLIDE_KEEP_LOWEST_ID ? 0u : overflow_prio(j, (uint32_t)t, r, pa, pb);
             k = ((uint64_t)pr << 32) | j;
@@ -344,7 +468,7 @@ __global__ __launch_bounds__(256) void big_buckets_kernel(const uint32_t* __rest
           keys[capp + i] = k;
         }
         __syncthreads();
-        bitonic_sort_u64(keys, kSortCap);
+        bitonic_sort_u64(keys, nsort);
       }
       uint64_t mine[kSortCap / 512];            // capp <= 1024: at most 4 per thread
       for (int i = threadIdx.x, q = 0; i < capp; i += 256, ++q)
@@ -369,11 +493,11 @@ void tables_split(int bits, int64_t N, int* hb, int* lb) {
   *lb = bits - h;
 }
 
-size_t tables_bh_words(int bits, int64_t N, int L) {
+size_t tables_bh_words(int bits, int64_t N, int L) {      // run boundaries per (table, slab)
   int hb, lb;
   tables_split(bits, N, &hb, &lb);
   const int64_t nslab = (N + kSlab - 1) / kSlab;
-  return (size_t)L * (size_t)(nslab > 0 ? nslab : 1) * ((size_t)1 << hb);
+  return (size_t)L * (size_t)(nslab > 0 ? nslab : 1) * (((size_t)1 << hb) + 1);
 }
 
 size_t tables_pbase_words(int bits, int64_t N, int L) {
@@ -382,11 +506,12 @@ size_t tables_pbase_words(int bits, int64_t N, int L) {
   return (size_t)L * (((size_t)1 << hb) + 1);
 }
 
-static size_t part_buckets_lds(int lb) {
+static int run_block(int nslab) { return nslab < kRunBlock ? nslab : kRunBlock; }
+static size_t part_buckets_lds(int lb, int nsb) {
   const size_t nlo = (size_t)1 << lb;
-  return (nlo + ((nlo + 63) >> 6) + kStageIds) * 4;
+  return (nlo + ((nlo + 63) >> 6) + 3 * (size_t)nsb + kStageIds / 64 + kStageIds + 1) * 4;
 }
-static size_t part_scatter_lds(int nbins) { return ((size_t)2 * kSlab + 3 * (size_t)nbins + 20) * 4; }
+static size_t slab_group_lds(int nbins) { return ((size_t)kSlab + (size_t)nbins + 20) * 4; }
 
 // Rows of W2 touched since the last build (one byte each, set by the training step) -> a list of
 // their ids and its length; the marks are cleared.  One thread per row, one counter update per
@@ -424,16 +549,14 @@ hipError_t tables_setup_attributes() {
 #define SLIDE_SET(K, BYTES) \
   e = hipFuncSetAttribute((const void*)&K, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(BYTES)); \
   if (e != hipSuccess) return e;
-  SLIDE_SET(part_buckets_kernel<false>, part_buckets_lds(13))
-  SLIDE_SET(part_buckets_kernel<true>, part_buckets_lds(13))
-  SLIDE_SET(part_scatter_kernel<false>, part_scatter_lds(2048))
-  SLIDE_SET(part_scatter_kernel<true>, part_scatter_lds(2048))
+  SLIDE_SET(part_buckets_kernel, part_buckets_lds(13, kRunBlock))
+  SLIDE_SET(slab_group_kernel, slab_group_lds(2048))
 #undef SLIDE_SET
   return hipSuccess;
 }
 
 hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const float* W2, uint32_t* codes_t,
-                               uint2* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
+                               uint32_t* entries, uint32_t* bh, uint32_t* pbase, uint64_t* worklist,
                                uint32_t wl_cap, Ctrl* ctrl, int policy, uint32_t r, uint32_t prio_a,
                                uint32_t prio_b, uint8_t* touched, int32_t* touched_rows, bool only_touched,
                                hipStream_t s) {
@@ -457,24 +580,14 @@ hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const flo
     if (touched && (e = launch_fill_u32((uint32_t*)touched, (size_t)ceil_div(td.N, 4), 0u, s)) != hipSuccess) return e;
     if ((e = launch_hash(hd, W2, td.N, codes_t, 1, td.N, nullptr, nullptr, hd.L, s)) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(part_hist_kernel, dim3(nslab, td.L), dim3(1024), (size_t)nbins * 4, s, codes_t, td.N, lb, nbins,
-                     bh, nslab);
+  // (2) every slab grouped by the high digit in place, (3) partition starts, (4) buckets
+  hipLaunchKernelGGL(slab_group_kernel, dim3(nslab, td.L), dim3(1024), slab_group_lds(nbins), s, codes_t, td.N, lb, nbins,
+                     bh, nslab, entries);
   hipLaunchKernelGGL(part_scan_kernel, dim3(td.L), dim3(1024), 0, s, bh, nslab, nbins, pbase, ctrl);
-  int rowbits = 1;
-  while (((int64_t)1 << rowbits) < td.N) ++rowbits;
-  if (lb + rowbits <= 32) {
-    hipLaunchKernelGGL(part_scatter_kernel<true>, dim3(nslab, td.L), dim3(1024), part_scatter_lds(nbins), s, codes_t, td.N,
-                       lb, rowbits, nbins, bh, nslab, pbase, (uint32_t*)entries);
-    hipLaunchKernelGGL(part_buckets_kernel<true>, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb), s,
-                       (const uint32_t*)entries, pbase, nbins, lb, rowbits, td.nb, td.N, td.C, td.off, td.ids, worklist,
-                       wl_cap, ctrl);
-  } else {
-    hipLaunchKernelGGL(part_scatter_kernel<false>, dim3(nslab, td.L), dim3(1024), part_scatter_lds(nbins), s, codes_t, td.N,
-                       lb, rowbits, nbins, bh, nslab, pbase, entries);
-    hipLaunchKernelGGL(part_buckets_kernel<false>, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb), s,
-                       (const uint2*)entries, pbase, nbins, lb, rowbits, td.nb, td.N, td.C, td.off, td.ids, worklist,
-                       wl_cap, ctrl);
-  }
+  const int nsb = run_block(nslab);
+  hipLaunchKernelGGL(part_buckets_kernel, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb, nsb), s, entries, bh, nslab,
+                     pbase, nbins, lb, td.nb, td.N, td.C, td.off, td.ids, worklist, wl_cap, ctrl, nsb);
+  hipLaunchKernelGGL(short_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, worklist, wl_cap, ctrl);
   hipLaunchKernelGGL(big_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, td.C, policy,
                      r, prio_a, prio_b, worklist, wl_cap, ctrl);
   return hipGetLastError();

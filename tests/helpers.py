@@ -6,10 +6,10 @@ from oracle import slide_oracle as so
 from paper_2201_12667_amd import slide, synth
 from paper_2201_12667_amd.slide import FLAG_BAD_LABEL
 
-# fp32 tolerance: |gpu - ref| <= REL*|ref| + FLOOR*max|ref| (REL from the stated 1e-4 relative bar; the
-# floor absorbs cancellation in sums of up to H = 2048 products: a few hundred fp32 ulps of the
-# largest element).
-REL, FLOOR = 1e-4, 2e-6
+# fp32 tolerance: |gpu - ref| <= REL*|ref| + FLOOR*max|ref| (REL is the stated 1e-4 relative bar; the
+# floor, about two fp32 ulps of the tensor's largest element, is what keeps the bar meaningful for
+# elements that cancel to nearly zero).
+REL, FLOOR = 1e-4, 1e-7
 
 
 def close(a, ref, rel=REL, floor=FLOOR):
