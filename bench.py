@@ -52,7 +52,7 @@ def main() -> int:
     ap.add_argument("--cpu-steps", type=int, default=20, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--cpu-steps-1thread", type=int, default=2,
                     help="oracle steps timed on a single thread after those (0 = skip)")
-    ap.add_argument("--breakdown", action="store_true", help="also time every stage on extra steps")
+    ap.add_argument("--breakdown", action="store_true", help="bracket every stage (not only the two row-gather launches) in the roofline pass")
     ap.add_argument("--sample-budget", type=int, default=0,
                     help="retrieved neurons kept per sample (0 = all, the configuration the metric is quoted on)")
     ap.add_argument("--sample-fill", action="store_true", help="fill an unmet budget with uniformly drawn neurons")
@@ -176,11 +176,12 @@ def main() -> int:
 
     # roofline pass: the next K batches, events on the caller's stream around the two row-gather launches
     model.reset_stats()
-    model.profile((1 << i_fwd) | (1 << i_upd))
+    model.profile(((1 << slide.NUM_STAGES) - 1) if args.breakdown else ((1 << i_fwd) | (1 << i_upd)))
     for s in range(W + K, W + 2 * K):
         model.train_step(batches[s])
     ms, n = model.profile_read()
     model.profile(0)
+    stage_ms = {slide.STAGES[i]: float(ms[i]) / int(n[i]) for i in range(slide.NUM_STAGES) if n[i]} if args.breakdown else None
     st = model.stats()
     steps_done = max(st["sum_steps"], 1)
     A, U, U1 = (st[k] / steps_done for k in ("sum_active_pairs", "sum_unique_out_rows", "sum_unique_in_rows"))
@@ -269,18 +270,12 @@ def main() -> int:
                        "compulsory_GBs_without_rebuild": compulsory / (raw_s / K) / 1e9,
                        "frac_of_peak_without_rebuild": compulsory / (raw_s / K) / 1e9 / HBM_PEAK_GBS},
     }
+    if stage_ms:
+        out["stage_ms"] = stage_ms
     if rebuilds_in_region:
         out["rebuild_in_region"] = {"avg_ms": rebuild_in_region_ms, "count": rebuilds_in_region,
                                     "incremental": bool(wl.incremental_rebuild),
                                     "rows_hashed_by_last": st_timed["rehashed_rows"]}
-
-    if args.breakdown:
-        model.profile((1 << slide.NUM_STAGES) - 1)
-        for s in range(W, W + K):
-            model.train_step(batches[s])
-        ms, n = model.profile_read()
-        model.profile(0)
-        out["stage_ms"] = {slide.STAGES[i]: float(ms[i]) / int(n[i]) for i in range(slide.NUM_STAGES) if n[i]}
 
     if args.cpu_steps > 0:
         from oracle import slide_oracle as so

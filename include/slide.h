@@ -32,7 +32,7 @@
 extern "C" {
 #endif
 
-#define SLIDE_ABI_VERSION 3u
+#define SLIDE_ABI_VERSION 4u
 
 typedef struct slide_ctx slide_ctx; /* opaque, host side */
 
@@ -49,6 +49,8 @@ enum slide_hash_kind { SLIDE_HASH_SIMHASH = 0, SLIDE_HASH_DWTA = 1 };
 
 /* Which members of an over-full bucket survive (both store survivors ascending by id). */
 enum slide_overflow_policy { SLIDE_KEEP_LOWEST_ID = 0, SLIDE_KEEP_PRIORITY = 1 };
+
+enum slide_row_major_mode { SLIDE_ROWS_AUTO = 0, SLIDE_ROWS_NEVER = 1, SLIDE_ROWS_ALWAYS = 2 };
 
 /* Bits of the sticky device status word returned (negated into SLIDE_EDATA) by slide_status. */
 #define SLIDE_FLAG_BAD_FEATURE 1u   /* x_indices entry outside [0, input_dim): ignored           */
@@ -89,6 +91,13 @@ typedef struct {
    * else writes W2 between builds: after changing W2 yourself, call slide_build_tables, which always
    * hashes every row.  Costs 5 bytes per output neuron of workspace. */
   int32_t incremental_rebuild;
+  /* How the float kernels walk the (sample, neuron) incidences of a batch.  Sample-major work (a sample's
+   * active neurons, rows gathered per incidence) suits batches whose samples share few rows; when every
+   * bucket is over capacity each sample retrieves L*C neurons and a touched row belongs to many samples:
+   * then the rows are streamed once and the batch's vectors are kept in LDS instead.  The results agree
+   * to rounding; integers are identical.  SLIDE_ROWS_AUTO decides per call from the configuration
+   * (batch * L * min(C, N / 2^bits) against N). */
+  int32_t row_major_mode;      /* slide_row_major_mode */
 } slide_config;
 
 typedef struct {

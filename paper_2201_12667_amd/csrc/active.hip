@@ -132,6 +132,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   if (i == 0 && tid == 0) {                              // consumed after this kernel
     ctrl->nlong2 = 0; ctrl->max_nu2 = 0;
     if (sp.W1) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }
+    for (int r = 0; r < kPairRegions; ++r) ctrl->p1r[r] = 0;
   }
 
   // the sample's slice of the sample-major arrays: room for every candidate plus its labels
@@ -346,12 +347,13 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   const uint32_t nch = ((uint32_t)n + kChunk - 1) / kChunk;
   if (tid == 0) {
     ad.cnt[i] = n; ad.ny[i] = (int32_t)sm[17]; ncand[i] = (int32_t)T; ad.as_base[i] = base_i;
-    // forward work items of this sample: room for their partial results (which block of slots does not
-    // matter: a sample's partial results are merged in the sample's own chunk order), and the largest
-    // number of items of any sample, which bounds the forward launch's enumeration
-    ad.chunk_ptr[i] = nch ? (int32_t)atomicAdd(&ctrl->chunk_alloc[ad.par], nch) : 0;
-    if (nch) atomicMax(&ctrl->max_nch[ad.par], nch);
-    if (i == 0) { ctrl->chunk_alloc[ad.par ^ 1] = 0; ctrl->max_nch[ad.par ^ 1] = 0; }   // the previous call's: clear for the next call
+    // forward work items of this sample: the partial results of its chunk c go to slot
+    // base_i / kChunk + i + c (the samples' slices of the sample-major arrays do not overlap, so neither
+    // do these), and the largest number of items of any sample bounds the forward launch's enumeration
+    // (most samples find the maximum already there: only a larger count updates it)
+    ad.chunk_ptr[i] = base_i / kChunk + i;
+    if (nch > *(volatile uint32_t*)&ctrl->max_nch[ad.par]) atomicMax(&ctrl->max_nch[ad.par], nch);
+    if (i == 0) ctrl->max_nch[ad.par ^ 1] = 0;           // the previous call's: clear for the next call
   }
 
   // per-tile counts -> exclusive prefix inside the sample (rank of the tile's first active neuron)

@@ -129,6 +129,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->NT1 = lo->DWpad / lo->TWF;
   if (c->sample_budget < 0) FAIL(SLIDE_EINVAL, "sample_budget must be >= 0");
   if (c->incremental_rebuild != 0 && c->incremental_rebuild != 1) FAIL(SLIDE_EINVAL, "incremental_rebuild must be 0 or 1");
+  if (c->row_major_mode < SLIDE_ROWS_AUTO || c->row_major_mode > SLIDE_ROWS_ALWAYS) FAIL(SLIDE_EINVAL, "unknown row_major_mode");
   const int64_t per_sample = std::min<int64_t>(std::max<int64_t>((int64_t)c->L * c->bucket_cap, c->sample_budget), lo->N);
   lo->PS = (int)per_sample;
   lo->Amax = (int64_t)c->max_batch * per_sample + c->max_labels_per_batch;
@@ -137,6 +138,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->max_chunks = lo->Amax / kChunk + c->max_batch + 1;
   lo->U2max = (int64_t)lo->NWpad * 32;
   lo->P1max = c->max_nnz_per_batch;
+  if (lo->P1max * kPairRegions >= ((int64_t)1 << 31)) FAIL(SLIDE_EINVAL, "max_nnz_per_batch too large");
   lo->U1max = (int64_t)lo->DWpad * 32;
   lo->long2 = lo->Amax / kLongRow + 1;
   lo->long1 = lo->P1max / kLongRow + 1;
@@ -169,7 +171,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->partials = take((size_t)lo->max_chunks * (H + 4) * 4);
   lo->msum = take(B * 8); lo->loss_i = take(B * 4);
   lo->umeta2 = take((size_t)lo->U2max * 16); lo->pairs2 = take(A * 8);
-  lo->umeta1 = take((size_t)lo->U1max * 16); lo->pairs1 = take((size_t)lo->P1max * 8);
+  lo->umeta1 = take((size_t)lo->U1max * 16); lo->pairs1 = take((size_t)lo->P1max * 8 * kPairRegions);
   lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->entries = take((size_t)lo->L * lo->N * 4);
   lo->bh = take(tables_bh_words(lo->bits, lo->N, lo->L) * 4);
   lo->pbase = take(tables_pbase_words(lo->bits, lo->N, lo->L) * 4);
@@ -197,6 +199,7 @@ struct slide_ctx {
   TablesDev td;
   uint32_t prio_a, prio_b;
   size_t lds_limit;
+  int num_cus = 256;             // compute units of the device (persistent launches are sized by it)
   int device = -1;               // device that was current at slide_init
   char* static_scratch = nullptr;   // this device's copy of the static scratch array
   int64_t t = 0, r = 0;
@@ -301,11 +304,23 @@ int check_batch(slide_ctx* ctx, const slide_batch* b, bool need_labels) {
   return SLIDE_OK;
 }
 
+// Whether this call's float kernels walk the incidences row-major (see slide_config::row_major_mode).
+// Automatic rule: the tables return about L * min(C, N / 2^bits) neurons per sample; when the batch's
+// total is several times the layer, a touched row belongs to several samples.
+bool row_major(const slide_ctx* ctx, int batch) {
+  const slide_config& c = ctx->cfg;
+  if (c.row_major_mode == SLIDE_ROWS_NEVER) return false;
+  if (c.row_major_mode == SLIDE_ROWS_ALWAYS) return true;
+  const int64_t per_bucket = std::max<int64_t>(1, ctx->lo.N >> ctx->lo.bits);
+  const int64_t est = (int64_t)batch * c.L * std::min<int64_t>(c.bucket_cap, per_bucket);
+  return est >= 4 * ctx->lo.N;
+}
+
 // Hidden activations, hash codes + active sets, and the logits pass; t1 and t2 (training only) are
 // the row-list constructions for the features and the active sets that ride in the logits launch (the
 // bit-matrix pointers of t2 are filled in here).
 int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out,
-                   const TransposeArgs& t1, TransposeArgs t2) {
+                   const TransposeArgs& t1, TransposeArgs t2, bool split_lists) {
   const Layout& lo = ctx->lo;
   const int B = b->batch;
   const float* h = b->hidden;
@@ -334,8 +349,18 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
                                ncand, ctx->ctrl(), ctx->lds_limit, s); }));
   t2.ids = ad.as_ids; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
+    // When the samples share most rows the logit workers keep the machine busy for long and the row
+    // lists are many: the lists get the machine to themselves first.
+    if (split_lists && (t1.ntiles || t2.ntiles)) {
+      hipError_t e = launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
+                                    ctx->at<float>(lo.partials), ctx->ctrl(), t1, t2, false, ctx->num_cus, s);
+      if (e != hipSuccess) return e;
+      return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
+                            ctx->at<float>(lo.partials), ctx->ctrl(), TransposeArgs{}, TransposeArgs{}, true,
+                            ctx->num_cus, s);
+    }
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
-                          ctx->at<float>(lo.partials), ctx->ctrl(), t1, t2, s); }));
+                          ctx->at<float>(lo.partials), ctx->ctrl(), t1, t2, true, ctx->num_cus, s); }));
   *ad_out = ad;
   return SLIDE_OK;
 }
@@ -478,6 +503,14 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   if (e == hipSuccess) { what = "hipFuncSetAttribute(active-set kernels)"; e = active_setup_attributes(&ctx->lds_limit); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(table kernels)"; e = tables_setup_attributes(); }
   if (e == hipSuccess) { what = "hipFuncSetAttribute(forward kernels)"; e = forward_setup_attributes(ctx->lds_limit); }
+  if (e == hipSuccess) { what = "hipFuncSetAttribute(update kernels)"; e = update_setup_attributes(ctx->lds_limit); }
+  if (e == hipSuccess) {
+    what = "hipDeviceGetAttribute(compute units)";
+    int dev = 0, cus = 0;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess && cus > 0) ctx->num_cus = cus;
+  }
   if (e == hipSuccess) {
     what = "hipGetSymbolAddress(static scratch)";
     void* p = nullptr;
@@ -554,11 +587,11 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   PairsDev p2, p1;
   p2.rows_per_tile = lo.TW * 32; p2.ntiles = lo.NT2; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
   p2.umeta = ctx->at<int4>(lo.umeta2); p2.pairs = ctx->at<int2>(lo.pairs2);
-  p2.pcount = nullptr; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
+  p2.pcount = nullptr; p2.region_pairs = 0; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
   p2.long_cap = (int)lo.long2; p2.max_nu = &ctx->ctrl()->max_nu2;
   p1.rows_per_tile = lo.TWF * 32; p1.ntiles = lo.NT1; p1.tile_nu = ctx->at<int32_t>(lo.tile_nu1);
   p1.umeta = ctx->at<int4>(lo.umeta1); p1.pairs = ctx->at<int2>(lo.pairs1);
-  p1.pcount = &ctx->ctrl()->p1; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
+  p1.pcount = ctx->ctrl()->p1r; p1.region_pairs = (uint32_t)lo.P1max; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
   p1.long_cap = (int)lo.long1; p1.max_nu = &ctx->ctrl()->max_nu1;
   const int Bpad = (b->batch + 63) & ~63;
   TransposeArgs t2{}, t1{};
@@ -569,7 +602,8 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
     t1.ids = b->x_indices; t1.xse = ctx->at<int2>(lo.xse); t1.x_nnz = b->nnz;
   }
   ActiveDev ad;
-  if ((rc = forward_common(ctx, b, true, s, &ad, t1, t2)) != SLIDE_OK) return rc;
+  const bool rows_mode = row_major(ctx, b->batch);
+  if ((rc = forward_common(ctx, b, true, s, &ad, t1, t2, rows_mode)) != SLIDE_OK) return rc;
   float* dh = ctx->at<float>(lo.dh);
   float* delta = ctx->at<float>(lo.delta);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_COMBINE, s, [&] {
@@ -597,7 +631,10 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
     fin.b1 = ctx->buf.b1; fin.mb1 = ctx->buf.mb1; fin.vb1 = ctx->buf.vb1;
     fin.tile_nu1 = p1.tile_nu; fin.ntiles1 = p1.ntiles;
   }
-  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_UPDATE, s, [&] { return launch_update(lo.H, out, in, fin, a, s); }));
+  const bool rows = rows_mode && update_sliced_applies(b->batch, lo.H, ctx->lds_limit);
+  HIPCHK(ctx, stage(ctx, SLIDE_STAGE_UPDATE, s, [&] {
+    return rows ? launch_update_sliced(lo.H, b->batch, out, in, fin, a, ctx->lds_limit, ctx->num_cus, s)
+                : launch_update(lo.H, out, in, fin, a, s); }));
   ctx->t = t;
   if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
     ctx->r += 1;
@@ -633,7 +670,7 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
     return SLIDE_OK;
   }
   ActiveDev ad;
-  if ((rc = forward_common(ctx, b, false, s, &ad, TransposeArgs{}, TransposeArgs{})) != SLIDE_OK) return rc;
+  if ((rc = forward_common(ctx, b, false, s, &ad, TransposeArgs{}, TransposeArgs{}, false)) != SLIDE_OK) return rc;
   if (ctx->lo.D > 0)   // the feature segments are only consumed by training: clear them again
     HIPCHK(ctx, launch_fill_u32(ctx->at<uint32_t>(ctx->lo.xse), (size_t)b->batch * ctx->lo.NT1 * 2, 0u, s));
   HIPCHK(ctx, launch_topk(ad, ctx->at<float>(ctx->lo.z), topk, d_out_ids, d_out_scores, s));

@@ -13,7 +13,10 @@ namespace slide {
 // The hidden layer as a launch of its own (prediction over all neurons; the training step runs it
 // inside the lookup workgroups).
 __global__ __launch_bounds__(64) void spmm_relu_kernel(SpmmArgs a, Ctrl* ctrl) {
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0; }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    ctrl->p1 = 0; ctrl->nlong1 = 0; ctrl->max_nu1 = 0;
+    for (int r = 0; r < kPairRegions; ++r) ctrl->p1r[r] = 0;
+  }
   spmm_sample(a, blockIdx.x, gridDim.x, blockIdx.y, threadIdx.x, nullptr, ctrl);
 }
 
@@ -35,9 +38,6 @@ hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s)
 // workers are bandwidth-bound.
 // ---------------------------------------------------------------------------------------------
 constexpr int kForwardThreads = 512;
-constexpr int kForwardBlocks = 768;    // logit workers
-constexpr int kForwardBlocksLong = 640;   // ... of which this many stay when each has several items
-constexpr int kForwardBlocksLongTiles = 512;   // ... or this many, when the tiles are many as well
 
 template <int LPR, int CH, bool FULL>
 __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const float* __restrict__ h, const float* __restrict__ W2,
@@ -141,38 +141,39 @@ __global__ __launch_bounds__(kForwardThreads) void forward_kernel(ActiveDev ad, 
                                                                   const float* __restrict__ b2, float* __restrict__ z,
                                                                   float* __restrict__ partials,
                                                                   const Ctrl* __restrict__ ctrl, TransposeArgs t1,
-                                                                  TransposeArgs t2) {
+                                                                  TransposeArgs t2, int nworkers) {
   extern __shared__ uint32_t dyn_lds[];
   // Workgroups start in index order and the machine holds a few hundred at a time.  The logit
   // workers go first (they are what the memory system is busy with); the tiles fill in behind them
   // as workers without an item leave, the feature tiles (fewer, and with a global counter on their
   // critical path) before the active-set tiles.
   const int k = blockIdx.x;
-  if (k < kForwardBlocks) {
+  if (k < nworkers) {
     // With several items per wave the workers would hold every slot of the machine until the end and
     // the tiles would run after them: then the last workers leave at once and make room.
     const int items = (int)ctrl->max_nch[ad.par] * ad.B;   // (upper bound: samples differ in length)
     // (more of them when the tiles are many for the amount of logit work)
     const int ntiles = t1.ntiles + t2.ntiles;
-    const int workers = items <= 2 * kForwardBlocks * (kForwardThreads / 64) ? kForwardBlocks
-                        : (items < 20 * ntiles ? kForwardBlocksLongTiles : kForwardBlocksLong);
+    const int workers = (ntiles == 0 || items <= 2 * nworkers * (kForwardThreads / 64)) ? nworkers
+                        : (items < 20 * ntiles ? nworkers * 2 / 3 : nworkers * 5 / 6);
     if (k >= workers) return;
     if (H == LPR * CH * 4) forward_items<LPR, CH, true>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
     else forward_items<LPR, CH, false>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
   }
-  else if (k < kForwardBlocks + t1.ntiles) transpose_tile<true>(t1, k - kForwardBlocks, dyn_lds);
-  else transpose_tile<false>(t2, k - kForwardBlocks - t1.ntiles, dyn_lds);
+  else if (k < nworkers + t1.ntiles) transpose_tile<true>(t1, k - nworkers, dyn_lds);
+  else transpose_tile<false>(t2, k - nworkers - t1.ntiles, dyn_lds);
 }
 
 template <int LPR, int CH>
 static hipError_t launch_fwd(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
                              float* partials, const Ctrl* ctrl, const TransposeArgs& t1, const TransposeArgs& t2,
-                             hipStream_t s) {
+                             int nworkers, hipStream_t s) {
   size_t lds = 0;
   if (t1.ntiles) lds = transpose_lds(t1.TW, t1.Bpad);
   if (t2.ntiles) lds = std::max(lds, transpose_lds(t2.TW, t2.Bpad));
-  hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(t2.ntiles + t1.ntiles + kForwardBlocks), dim3(kForwardThreads),
-                     lds, s, ad, H, h, W2, b2, z, partials, ctrl, t1, t2);
+  if (t2.ntiles + t1.ntiles + nworkers == 0) return hipSuccess;
+  hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(t2.ntiles + t1.ntiles + nworkers), dim3(kForwardThreads),
+                     lds, s, ad, H, h, W2, b2, z, partials, ctrl, t1, t2, nworkers);
   return hipGetLastError();
 }
 
@@ -195,8 +196,10 @@ hipError_t forward_setup_attributes(size_t lds_limit) {
 
 hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
                           float* partials, const Ctrl* ctrl, const TransposeArgs& t1, const TransposeArgs& t2,
-                          hipStream_t s) {
-#define SLIDE_FWD(L_, C_) return launch_fwd<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, t1, t2, s)
+                          bool logits, int num_cus, hipStream_t s) {
+  // three logit workgroups of 16 waves per compute unit (768 on the 256 of an MI355X)
+  const int nworkers = logits ? 3 * num_cus : 0;
+#define SLIDE_FWD(L_, C_) return launch_fwd<L_, C_>(ad, H, h, W2, b2, z, partials, ctrl, t1, t2, nworkers, s)
   if (H <= 32) SLIDE_FWD(8, 1);
   if (H <= 64) SLIDE_FWD(8, 2);
   if (H <= 128) SLIDE_FWD(8, 4);

@@ -12,6 +12,7 @@ constexpr int kChunk = 64;         // active pairs per forward work item
 constexpr int kSmallBucket = 8;    // buckets up to this size are sorted by one thread
 constexpr int kSortCap = 2048;     // keys held in LDS by the big-bucket sorter
 constexpr int kLongRow = 32;       // rows touched by more samples than this are reduced by a whole wave
+constexpr int kPairRegions = 32;   // the input layer's pair space is handed out from this many counters (tile % regions)
 
 // Device-side counters, one block at the start of the workspace.
 struct Ctrl {
@@ -26,6 +27,10 @@ struct Ctrl {
   uint32_t nlong2, nlong1; // long rows queued by the two transpositions
   uint32_t max_nu2, max_nu1; // most touched rows in any tile
   uint32_t pad[1];
+  // Pair space of the input layer's row lists: region r (tiles with tile % kPairRegions == r) is handed
+  // out from p1r[r].  (Updates of one word from every workgroup of a launch queue up behind each other
+  // for tens of nanoseconds apiece, so per-launch counters that many workgroups bump are spread out.)
+  uint32_t p1r[kPairRegions];
   // forward work items (chunks of kChunk active neurons): room for their partial results is handed out
   // by the lookup workgroups; a call uses counter (call number & 1) and clears the other
   uint32_t chunk_alloc[2];
@@ -111,7 +116,8 @@ struct PairsDev {
   int32_t* tile_nu; // [ntiles] touched rows in the tile
   int4* umeta;      // [slots] (row id, first pair, pairs, 0)
   int2* pairs;      // [pairs] (sample, index into the coefficient array)
-  uint32_t* pcount; // pair space counter (input layer only)
+  uint32_t* pcount; // pair space counters, kPairRegions of them (input layer only)
+  uint32_t region_pairs; // pair slots per region
   int32_t* longlist; // [long_cap] slots of rows with more than kLongRow pairs
   uint32_t* nlong;
   int long_cap;
@@ -152,11 +158,11 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const flo
 
 // ---- output.hip -----------------------------------------------------------------------
 hipError_t launch_spmm_relu(int B, const SpmmArgs& a, Ctrl* ctrl, hipStream_t s);
-// Logits over the active sets; the same launch builds the two sets of row lists (t1: features, t2:
-// active sets; ntiles = 0 leaves one out).
+// Logits over the active sets (logits = true: three worker workgroups per compute unit); the same
+// launch builds the two sets of row lists (t1: features, t2: active sets; ntiles = 0 leaves one out).
 hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const float* W2, const float* b2, float* z,
                           float* partials, const Ctrl* ctrl, const TransposeArgs& t1, const TransposeArgs& t2,
-                          hipStream_t s);
+                          bool logits, int num_cus, hipStream_t s);
 hipError_t forward_setup_attributes(size_t lds_limit);
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
@@ -202,6 +208,12 @@ struct FinishArgs {
 // the rows of W2 (+ b2).
 hipError_t launch_update(int H, const RowUpdate& out, const RowUpdate& in, const FinishArgs& fin, const AdamDev& ad,
                          hipStream_t s);
+// The same launch for batches whose samples share most rows: sample vectors staged in LDS by column
+// slices (see update.hip).  update_sliced_applies: whether a batch of B vectors of length H fits.
+bool update_sliced_applies(int B, int H, size_t lds_limit);
+hipError_t update_setup_attributes(size_t lds_limit);
+hipError_t launch_update_sliced(int H, int B, const RowUpdate& out, const RowUpdate& in, const FinishArgs& fin,
+                                const AdamDev& ad, size_t lds_limit, int num_cus, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 

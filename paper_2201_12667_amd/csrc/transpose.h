@@ -26,6 +26,8 @@ namespace slide {
 // the segments again; a pair's place in the row's list is the number of lower samples in the row's
 // LDS mask, so every pair is written straight to its final position: ascending samples per row,
 // no sort, no global atomics on the data.
+constexpr int kInFlight = 4;    // ids a thread requests before it uses the first
+
 template <bool FEAT, int TW>
 __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int tileno, uint32_t* lds) {
   constexpr int ROWS = TW * 32;
@@ -38,16 +40,96 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
   uint32_t* wu = rowoff + ROWS;                          // [TW] touched rows of each 32-row word (bit mask)
   uint32_t* wnp = wu + TW;                               // [TW] pairs of the word, then pairs before it
   uint32_t* wou = wnp + TW;                              // [TW] rows before the word
-  uint32_t* blk = wou + TW;                              // [2] pair base of the tile, sum of ranks
-  uint16_t* rowcnt = (uint16_t*)(blk + 2);               // [ROWS] pairs of the row
+  uint32_t* blk = wou + TW;                              // [4] pair base of the tile, sum of ranks, long rows, their queue base
+  uint32_t* lq = blk + 4;                                // [ROWS] slots of the tile's long rows (queued together at the end)
+  uint16_t* rowcnt = (uint16_t*)(lq + ROWS);             // [ROWS] pairs of the row
   uint16_t* rowgrp = rowcnt + ROWS;                      // [groups][ROWS] pairs of the row in lower sample groups
   const int tid = threadIdx.x, lane = tid & 63, b31 = tid & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t below = (1u << b31) - 1u;
   const int row0 = tileno * ROWS;
 
+  if (FEAT) {
+    // Most tiles of a wide input layer hold few features of the batch, or none: one look at the
+    // segments settles it.  None: nothing to do.  At most 64: one wave sorts the (row, sample) keys in
+    // its lanes and writes the tile's lists, without the transposed bit tile.
+    if (tid == 0) { blk[1] = 0; blk[2] = 0; }
+    __syncthreads();
+    uint32_t mine = 0;
+    for (int i = tid; i < B; i += blockDim.x) {
+      const int2 v = ta.xse[(size_t)tileno * B + i];
+      const int lo = max(v.x, 0), hi = min(v.y, ta.x_nnz);
+      mine += hi > lo ? (uint32_t)(hi - lo) : 0u;
+    }
+    mine = wave_sum(mine);
+    if (lane == 0 && mine) atomicAdd(&blk[1], mine);
+    __syncthreads();
+    const uint32_t total = blk[1];
+    if (total <= 64u) {
+      uint32_t* skey = T;                                // [64] row in tile << 16 | sample
+      uint32_t* spos = T + 64;                           // [64] position in the batch's feature arrays
+      if (total) {
+        for (int i = tid; i < B; i += blockDim.x) {
+          const int2 v = ta.xse[(size_t)tileno * B + i];
+          const int lo = max(v.x, 0), hi = min(v.y, ta.x_nnz);
+          for (int p = lo; p < hi; ++p) {
+            const int r = ids[p] - row0;
+            if ((unsigned)r < (unsigned)ROWS) {
+              const uint32_t at = atomicAdd(&blk[2], 1u);
+              if (at < 64u) { skey[at] = ((uint32_t)r << 16) | (uint32_t)i; spos[at] = (uint32_t)p; }
+            }
+          }
+        }
+      }
+      __syncthreads();
+      const uint32_t n = min(blk[2], 64u);
+      if (wave == 0) {
+        uint32_t key = (uint32_t)lane < n ? skey[lane] : 0xffffffffu;
+        uint32_t pos = (uint32_t)lane < n ? spos[lane] : 0u;
+#pragma unroll
+        for (int k = 2; k <= 64; k <<= 1)                 // bitonic sort across the lanes, ascending keys
+#pragma unroll
+          for (int j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t okey = __shfl_xor(key, j), opos = __shfl_xor(pos, j);
+            const bool up = (lane & k) == 0, lower = (lane & j) == 0;
+            const bool take = (lower == up) ? okey < key : okey > key;
+            if (take) { key = okey; pos = opos; }
+          }
+        const uint32_t prev = __shfl_up(key, 1);
+        const bool head = (uint32_t)lane < n && (lane == 0 || (prev >> 16) != (key >> 16));
+        const unsigned long long heads = __ballot(head);
+        const uint32_t nu = (uint32_t)__popcll(heads);
+        uint32_t base = 0;
+        if (lane == 0) {
+          pd.tile_nu[tileno] = (int32_t)nu;
+          base = n ? (uint32_t)(tileno % kPairRegions) * pd.region_pairs + atomicAdd(&pd.pcount[tileno % kPairRegions], n) : 0u;
+          if (nu > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, nu);
+        }
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        if ((uint32_t)lane < n) pd.pairs[base + lane] = make_int2((int)(key & 0xffffu), (int)pos);
+        if (head) {
+          const unsigned long long above = lane < 63 ? heads >> (lane + 1) : 0ull;
+          const uint32_t c = above ? (uint32_t)__ffsll((long long)above) : n - (uint32_t)lane;
+          const uint32_t us = (uint32_t)tileno * (uint32_t)ROWS + (uint32_t)__popcll(heads & ((1ull << lane) - 1ull));
+          pd.umeta[us] = make_int4(row0 + (int)(key >> 16), (int)(base + lane), (int)c, 0);
+          if (ta.touched) ta.touched[row0 + (int)(key >> 16)] = 1;
+          if ((int)c > kLongRow) {
+            const uint32_t l = atomicAdd(pd.nlong, 1u);
+            if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
+          }
+        }
+      }
+      for (int i = tid; i < B; i += blockDim.x) {        // leave the segments all-zero for the next batch
+        int2* se = ta.xse + (size_t)tileno * B + i;
+        const int2 v = *se;
+        if (v.x | v.y) *se = make_int2(0, 0);
+      }
+      return;
+    }
+    __syncthreads();                                     // (blk is set up again below)
+  }
   for (int q = tid; q < GW * ROWS; q += blockDim.x) T[q] = 0;
-  if (tid == 0) blk[1] = 0;
+  if (tid == 0) { blk[1] = 0; blk[2] = 0; }
   __syncthreads();
 
   // segment of sample i inside this tile; rank0 = the sample's rank at the tile start (active sets)
@@ -74,12 +156,12 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
     if (share) rank0 = 0;
     uint32_t* tc = T + (size_t)(i >> 5) * ROWS;
     const uint32_t ibit = 1u << (i & 31);
-    for (int p = lo + 4 * share; p < hi; p += 4 * shares) {   // four ids in flight
-      int r[4];
+    for (int p = lo + kInFlight * share; p < hi; p += kInFlight * shares) {   // kInFlight ids in flight
+      int r[kInFlight];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
+      for (int k = 0; k < kInFlight; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int k = 0; k < kInFlight; ++k)
         if ((unsigned)r[k] < (unsigned)ROWS) atomicOr(&tc[r[k]], ibit);
     }
     if (!FEAT) {
@@ -120,7 +202,8 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
     if (lane == 63) {
       nu_tile = cin;
       pd.tile_nu[tileno] = (int32_t)cin;
-      blk[0] = FEAT ? (pin ? atomicAdd(pd.pcount, pin) : 0u) : blk[1];
+      blk[0] = FEAT ? (pin ? (uint32_t)(tileno % kPairRegions) * pd.region_pairs + atomicAdd(&pd.pcount[tileno % kPairRegions], pin) : 0u)
+                    : blk[1];
     }
   }
   __syncthreads();
@@ -135,10 +218,7 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
       const uint32_t us = slot0 + wou[w] + __popc(wu[w] & below);
       pd.umeta[us] = make_int4(row0 + r, (int)(blk0 + wnp[w] + rowoff[r]), (int)c, 0);
       if (ta.touched) ta.touched[row0 + r] = 1;
-      if ((int)c > kLongRow) {
-        const uint32_t l = atomicAdd(pd.nlong, 1u);
-        if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
-      }
+      if ((int)c > kLongRow) lq[atomicAdd(&blk[2], 1u)] = us;   // (one update of the global queue per tile, below)
     }
   }
 
@@ -154,12 +234,12 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
     const uint32_t* t_lo = T + (size_t)(2 * g) * ROWS;
     const uint32_t* t_hi = t_lo + ROWS;
     const uint16_t* grp = rowgrp + (size_t)g * ROWS;
-    for (int p = lo + 4 * share; p < hi; p += 4 * shares) {
-      int r[4];
+    for (int p = lo + kInFlight * share; p < hi; p += kInFlight * shares) {
+      int r[kInFlight];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
+      for (int k = 0; k < kInFlight; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < kInFlight; ++k) {
         if ((unsigned)r[k] >= (unsigned)ROWS) continue;
         const int row = r[k];
         const uint32_t place = blk0 + wnp[row >> 5] + rowoff[row] + grp[row] + __popc(t_lo[row] & lo_mask) +
@@ -168,8 +248,18 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
       }
     }
   }
+  __syncthreads();
+  {                                                      // the tile's long rows join the queue as one stretch
+    const uint32_t nl = blk[2];
+    if (nl) {
+      if (tid == 0) blk[3] = atomicAdd(pd.nlong, nl);
+      __syncthreads();
+      const uint32_t base = blk[3];
+      for (uint32_t q = tid; q < nl; q += blockDim.x)
+        if (base + q < (uint32_t)pd.long_cap) pd.longlist[base + q] = (int32_t)lq[q];
+    }
+  }
   if (FEAT) {                                            // leave the segments all-zero for the next batch
-    __syncthreads();
     for (int i = tid; i < B; i += blockDim.x) {
       int2* se = ta.xse + (size_t)tileno * B + i;
       const int2 v = *se;
@@ -194,7 +284,7 @@ __device__ __forceinline__ void transpose_tile(const TransposeArgs& ta, int tile
 
 inline size_t transpose_lds(int TW, int Bpad) {
   const size_t rows = (size_t)TW * 32, GW = (size_t)Bpad >> 5, groups = (size_t)Bpad >> 6;
-  return (rows * GW + rows + (size_t)TW * 3 + 2) * 4 + rows * 2 + groups * rows * 2;
+  return (rows * GW + rows + (size_t)TW * 3 + 4 + rows) * 4 + rows * 2 + groups * rows * 2;
 }
 
 }  // namespace slide

@@ -8,16 +8,25 @@
 // and no atomics.  V is the hidden activations (output layer) or their gradient (input layer),
 // small enough to stay cache resident.  Rows that are not listed are never touched.
 #include "slide_internal.h"
+#include "wave_ops.h"
+
+#include <algorithm>
 
 namespace slide {
 
 constexpr int kUpdateThreads = 256;
 constexpr int kUpdateBlocksOut = 2048;
 
+// One element of the Adam update.  The square root and the reciprocal are the hardware's one-ulp
+// instructions rather than the correctly rounded library sequences (about 25 instructions per element
+// otherwise, which the row kernels feel once the rows come from cache): the step
+// lr * mhat / (sqrt(vhat) + eps) is off by a few units in its last place, i.e. by about 1e-7 of a
+// quantity that is itself at most lr.  (A denormal vhat may be taken as zero by the square root; eps
+// dominates the denominator long before that.)
 __device__ __forceinline__ void adam1(float& w, float& m, float& v, float g, const AdamDev& a) {
   m = a.beta1 * m + a.omb1 * g;
   v = a.beta2 * v + a.omb2 * g * g;
-  w = w - a.lr * (m * a.inv_bc1) / (sqrtf(v * a.inv_bc2) + a.eps);
+  w = w - (a.lr * (m * a.inv_bc1)) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v * a.inv_bc2) + a.eps);
 }
 
 // Gradient of one row from its pair list, pairs first, first + stride, ... (this lane group's share).
@@ -262,14 +271,17 @@ __device__ void finish_role(int H, const FinishArgs& f, const AdamDev& ad, int b
   __shared__ float red[256];
   __shared__ unsigned long long ured[4][256];
   const int tid = threadIdx.x;
+  const bool act = tid < 256;             // (workgroups may be larger: the first 256 threads do the work)
   if (block == 0) {
     float acc = 0.f;
-    for (int i = tid; i < B; i += 256) acc += loss_i[i];
     unsigned long long u2 = 0, u1 = 0, pairs = 0, cand = 0;
-    for (int t = tid; t < ntiles2; t += 256) u2 += (unsigned long long)tile_nu2[t];
-    for (int t = tid; t < ntiles1; t += 256) u1 += (unsigned long long)tile_nu1[t];
-    for (int i = tid; i < B; i += 256) { pairs += (unsigned long long)f.cnt[i]; cand += (unsigned long long)f.ncand[i]; }
-    red[tid] = acc; ured[0][tid] = u2; ured[1][tid] = u1; ured[2][tid] = pairs; ured[3][tid] = cand;
+    if (act) {
+      for (int i = tid; i < B; i += 256) acc += loss_i[i];
+      for (int t = tid; t < ntiles2; t += 256) u2 += (unsigned long long)tile_nu2[t];
+      for (int t = tid; t < ntiles1; t += 256) u1 += (unsigned long long)tile_nu1[t];
+      for (int i = tid; i < B; i += 256) { pairs += (unsigned long long)f.cnt[i]; cand += (unsigned long long)f.ncand[i]; }
+      red[tid] = acc; ured[0][tid] = u2; ured[1][tid] = u1; ured[2][tid] = pairs; ured[3][tid] = cand;
+    }
     __syncthreads();
     for (int d = 128; d > 0; d >>= 1) {
       if (tid < d) {
@@ -296,9 +308,9 @@ __device__ void finish_role(int H, const FinishArgs& f, const AdamDev& ad, int b
   const int col = tid & 31, part = tid >> 5;
   const int u = block * 32 + col;
   float g = 0.f;
-  if (u < H)
+  if (act && u < H)
     for (int i = part; i < B; i += 8) g += dh[(size_t)i * H + u];
-  red[tid] = g;
+  if (act) red[tid] = g;
   __syncthreads();
   if (part == 0 && u < H) {
     float s = red[col];
@@ -330,6 +342,277 @@ static hipError_t launch_up(int H, const RowUpdate& out, const RowUpdate& in, co
                             const AdamDev& ad, hipStream_t s) {
   hipLaunchKernelGGL((update_kernel<LPR, CH, UNR>), dim3(fin.nblocks + out.nblocks), dim3(kUpdateThreads), 0, s, H,
                      out, in, fin, ad);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same update for batches whose samples share most rows (saturated buckets: a touched row is
+// listed by many samples, and the list lengths have a heavy tail).  Then a pair -- one (row, sample)
+// incidence -- costs one read of the sample's vector, and reading it from the cache hierarchy is
+// what bounds the plain kernel; and lane groups that each walk their own list spend most steps waiting
+// for the longest of them.  Here a workgroup first copies a slice of CW columns of all B sample vectors
+// into LDS (B*CW floats) and then walks the row lists for that slice only, a WAVE per row: lane l owns
+// columns l*CPL .. of the slice, the list entries and coefficients are fetched 64 at a time (a lane
+// each) and handed round as wave-uniform values, so a pair costs one LDS read and no step is shared
+// with another row.  The slices of a row are independent (gradient, moments and weights are per
+// column), so H/CW workgroups update a row together, each its own columns; the one with the first
+// columns also takes the bias.  Sums run over ascending samples as in the plain kernel.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSlicedThreads = 1024;
+constexpr int kSlicedPad = 4;            // floats between the LDS rows of two samples (spreads them over the banks)
+constexpr size_t kSlicedStatic = 10240;  // LDS the launch's other role (finish_role) declares statically
+
+// Sum of a float over the wave in a fixed order (butterfly), returned in every lane.
+__device__ __forceinline__ float wave_sum_f32(float v) {
+  v += dpp_f32<kDppQuadSwap1>(v);
+  v += dpp_f32<kDppQuadSwap2>(v);
+  v += dpp_f32<kDppRowHalfMirror>(v);
+  v += dpp_f32<kDppRowMirror>(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+
+template <int CPL> struct LaneCols { typedef float type; };
+template <> struct LaneCols<2> { typedef float2 type; };
+
+template <int CPL>
+__device__ __forceinline__ void fma_cols(typename LaneCols<CPL>::type& g, float d, const typename LaneCols<CPL>::type& x) {
+  if constexpr (CPL == 2) { g.x += d * x.x; g.y += d * x.y; } else { g += d * x; }
+}
+
+// The rows of one matrix, columns [c0, c0 + 64*CPL): share `part` of `nparts` of the rows.
+// The workgroup fills its compute unit alone (the LDS slice), so nothing but the wave itself can hide
+// the chain header -> list entries -> coefficients: the headers are fetched three rows ahead, the
+// first 64 list entries two ahead, their coefficients one ahead.
+template <int CPL>
+__device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const AdamDev& ad, const float* ldsV,
+                                    const uint32_t* tpre, int part, int nparts) {
+  typedef typename LaneCols<CPL>::type cols_t;
+  constexpr int PITCH = 64 * CPL + kSlicedPad;
+  const PairsDev& pd = ru.pd;
+  const float* __restrict__ coef = ru.coef;
+  const int lane = threadIdx.x & 63;
+  constexpr int WPB = kSlicedThreads / 64;
+  const int wave_global = __builtin_amdgcn_readfirstlane(part * WPB + (threadIdx.x >> 6)), nwaves = nparts * WPB;
+  const int col = c0 + lane * CPL;
+  const bool col_ok = col < H;                             // (H is a multiple of 4, so a lane's columns go together)
+  const bool bias_lane_any = c0 == 0 && ru.bias != nullptr;   // (uniform) this workgroup also updates the biases
+  const bool bias_lane = bias_lane_any && lane == 0;
+  const float* lds_mine = ldsV + lane * CPL;
+  // The touched rows sit in per-tile slot ranges (tile t: slots t*rows_per_tile .. + tile_nu[t]).  With
+  // the running sum of tile_nu in LDS (tpre, when the tiles are few enough) a wave takes a contiguous
+  // stretch of the touched rows and finds their slots by stepping through the sums; otherwise it visits
+  // the slots r * ntiles + t (the tiles' r-th rows side by side) and skips the empty ones.
+  const bool dense = tpre != nullptr;
+  int count, lo = 0, tc = 0;
+  if (dense) {
+    const uint32_t U = tpre[pd.ntiles];
+    lo = (int)((uint64_t)U * (uint32_t)wave_global / (uint32_t)nwaves);
+    count = (int)((uint64_t)U * (uint32_t)(wave_global + 1) / (uint32_t)nwaves) - lo;
+    int a = 0, b = pd.ntiles;                              // last tile whose sum is <= lo
+    while (b - a > 1) { const int mid = (a + b) >> 1; if (tpre[mid] <= (uint32_t)lo) a = mid; else b = mid; }
+    tc = a;
+  } else {
+    const int nrows = pd.ntiles * (int)*pd.max_nu;
+    count = wave_global < nrows ? (nrows - wave_global + nwaves - 1) / nwaves : 0;
+  }
+  // header of the k-th row of this wave: (row, first list entry, entries, -); entries = 0: none.
+  // (Called with ascending k, so the tile cursor only moves forward.)
+  auto header = [&](int k) -> int4 {
+    if (k >= count) return make_int4(0, 0, 0, 0);
+    int slot;
+    if (dense) {
+      const uint32_t g = (uint32_t)(lo + k);
+      while (g >= tpre[tc + 1]) ++tc;
+      slot = tc * pd.rows_per_tile + (int)(g - tpre[tc]);
+    } else {
+      const int idx = wave_global + k * nwaves;
+      const int r = idx / pd.ntiles, t = idx - r * pd.ntiles;
+      if (r >= pd.tile_nu[t]) return make_int4(0, 0, 0, 0);
+      slot = t * pd.rows_per_tile + r;
+    }
+    return pd.umeta[slot];                                 // (not looked at before its turn comes: see below)
+  };
+  auto entry = [&](const int4& m, int q0) -> int2 {        // this lane's entry of the batch that starts at q0
+    const int q = q0 + lane;
+    return pd.pairs[(uint32_t)m.y + (q < m.z ? q : 0)];
+  };
+  auto coefficient = [&](const int4& m, int q0, int2& e) -> float {   // its coefficient; lanes past the end: sample 0, 0
+    const bool ok = q0 + lane < m.z;
+    const float dv = coef[ok ? e.y : 0];
+    if (!ok) e.x = 0;
+    return ok ? dv : 0.f;
+  };
+  // Software pipeline over the wave's rows.  Vector loads and stores share one in-order counter on this
+  // target, and once both kinds are outstanding a wait for any load waits for everything, so the loop
+  // has one point per row where it waits (its top) and everything outstanding there was issued a whole
+  // row of LDS arithmetic earlier: row k's header was requested during row k-3, its first 64 list
+  // entries during k-2, their coefficients and the row's old w, m, v during k-1; row k's results are
+  // stored during k+1.
+  auto scalar = [](const int4& m) {
+    return make_int4(__builtin_amdgcn_readfirstlane(m.x), __builtin_amdgcn_readfirstlane(m.y),
+                     __builtin_amdgcn_readfirstlane(m.z), 0);
+  };
+  auto row_offset = [&](const int4& m) -> size_t { return (size_t)m.x * H + col; };
+  int4 m0 = header(0), m1 = header(1), m2 = header(2);
+  int2 e0 = entry(m0, 0), e1 = entry(m1, 0);
+  float d0 = coefficient(m0, 0, e0);
+  cols_t w0, mo0, v0;                                      // old values of row k (requested during row k-1)
+  float b0w = 0.f, b0m = 0.f, b0v = 0.f;
+  if (col_ok && m0.z > 0) { const size_t ro = row_offset(m0); w0 = *(const cols_t*)(ru.W + ro); mo0 = *(const cols_t*)(ru.M + ro); v0 = *(const cols_t*)(ru.Vv + ro); }
+  if (bias_lane && m0.z > 0) { b0w = ru.bias[m0.x]; b0m = ru.mbias[m0.x]; b0v = ru.vbias[m0.x]; }
+  cols_t ws, ms, vs;                                       // results of the previous row, not stored yet
+  float bsw = 0.f, bsm = 0.f, bsv = 0.f;
+  size_t ro_s = 0;
+  int j_s = -1;                                            // row they belong to (-1: nothing pending)
+  for (int k = 0; k < count; ++k) {
+    const int4 cur = scalar(m0);                           // ---- the one waiting point of this row
+    const int2 ecur = e0;
+    const float dcur = d0;
+    const cols_t wc = w0, mc = mo0, vc = v0;
+    const float bcw = b0w, bcm = b0m, bcv = b0v;
+    // ---- requests for the rows to come, and the previous row's stores
+    const int4 m3 = header(k + 3);
+    int2 e2 = entry(m2, 0);
+    float d1 = coefficient(m1, 0, e1);
+    if (col_ok && m1.z > 0) { const size_t ro = row_offset(m1); w0 = *(const cols_t*)(ru.W + ro); mo0 = *(const cols_t*)(ru.M + ro); v0 = *(const cols_t*)(ru.Vv + ro); }
+    if (bias_lane && m1.z > 0) { b0w = ru.bias[m1.x]; b0m = ru.mbias[m1.x]; b0v = ru.vbias[m1.x]; }
+    if (j_s >= 0) {
+      if (col_ok) { *(cols_t*)(ru.W + ro_s) = ws; *(cols_t*)(ru.M + ro_s) = ms; *(cols_t*)(ru.Vv + ro_s) = vs; }
+      if (bias_lane) { ru.bias[j_s] = bsw; ru.mbias[j_s] = bsm; ru.vbias[j_s] = bsv; }
+      j_s = -1;
+    }
+    // ---- this row: gradient from LDS, Adam in registers
+    const int cn = cur.z;
+    if (cn > 0) {
+      cols_t g;
+      if constexpr (CPL == 2) g = make_float2(0.f, 0.f); else g = 0.f;
+      float gb = 0.f;
+      int2 e = ecur;
+      float d = dcur;
+      for (int q0 = 0; q0 < cn; q0 += 64) {
+        int2 en = e;
+        const bool more = q0 + 64 < cn;                    // (uniform; rows this long wait in place)
+        if (more) en = entry(cur, q0 + 64);
+        const int n = min(64, cn - q0);
+        for (int a0 = 0; a0 < n; a0 += 8) {                // lanes past the end hold (sample 0, 0.0)
+          cols_t x[8];
+          float dd[8];
+#pragma unroll
+          for (int a = 0; a < 8; ++a) {
+            const int si = __builtin_amdgcn_readlane(e.x, a0 + a);
+            dd[a] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d), a0 + a));
+            x[a] = *(const cols_t*)(lds_mine + (size_t)si * PITCH);
+          }
+#pragma unroll
+          for (int a = 0; a < 8; ++a) fma_cols<CPL>(g, dd[a], x[a]);
+        }
+        if (bias_lane_any) gb += wave_sum_f32(d);          // (lanes past the end hold 0; fixed order)
+        if (more) { e = en; d = coefficient(cur, q0 + 64, e); }
+      }
+      ws = wc; ms = mc; vs = vc;
+      if constexpr (CPL == 2) { adam1(ws.x, ms.x, vs.x, g.x, ad); adam1(ws.y, ms.y, vs.y, g.y, ad); }
+      else adam1(ws, ms, vs, g, ad);
+      bsw = bcw; bsm = bcm; bsv = bcv;
+      adam1(bsw, bsm, bsv, gb, ad);
+      ro_s = (size_t)cur.x * H + col;
+      j_s = cur.x;
+    }
+    m0 = m1; m1 = m2; m2 = m3;
+    e0 = e1; e1 = e2; d0 = d1;
+  }
+  if (j_s >= 0) {
+    if (col_ok) { *(cols_t*)(ru.W + ro_s) = ws; *(cols_t*)(ru.M + ro_s) = ms; *(cols_t*)(ru.Vv + ro_s) = vs; }
+    if (bias_lane) { ru.bias[j_s] = bsw; ru.mbias[j_s] = bsm; ru.vbias[j_s] = bsv; }
+  }
+}
+
+template <int CPL>
+__global__ __launch_bounds__(kSlicedThreads) void update_sliced_kernel(int H, int B, RowUpdate out, RowUpdate in,
+                                                                       FinishArgs fin, AdamDev ad, int nslices,
+                                                                       int parts, int tile_words) {
+  extern __shared__ float ldsV[];                          // [B][64*CPL + kSlicedPad], then [tile_words] tile sums
+  constexpr int CW = 64 * CPL, PITCH = CW + kSlicedPad;
+  uint32_t* tsum = (uint32_t*)(ldsV + (size_t)B * PITCH);
+  __shared__ uint32_t wsum[kSlicedThreads / 64];
+  int blk = blockIdx.x;
+  if (blk < fin.nblocks) { finish_role(H, fin, ad, blk); return; }
+  blk -= fin.nblocks;
+  // neighbours in launch order take the slices of the same share of the rows: they read the same
+  // lists and coefficients at about the same time
+  const int slice = blk % nslices, part = blk / nslices;
+  const int c0 = slice * CW;
+  for (int which = 0; which < 2; ++which) {
+    const RowUpdate& ru = which == 0 ? in : out;
+    if (!ru.W) continue;
+    __syncthreads();                                       // the previous matrix's readers are done
+    for (int idx = threadIdx.x; idx < B * (CW / 4); idx += kSlicedThreads) {
+      const int i = idx / (CW / 4), q = idx - i * (CW / 4);
+      const int col = c0 + q * 4;
+      const float4 x = col < H ? *(const float4*)(ru.V + (size_t)i * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+      *(float4*)(ldsV + (size_t)i * PITCH + q * 4) = x;
+    }
+    // running sum of the touched rows per tile (tsum[t] = rows in tiles before t), when it fits
+    const int nt = ru.pd.ntiles;
+    const bool dense = nt + 1 <= tile_words;
+    if (dense) {
+      uint32_t carry = 0;
+      for (int base = 0; base < nt; base += kSlicedThreads) {   // (uniform trip count)
+        const int t = base + (int)threadIdx.x;
+        const uint32_t v = t < nt ? (uint32_t)ru.pd.tile_nu[t] : 0u;
+        const uint32_t inc = wave_incl_scan_add(v);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+        for (int w = 0; w < kSlicedThreads / 64; ++w) { const uint32_t x = wsum[w]; if (w < (int)(threadIdx.x >> 6)) before += x; total += x; }
+        if (t < nt) tsum[t] = carry + before + inc - v;
+        carry += total;
+      }
+      if (threadIdx.x == 0) tsum[nt] = carry;
+    }
+    __syncthreads();
+    rowgrad_adam_sliced<CPL>(H, c0, ru, ad, ldsV, dense ? tsum : nullptr, part, parts);
+  }
+}
+
+// Columns per slice for a batch of B vectors of length H (0: the sliced kernel does not apply).
+static int sliced_width(int B, int H, size_t lds_limit) {
+  for (int cw = 128; cw >= 64; cw >>= 1) {
+    if (cw > 64 && cw / 2 >= H) continue;                  // a narrower slice still covers the vector
+    if ((size_t)B * (cw + kSlicedPad) * 4 + kSlicedStatic <= lds_limit) return cw;
+  }
+  return 0;
+}
+
+bool update_sliced_applies(int B, int H, size_t lds_limit) { return sliced_width(B, H, lds_limit) != 0; }
+
+hipError_t update_setup_attributes(size_t lds_limit) {
+  if (lds_limit <= kSlicedStatic) return hipErrorInvalidValue;
+  const int dyn = (int)(lds_limit - kSlicedStatic);
+  hipError_t e = hipFuncSetAttribute((const void*)update_sliced_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)update_sliced_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+  return e;
+}
+
+hipError_t launch_update_sliced(int H, int B, const RowUpdate& out_, const RowUpdate& in_, const FinishArgs& fin_,
+                                const AdamDev& ad, size_t lds_limit, int num_cus, hipStream_t s) {
+  RowUpdate out = out_, in = in_;
+  FinishArgs fin = fin_;
+  fin.nblocks = fin.b1 ? ceil_div(H, 32) : 1;
+  const int cw = sliced_width(B, H, lds_limit);
+  if (!cw) return hipErrorInvalidValue;
+  const int nslices = ceil_div(H, cw);
+  // one workgroup per compute unit, the short-lived ones of the other role included
+  const int parts = (num_cus - fin.nblocks) / nslices > 0 ? (num_cus - fin.nblocks) / nslices : 1;
+  // what the slice leaves of the LDS holds the running sums of touched rows per tile (if the tiles fit)
+  const size_t slice_bytes = (size_t)B * (cw + kSlicedPad) * 4;
+  const int tile_words = (int)std::min<size_t>((lds_limit - kSlicedStatic - slice_bytes) / 4, 8192);
+  const size_t lds = slice_bytes + (size_t)tile_words * 4;
+  const dim3 grid(fin.nblocks + nslices * parts), block(kSlicedThreads);
+  if (cw == 128) hipLaunchKernelGGL((update_sliced_kernel<2>), grid, block, lds, s, H, B, out, in, fin, ad, nslices, parts, tile_words);
+  else hipLaunchKernelGGL((update_sliced_kernel<1>), grid, block, lds, s, H, B, out, in, fin, ad, nslices, parts, tile_words);
   return hipGetLastError();
 }
 

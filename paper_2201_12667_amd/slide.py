@@ -16,7 +16,8 @@ SLIDE_OK, SLIDE_EINVAL, SLIDE_ENOMEM, SLIDE_EHIP, SLIDE_ESTATE, SLIDE_EDATA = 0,
 HASH_SIMHASH, HASH_DWTA = 0, 1
 KEEP_LOWEST_ID, KEEP_PRIORITY = 0, 1
 FLAG_BAD_FEATURE, FLAG_UNSORTED, FLAG_BAD_LABEL = 1, 2, 4
-ABI_VERSION = 3
+ABI_VERSION = 4
+ROWS_AUTO, ROWS_NEVER, ROWS_ALWAYS = 0, 1, 2
 STATIC_MAX_BATCH = 64
 STAGES = ["hidden", "lookup", "forward", "combine", "update", "rebuild"]
 NUM_STAGES = len(STAGES)
@@ -37,7 +38,7 @@ class slide_config(C.Structure):
                 ("rebuild_every", C.c_int32),
                 ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
                 ("sample_budget", C.c_int32), ("sample_fill", C.c_int32), ("sample_seed", C.c_uint32),
-                ("incremental_rebuild", C.c_int32)]
+                ("incremental_rebuild", C.c_int32), ("row_major_mode", C.c_int32)]
 
 
 class slide_mem_req(C.Structure):
@@ -123,7 +124,7 @@ class SlideError(RuntimeError):
 def make_config(*, input_dim, hidden_dim, num_classes, max_batch, max_nnz_per_batch, max_labels_per_batch,
                 hash_kind, K, L, bucket_cap, rebuild_every, lr, beta1=0.9, beta2=0.999, eps=1e-8, dwta_bin=8,
                 srp_nnz=0, overflow_policy=KEEP_PRIORITY, sample_budget=0, sample_fill=False,
-                sample_seed=1, incremental_rebuild=False) -> slide_config:
+                sample_seed=1, incremental_rebuild=False, row_major_mode=ROWS_AUTO) -> slide_config:
     c = slide_config()
     c.struct_size, c.abi_version = C.sizeof(slide_config), ABI_VERSION
     c.input_dim, c.num_classes, c.hidden_dim, c.max_batch = input_dim, num_classes, hidden_dim, max_batch
@@ -133,6 +134,7 @@ def make_config(*, input_dim, hidden_dim, num_classes, max_batch, max_nnz_per_ba
     c.lr, c.beta1, c.beta2, c.eps = lr, beta1, beta2, eps
     c.sample_budget, c.sample_fill, c.sample_seed = sample_budget, int(bool(sample_fill)), sample_seed
     c.incremental_rebuild = int(bool(incremental_rebuild))
+    c.row_major_mode = int(row_major_mode)
     return c
 
 
@@ -350,4 +352,4 @@ def config_from_workload(wl, max_nnz_per_batch=None, max_labels_per_batch=None) 
                        srp_nnz=wl.srp_nnz if wl.hash_kind == HASH_SIMHASH else 0,
                        overflow_policy=wl.overflow_policy, sample_budget=wl.sample_budget,
                        sample_fill=wl.sample_fill, sample_seed=wl.sample_seed,
-                       incremental_rebuild=wl.incremental_rebuild)
+                       incremental_rebuild=wl.incremental_rebuild, row_major_mode=wl.row_major_mode)

@@ -52,6 +52,7 @@ class Workload:
     sample_fill: bool = False        # fill an unmet budget with uniformly drawn neurons
     sample_seed: int = 1
     incremental_rebuild: bool = False   # scheduled rebuilds rehash only the rows updated since the last build
+    row_major_mode: int = 0             # 0 = the library decides, 1 = sample-major kernels, 2 = row-major kernels
     # input recipe
     nnz_mode: str = "poisson"        # "exact" | "poisson"
     nnz_mean: float = 75.0

@@ -433,6 +433,38 @@ def test_sampling_budget_steps_match_oracle(name, wl):
     model.destroy()
 
 
+@pytest.mark.parametrize("name,wl", [
+    ("dwta-small", synth.small(synth.HASH_DWTA, row_major_mode=2)),
+    ("simhash-saturated", synth.small(synth.HASH_SIMHASH, K=3, L=9, bucket_cap=64, row_major_mode=2)),
+    ("dense-hidden", synth.small(synth.HASH_DWTA, input_dim=0, batch=70, num_classes=9973, row_major_mode=2)),
+    ("cfg0", __import__("dataclasses").replace(synth.config(0), row_major_mode=2)),
+    ("h32-b300", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=4, L=7, batch=300, num_classes=5003, input_dim=1900,
+                             nnz_mean=6.0, bucket_cap=32, row_major_mode=2)),
+    ("h200-b130", synth.small(synth.HASH_DWTA, hidden_dim=200, K=2, L=13, batch=130, num_classes=4099, input_dim=1200,
+                              bucket_cap=32, row_major_mode=2)),
+    ("h1024-b37", synth.small(synth.HASH_DWTA, hidden_dim=1024, K=2, L=6, num_classes=3001, input_dim=900,
+                              bucket_cap=64, row_major_mode=2)),
+    ("h64-b1100", synth.small(synth.HASH_SIMHASH, hidden_dim=64, K=3, L=5, batch=1100, num_classes=4001, input_dim=700,
+                              nnz_mean=5.0, bucket_cap=32, row_major_mode=2)),
+    ("h20-b2048-falls-back", synth.small(synth.HASH_SIMHASH, hidden_dim=20, K=3, L=4, batch=2048, num_classes=3001,
+                                         input_dim=0, bucket_cap=8, row_major_mode=2)),
+    ("single-sample", synth.small(synth.HASH_DWTA, batch=1, row_major_mode=2)),
+])
+def test_row_major_kernels_match_oracle(name, wl):
+    """The kernels for batches whose samples share most rows (rows streamed once, the batch's vectors
+    in LDS), forced on: three steps, each from the oracle's state, the third after a rebuild."""
+    _say("row-major", name)
+    gen, model, orc = make_pair(wl)
+    model.build_tables()
+    orc.build_tables()
+    for s in range(3):
+        load_state(model, orc)
+        res = compare_step(model, orc, gen.batch(s))
+        _say(s, {k: round(v, 3) for k, v in res.items() if not k.startswith("_")})
+        assert_ok(res)
+    model.destroy()
+
+
 def _random_workloads():
     rng = np.random.default_rng(2024)
     out = []
