@@ -17,8 +17,12 @@
  *     on that stream and returns without synchronising, unless stated otherwise.
  *   - Return value: SLIDE_OK (0) or a negative slide_error.  Errors found on the host are
  *     returned at once and leave device state untouched.  Errors found on the device (a feature
- *     index or label out of range, unsorted feature indices) never fault: the offending entry is
- *     ignored, a sticky flag is set, and slide_status reports it.
+ *     index or label out of range, unsorted feature indices) never fault, a sticky flag is set, and
+ *     slide_status reports it.  A label outside the layer is left out of its sample's label set
+ *     (the step is the one the batch without that entry would give).  A feature index outside the
+ *     input layer is left out of the forward pass; with that flag, or with unsorted / repeated feature
+ *     indices in a sample, the step's update of W1 and b1 is UNSPECIFIED (entries next to the
+ *     offending one may be missing from the gradient): treat the step as lost for the hidden layer.
  *   - Matrices are row-major fp32: W1 [input_dim][hidden_dim] (one row per input feature),
  *     W2 [num_classes][hidden_dim] (one row per output neuron).  Ids are int32.
  */
@@ -53,9 +57,11 @@ enum slide_overflow_policy { SLIDE_KEEP_LOWEST_ID = 0, SLIDE_KEEP_PRIORITY = 1 }
 enum slide_row_major_mode { SLIDE_ROWS_AUTO = 0, SLIDE_ROWS_NEVER = 1, SLIDE_ROWS_ALWAYS = 2 };
 
 /* Bits of the sticky device status word returned (negated into SLIDE_EDATA) by slide_status. */
-#define SLIDE_FLAG_BAD_FEATURE 1u   /* x_indices entry outside [0, input_dim): ignored           */
-#define SLIDE_FLAG_UNSORTED 2u      /* x_indices of a sample not strictly ascending               */
-#define SLIDE_FLAG_BAD_LABEL 4u     /* y_indices entry outside [0, num_classes): ignored          */
+#define SLIDE_FLAG_BAD_FEATURE 1u   /* x_indices entry outside [0, input_dim): left out of the forward pass; */
+                                    /* the step's W1 / b1 update is unspecified                              */
+#define SLIDE_FLAG_UNSORTED 2u      /* x_indices of a sample not strictly ascending: the step's W1 / b1      */
+                                    /* update is unspecified                                                 */
+#define SLIDE_FLAG_BAD_LABEL 4u     /* y_indices entry outside [0, num_classes): left out of the label set   */
 
 typedef struct {
   uint32_t struct_size;      /* sizeof(slide_config)                                            */
@@ -157,23 +163,25 @@ typedef struct {
   int64_t sum_active_pairs, sum_unique_out_rows, sum_unique_in_rows, sum_candidates, sum_steps;
 } slide_stats;
 
-/* Sizes of the tables and workspace buffers for this configuration (host only). */
+/* Sizes of the tables and workspace buffers for this configuration (host only; no passage of the
+ * paper: the caller owns all device memory, and this says how much of it the hashing parameters of
+ * Section 4.1 and the batch limits imply).  Also rejects configurations the kernels cannot run. */
 int slide_query_memory(const slide_config* cfg, slide_mem_req* out);
 
 /* Validates the configuration and buffers, copies the hash-function parameters into the
  * workspace (synchronous), and returns a context.  Parameters must already be initialised
- * (Algorithm 1: "initialize layers with randomly generated weights"); the library has no
- * random number generator.  Adam state is used as given (normally zero). */
+ * (Algorithm 1, the initialisation step: random weights); the library has no random number
+ * generator.  Adam state is used as given (normally zero). */
 int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_hash_params* hp,
                slide_ctx** out);
 
-/* Algorithm 1, "initialize hash tables / hash weights to hash tables" (Section 2.1 phase 1):
- * hashes every row of the current W2 into L tables.  The first call is the initial build;
+/* Algorithm 1, the table-construction step before the loop (Section 2.1 phase 1): hashes every
+ * row of the current W2 into L tables.  The first call is the initial build;
  * later explicit calls count as rebuilds. */
 int slide_build_tables(slide_ctx* ctx, void* hip_stream);
 
-/* Replaces the hash functions (Algorithm 1 rebuilds "hash tables and hash functions" on its
- * schedule; the library draws no random numbers, so the caller supplies the new functions).
+/* Replaces the hash functions (Algorithm 1's rebuild step renews the functions together with the
+ * tables; the library draws no random numbers, so the caller supplies the new functions).
  * Synchronises the stream, uploads the parameters, and marks the tables stale: slide_build_tables
  * must run before the next slide_train_step / slide_predict; it counts as a rebuild.  Same
  * validation and ownership as in slide_init (host arrays, copied). */
@@ -186,8 +194,9 @@ int slide_set_hash_params(slide_ctx* ctx, const slide_hash_params* params, void*
  * to d_loss (device, one float). */
 int slide_train_step(slide_ctx* ctx, const slide_batch* batch, float* d_loss, void* hip_stream);
 
-/* Inference: scores of the neurons retrieved by the hash tables (mode 0, labels not used) or of
- * all N neurons (mode 1); the topk largest per sample go to d_out_ids / d_out_scores
+/* Inference (Section 2.1: the tables are queried with the layer input and only the retrieved
+ * neurons are scored; Section 4 reports accuracy on full predictions): scores of the neurons
+ * retrieved by the hash tables (mode 0, labels not used) or of all N neurons (mode 1); the topk largest per sample go to d_out_ids / d_out_scores
  * ([batch][topk], device), ties to the lower id, missing entries id -1 / score -inf. topk <= 64. */
 int slide_predict(slide_ctx* ctx, const slide_batch* batch, int mode, int topk,
                   int32_t* d_out_ids, float* d_out_scores, void* hip_stream);
@@ -197,8 +206,8 @@ int slide_predict(slide_ctx* ctx, const slide_batch* batch, int mode, int topk,
  * of all N neurons, the topk best per sample), with every intermediate -- the hidden activations in
  * sparse-input mode, one chunk of scores, the running best lists, the candidate buffers and their
  * counters -- in a fixed array of SLIDE_STATIC_SCRATCH_MIB MiB inside the library's device image instead
- * of the context's workspace.  Same arguments, results and ordering rules as slide_predict; allocates
- * nothing on host paths that touch the device and calls no allocating routine.
+ * of the context's workspace.  Same arguments, results and ordering rules as slide_predict; calls no
+ * hipMalloc / hipFree or other allocating routine.
  * Limits: batch <= SLIDE_STATIC_MAX_BATCH (SLIDE_ENOMEM beyond); the context's device must be current
  * (SLIDE_ESTATE otherwise).  Every call on a GPU shares that GPU's array, whatever the context or
  * stream: calls that overlap on one GPU race; calls on one stream are ordered and safe.  The array
@@ -209,10 +218,12 @@ int slide_predict_static(slide_ctx* ctx, const slide_batch* batch, int topk, int
                          float* d_out_scores, void* hip_stream);
 
 /* Synchronises the stream; returns SLIDE_OK, SLIDE_EHIP, or SLIDE_EDATA with the flag bits in
- * *flags (may be NULL).  The flags are then cleared. */
+ * *flags (may be NULL).  The flags are then cleared.  (Housekeeping, no passage of the paper: this is
+ * how the device-side checks of the batch arrays of Section 3.6 reach the caller.) */
 int slide_status(slide_ctx* ctx, void* hip_stream, uint32_t* flags);
 
-/* Synchronises the stream and copies the counters. */
+/* Synchronises the stream and copies the counters (measurement aid; the sparsity the paper's argument
+ * rests on -- active neurons per sample, Sections 1 and 2.1 -- is read off these). */
 int slide_get_stats(slide_ctx* ctx, void* hip_stream, slide_stats* out);
 
 /* Launches of a step, in order, for slide_profile. */

@@ -1,4 +1,4 @@
-// Active-set retrieval (paper Algorithm 1 "retrieve active neurons"; Figure 1: the union of the
+// Active-set retrieval (paper Algorithm 1, the retrieval step of the loop body; Figure 1: the union of the
 // neurons returned by every table) and the index structures the float kernels consume.
 //
 //  lookup_union : one workgroup per sample.  Reads one bucket per table, sets one bit per candidate
@@ -421,7 +421,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
   }
 }
 
-static size_t lookup_fixed_lds(int L, int H, int NT, int NH) {
+size_t lookup_fixed_lds(int L, int H, int NT, int NH) {
   return ((size_t)2 * L + 1 + 20 + H + NT + kSelWords) * 4 + (((size_t)NH + 3) & ~(size_t)3);
 }
 
@@ -447,6 +447,9 @@ hipError_t launch_lookup_union(const ActiveDev& ad, const HashDev& hd, const flo
                                const int32_t* y_indices, int include_labels, int32_t* ncand, Ctrl* ctrl,
                                size_t lds_limit, hipStream_t s) {
   const size_t fixed = lookup_fixed_lds(ad.L, hd.H, ad.NT, hd.NH);
+  // (slide_init has refused configurations whose fixed part leaves less than kLookupMinSegment words:
+  // with a tiny segment the kernel would sweep all candidates once per few hundred neurons)
+  if (fixed + (size_t)kLookupMinSegment * 4 > lds_limit) return hipErrorInvalidValue;
   size_t avail = (lds_limit - fixed) / 4;
   int segw = (int)(avail / 32 * 32);
   if (segw > ad.NWpad) segw = ad.NWpad;

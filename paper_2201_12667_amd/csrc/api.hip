@@ -136,6 +136,14 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   if (lo->Amax >= ((int64_t)1 << 31) - 64) FAIL(SLIDE_EINVAL, "max_batch * L * bucket_cap does not fit 31 bits");
   if ((int64_t)c->L * lo->N >= ((int64_t)1 << 32)) FAIL(SLIDE_EINVAL, "L * num_classes does not fit 32 bits");
   lo->max_chunks = lo->Amax / kChunk + c->max_batch + 1;
+  {
+    // the lookup kernel keeps, besides a segment of the per-sample bitmap, 2L + H + NT words and K*L bytes
+    // in LDS: that has to leave room for a segment worth sweeping
+    const size_t fixed = lookup_fixed_lds(c->L, c->hidden_dim, lo->NT, c->K * c->L);
+    if (fixed + (size_t)kLookupMinSegment * 4 > kDeviceLdsBytes)
+      FAIL(SLIDE_EINVAL, "L, K*L, hidden_dim and num_classes / tile need %zu bytes of LDS in the lookup kernel; "
+                         "%zu are available", fixed + (size_t)kLookupMinSegment * 4, kDeviceLdsBytes);
+  }
   lo->U2max = (int64_t)lo->NWpad * 32;
   lo->P1max = c->max_nnz_per_batch;
   if (lo->P1max * kPairRegions >= ((int64_t)1 << 31)) FAIL(SLIDE_EINVAL, "max_nnz_per_batch too large");
@@ -200,6 +208,7 @@ struct slide_ctx {
   uint32_t prio_a, prio_b;
   size_t lds_limit;
   int num_cus = 256;             // compute units of the device (persistent launches are sized by it)
+  int nxcd = 1;                  // accelerator dies (workgroup k of a launch runs on die k % nxcd); 1 = unknown
   int device = -1;               // device that was current at slide_init
   char* static_scratch = nullptr;   // this device's copy of the static scratch array
   int64_t t = 0, r = 0;
@@ -262,8 +271,6 @@ hipError_t stage(slide_ctx* ctx, int id, hipStream_t s, F&& launch) {
   return e;
 }
 
-constexpr int kFusedHiddenBatch = 256;   // compute units of the target machine
-
 SpmmArgs make_spmm(slide_ctx* ctx, const slide_batch* b) {
   const Layout& lo = ctx->lo;
   SpmmArgs a{};
@@ -282,6 +289,7 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ad.cnt = c->at<int32_t>(lo.cnt); ad.ny = c->at<int32_t>(lo.ny);
   ad.PS = lo.PS; ad.num_labels = 0;
   ad.budget = 0; ad.fill = 0; ad.sample_seed = c->cfg.sample_seed; ad.step = 0;
+  ad.par = 0; ad.nxcd = c->nxcd;
   ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
   ad.as_ids = c->at<int32_t>(lo.as_ids); ad.as_lab = c->at<uint8_t>(lo.as_lab); ad.ylist = c->at<int32_t>(lo.ylist);
   return ad;
@@ -331,7 +339,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
     // One lookup workgroup per sample holds a compute unit (its bitmap fills the LDS): while the batch
     // fits the machine in one round the hidden layer rides in it; a larger batch would pay the hidden
     // layer's latency once per round, so it gets its own, fully parallel launch.
-    if (B > kFusedHiddenBatch) {
+    if (B > ctx->num_cus) {
       HIPCHK(ctx, stage(ctx, SLIDE_STAGE_HIDDEN, s, [&] { return launch_spmm_relu(B, sp, ctx->ctrl(), s); }));
       sp = SpmmArgs{};
     }
@@ -342,6 +350,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   ActiveDev ad = make_active(ctx, B);
   ad.num_labels = with_labels ? b->num_labels : 0;
   ad.par = (int)(ctx->calls++ & 1);
+  ad.nxcd = ctx->nxcd;
   if (with_labels) { ad.budget = ctx->cfg.sample_budget; ad.fill = ctx->cfg.sample_fill; ad.step = (uint32_t)(ctx->t + 1); }
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
@@ -510,6 +519,12 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
     e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess && cus > 0) ctx->num_cus = cus;
+    hipDeviceProp_t prop;
+    if (e == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+      // gfx942 / gfx950 parts are built from dies of 32 active compute units (MI355X: 8 x 32)
+      const std::string arch = prop.gcnArchName;
+      if ((arch.rfind("gfx950", 0) == 0 || arch.rfind("gfx942", 0) == 0) && cus % 32 == 0) ctx->nxcd = cus / 32;
+    }
   }
   if (e == hipSuccess) {
     what = "hipGetSymbolAddress(static scratch)";
@@ -525,6 +540,11 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
   }
   if (cfg->sample_budget > 0 && !lookup_bitmap_fits(lo.NWpad, lo.NT, lo.L, H, NH, ctx->lds_limit)) {
     set_err(nullptr, SLIDE_EINVAL, "sample_budget needs the per-sample bitmap in LDS: num_classes is too large");
+    slide_destroy(ctx);
+    return SLIDE_EINVAL;
+  }
+  if (lookup_fixed_lds(lo.L, H, lo.NT, NH) + (size_t)kLookupMinSegment * 4 > ctx->lds_limit) {
+    set_err(nullptr, SLIDE_EINVAL, "the lookup kernel needs more LDS than the device offers (%zu bytes)", ctx->lds_limit);
     slide_destroy(ctx);
     return SLIDE_EINVAL;
   }
@@ -550,9 +570,13 @@ int slide_init(const slide_config* cfg, const slide_buffers* buf, const slide_ha
 
 int slide_build_tables(slide_ctx* ctx, void* hip_stream) {
   if (!ctx) return SLIDE_EINVAL;
+  // the rebuild count enters the overflow priorities: the build runs with the count it will have, and the
+  // count is kept only if the build was enqueued
+  const int64_t r_before = ctx->r;
   if (ctx->ever_built) ctx->r += 1;
   const int rc = do_build(ctx, (hipStream_t)hip_stream, false);
   if (rc == SLIDE_OK) { ctx->built = true; ctx->ever_built = true; }
+  else ctx->r = r_before;
   return rc;
 }
 
@@ -634,11 +658,11 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   const bool rows = rows_mode && update_sliced_applies(b->batch, lo.H, ctx->lds_limit);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_UPDATE, s, [&] {
     return rows ? launch_update_sliced(lo.H, b->batch, out, in, fin, a, ctx->lds_limit, ctx->num_cus, s)
-                : launch_update(lo.H, out, in, fin, a, s); }));
+                : launch_update(lo.H, out, in, fin, a, ctx->num_cus, s); }));
   ctx->t = t;
   if (c.rebuild_every > 0 && t % c.rebuild_every == 0) {
     ctx->r += 1;
-    if ((rc = do_build(ctx, s, true)) != SLIDE_OK) return rc;
+    if ((rc = do_build(ctx, s, true)) != SLIDE_OK) { ctx->r -= 1; return rc; }
   }
   return SLIDE_OK;
 }

@@ -51,14 +51,17 @@ __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const 
   // so when samples share rows (saturated buckets) a row is fetched once and then found in L2.  With
   // many chunks per sample every XCD (workgroup k runs on XCD k % 8, each with its own L2) also takes
   // its own eighth of the chunk indices, a contiguous one, so that the stretches it works on at the
-  // same time are neighbours and a row is fetched by one XCD only.
+  // same time are neighbours and a row is fetched by one XCD only.  (That workgroup k runs on die
+  // k % nxcd is how this device family hands out workgroups; slide_init sets nxcd = 1, which turns the
+  // split off, when it does not recognise the device.)
   const int B = ad.B;
   const int maxnch = (int)ctrl->max_nch[ad.par];
-  const bool affine = maxnch >= 64;                  // (otherwise the XCDs would get unequal shares)
-  const int xcd = block & 7;
-  const int c_lo = affine ? xcd * maxnch / 8 : 0, c_hi = affine ? (xcd + 1) * maxnch / 8 : maxnch;
-  const int lwave = (affine ? (block >> 3) : block) * WPB + (threadIdx.x >> 6);
-  const int lwaves = (affine ? (nblocks >> 3) : nblocks) * WPB;
+  const int nx = ad.nxcd;
+  const bool affine = nx > 1 && maxnch >= 8 * nx && nblocks % nx == 0;   // (otherwise the dies would get unequal shares)
+  const int xcd = block % nx;
+  const int c_lo = affine ? xcd * maxnch / nx : 0, c_hi = affine ? (xcd + 1) * maxnch / nx : maxnch;
+  const int lwave = (affine ? (block / nx) : block) * WPB + (threadIdx.x >> 6);
+  const int lwaves = (affine ? (nblocks / nx) : nblocks) * WPB;
   const int T = (c_hi - c_lo) * B;
   const int PS = H + 4;
   for (int t = lwave; t < T; t += lwaves) {

@@ -97,6 +97,7 @@ struct ActiveDev {
   int PS;                          // slots reserved per sample for candidates: min(L*C, N)
   int num_labels;                  // label entries in the batch
   int par;                         // which work-item counter this call uses
+  int nxcd;                        // accelerator dies whose workgroups alternate in launch order (1: unknown)
   int budget, fill;                // sampling budget of this call (0 = none) and its fill option
   uint32_t sample_seed, step;      // keys of the counter-based generator: seed, number of the step being run
   uint32_t* act;                   // [NT][B][TW] bitmap spill, used only when a sample's bitmap exceeds LDS
@@ -146,6 +147,10 @@ struct SpmmArgs {
   int2* xse;                     // [tiles][B] feature segments per tile (output)
 };
 
+constexpr int kLookupMinSegment = 1024;   // bitmap words the lookup kernel must be able to hold at a time
+constexpr size_t kDeviceLdsBytes = 160 * 1024;   // LDS of a gfx950 compute unit (the only target)
+// LDS the lookup kernel needs besides its bitmap segment.
+size_t lookup_fixed_lds(int L, int H, int NT, int NH);
 hipError_t active_setup_attributes(size_t* lds_limit_out);
 bool lookup_bitmap_fits(int NWpad, int NT, int L, int H, int NH, size_t lds_limit);
 // sp.W1 != nullptr: the workgroup of a sample first computes the sample's hidden activations (h is
@@ -207,7 +212,7 @@ struct FinishArgs {
 // One launch, three roles by workgroup index: loss mean + hidden bias + statistics, the rows of W1,
 // the rows of W2 (+ b2).
 hipError_t launch_update(int H, const RowUpdate& out, const RowUpdate& in, const FinishArgs& fin, const AdamDev& ad,
-                         hipStream_t s);
+                         int num_cus, hipStream_t s);
 // The same launch for batches whose samples share most rows: sample vectors staged in LDS by column
 // slices (see update.hip).  update_sliced_applies: whether a batch of B vectors of length H fits.
 bool update_sliced_applies(int B, int H, size_t lds_limit);

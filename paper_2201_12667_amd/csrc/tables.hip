@@ -1,4 +1,4 @@
-// Hash-table build / rebuild (paper Algorithm 1 "hash weights to hash tables", rebuilt on a
+// Hash-table build / rebuild (paper Algorithm 1, the table-construction step before the loop, rebuilt on a
 // schedule, Section 3.1).  Layout: per table a CSR over the 2^bits codes -- off[t][code] is the
 // start of the bucket inside ids[t][0..N).  A bucket's first min(size, C) ids are its kept members,
 // ascending by id; which members are kept when size > C is decided by the smallest

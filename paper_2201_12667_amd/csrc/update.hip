@@ -1,5 +1,5 @@
 // Sparse backpropagation into the parameters fused with row-sparse Adam (paper Algorithm 1:
-// gradients reach only the active neurons, then "update weights with Adam"; Section 3.5: every
+// gradients reach only the active neurons, then the optimizer step after the batch; Section 3.5: every
 // weight and bias carries a momentum and a velocity value; constants of Section 4.1).
 //
 // rowgrad_adam: each touched row is read once (w, m, v), its gradient is formed in registers from
@@ -15,7 +15,6 @@
 namespace slide {
 
 constexpr int kUpdateThreads = 256;
-constexpr int kUpdateBlocksOut = 2048;
 
 // One element of the Adam update.  The square root and the reciprocal are the hardware's one-ulp
 // instructions rather than the correctly rounded library sequences (about 25 instructions per element
@@ -387,7 +386,7 @@ __device__ __forceinline__ void fma_cols(typename LaneCols<CPL>::type& g, float 
 // first 64 list entries two ahead, their coefficients one ahead.
 template <int CPL>
 __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const AdamDev& ad, const float* ldsV,
-                                    const uint32_t* tpre, int part, int nparts) {
+                                    const uint32_t* tpre, uint32_t* cursor, int part, int nparts) {
   typedef typename LaneCols<CPL>::type cols_t;
   constexpr int PITCH = 64 * CPL + kSlicedPad;
   const PairsDev& pd = ru.pd;
@@ -401,29 +400,35 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
   const bool bias_lane = bias_lane_any && lane == 0;
   const float* lds_mine = ldsV + lane * CPL;
   // The touched rows sit in per-tile slot ranges (tile t: slots t*rows_per_tile .. + tile_nu[t]).  With
-  // the running sum of tile_nu in LDS (tpre, when the tiles are few enough) a wave takes a contiguous
-  // stretch of the touched rows and finds their slots by stepping through the sums; otherwise it visits
-  // the slots r * ntiles + t (the tiles' r-th rows side by side) and skips the empty ones.
+  // the running sum of tile_nu in LDS (tpre, when the tiles are few enough) the workgroup owns a
+  // contiguous stretch of the touched rows and its waves draw rows from it one at a time through an LDS
+  // counter (the lists' lengths have a heavy tail: a fixed share per wave leaves most waves waiting for
+  // the few with the long lists); a row's slot is found by stepping through the sums.  Otherwise a wave
+  // visits the slots r * ntiles + t (the tiles' r-th rows side by side) and skips the empty ones.
   const bool dense = tpre != nullptr;
-  int count, lo = 0, tc = 0;
+  int count = 0x7fffffff, tc = 0;
+  uint32_t hi = 0;
   if (dense) {
     const uint32_t U = tpre[pd.ntiles];
-    lo = (int)((uint64_t)U * (uint32_t)wave_global / (uint32_t)nwaves);
-    count = (int)((uint64_t)U * (uint32_t)(wave_global + 1) / (uint32_t)nwaves) - lo;
+    const uint32_t lo = (uint32_t)((uint64_t)U * (uint32_t)part / (uint32_t)nparts);
+    hi = (uint32_t)((uint64_t)U * (uint32_t)(part + 1) / (uint32_t)nparts);
     int a = 0, b = pd.ntiles;                              // last tile whose sum is <= lo
-    while (b - a > 1) { const int mid = (a + b) >> 1; if (tpre[mid] <= (uint32_t)lo) a = mid; else b = mid; }
+    while (b - a > 1) { const int mid = (a + b) >> 1; if (tpre[mid] <= lo) a = mid; else b = mid; }
     tc = a;
   } else {
     const int nrows = pd.ntiles * (int)*pd.max_nu;
     count = wave_global < nrows ? (nrows - wave_global + nwaves - 1) / nwaves : 0;
   }
-  // header of the k-th row of this wave: (row, first list entry, entries, -); entries = 0: none.
-  // (Called with ascending k, so the tile cursor only moves forward.)
+  // header of the k-th row of this wave: (row, first list entry, entries, -); entries = 0: an empty slot,
+  // entries < 0: no more rows.  (Called once per k, ascending, so the tile cursor only moves forward.)
   auto header = [&](int k) -> int4 {
-    if (k >= count) return make_int4(0, 0, 0, 0);
+    if (k >= count) return make_int4(0, 0, -1, 0);
     int slot;
     if (dense) {
-      const uint32_t g = (uint32_t)(lo + k);
+      uint32_t g = 0;
+      if (lane == 0) g = atomicAdd(cursor, 1u);
+      g = (uint32_t)__builtin_amdgcn_readfirstlane((int)g);
+      if (g >= hi) { count = k; return make_int4(0, 0, -1, 0); }   // (the counter only grows: later draws fail too)
       while (g >= tpre[tc + 1]) ++tc;
       slot = tc * pd.rows_per_tile + (int)(g - tpre[tc]);
     } else {
@@ -468,6 +473,7 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
   int j_s = -1;                                            // row they belong to (-1: nothing pending)
   for (int k = 0; k < count; ++k) {
     const int4 cur = scalar(m0);                           // ---- the one waiting point of this row
+    if (cur.z < 0) break;                                  // (no more rows; uniform)
     const int2 ecur = e0;
     const float dcur = d0;
     const cols_t wc = w0, mc = mo0, vc = v0;
@@ -536,6 +542,7 @@ __global__ __launch_bounds__(kSlicedThreads) void update_sliced_kernel(int H, in
   constexpr int CW = 64 * CPL, PITCH = CW + kSlicedPad;
   uint32_t* tsum = (uint32_t*)(ldsV + (size_t)B * PITCH);
   __shared__ uint32_t wsum[kSlicedThreads / 64];
+  __shared__ uint32_t row_cursor;                          // next touched row of this workgroup's stretch
   int blk = blockIdx.x;
   if (blk < fin.nblocks) { finish_role(H, fin, ad, blk); return; }
   blk -= fin.nblocks;
@@ -570,10 +577,13 @@ __global__ __launch_bounds__(kSlicedThreads) void update_sliced_kernel(int H, in
         if (t < nt) tsum[t] = carry + before + inc - v;
         carry += total;
       }
-      if (threadIdx.x == 0) tsum[nt] = carry;
+      if (threadIdx.x == 0) {
+        tsum[nt] = carry;
+        row_cursor = (uint32_t)((uint64_t)carry * (uint32_t)part / (uint32_t)parts);
+      }
     }
     __syncthreads();
-    rowgrad_adam_sliced<CPL>(H, c0, ru, ad, ldsV, dense ? tsum : nullptr, part, parts);
+    rowgrad_adam_sliced<CPL>(H, c0, ru, ad, ldsV, dense ? tsum : nullptr, &row_cursor, part, parts);
   }
 }
 
@@ -617,10 +627,10 @@ hipError_t launch_update_sliced(int H, int B, const RowUpdate& out_, const RowUp
 }
 
 hipError_t launch_update(int H, const RowUpdate& out_, const RowUpdate& in_, const FinishArgs& fin_,
-                         const AdamDev& ad, hipStream_t s) {
+                         const AdamDev& ad, int num_cus, hipStream_t s) {
   RowUpdate out = out_, in = in_;
   FinishArgs fin = fin_;
-  out.nblocks = kUpdateBlocksOut;
+  out.nblocks = 8 * num_cus;          // twice what the device holds at four waves per SIMD: the tail stays short
   in.nblocks = in.W ? 1 : 0;          // present / absent
   fin.nblocks = fin.b1 ? ceil_div(H, 32) : 1;
 #define SLIDE_UP(L_, C_, U_) return launch_up<L_, C_, U_>(H, out, in, fin, ad, s)

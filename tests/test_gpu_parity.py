@@ -288,6 +288,35 @@ def test_bad_batch_data_is_flagged_not_fatal():
     fresh.destroy()
 
 
+def test_batches_beyond_the_configured_capacities_are_refused():
+    """SLIDE_ENOMEM on the host, before any launch: more stored features or label entries in a batch than
+    the configuration reserved room for, and a read-back buffer smaller than the active sets."""
+    _say("capacities")
+    from paper_2201_12667_amd import slide
+    import ctypes as C
+    wl = synth.small(synth.HASH_DWTA, batch=8, num_classes=3000, input_dim=500)
+    gen = synth.Generator(wl, 0)
+    b = gen.batch(0)
+    nnz, nlab = int(b["x_indptr"][-1]), int(b["y_indptr"][-1])
+    for over in ({"max_nnz_per_batch": nnz - 1}, {"max_labels_per_batch": nlab - 1}):
+        _, model, _ = make_pair(wl, **over)
+        model.build_tables()
+        with pytest.raises(slide.SlideError) as e:
+            model.train_step(model.to_device(b))
+        assert e.value.code == slide.SLIDE_ENOMEM
+        assert model.stats()["steps"] == 0                 # nothing ran
+        model.destroy()
+    _, model, _ = make_pair(wl, max_nnz_per_batch=nnz, max_labels_per_batch=nlab)   # exactly enough: accepted
+    model.build_tables()
+    model.train_step(model.to_device(b))
+    assert model.status() == 0
+    as_ptr = np.zeros(wl.batch + 1, dtype=np.int64)
+    ids = np.zeros(4, dtype=np.int32)
+    rc = model.L.slide_debug_get_active(model.ctx, as_ptr.ctypes.data, ids.ctypes.data, None, None, None, 4)
+    assert rc == slide.SLIDE_ENOMEM and as_ptr[-1] > 4     # the sizes are reported, the ids are not copied
+    model.destroy()
+
+
 @pytest.mark.parametrize("kind", [synth.HASH_DWTA, synth.HASH_SIMHASH])
 def test_predict_mode0_matches_oracle(kind):
     _say("predict", kind)
