@@ -147,21 +147,41 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
   };
 
   // ---- pass 1: transposed tile -------------------------------------------------------------------
+  // A thread's first kKeep ids of each segment stay in registers (as rows of the tile) together with the
+  // segment's ends: the second pass then needs no memory read at all for them.
+  constexpr int kKeep = 8, kSegs = 4;                    // (kSegs >= Bpad * shares / blockDim: batches up to 2048)
   const int shares = max(1, (int)blockDim.x / Bpad);     // threads per sample
-  for (int idx = tid; idx < Bpad * shares; idx += blockDim.x) {
+  int klo[kSegs], khi[kSegs], krow[kSegs][kKeep];
+#pragma unroll
+  for (int j = 0; j < kSegs; ++j) {
+    const int idx = tid + j * (int)blockDim.x;
+    klo[j] = 0; khi[j] = 0;
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) krow[j][k] = -1;
+    if (idx >= Bpad * shares) continue;
     const int i = idx % Bpad, share = idx / Bpad;
     int lo, hi;
     uint32_t rank0;
     segment(i, lo, hi, rank0);
     if (share) rank0 = 0;
+    klo[j] = lo; khi[j] = hi;
     uint32_t* tc = T + (size_t)(i >> 5) * ROWS;
     const uint32_t ibit = 1u << (i & 31);
-    for (int p = lo + kInFlight * share; p < hi; p += kInFlight * shares) {   // kInFlight ids in flight
-      int r[kInFlight];
+    // this thread's ids: lo + 4*share + (0..3), then every 4*shares further on
 #pragma unroll
-      for (int k = 0; k < kInFlight; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
+    for (int k = 0; k < kKeep; ++k) {
+      const int p = lo + 4 * share + (k >> 2) * 4 * shares + (k & 3);
+      krow[j][k] = p < hi ? ids[p] - row0 : -1;
+    }
 #pragma unroll
-      for (int k = 0; k < kInFlight; ++k)
+    for (int k = 0; k < kKeep; ++k)
+      if ((unsigned)krow[j][k] < (unsigned)ROWS) atomicOr(&tc[krow[j][k]], ibit);
+    for (int p = lo + 4 * share + (kKeep / 4) * 4 * shares; p < hi; p += 4 * shares) {   // longer segments
+      int r[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
         if ((unsigned)r[k] < (unsigned)ROWS) atomicOr(&tc[r[k]], ibit);
     }
     if (!FEAT) {
@@ -223,29 +243,33 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
   }
 
   // ---- pass 2: emit ----------------------------------------------------------------------------------
-  for (int idx = tid; idx < Bpad * shares; idx += blockDim.x) {
+#pragma unroll
+  for (int j = 0; j < kSegs; ++j) {
+    const int idx = tid + j * (int)blockDim.x;
+    if (idx >= Bpad * shares) continue;
     const int i = idx % Bpad, share = idx / Bpad;
-    int lo, hi;
-    uint32_t rank0;
-    segment(i, lo, hi, rank0);
+    const int lo = klo[j], hi = khi[j];
     const int g = i >> 6;
     const uint32_t lo_mask = (i & 32) ? 0xffffffffu : ((1u << (i & 31)) - 1u);
     const uint32_t hi_mask = (i & 32) ? ((1u << (i & 31)) - 1u) : 0u;
     const uint32_t* t_lo = T + (size_t)(2 * g) * ROWS;
     const uint32_t* t_hi = t_lo + ROWS;
     const uint16_t* grp = rowgrp + (size_t)g * ROWS;
-    for (int p = lo + kInFlight * share; p < hi; p += kInFlight * shares) {
-      int r[kInFlight];
+    auto emit = [&](int row, int pos) {
+      const uint32_t place = blk0 + wnp[row >> 5] + rowoff[row] + grp[row] + __popc(t_lo[row] & lo_mask) +
+                             __popc(t_hi[row] & hi_mask);
+      pd.pairs[place] = make_int2(i, pos);
+    };
 #pragma unroll
-      for (int k = 0; k < kInFlight; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
+    for (int k = 0; k < kKeep; ++k)
+      if ((unsigned)krow[j][k] < (unsigned)ROWS) emit(krow[j][k], lo + 4 * share + (k >> 2) * 4 * shares + (k & 3));
+    for (int p = lo + 4 * share + (kKeep / 4) * 4 * shares; p < hi; p += 4 * shares) {
+      int r[4];
 #pragma unroll
-      for (int k = 0; k < kInFlight; ++k) {
-        if ((unsigned)r[k] >= (unsigned)ROWS) continue;
-        const int row = r[k];
-        const uint32_t place = blk0 + wnp[row >> 5] + rowoff[row] + grp[row] + __popc(t_lo[row] & lo_mask) +
-                               __popc(t_hi[row] & hi_mask);
-        pd.pairs[place] = make_int2(i, p + k);
-      }
+      for (int k = 0; k < 4; ++k) r[k] = p + k < hi ? ids[p + k] - row0 : -1;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if ((unsigned)r[k] < (unsigned)ROWS) emit(r[k], p + k);
     }
   }
   __syncthreads();
