@@ -359,15 +359,11 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   t2.ids = ad.as_ids; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
     // When the samples share most rows the logit workers keep the machine busy for long and the row
-    // lists are many: the lists get the machine to themselves first.
-    if (split_lists && (t1.ntiles || t2.ntiles)) {
-      hipError_t e = launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
-                                    ctx->at<float>(lo.partials), ctx->ctrl(), t1, t2, false, ctx->num_cus, s);
-      if (e != hipSuccess) return e;
+    // lists are many: the lists then ride in the combine launch instead (see slide_train_step).
+    if (split_lists)
       return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
                             ctx->at<float>(lo.partials), ctx->ctrl(), TransposeArgs{}, TransposeArgs{}, true,
                             ctx->num_cus, s);
-    }
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
                           ctx->at<float>(lo.partials), ctx->ctrl(), t1, t2, true, ctx->num_cus, s); }));
   *ad_out = ad;
@@ -628,12 +624,13 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   ActiveDev ad;
   const bool rows_mode = row_major(ctx, b->batch);
   if ((rc = forward_common(ctx, b, true, s, &ad, t1, t2, rows_mode)) != SLIDE_OK) return rc;
+  t2.ids = ad.as_ids; t2.rankT = ad.rankT; t2.as_base = ad.as_base;   // (for the lists that ride in the combine launch)
   float* dh = ctx->at<float>(lo.dh);
   float* delta = ctx->at<float>(lo.delta);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_COMBINE, s, [&] {
     return launch_combine(ad, lo.H, ctx->last_h, ctx->at<float>(lo.z), ctx->at<float>(lo.partials), ctx->buf.W2,
                           b->y_indptr, ad.ylist, delta, dh, b->dhidden_out, ctx->at<float>(lo.loss_i),
-                          ctx->at<float>(lo.msum), s); }));
+                          ctx->at<float>(lo.msum), rows_mode ? t1 : TransposeArgs{}, rows_mode ? t2 : TransposeArgs{}, s); }));
   ctx->last_dh = dh;
   const int64_t t = ctx->t + 1;
   AdamDev a;

@@ -185,6 +185,8 @@ static hipError_t fwd_attr(int lim) {
   return hipFuncSetAttribute((const void*)forward_kernel<LPR, CH>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
 }
 
+static hipError_t combine_setup_attributes(int lim);
+
 hipError_t forward_setup_attributes(size_t lds_limit) {
   const int lim = (int)std::min<size_t>(lds_limit, 72 * 1024);
   hipError_t e = fwd_attr<8, 1>(lim);
@@ -194,6 +196,7 @@ hipError_t forward_setup_attributes(size_t lds_limit) {
   if (e == hipSuccess) e = fwd_attr<32, 4>(lim);
   if (e == hipSuccess) e = fwd_attr<64, 4>(lim);
   if (e == hipSuccess) e = fwd_attr<64, 8>(lim);
+  if (e == hipSuccess) e = combine_setup_attributes(lim);
   return e;
 }
 
@@ -222,21 +225,30 @@ hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const floa
 // ---------------------------------------------------------------------------------------------
 constexpr int kCombineThreads = 512;
 
-__global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, int H, const float* __restrict__ h,
-                                                      const float* __restrict__ z,
-                                                      const float* __restrict__ partials,
-                                                      const float* __restrict__ W2,
-                                                      const int32_t* __restrict__ y_indptr,
-                                                      const int32_t* __restrict__ ylist,
-                                                      float* __restrict__ delta, float* __restrict__ dh,
-                                                      float* __restrict__ dh_copy, float* __restrict__ loss_i,
-                                                      float* __restrict__ msum) {
+struct CombineArgs {
+  const float *h, *z, *partials, *W2;
+  const int32_t *y_indptr, *ylist;
+  float *delta, *dh, *dh_copy, *loss_i, *msum;
+};
+
+__device__ __forceinline__ void combine_sample(const ActiveDev& ad, int H, const CombineArgs& ca, int sample) {
+  const float* __restrict__ h = ca.h;
+  const float* __restrict__ z = ca.z;
+  const float* __restrict__ partials = ca.partials;
+  const float* __restrict__ W2 = ca.W2;
+  const int32_t* __restrict__ y_indptr = ca.y_indptr;
+  const int32_t* __restrict__ ylist = ca.ylist;
+  float* __restrict__ delta = ca.delta;
+  float* __restrict__ dh = ca.dh;
+  float* __restrict__ dh_copy = ca.dh_copy;
+  float* __restrict__ loss_i = ca.loss_i;
+  float* __restrict__ msum = ca.msum;
   constexpr int kMaxCh = 1024, kMaxLab = 256;            // LDS-staged chunk scales / label rows; more fall back to global reads
   __shared__ float red[kCombineThreads / 64];
   __shared__ float scale[kMaxCh];                        // exp(M_c - M) per forward work item of the sample
   __shared__ int ylab[kMaxLab];                          // neuron of each label entry, -1 = not counted
   __shared__ float ms[2];
-  const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const int i = sample, tid = threadIdx.x, lane = tid & 63;
   const int c0 = ad.chunk_ptr[i], nch = (ad.cnt[i] + kChunk - 1) / kChunk;
   const int first = ad.as_base[i], n = ad.cnt[i];
   const int ny = ad.ny[i];
@@ -316,11 +328,32 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, 
   }
 }
 
+// The samples' workgroups; behind them, optionally, the row-list tiles (t1: features, t2: active sets):
+// the lists depend on the lookup only and are not needed before the update launch, and when they are many
+// (batches whose samples share most rows) they are best kept out of the logit workers' way.
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, int H, CombineArgs ca, TransposeArgs t1,
+                                                                  TransposeArgs t2) {
+  extern __shared__ uint32_t dyn_lds[];
+  const int k = blockIdx.x;
+  if (k < ad.B) combine_sample(ad, H, ca, k);
+  else if (k < ad.B + t1.ntiles) transpose_tile<true>(t1, k - ad.B, dyn_lds);
+  else transpose_tile<false>(t2, k - ad.B - t1.ntiles, dyn_lds);
+}
+
+static hipError_t combine_setup_attributes(int lim) {
+  return hipFuncSetAttribute((const void*)combine_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+}
+
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
-                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3(ad.B), dim3(kCombineThreads), 0, s, ad, H, h, z, partials, W2, y_indptr,
-                     ylist, delta, dh, dh_copy, loss_i, msum);
+                          float* dh, float* dh_copy, float* loss_i, float* msum, const TransposeArgs& t1,
+                          const TransposeArgs& t2, hipStream_t s) {
+  static_assert(kCombineThreads == kForwardThreads, "the tiles are written for one workgroup size");
+  CombineArgs ca{h, z, partials, W2, y_indptr, ylist, delta, dh, dh_copy, loss_i, msum};
+  size_t lds = 0;
+  if (t1.ntiles) lds = transpose_lds(t1.TW, t1.Bpad);
+  if (t2.ntiles) lds = std::max(lds, transpose_lds(t2.TW, t2.Bpad));
+  hipLaunchKernelGGL(combine_kernel, dim3(ad.B + t1.ntiles + t2.ntiles), dim3(kCombineThreads), lds, s, ad, H, ca, t1, t2);
   return hipGetLastError();
 }
 

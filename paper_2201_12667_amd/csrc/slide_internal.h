@@ -171,7 +171,8 @@ hipError_t launch_forward(const ActiveDev& ad, int H, const float* h, const floa
 hipError_t forward_setup_attributes(size_t lds_limit);
 hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const float* z, const float* partials,
                           const float* W2, const int32_t* y_indptr, const int32_t* ylist, float* delta,
-                          float* dh, float* dh_copy, float* loss_i, float* msum, hipStream_t s);
+                          float* dh, float* dh_copy, float* loss_i, float* msum, const TransposeArgs& t1,
+                          const TransposeArgs& t2, hipStream_t s);
 hipError_t launch_topk(const ActiveDev& ad, const float* z, int topk, int32_t* out_ids,
                        float* out_scores, hipStream_t s);
 
