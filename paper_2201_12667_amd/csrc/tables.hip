@@ -333,6 +333,10 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
         for (uint32_t q = a; q < a + sz; ++q) seg[q] = idl[q];
       }
       const uint32_t n8 = (big || sz > 8u) ? 0u : sz;
+      if (!__any(n8 > 1u)) {                             // (sparse tables: nearly every bucket is empty or a single id)
+        if (n8 == 1u) seg[a] = idl[a];
+        continue;
+      }
       int32_t v[8];
 #pragma unroll
       for (int i = 0; i < 4; ++i) v[i] = (uint32_t)i < n8 ? idl[a + i] : 0x7fffffff;
@@ -486,7 +490,7 @@ __global__ __launch_bounds__(256) void big_buckets_kernel(const uint32_t* __rest
 // Split of the code into partition digit (high hb bits) and in-partition digit (low lb bits).
 void tables_split(int bits, int64_t N, int* hb, int* lb) {
   int want = 0;
-  while (want < 11 && ((int64_t)4096 << want) < N) ++want;     // about 2048 to 4096 rows per partition
+  while (want < 11 && ((int64_t)2048 << want) < N) ++want;     // about 1024 to 2048 rows per partition
   int h = want < bits ? want : bits;
   if (bits - h > 13) h = bits - 13;                            // low digit counters must fit in LDS
   *hb = h;
