@@ -5,7 +5,7 @@
 //                 and per label in an LDS bitmap over the neuron ids (deduplication and sorting
 //                 are free: the bitmap is swept in id order), writes per-tile population counts
 //                 (their prefix splits the sample's id list into one segment per tile of rows).
-//                 It also emits the compact ascending id list per sample + label flags and hands
+//                 It also emits the compact ascending id list per sample + the labels' slots and hands
 //                 the sample its forward work items (chunks of kChunk active neurons).
 #include "slide_internal.h"
 #include "spmm.h"
@@ -167,12 +167,17 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
 
   // a1 (sparse-input mode): the sample's hidden activations, by the first waves of the workgroup;
   // the first bitmap segment is cleared meanwhile.  Dense-hidden mode: the activations are read.
-  clear_segment(min(segw, ad.NWpad));
-  if (sp.W1) {
-    const int wave = tid >> 6;
-    if (wave * 128 < hd.H) spmm_sample(sp, i, ad.B, wave, lane, hvec, ctrl);
+  if (sp.W1 && hd.H <= nthr && spmm_stage_rows(segw, hd.H, nthr) >= 32) {
+    spmm_sample_staged(sp, i, ad.B, (float*)bm, segw, hvec, ctrl);   // (the bitmap's room is free until it is cleared)
+    clear_segment(min(segw, ad.NWpad));
   } else {
-    for (int c = tid; c < hd.H; c += nthr) hvec[c] = h[(size_t)i * hd.H + c];
+    clear_segment(min(segw, ad.NWpad));
+    if (sp.W1) {
+      const int wave = tid >> 6;
+      if (wave * 128 < hd.H) spmm_sample(sp, i, ad.B, wave, lane, hvec, ctrl);
+    } else {
+      for (int c = tid; c < hd.H; c += nthr) hvec[c] = h[(size_t)i * hd.H + c];
+    }
   }
   __syncthreads();                                       // (also orders the counters' reset before the labels)
   segment_labels(0, min(segw, ad.NWpad));
@@ -317,11 +322,18 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
     const int sw = min(segw, ad.NWpad - seg0);
     const int64_t lo = (int64_t)seg0 * 32, hi = lo + (int64_t)sw * 32;
     if (seg0 > 0) { clear_segment(sw); __syncthreads(); segment_labels(seg0, sw); __syncthreads(); }
-    for (uint32_t c = tid; c < T; c += nthr) {
+    auto candidate = [&](uint32_t c) -> int {           // the c-th of the sample's T bucket entries
       int a = 0, b = ad.L;                              // last t with pos[t] <= c
       while (b - a > 1) { const int mid = (a + b) >> 1; if (pos[mid] <= c) a = mid; else b = mid; }
-      const int j = ids[(size_t)a * ad.N + o0s[a] + (c - pos[a])];
-      if (j >= lo && j < hi) atomicOr(&bm[(j - lo) >> 5], 1u << (j & 31));
+      return ids[(size_t)a * ad.N + o0s[a] + (c - pos[a])];
+    };
+    for (uint32_t c0 = 0; c0 < T; c0 += 4 * nthr) {     // four entries per thread in flight
+      int j[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { const uint32_t c = c0 + u * nthr + tid; j[u] = c < T ? candidate(c) : -1; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (j[u] >= lo && j[u] < hi) atomicOr(&bm[(j[u] - lo) >> 5], 1u << (j[u] & 31));
     }
     __syncthreads();
     if (budgeted) apply_budget();
@@ -386,15 +398,14 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
         while (word) {
           const int b = __ffs(word) - 1;
           ad.as_ids[slot] = (4 * q + k) * 32 + b;
-          ad.as_lab[slot] = 0;
           ++slot;
           word &= word - 1;
         }
       }
     }
   }
-  __syncthreads();                                   // the sweep's flag writes (0) come before the labels' (1)
-  // label flags, and for every label entry its slot (-1 for invalid or repeated entries)
+  if (!in_lds) __syncthreads();                      // (the labels are then looked up in the list just written)
+  // for every label entry its slot (-1 for invalid or repeated entries): these slots are the label flags
   for (int q = tid; q < nlab; q += nthr) {
     const int y = y_indices[y0 + q];
     int slot = -1;
@@ -412,7 +423,6 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
         found = a < n && ad.as_ids[base_i + a] == y;
       }
       if (found) {
-        ad.as_lab[base_i + a] = 1;
         slot = base_i + a;
         for (int q2 = 0; q2 < q; ++q2) if (y_indices[y0 + q2] == y) { slot = -1; break; }
       }

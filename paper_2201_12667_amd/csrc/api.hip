@@ -64,7 +64,7 @@ struct Layout {
   size_t hash_words;
   // workspace offsets
   size_t ctrl, hashw, hashoff, xse, zc, best, cand, ccnt, h, dh, codes, act, rankT, cnt, ny, ncand, as_base, chunk_ptr, tile_nu2, tile_nu1, longlist2, longlist1, as_ids,
-      as_lab, ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, touched, touched_rows, ws_total;
+      ylist, z, delta, partials, msum, loss_i, umeta2, pairs2, umeta1, pairs1, codes_t, entries, bh, pbase, worklist, touched, touched_rows, ws_total;
   // tables offsets
   size_t t_off, t_ids, tables_total;
 };
@@ -174,7 +174,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->as_base = take(B * 4); lo->chunk_ptr = take((B + 1) * 4);
   lo->tile_nu2 = take((size_t)lo->NT2 * 4); lo->tile_nu1 = take((size_t)lo->NT1 * 4 + 4);
   lo->longlist2 = take((size_t)lo->long2 * 4); lo->longlist1 = take((size_t)lo->long1 * 4);
-  lo->as_ids = take(A * 4); lo->as_lab = take(A); lo->ylist = take((size_t)c->max_labels_per_batch * 4 + 4);
+  lo->as_ids = take(A * 4); lo->ylist = take((size_t)c->max_labels_per_batch * 4 + 4);
   lo->z = take(A * 4); lo->delta = take(A * 4);
   lo->partials = take((size_t)lo->max_chunks * (H + 4) * 4);
   lo->msum = take(B * 8); lo->loss_i = take(B * 4);
@@ -216,6 +216,7 @@ struct slide_ctx {
   bool ever_built = false;       // a build has happened (later ones count as rebuilds)
   bool codes_current = false;    // codes_t holds the codes of W2 under the current hash functions, up to the marked rows
   int last_B = 0;
+  int last_labels = 0;           // label entries of the last forward pass (0: prediction)
   uint64_t calls = 0;            // forward passes launched (selects the set of per-call device accumulators)
   const float* last_h = nullptr;
   float* last_dh = nullptr;
@@ -291,7 +292,7 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ad.budget = 0; ad.fill = 0; ad.sample_seed = c->cfg.sample_seed; ad.step = 0;
   ad.par = 0; ad.nxcd = c->nxcd;
   ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
-  ad.as_ids = c->at<int32_t>(lo.as_ids); ad.as_lab = c->at<uint8_t>(lo.as_lab); ad.ylist = c->at<int32_t>(lo.ylist);
+  ad.as_ids = c->at<int32_t>(lo.as_ids); ad.ylist = c->at<int32_t>(lo.ylist);
   return ad;
 }
 
@@ -346,6 +347,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   }
   ctx->last_h = h;
   ctx->last_B = B;
+  ctx->last_labels = with_labels ? b->num_labels : 0;
   uint32_t* codes = ctx->at<uint32_t>(lo.codes);
   ActiveDev ad = make_active(ctx, B);
   ad.num_labels = with_labels ? b->num_labels : 0;
@@ -684,6 +686,7 @@ int slide_predict(slide_ctx* ctx, const slide_batch* b, int mode, int topk, int3
     }
     ctx->last_h = h;
     ctx->last_B = b->batch;
+    ctx->last_labels = 0;
     ctx->last_dh = nullptr;
     HIPCHK(ctx, launch_dense_topk(b->batch, lo.N, lo.H, h, ctx->buf.W2, ctx->buf.b2, topk, ctx->at<float>(lo.zc),
                                   lo.dense_chunk, ctx->at<uint64_t>(lo.best), ctx->at<uint64_t>(lo.cand),
@@ -737,6 +740,7 @@ int slide_predict_static(slide_ctx* ctx, const slide_batch* b, int topk, int32_t
   }
   ctx->last_h = h;
   ctx->last_B = b->batch;
+  ctx->last_labels = 0;
   ctx->last_dh = nullptr;
   HIPCHK(ctx, launch_dense_topk(b->batch, lo.N, lo.H, h, ctx->buf.W2, ctx->buf.b2, topk, zc, chunk, best, cand, ccnt,
                                 d_out_ids, d_out_scores, s));
@@ -861,9 +865,20 @@ int slide_debug_get_active(slide_ctx* ctx, int64_t* h_as_ptr, int32_t* h_as_ids,
     const size_t n = (size_t)cnt[i], src = (size_t)base[i], dst = (size_t)h_as_ptr[i];
     if (!n) continue;
     if (h_as_ids) HIPCHK(ctx, hipMemcpy(h_as_ids + dst, ctx->at<int32_t>(ctx->lo.as_ids) + src, n * 4, hipMemcpyDeviceToHost));
-    if (h_is_label) HIPCHK(ctx, hipMemcpy(h_is_label + dst, ctx->at<uint8_t>(ctx->lo.as_lab) + src, n, hipMemcpyDeviceToHost));
     if (h_logits) HIPCHK(ctx, hipMemcpy(h_logits + dst, ctx->at<float>(ctx->lo.z) + src, n * 4, hipMemcpyDeviceToHost));
     if (h_delta) HIPCHK(ctx, hipMemcpy(h_delta + dst, ctx->at<float>(ctx->lo.delta) + src, n * 4, hipMemcpyDeviceToHost));
+  }
+  if (h_is_label) {
+    // the device keeps the label flags as the slot of every counted label entry
+    std::fill(h_is_label, h_is_label + A, (uint8_t)0);
+    std::vector<int32_t> slots((size_t)ctx->last_labels);
+    if (!slots.empty())
+      HIPCHK(ctx, hipMemcpy(slots.data(), ctx->at<int32_t>(ctx->lo.ylist), slots.size() * 4, hipMemcpyDeviceToHost));
+    for (const int32_t slot : slots) {
+      if (slot < 0) continue;
+      const int i = (int)(std::upper_bound(base.begin(), base.end(), slot) - base.begin()) - 1;   // bases ascend
+      if (i >= 0 && slot - base[i] < cnt[i]) h_is_label[h_as_ptr[i] + (slot - base[i])] = 1;
+    }
   }
   return SLIDE_OK;
 }

@@ -247,6 +247,7 @@ __device__ __forceinline__ void combine_sample(const ActiveDev& ad, int H, const
   __shared__ float red[kCombineThreads / 64];
   __shared__ float scale[kMaxCh];                        // exp(M_c - M) per forward work item of the sample
   __shared__ int ylab[kMaxLab];                          // neuron of each label entry, -1 = not counted
+  __shared__ int yslot[kMaxLab];                         // its slot in the sample-major arrays, -1 = not counted
   __shared__ float ms[2];
   const int i = sample, tid = threadIdx.x, lane = tid & 63;
   const int c0 = ad.chunk_ptr[i], nch = (ad.cnt[i] + kChunk - 1) / kChunk;
@@ -260,6 +261,7 @@ __device__ __forceinline__ void combine_sample(const ActiveDev& ad, int H, const
   // label rows: both lookups for all labels at once (a chain of dependent reads per label otherwise)
   for (int q = tid; q < min(nlab, kMaxLab); q += kCombineThreads) {
     const int slot = ylist[y0 + q];
+    yslot[q] = slot;
     ylab[q] = slot >= 0 ? ad.as_ids[slot] : -1;
   }
   // soft-max normaliser from the partial states: wave 0, one lane per work item, fixed butterfly order
@@ -307,16 +309,31 @@ __device__ __forceinline__ void combine_sample(const ActiveDev& ad, int H, const
   float lacc = 0.f;
   const float logs = live ? __logf(s) : 0.f;
   const float yv = ny > 0 ? 1.0f / (float)ny : 0.f;
+  // A slot holds a label iff a counted label entry names it.  Few entries (the usual case): every
+  // slot is compared with them.  Many: the labels' slots are rewritten in a second pass.
+  constexpr int kFewLabels = 16;
+  const bool few = nlab <= kFewLabels;
   for (int q = tid; q < n; q += kCombineThreads) {
     const int slot = first + q;
     float d = 0.f;
     if (live) {
       const float zz = z[slot];
-      const bool lab = ad.as_lab[slot] != 0;
+      bool lab = false;
+      if (few) for (int y = 0; y < nlab; ++y) lab |= yslot[y] == slot;
       d = (__expf(zz - Mi) / s - (lab ? yv : 0.f)) * invB;
       if (lab) lacc -= yv * (zz - Mi - logs);
     }
     delta[slot] = d;
+  }
+  if (!few) {
+    __syncthreads();                                     // (orders the first pass's writes before these)
+    for (int q = tid; q < nlab; q += kCombineThreads) {
+      const int slot = q < kMaxLab ? yslot[q] : ylist[y0 + q];
+      if (slot < 0 || !live) continue;
+      const float zz = z[slot];
+      delta[slot] = (__expf(zz - Mi) / s - yv) * invB;
+      lacc -= yv * (zz - Mi - logs);
+    }
   }
   for (int d = 32; d > 0; d >>= 1) lacc += __shfl_xor(lacc, d);
   if ((tid & 63) == 0) red[tid >> 6] = lacc;

@@ -107,7 +107,6 @@ struct ActiveDev {
   int32_t* chunk_ptr;              // [B] where the partial results of the sample's work items start
   int32_t* as_base;                // [B] first slot of sample i = i*PS + (label entries before sample i)
   int32_t* as_ids;                 // [slots] ascending ids of sample i at as_base[i] .. +cnt[i]
-  uint8_t* as_lab;                 // [slots]
   int32_t* ylist;                  // [labels] slot of each label entry, -1 for invalid / repeated ones
 };
 // Row lists: for every touched row the ascending samples that touch it.  Row slots are grouped by tile:

@@ -7,6 +7,105 @@
 namespace slide {
 
 // ---------------------------------------------------------------------------------------------
+// The same hidden layer by a whole workgroup, for a caller that can lend `stage_words` words of LDS.
+// When one wave owns the sample the layer costs a chain of dependent row fetches (sixteen in flight
+// at a time); here the indices and values of up to `cap` features are read once into LDS, every
+// thread fetches its share of their W1 rows at once into LDS, and then one thread per column runs
+// the multiply-adds over the staged rows in storage order: the same arithmetic, bit for bit (a
+// feature index outside [0, D) contributes 0 * 0, which leaves every sum as it is).  The feature
+// segments per tile and the data flags are derived from the staged indices exactly as spmm_sample
+// derives them.  Needs H <= blockDim.x.  Every thread of the workgroup must call; ends with the
+// result in hvec (LDS) and in a.h, after a barrier.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int spmm_stage_rows(int stage_words, int H, int nthr) {
+  const int cap = (stage_words - 2) / (H + 2);           // a row, its feature index and its value; two carries
+  return cap > nthr ? nthr : cap;
+}
+
+__device__ __forceinline__ void spmm_sample_staged(const SpmmArgs& a, int i, int B, float* stage, int stage_words,
+                                                   float* hvec, Ctrl* ctrl) {
+  const int64_t D = a.D;
+  const int H = a.H, H4 = H >> 2, rows_per_tile = a.rows_per_tile;
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const float* __restrict__ W1 = a.W1;
+  int2* __restrict__ xse = a.xse;
+  const int cap = spmm_stage_rows(stage_words, H, nthr);
+  int* sk = (int*)(stage + (size_t)cap * H);             // [cap] feature of the staged row, -1: left out
+  float* sv = (float*)(sk + cap);                        // [cap] its value (0 when left out)
+  int* carry = (int*)(sv + cap);                         // [0] entry before the batch, [1] last valid feature before it
+  const int p0 = max(a.x_indptr[i], 0), p1 = min(a.x_indptr[i + 1], a.nnz_total);
+  float acc = tid < H ? a.b1[tid] : 0.f;
+  uint32_t flags = 0;
+  if (tid == 0) { carry[0] = -1; carry[1] = -1; }
+  for (int pb = p0; pb < p1; pb += cap) {
+    const int cnt = min(cap, p1 - pb);
+    int kk = -1;
+    if (tid < cnt) {
+      const int k = a.x_indices[pb + tid];
+      const float v = a.x_values[pb + tid];
+      const bool bad = k < 0 || k >= D;
+      if (bad) flags |= SLIDE_FLAG_BAD_FEATURE;
+      kk = bad ? -1 : k;
+      sk[tid] = kk;
+      sv[tid] = bad ? 0.f : v;
+    }
+    __syncthreads();
+    const int total = cnt * H4;
+    for (int idx0 = 0; idx0 < total; idx0 += 4 * nthr) {  // four row pieces per thread in flight
+      float4 w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = idx0 + u * nthr + tid;
+        const int k = idx < total ? sk[idx / H4] : -1;
+        w[u] = k >= 0 ? *(const float4*)(W1 + (size_t)k * H + 4 * (idx % H4)) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = idx0 + u * nthr + tid;
+        if (idx < total) ((float4*)stage)[idx] = w[u];
+      }
+    }
+    if (kk >= 0) {
+      // order: against the last valid feature before this one
+      int q = tid - 1;
+      while (q >= 0 && sk[q] < 0) --q;
+      const int prev = q >= 0 ? sk[q] : carry[1];
+      if (kk <= prev) flags |= SLIDE_FLAG_UNSORTED;
+      // segment ends: a feature whose predecessor lies in another tile starts its own tile's segment
+      // and ends the predecessor's
+      if (xse) {
+        const int before = tid > 0 ? sk[tid - 1] : carry[0];
+        const int tile = kk / rows_per_tile, tb = before >= 0 ? before / rows_per_tile : -1;
+        if (tb != tile) {
+          xse[(size_t)tile * B + i].x = pb + tid;
+          if (tb >= 0) xse[(size_t)tb * B + i].y = pb + tid;
+        }
+        if (pb + tid == p1 - 1) xse[(size_t)tile * B + i].y = p1;
+      }
+    }
+    __syncthreads();
+    if (tid < H) {
+#pragma unroll 8
+      for (int q = 0; q < cnt; ++q) acc = fmaf(sv[q], stage[(size_t)q * H + tid], acc);
+    }
+    if (tid == 0 && pb + cap < p1) {                     // carries for the next batch
+      int q = cnt - 1;
+      while (q >= 0 && sk[q] < 0) --q;
+      if (q >= 0) carry[1] = sk[q];
+      carry[0] = sk[cnt - 1];
+    }
+    __syncthreads();
+  }
+  if (tid < H) {
+    const float r = acc > 0.f ? acc : 0.f;
+    a.h[(size_t)i * H + tid] = r;
+    hvec[tid] = r;
+  }
+  if (flags) atomicOr(&ctrl->status, flags);
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------
 // h[i][:] = max(0, b1 + sum_k x_ik * W1[k][:]), one fused multiply-add per stored feature, in
 // storage order (so any other fp32 implementation using the same order gets the same bits).
 // One wave per (sample, 128 columns); each lane owns two columns and reads a float2 per W1 row.

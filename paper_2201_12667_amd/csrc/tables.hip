@@ -47,7 +47,7 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s) {
   return hipGetLastError();
 }
 
-constexpr int kSlabBits = 14;
+constexpr int kSlabBits = 15;
 constexpr int kSlab = 1 << kSlabBits;   // rows per slab of the grouping pass
 constexpr int kRunBlock = 1024;         // slabs whose run boundaries a bucket workgroup holds in LDS at a time
 
