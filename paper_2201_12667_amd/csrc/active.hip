@@ -343,7 +343,7 @@ __global__ __launch_bounds__(1024) void lookup_union_kernel(
       const uint4 wd = q < sw / 4 ? ((const uint4*)bm)[q] : make_uint4(0u, 0u, 0u, 0u);
       uint32_t c = __popc(wd.x) + __popc(wd.y) + __popc(wd.z) + __popc(wd.w);
       my_cnt += c;
-      if (q < sw / 4 && segw < ad.NWpad) {               // spill: re-read by the id sweep
+      if (q < sw / 4 && (segw < ad.NWpad || ad.write_act)) {   // spill: re-read by the id sweep / by the row lists
         uint32_t* dst = &ad.act[act_index(ad, i, seg0 + 4 * q)];
         *(uint4*)dst = wd;
       }

@@ -146,7 +146,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   }
   lo->U2max = (int64_t)lo->NWpad * 32;
   lo->P1max = c->max_nnz_per_batch;
-  if (lo->P1max * kPairRegions >= ((int64_t)1 << 31)) FAIL(SLIDE_EINVAL, "max_nnz_per_batch too large");
+  if (lo->P1max * kPairRegions + (int64_t)lo->NT1 * 64 >= ((int64_t)1 << 31)) FAIL(SLIDE_EINVAL, "max_nnz_per_batch too large");
   lo->U1max = (int64_t)lo->DWpad * 32;
   lo->long2 = lo->Amax / kLongRow + 1;
   lo->long1 = lo->P1max / kLongRow + 1;
@@ -179,7 +179,7 @@ int make_layout(const slide_config* c, Layout* lo, std::string& err) {
   lo->partials = take((size_t)lo->max_chunks * (H + 4) * 4);
   lo->msum = take(B * 8); lo->loss_i = take(B * 4);
   lo->umeta2 = take((size_t)lo->U2max * 16); lo->pairs2 = take(A * 8);
-  lo->umeta1 = take((size_t)lo->U1max * 16); lo->pairs1 = take((size_t)lo->P1max * 8 * kPairRegions);
+  lo->umeta1 = take((size_t)lo->U1max * 16); lo->pairs1 = take(((size_t)lo->P1max * kPairRegions + (size_t)lo->NT1 * 64) * 8);
   lo->codes_t = take((size_t)lo->L * lo->N * 4); lo->entries = take((size_t)lo->L * lo->N * 4);
   lo->bh = take(tables_bh_words(lo->bits, lo->N, lo->L) * 4);
   lo->pbase = take(tables_pbase_words(lo->bits, lo->N, lo->L) * 4);
@@ -290,7 +290,7 @@ ActiveDev make_active(const slide_ctx* c, int B) {
   ad.cnt = c->at<int32_t>(lo.cnt); ad.ny = c->at<int32_t>(lo.ny);
   ad.PS = lo.PS; ad.num_labels = 0;
   ad.budget = 0; ad.fill = 0; ad.sample_seed = c->cfg.sample_seed; ad.step = 0;
-  ad.par = 0; ad.nxcd = c->nxcd;
+  ad.par = 0; ad.nxcd = c->nxcd; ad.write_act = 0;
   ad.as_base = c->at<int32_t>(lo.as_base); ad.chunk_ptr = c->at<int32_t>(lo.chunk_ptr);
   ad.as_ids = c->at<int32_t>(lo.as_ids); ad.ylist = c->at<int32_t>(lo.ylist);
   return ad;
@@ -329,7 +329,7 @@ bool row_major(const slide_ctx* ctx, int batch) {
 // the row-list constructions for the features and the active sets that ride in the logits launch (the
 // bit-matrix pointers of t2 are filled in here).
 int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipStream_t s, ActiveDev* ad_out,
-                   const TransposeArgs& t1, TransposeArgs t2, bool split_lists) {
+                   const TransposeArgs& t1, TransposeArgs t2, bool write_act) {
   const Layout& lo = ctx->lo;
   const int B = b->batch;
   const float* h = b->hidden;
@@ -353,6 +353,7 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
   ad.num_labels = with_labels ? b->num_labels : 0;
   ad.par = (int)(ctx->calls++ & 1);
   ad.nxcd = ctx->nxcd;
+  ad.write_act = write_act ? 1 : 0;                    // (row lists from the bitmaps: see slide_train_step)
   if (with_labels) { ad.budget = ctx->cfg.sample_budget; ad.fill = ctx->cfg.sample_fill; ad.step = (uint32_t)(ctx->t + 1); }
   int32_t* ncand = ctx->at<int32_t>(lo.ncand);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_LOOKUP, s, [&] {
@@ -360,12 +361,6 @@ int forward_common(slide_ctx* ctx, const slide_batch* b, bool with_labels, hipSt
                                ncand, ctx->ctrl(), ctx->lds_limit, s); }));
   t2.ids = ad.as_ids; t2.rankT = ad.rankT; t2.as_base = ad.as_base;
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_FORWARD, s, [&] {
-    // When the samples share most rows the logit workers keep the machine busy for long and the row
-    // lists are many: the lists then ride in the combine launch instead (see slide_train_step).
-    if (split_lists)
-      return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
-                            ctx->at<float>(lo.partials), ctx->ctrl(), TransposeArgs{}, TransposeArgs{}, true,
-                            ctx->num_cus, s);
     return launch_forward(ad, lo.H, h, ctx->buf.W2, ctx->buf.b2, ctx->at<float>(lo.z),
                           ctx->at<float>(lo.partials), ctx->ctrl(), t1, t2, true, ctx->num_cus, s); }));
   *ad_out = ad;
@@ -609,11 +604,11 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   PairsDev p2, p1;
   p2.rows_per_tile = lo.TW * 32; p2.ntiles = lo.NT2; p2.tile_nu = ctx->at<int32_t>(lo.tile_nu2);
   p2.umeta = ctx->at<int4>(lo.umeta2); p2.pairs = ctx->at<int2>(lo.pairs2);
-  p2.pcount = nullptr; p2.region_pairs = 0; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
+  p2.pcount = nullptr; p2.region_pairs = 0; p2.region0 = 0; p2.longlist = ctx->at<int32_t>(lo.longlist2); p2.nlong = &ctx->ctrl()->nlong2;
   p2.long_cap = (int)lo.long2; p2.max_nu = &ctx->ctrl()->max_nu2;
   p1.rows_per_tile = lo.TWF * 32; p1.ntiles = lo.NT1; p1.tile_nu = ctx->at<int32_t>(lo.tile_nu1);
   p1.umeta = ctx->at<int4>(lo.umeta1); p1.pairs = ctx->at<int2>(lo.pairs1);
-  p1.pcount = ctx->ctrl()->p1r; p1.region_pairs = (uint32_t)lo.P1max; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
+  p1.pcount = ctx->ctrl()->p1r; p1.region_pairs = (uint32_t)lo.P1max; p1.region0 = 0; p1.longlist = ctx->at<int32_t>(lo.longlist1); p1.nlong = &ctx->ctrl()->nlong1;
   p1.long_cap = (int)lo.long1; p1.max_nu = &ctx->ctrl()->max_nu1;
   const int Bpad = (b->batch + 63) & ~63;
   TransposeArgs t2{}, t1{};
@@ -622,17 +617,28 @@ int slide_train_step(slide_ctx* ctx, const slide_batch* b, float* d_loss, void* 
   if (lo.D > 0) {
     t1.B = b->batch; t1.Bpad = Bpad; t1.TW = lo.TWF; t1.ntiles = lo.NT1; t1.pd = p1;
     t1.ids = b->x_indices; t1.xse = ctx->at<int2>(lo.xse); t1.x_nnz = b->nnz;
+    t1.grouped = (int64_t)b->nnz <= 16 * (int64_t)lo.NT1 ? 1 : 0;   // (a handful of features per tile on average)
+    if (t1.grouped) { p1.region0 = (uint32_t)lo.NT1 * 64u; t1.pd = p1; }
   }
   ActiveDev ad;
   const bool rows_mode = row_major(ctx, b->batch);
-  if ((rc = forward_common(ctx, b, true, s, &ad, t1, t2, rows_mode)) != SLIDE_OK) return rc;
+  // Where the row lists are built.  Usually behind the logit workers of the forward launch.  When the
+  // samples share most rows the logit workers keep the machine busy for long and the lists are many:
+  // they then ride in the combine launch (they are not needed before the update).  The feature tiles of
+  // a very wide input layer, taken a wave each, ride there too.
+  const bool t1_late = rows_mode || t1.grouped, t2_late = rows_mode;
+  if ((rc = forward_common(ctx, b, true, s, &ad, t1_late ? TransposeArgs{} : t1, t2_late ? TransposeArgs{} : t2,
+                           rows_mode)) != SLIDE_OK) return rc;
   t2.ids = ad.as_ids; t2.rankT = ad.rankT; t2.as_base = ad.as_base;   // (for the lists that ride in the combine launch)
+  // With many ids per sample and tile the lists are built from the samples' bitmaps (one coalesced read per
+  // sample and tile) instead of chains of reads of the id lists.
+  if (rows_mode) t2.act = ad.act;
   float* dh = ctx->at<float>(lo.dh);
   float* delta = ctx->at<float>(lo.delta);
   HIPCHK(ctx, stage(ctx, SLIDE_STAGE_COMBINE, s, [&] {
     return launch_combine(ad, lo.H, ctx->last_h, ctx->at<float>(lo.z), ctx->at<float>(lo.partials), ctx->buf.W2,
                           b->y_indptr, ad.ylist, delta, dh, b->dhidden_out, ctx->at<float>(lo.loss_i),
-                          ctx->at<float>(lo.msum), rows_mode ? t1 : TransposeArgs{}, rows_mode ? t2 : TransposeArgs{}, s); }));
+                          ctx->at<float>(lo.msum), t1_late ? t1 : TransposeArgs{}, t2_late ? t2 : TransposeArgs{}, s); }));
   ctx->last_dh = dh;
   const int64_t t = ctx->t + 1;
   AdamDev a;

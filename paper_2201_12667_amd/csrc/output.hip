@@ -163,8 +163,10 @@ __global__ __launch_bounds__(kForwardThreads) void forward_kernel(ActiveDev ad, 
     if (H == LPR * CH * 4) forward_items<LPR, CH, true>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
     else forward_items<LPR, CH, false>(ad, H, h, W2, b2, z, partials, ctrl, k, workers);
   }
-  else if (k < nworkers + t1.ntiles) transpose_tile<true>(t1, k - nworkers, dyn_lds);
-  else transpose_tile<false>(t2, k - nworkers - t1.ntiles, dyn_lds);
+  else {
+    if (k >= nworkers + t1.ntiles) transpose_tile<false, false>(t2, k - nworkers - t1.ntiles, dyn_lds);
+    else transpose_tile<true, false>(t1, k - nworkers, dyn_lds);
+  }
 }
 
 template <int LPR, int CH>
@@ -174,6 +176,7 @@ static hipError_t launch_fwd(const ActiveDev& ad, int H, const float* h, const f
   size_t lds = 0;
   if (t1.ntiles) lds = transpose_lds(t1.TW, t1.Bpad);
   if (t2.ntiles) lds = std::max(lds, transpose_lds(t2.TW, t2.Bpad));
+  if (t1.grouped) return hipErrorInvalidValue;           // (grouped feature tiles ride in the combine launch)
   if (t2.ntiles + t1.ntiles + nworkers == 0) return hipSuccess;
   hipLaunchKernelGGL((forward_kernel<LPR, CH>), dim3(t2.ntiles + t1.ntiles + nworkers), dim3(kForwardThreads),
                      lds, s, ad, H, h, W2, b2, z, partials, ctrl, t1, t2, nworkers);
@@ -282,6 +285,54 @@ __device__ __forceinline__ void combine_sample(const ActiveDev& ad, int H, const
   __syncthreads();
   const float Mi = ms[0], s = ms[1];
   const bool live = n > 0 && ny > 0;
+  // Hidden gradient: column u sums the chunks' partial sums (scaled) and subtracts the label rows.  A
+  // column's chain of reads is what this costs, so when the workgroup has several threads per column
+  // each takes a stretch of the chunks (eight reads in flight) and the stretches are added in order.
+  const int nsub = H <= kCombineThreads ? kCombineThreads / H : 1;
+  if (nsub > 1) {
+    __shared__ float part[kCombineThreads];              // [nsub][H] sums of the stretches
+    __shared__ float ysum[kCombineThreads];              // [H] sum of the label rows
+    const int u = tid % H, sub = tid / H;
+    if (sub < nsub) {
+      float acc = 0.f, accy = 0.f;
+      if (live && h[(size_t)i * H + u] > 0.f) {
+        const float* pu = pmine + 4 + u;
+        const int nchl = min(nch, kMaxCh), per = (nchl + nsub - 1) / nsub;
+        const int ce = min(nchl, (sub + 1) * per);
+        int c = sub * per;
+        for (; c + 8 <= ce; c += 8) {
+          float a[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) a[k] = pu[(size_t)(c + k) * PS];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) acc += a[k] * scale[c + k];
+        }
+        for (; c < ce; ++c) acc += pu[(size_t)c * PS] * scale[c];
+        if (sub == nsub - 1) {
+          for (c = kMaxCh; c < nch; ++c) acc += pu[(size_t)c * PS] * __expf(pu[(size_t)c * PS - 4 - u] - Mi);
+          for (int q = 0; q < nlab; ++q) {
+            int j;
+            if (q < kMaxLab) j = ylab[q];
+            else { const int slot = ylist[y0 + q]; j = slot >= 0 ? ad.as_ids[slot] : -1; }
+            if (j >= 0) accy += W2[(size_t)j * H + u];
+          }
+          ysum[u] = accy;
+        }
+      }
+      part[tid] = acc;
+    }
+    __syncthreads();
+    if (tid < H) {
+      float g = 0.f;
+      if (live && h[(size_t)i * H + tid] > 0.f) {
+        float acc = 0.f;
+        for (int k = 0; k < nsub; ++k) acc += part[k * H + tid];
+        g = (acc / s - ysum[tid] / (float)ny) * invB;
+      }
+      dh[(size_t)i * H + tid] = g;
+      if (dh_copy) dh_copy[(size_t)i * H + tid] = g;
+    }
+  } else
   for (int u = tid; u < H; u += kCombineThreads) {
     float g = 0.f;
     if (live && h[(size_t)i * H + u] > 0.f) {
@@ -313,17 +364,26 @@ __device__ __forceinline__ void combine_sample(const ActiveDev& ad, int H, const
   // slot is compared with them.  Many: the labels' slots are rewritten in a second pass.
   constexpr int kFewLabels = 16;
   const bool few = nlab <= kFewLabels;
-  for (int q = tid; q < n; q += kCombineThreads) {
-    const int slot = first + q;
-    float d = 0.f;
-    if (live) {
-      const float zz = z[slot];
-      bool lab = false;
-      if (few) for (int y = 0; y < nlab; ++y) lab |= yslot[y] == slot;
-      d = (__expf(zz - Mi) / s - (lab ? yv : 0.f)) * invB;
-      if (lab) lacc -= yv * (zz - Mi - logs);
+  for (int q0 = tid; q0 < n; q0 += 4 * kCombineThreads) {  // four logits per thread in flight
+    float zz[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int q = q0 + k * kCombineThreads;
+      zz[k] = (live && q < n) ? z[first + q] : 0.f;
     }
-    delta[slot] = d;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int q = q0 + k * kCombineThreads, slot = first + q;
+      if (q >= n) continue;
+      float d = 0.f;
+      if (live) {
+        bool lab = false;
+        if (few) for (int y = 0; y < nlab; ++y) lab |= yslot[y] == slot;
+        d = (__expf(zz[k] - Mi) / s - (lab ? yv : 0.f)) * invB;
+        if (lab) lacc -= yv * (zz[k] - Mi - logs);
+      }
+      delta[slot] = d;
+    }
   }
   if (!few) {
     __syncthreads();                                     // (orders the first pass's writes before these)
@@ -348,13 +408,14 @@ __device__ __forceinline__ void combine_sample(const ActiveDev& ad, int H, const
 // The samples' workgroups; behind them, optionally, the row-list tiles (t1: features, t2: active sets):
 // the lists depend on the lookup only and are not needed before the update launch, and when they are many
 // (batches whose samples share most rows) they are best kept out of the logit workers' way.
-__global__ __launch_bounds__(kCombineThreads) void combine_kernel(ActiveDev ad, int H, CombineArgs ca, TransposeArgs t1,
+__global__ __launch_bounds__(kCombineThreads, 6) void combine_kernel(ActiveDev ad, int H, CombineArgs ca, TransposeArgs t1,
                                                                   TransposeArgs t2) {
   extern __shared__ uint32_t dyn_lds[];
   const int k = blockIdx.x;
+  const int r1 = transpose_roles(t1, kCombineThreads);
   if (k < ad.B) combine_sample(ad, H, ca, k);
-  else if (k < ad.B + t1.ntiles) transpose_tile<true>(t1, k - ad.B, dyn_lds);
-  else transpose_tile<false>(t2, k - ad.B - t1.ntiles, dyn_lds);
+  else if (k >= ad.B + r1) transpose_tile<false, true>(t2, k - ad.B - r1, dyn_lds);
+  else feature_tile_role(t1, k - ad.B, dyn_lds);
 }
 
 static hipError_t combine_setup_attributes(int lim) {
@@ -370,7 +431,8 @@ hipError_t launch_combine(const ActiveDev& ad, int H, const float* h, const floa
   size_t lds = 0;
   if (t1.ntiles) lds = transpose_lds(t1.TW, t1.Bpad);
   if (t2.ntiles) lds = std::max(lds, transpose_lds(t2.TW, t2.Bpad));
-  hipLaunchKernelGGL(combine_kernel, dim3(ad.B + t1.ntiles + t2.ntiles), dim3(kCombineThreads), lds, s, ad, H, ca, t1, t2);
+  hipLaunchKernelGGL(combine_kernel, dim3(ad.B + transpose_roles(t1, kCombineThreads) + t2.ntiles), dim3(kCombineThreads), lds, s, ad, H,
+                     ca, t1, t2);
   return hipGetLastError();
 }
 

@@ -100,7 +100,8 @@ struct ActiveDev {
   int nxcd;                        // accelerator dies whose workgroups alternate in launch order (1: unknown)
   int budget, fill;                // sampling budget of this call (0 = none) and its fill option
   uint32_t sample_seed, step;      // keys of the counter-based generator: seed, number of the step being run
-  uint32_t* act;                   // [NT][B][TW] bitmap spill, used only when a sample's bitmap exceeds LDS
+  uint32_t* act;                   // [NT][B][TW] the samples' bitmaps, tile-major: written when a bitmap exceeds the LDS
+  int write_act;                   // ... or when the row lists are to be built from the bitmaps (!= 0)
   uint32_t* rankT;                 // [NT+1][B] active neurons of the sample below the tile (last row: |AS_i|)
   int32_t* cnt;                    // [B] |AS_i|
   int32_t* ny;                     // [B] distinct labels
@@ -118,6 +119,7 @@ struct PairsDev {
   int2* pairs;      // [pairs] (sample, index into the coefficient array)
   uint32_t* pcount; // pair space counters, kPairRegions of them (input layer only)
   uint32_t region_pairs; // pair slots per region
+  uint32_t region0;      // pair slots ahead of the regions (64 per tile when a wave takes a tile: no counter)
   int32_t* longlist; // [long_cap] slots of rows with more than kLongRow pairs
   uint32_t* nlong;
   int long_cap;
@@ -126,9 +128,12 @@ struct PairsDev {
 
 struct TransposeArgs {
   int B, Bpad, TW, ntiles;       // a tile is TW*32 rows; ntiles = 0: nothing to do
+  int grouped;                   // features only: a wave per tile, a workgroup per group of tiles (tiles that hold
+                                 // a handful of the batch's features each)
   const int32_t* ids;            // ascending id list per sample (active-set ids / CSR feature indices)
   const uint32_t* rankT;         // [ntiles+1][B] (active sets only) ids of the sample below the tile
   const int32_t* as_base;        // [B]           (active sets only) first slot of the sample
+  const uint32_t* act;           // [ntiles][B][TW] (active sets only, optional) the samples' bitmaps: read instead of ids
   int2* xse;                     // [ntiles][B]   (features only) positions [start, end) of the sample's
                                  // features inside the tile; (0, 0) = none
   int x_nnz;                     // features only: entries in the batch's CSR arrays

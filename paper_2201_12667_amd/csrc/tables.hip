@@ -143,8 +143,9 @@ __global__ __launch_bounds__(1024) void part_scan_kernel(const uint32_t* __restr
 }
 
 constexpr int kStageIds = 4096;    // ids of a partition staged in LDS by part_buckets (larger partitions go through memory)
-constexpr int kRankMax = 64;       // staged buckets up to this size are ordered by counting, in place
+constexpr int kRankMax = 64;       // staged buckets up to this size are sorted where they are staged
 constexpr int kWaveSort = 64;      // queued buckets up to this size (within capacity) are sorted by one wave
+constexpr int kMedCap = kStageIds / 9 + 1;   // staged buckets of more than eight ids that a partition can hold
 constexpr int kSlotBatch = 16;     // 64-entry pieces of runs a wave keeps in flight
 
 // One workgroup per (partition d, table t): buckets (d << lb) .. (d << lb) + 2^lb - 1.  The partition's
@@ -172,6 +173,8 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   const int slot_cap = nsb + kStageIds / 64;
   int32_t* idl = (int32_t*)(slots + slot_cap);                 // [kStageIds] the partition's ids grouped by bucket
   uint32_t* nslots_p = (uint32_t*)(idl + kStageIds);           // [1]
+  uint32_t* nmed_p = nslots_p + 1;                             // [2] staged buckets of 9 .. 16 ids / of 17 .. kRankMax
+  uint32_t* medq = nmed_p + 2;                                 // [kMedCap] the former from the front, the latter from the back
   const uint32_t* tent = entries + t * N;
   const uint32_t* truns = runs + t * nslab * (size_t)(nbins + 1) + d;
   // The partition's entries are visited twice (count, then place).  The slabs are taken in blocks of nsb:
@@ -243,6 +246,7 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   bool cached = false;
   int ns0 = 0;
   for (int b = tid; b < nlo; b += 256) cur[b] = 0;
+  if (tid < 2) nmed_p[tid] = 0;
   if (single) {
     ns0 = prepare(0);
     const int nslots = (int)*nslots_p;
@@ -310,10 +314,10 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   };
   if (staged) {
     // The ids sit in idl grouped by bucket, in arrival order; a thread takes a bucket.  Up to eight
-    // ids (nearly every bucket) are sorted in registers by a fixed network of comparators -- the same
-    // instructions in every lane, whatever the bucket's size -- and go straight to the table.  Longer
-    // buckets are sorted in LDS by their thread; those beyond kRankMax or over capacity are copied as
-    // they are and queued.
+    // ids (nearly every bucket of a fresh layer) are sorted in registers by a fixed network of
+    // comparators -- the same instructions in every lane, whatever the bucket's size -- and go straight
+    // to the table.  Longer buckets are noted for the pass below; those beyond kRankMax or over
+    // capacity are copied as they are and queued.
     for (int b0 = 0; b0 < nlo; b0 += 256) {
       const int b = b0 + tid;                        // (every lane runs the loop: the network is wave-wide)
       const uint32_t a = (b && b < nlo) ? cur[b - 1] : 0u, sz = b < nlo ? cur[b] - a : 0u;
@@ -322,15 +326,10 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
       if (big) {
         for (uint32_t q = a; q < a + sz; ++q) seg[q] = idl[q];
         enqueue(b, sz);
-      } else if (sz > 8u) {
-        int32_t* p = idl + a;
-        for (uint32_t i = 1; i < sz; ++i) {
-          const int32_t key = p[i];
-          int q = (int)i - 1;
-          while (q >= 0 && p[q] > key) { p[q + 1] = p[q]; --q; }
-          p[q + 1] = key;
-        }
-        for (uint32_t q = a; q < a + sz; ++q) seg[q] = idl[q];
+      } else if (sz > 16u) {
+        medq[kMedCap - 1 - atomicAdd(&nmed_p[1], 1u)] = (uint32_t)b;   // (lane groups / waves order these below:
+      } else if (sz > 8u) {                                             //  at most kStageIds / 9 of them exist)
+        medq[atomicAdd(&nmed_p[0], 1u)] = (uint32_t)b;
       }
       const uint32_t n8 = (big || sz > 8u) ? 0u : sz;
       if (!__any(n8 > 1u)) {                             // (sparse tables: nearly every bucket is empty or a single id)
@@ -358,6 +357,36 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         if ((uint32_t)i < n8) seg[a + i] = v[i];
+    }
+    // Longer buckets (a trained layer has many): one thread sorting its bucket alone would hold up its
+    // wave for the square of the bucket's length.  9 .. 16 ids: a row of 16 lanes each, an id per lane,
+    // its place = the number of smaller ids in the row (register moves only).  17 .. kRankMax: a wave
+    // each, a bitonic sort across the lanes.
+    __syncthreads();
+    const uint32_t nrow = nmed_p[0], nwav = nmed_p[1];
+    for (uint32_t m0 = 0; m0 < nrow; m0 += 16) {
+      const uint32_t m = m0 + (uint32_t)(tid >> 4);
+      const int l16 = tid & 15;
+      uint32_t a = 0, sz = 0;
+      if (m < nrow) { const uint32_t b = medq[m]; a = b ? cur[b - 1] : 0u; sz = cur[b] - a; }
+      const int32_t key = (uint32_t)l16 < sz ? idl[a + l16] : 0x7fffffff;
+      const uint32_t rank = row_rank_i32(key);
+      if ((uint32_t)l16 < sz) seg[a + rank] = key;
+    }
+    for (uint32_t m = wave; m < nwav; m += 4) {
+      const uint32_t b = medq[kMedCap - 1 - m];
+      const uint32_t a = b ? cur[b - 1] : 0u, sz = cur[b] - a;
+      int32_t key = (uint32_t)lane < sz ? idl[a + lane] : 0x7fffffff;
+#pragma unroll
+      for (int k = 2; k <= 64; k <<= 1)
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+          const int32_t other = __shfl_xor(key, j);
+          const bool up = (lane & k) == 0, lower = (lane & j) == 0;
+          const int32_t mn = key < other ? key : other, mx = key < other ? other : key;
+          key = (lower == up) ? mn : mx;
+        }
+      if ((uint32_t)lane < sz) seg[a + lane] = key;
     }
   } else {
     for (int b = tid; b < nlo; b += 256) {
@@ -513,7 +542,7 @@ size_t tables_pbase_words(int bits, int64_t N, int L) {
 static int run_block(int nslab) { return nslab < kRunBlock ? nslab : kRunBlock; }
 static size_t part_buckets_lds(int lb, int nsb) {
   const size_t nlo = (size_t)1 << lb;
-  return (nlo + ((nlo + 63) >> 6) + 3 * (size_t)nsb + kStageIds / 64 + kStageIds + 1) * 4;
+  return (nlo + ((nlo + 63) >> 6) + 3 * (size_t)nsb + kStageIds / 64 + kStageIds + 3 + kMedCap) * 4;
 }
 static size_t slab_group_lds(int nbins) { return ((size_t)kSlab + (size_t)nbins + 20) * 4; }
 
@@ -598,3 +627,4 @@ hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const flo
 }
 
 }  // namespace slide
+

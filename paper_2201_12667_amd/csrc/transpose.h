@@ -28,7 +28,7 @@ namespace slide {
 // no sort, no global atomics on the data.
 constexpr int kInFlight = 4;    // ids a thread requests before it uses the first
 
-template <bool FEAT, int TW>
+template <bool FEAT, int TW, bool BITS = false>
 __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int tileno, uint32_t* lds) {
   constexpr int ROWS = TW * 32;
   const int B = ta.B, Bpad = ta.Bpad;
@@ -102,7 +102,7 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
         uint32_t base = 0;
         if (lane == 0) {
           pd.tile_nu[tileno] = (int32_t)nu;
-          base = n ? (uint32_t)(tileno % kPairRegions) * pd.region_pairs + atomicAdd(&pd.pcount[tileno % kPairRegions], n) : 0u;
+          base = n ? pd.region0 + (uint32_t)(tileno % kPairRegions) * pd.region_pairs + atomicAdd(&pd.pcount[tileno % kPairRegions], n) : 0u;
           if (nu > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, nu);
         }
         base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
@@ -167,6 +167,33 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
     klo[j] = lo; khi[j] = hi;
     uint32_t* tc = T + (size_t)(i >> 5) * ROWS;
     const uint32_t ibit = 1u << (i & 31);
+    if (BITS && !FEAT && TW >= 4) {
+      // from the sample's bitmap of the tile (TW words, one coalesced read): the thread's share of the words
+      if (i < B) {
+        const uint32_t* sw = ta.act + ((size_t)tileno * B + i) * TW;
+        const int w0 = share * TW / shares, w1 = (share + 1) * TW / shares;
+#pragma unroll
+        for (int w4 = 0; w4 < TW; w4 += 4) {
+          if (w4 + 4 <= w0 || w4 >= w1) continue;
+          const uint4 q = *(const uint4*)(sw + w4);
+          const uint32_t ww[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            uint32_t word = (w4 + k >= w0 && w4 + k < w1) ? ww[k] : 0u;
+            while (word) {
+              const int b = __ffs(word) - 1;
+              word &= word - 1;
+              atomicOr(&tc[(w4 + k) * 32 + b], ibit);
+            }
+          }
+        }
+      }
+      if (!FEAT) {
+        const uint32_t s = wave_sum(rank0);
+        if (lane == 0 && s) atomicAdd(&blk[1], s);
+      }
+      continue;
+    }
     // this thread's ids: lo + 4*share + (0..3), then every 4*shares further on
 #pragma unroll
     for (int k = 0; k < kKeep; ++k) {
@@ -222,7 +249,7 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
     if (lane == 63) {
       nu_tile = cin;
       pd.tile_nu[tileno] = (int32_t)cin;
-      blk[0] = FEAT ? (pin ? (uint32_t)(tileno % kPairRegions) * pd.region_pairs + atomicAdd(&pd.pcount[tileno % kPairRegions], pin) : 0u)
+      blk[0] = FEAT ? (pin ? pd.region0 + (uint32_t)(tileno % kPairRegions) * pd.region_pairs + atomicAdd(&pd.pcount[tileno % kPairRegions], pin) : 0u)
                     : blk[1];
     }
   }
@@ -260,6 +287,31 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
                              __popc(t_hi[row] & hi_mask);
       pd.pairs[place] = make_int2(i, pos);
     };
+    if (BITS && !FEAT && TW >= 4) {
+      // the bitmap again: a set bit's coefficient index is the segment's start plus the bits below it
+      if (i < B) {
+        const uint32_t* sw = ta.act + ((size_t)tileno * B + i) * TW;
+        const int w0 = share * TW / shares, w1 = (share + 1) * TW / shares;
+        int pos = lo;
+#pragma unroll
+        for (int w4 = 0; w4 < TW; w4 += 4) {
+          if (w4 >= w1) continue;
+          const uint4 q = *(const uint4*)(sw + w4);
+          const uint32_t ww[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            uint32_t word = ww[k];
+            if (w4 + k < w0 || w4 + k >= w1) { pos += __popc(word); continue; }
+            while (word) {
+              const int b = __ffs(word) - 1;
+              word &= word - 1;
+              emit((w4 + k) * 32 + b, pos++);
+            }
+          }
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int k = 0; k < kKeep; ++k)
       if ((unsigned)krow[j][k] < (unsigned)ROWS) emit(krow[j][k], lo + 4 * share + (k >> 2) * 4 * shares + (k & 3));
@@ -294,21 +346,166 @@ __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int ti
   if (wave == 0 && lane == 63 && nu_tile > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, nu_tile);
 }
 
-template <bool FEAT>
+// Feature tiles of a very wide input layer: nearly every tile holds a handful of the batch's features,
+// or none, and a workgroup per tile would spend its time on fixed latencies.  Here a workgroup takes
+// as many consecutive tiles as it has waves, a wave per tile: the wave counts the tile's entries,
+// gathers up to 64 of them in its own corner of the LDS, sorts the (row, sample) keys across its lanes
+// and writes the tile's lists.  Tiles with more entries are left to the whole workgroup afterwards.
+template <int TW>
+__device__ __forceinline__ int feature_tile_group_t(const TransposeArgs& ta, int group, uint32_t* lds, int* big) {
+  constexpr int ROWS = TW * 32;
+  const int B = ta.B;
+  const PairsDev& pd = ta.pd;
+  const int32_t* __restrict__ ids = ta.ids;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)blockDim.x >> 6;
+  int& nbig = big[16];                                   // big[0 .. 15]: tiles left to the workgroup (one per wave at most)
+  if (tid == 0) nbig = 0;
+  __syncthreads();
+  const int tileno = group * nw + wave;
+  if (tileno < ta.ntiles) {
+    const int row0 = tileno * ROWS;
+    uint32_t* skey = lds + wave * 132;                   // [64] row in tile << 16 | sample
+    uint32_t* spos = skey + 64;                          // [64] position in the batch's feature arrays
+    uint32_t* cnt = spos + 64;                           // [1]
+    // the tile's segments, four per lane at a time with their reads in flight together (a batch of up to
+    // 256 samples: the registers of the count serve the gather as well)
+    int2 v[4];
+    auto load_chunk = [&](int i0) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int i = i0 + k * 64 + lane;
+        v[k] = i < B ? ta.xse[(size_t)tileno * B + i] : make_int2(0, 0);
+      }
+    };
+    const int nchunk = (B + 255) >> 8;
+    uint32_t total = 0;
+    for (int ch = 0; ch < nchunk; ++ch) {
+      load_chunk(ch << 8);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int lo = max(v[k].x, 0), hi = min(v[k].y, ta.x_nnz);
+        total += hi > lo ? (uint32_t)(hi - lo) : 0u;
+      }
+    }
+    total = wave_sum(total);
+    if (total > 64u) {
+      if (lane == 0) big[atomicAdd(&nbig, 1)] = tileno;
+    } else {
+      if (lane == 0) *cnt = 0;
+      __builtin_amdgcn_wave_barrier();
+      for (int ch = 0; ch < nchunk; ++ch) {              // (an empty tile still clears what bad data may have left)
+          if (nchunk > 1) load_chunk(ch << 8);
+          int first[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {                   // (nearly every segment holds one feature)
+            const int lo = max(v[k].x, 0), hi = min(v[k].y, ta.x_nnz);
+            first[k] = hi > lo ? ids[lo] : -1;
+          }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int i = (ch << 8) + k * 64 + lane;
+            const int lo = max(v[k].x, 0), hi = min(v[k].y, ta.x_nnz);
+            for (int p = lo; p < hi; ++p) {
+              const int r = (p == lo ? first[k] : ids[p]) - row0;
+              if ((unsigned)r < (unsigned)ROWS) {
+                const uint32_t at = atomicAdd(cnt, 1u);
+                if (at < 64u) { skey[at] = ((uint32_t)r << 16) | (uint32_t)i; spos[at] = (uint32_t)p; }
+              }
+            }
+            if (v[k].x | v[k].y) ta.xse[(size_t)tileno * B + i] = make_int2(0, 0);   // all-zero again for the next batch
+          }
+        }
+      __builtin_amdgcn_wave_barrier();
+      const uint32_t n = min(*cnt, 64u);
+      uint32_t key = (uint32_t)lane < n ? skey[lane] : 0xffffffffu;
+      uint32_t pos = (uint32_t)lane < n ? spos[lane] : 0u;
+#pragma unroll
+      for (int k = 2; k <= 64; k <<= 1)                   // bitonic sort across the lanes, ascending keys
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+          const uint32_t okey = __shfl_xor(key, j), opos = __shfl_xor(pos, j);
+          const bool up = (lane & k) == 0, lower = (lane & j) == 0;
+          const bool take = (lower == up) ? okey < key : okey > key;
+          if (take) { key = okey; pos = opos; }
+        }
+      const uint32_t prev = __shfl_up(key, 1);
+      const bool head = (uint32_t)lane < n && (lane == 0 || (prev >> 16) != (key >> 16));
+      const unsigned long long heads = __ballot(head);
+      const uint32_t nu = (uint32_t)__popcll(heads);
+      if (lane == 0) {
+        pd.tile_nu[tileno] = (int32_t)nu;
+        if (nu > *(volatile uint32_t*)pd.max_nu) atomicMax(pd.max_nu, nu);
+      }
+      const uint32_t base = (uint32_t)tileno * 64u;      // (these tiles have 64 pairs of room each, ahead of the regions)
+      if ((uint32_t)lane < n) pd.pairs[base + lane] = make_int2((int)(key & 0xffffu), (int)pos);
+      if (head) {
+        const unsigned long long above = lane < 63 ? heads >> (lane + 1) : 0ull;
+        const uint32_t c = above ? (uint32_t)__ffsll((long long)above) : n - (uint32_t)lane;
+        const uint32_t us = (uint32_t)tileno * (uint32_t)ROWS + (uint32_t)__popcll(heads & ((1ull << lane) - 1ull));
+        pd.umeta[us] = make_int4(row0 + (int)(key >> 16), (int)(base + lane), (int)c, 0);
+        if (ta.touched) ta.touched[row0 + (int)(key >> 16)] = 1;
+        if ((int)c > kLongRow) {
+          const uint32_t l = atomicAdd(pd.nlong, 1u);
+          if (l < (uint32_t)pd.long_cap) pd.longlist[l] = (int32_t)us;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  return __builtin_amdgcn_readfirstlane(nbig);
+}
+
+// The feature tiles of workgroup role `role` of a launch: its own tile, or -- in grouped mode -- the
+// tiles of its group that its waves could not finish alone.
+template <int TW>
+__device__ __forceinline__ void feature_tile_role_t(const TransposeArgs& ta, int role, uint32_t* lds) {
+  __shared__ int big[17];                                // [0 .. 15] tiles left to the whole workgroup, [16] their number
+  int nb = 1;
+  if (ta.grouped) nb = feature_tile_group_t<TW>(ta, role, lds, big);
+#pragma unroll 1
+  for (int q = 0; q < nb; ++q) {
+    const int t = ta.grouped ? __builtin_amdgcn_readfirstlane(big[q]) : role;
+    __syncthreads();
+    transpose_tile_t<true, TW, false>(ta, t, lds);
+  }
+}
+
+// (the choice of the tile size stays outside the loop above: one copy of the tile code per loop)
+__device__ __forceinline__ void feature_tile_role(const TransposeArgs& ta, int role, uint32_t* lds) {
+  switch (ta.TW) {
+    case 32: feature_tile_role_t<32>(ta, role, lds); break;
+    case 16: feature_tile_role_t<16>(ta, role, lds); break;
+    case 8: feature_tile_role_t<8>(ta, role, lds); break;
+    case 4: feature_tile_role_t<4>(ta, role, lds); break;
+    case 2: feature_tile_role_t<2>(ta, role, lds); break;
+    default: feature_tile_role_t<1>(ta, role, lds); break;
+  }
+}
+
+template <bool FEAT, bool BITS>
 __device__ __forceinline__ void transpose_tile(const TransposeArgs& ta, int tileno, uint32_t* lds) {
   switch (ta.TW) {
-    case 32: transpose_tile_t<FEAT, 32>(ta, tileno, lds); break;
-    case 16: transpose_tile_t<FEAT, 16>(ta, tileno, lds); break;
-    case 8: transpose_tile_t<FEAT, 8>(ta, tileno, lds); break;
-    case 4: transpose_tile_t<FEAT, 4>(ta, tileno, lds); break;
-    case 2: transpose_tile_t<FEAT, 2>(ta, tileno, lds); break;
-    default: transpose_tile_t<FEAT, 1>(ta, tileno, lds); break;
+    case 32: transpose_tile_t<FEAT, 32, BITS>(ta, tileno, lds); break;
+    case 16: transpose_tile_t<FEAT, 16, BITS>(ta, tileno, lds); break;
+    case 8: transpose_tile_t<FEAT, 8, BITS>(ta, tileno, lds); break;
+    case 4: transpose_tile_t<FEAT, 4, BITS>(ta, tileno, lds); break;
+    case 2: transpose_tile_t<FEAT, 2, BITS>(ta, tileno, lds); break;
+    default: transpose_tile_t<FEAT, 1, BITS>(ta, tileno, lds); break;
   }
+}
+
+// Workgroups a launch spends on the tiles of `t` (workgroups of `threads` threads).
+__host__ __device__ inline int transpose_roles(const TransposeArgs& t, int threads) {
+  const int per = threads >> 6;
+  return t.grouped ? (t.ntiles + per - 1) / per : t.ntiles;
 }
 
 inline size_t transpose_lds(int TW, int Bpad) {
   const size_t rows = (size_t)TW * 32, GW = (size_t)Bpad >> 5, groups = (size_t)Bpad >> 6;
-  return (rows * GW + rows + (size_t)TW * 3 + 4 + rows) * 4 + rows * 2 + groups * rows * 2;
+  const size_t tile = (rows * GW + rows + (size_t)TW * 3 + 4 + rows) * 4 + rows * 2 + groups * rows * 2;
+  const size_t waves = 16 * 132 * 4;                     // a corner per wave when the waves take a tile each
+  return tile > waves ? tile : waves;
 }
 
 }  // namespace slide

@@ -10,6 +10,7 @@ namespace slide {
 constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm:[1,0,3,2]
 constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm:[2,3,0,1]
 constexpr int kDppRowShr = 0x110;        // + n: lane i reads lane i-n of its 16-lane row
+constexpr int kDppRowRor = 0x120;        // + n: lane i reads lane (i - n) mod 16 of its row
 constexpr int kDppRowMirror = 0x140;     // lane i reads lane 15-i of its row
 constexpr int kDppRowHalfMirror = 0x141; // lane i reads lane 7-i of its half row
 constexpr int kDppRowBcast15 = 0x142;    // lane 15 of each row to the whole next row
@@ -84,6 +85,17 @@ __device__ __forceinline__ uint32_t small_group_incl_scan_add(uint32_t v, int G)
 }
 // Sum over aligned groups of G lanes, valid in the LAST lane of each group.
 __device__ __forceinline__ uint32_t group_sum_last(uint32_t v, int G) { return group_incl_scan_add(v, G); }
+
+// Number of the other 15 lanes of the 16-lane row whose value is smaller (values distinct within a
+// row, up to repeated padding values that no lane uses): the lane's rank in the row's order.
+__device__ __forceinline__ uint32_t row_rank_i32(int32_t v) {
+  uint32_t r = 0;
+#define SLIDE_ROR(n) r += (int32_t)dpp_u32<kDppRowRor + n>(0u, (uint32_t)v) < v ? 1u : 0u;
+  SLIDE_ROR(1) SLIDE_ROR(2) SLIDE_ROR(3) SLIDE_ROR(4) SLIDE_ROR(5) SLIDE_ROR(6) SLIDE_ROR(7) SLIDE_ROR(8)
+  SLIDE_ROR(9) SLIDE_ROR(10) SLIDE_ROR(11) SLIDE_ROR(12) SLIDE_ROR(13) SLIDE_ROR(14) SLIDE_ROR(15)
+#undef SLIDE_ROR
+  return r;
+}
 
 // Sum over aligned groups of 8 / 16 lanes, returned in every lane of the group.
 __device__ __forceinline__ float sum8(float v) {

@@ -101,6 +101,14 @@ def test_degenerate_tables_all_rows_identical():
                                   input_dim=700, nnz_mean=5.0, bucket_cap=8)),
     ("b2048-tile128", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=5, L=4, batch=2048, num_classes=3001,
                                   input_dim=0, bucket_cap=8)),
+    # very wide inputs: the feature tiles hold a handful of the batch's features each (a wave per tile),
+    # the tiles of the popular features far more (left to the whole workgroup); uniform features: no such tile
+    ("wide-input-zipf", synth.small(synth.HASH_DWTA, hidden_dim=64, K=3, L=9, batch=256, num_classes=6007,
+                                    input_dim=300001, nnz_mean=8.0, bucket_cap=8)),
+    ("wide-input-uniform", synth.small(synth.HASH_SIMHASH, hidden_dim=32, K=6, L=7, batch=70, num_classes=5003,
+                                       input_dim=150001, nnz_mean=3.0, bucket_cap=8, feat_zipf_s=None)),
+    ("wide-input-b600", synth.small(synth.HASH_DWTA, hidden_dim=32, K=3, L=5, batch=600, num_classes=4001,
+                                    input_dim=400001, nnz_mean=4.0, bucket_cap=8)),
     # the largest bucket capacity: every bucket holds more than 1024 neurons, 5120 candidates per sample
     ("cap1024", synth.small(synth.HASH_SIMHASH, K=4, L=5, bucket_cap=1024, num_classes=60000, batch=9)),
 ])
