@@ -33,12 +33,83 @@ __device__ __forceinline__ uint32_t dwta_key(float x) {
 //
 // Winner position of elementary hash e for the vector whose keys start at byte address col0 of the
 // tile; -1 when the bin has no entry.  Strictly greater wins, so ties keep the lowest position.
+// Eight keys of the lane's vector at the (wave-uniform) byte offsets o[0..8) of the tile, whose vector
+// of lane l starts 4*l bytes into every coordinate's row: the read that adds the lane number to a scalar
+// base address, so that no lane spends an instruction on the address (a wait state between the write of
+// the base register and the read is required on this family).  tile_base: LDS address of the tile.
+__device__ __forceinline__ void read8_lane_rows(uint32_t (&k)[8], const uint32_t* __restrict__ o, uint32_t tile_base) {
+  asm volatile(
+      "s_add_u32 m0, %16, %8\n\ts_nop 0\n\tds_read_addtid_b32 %0\n\t"
+      "s_add_u32 m0, %16, %9\n\ts_nop 0\n\tds_read_addtid_b32 %1\n\t"
+      "s_add_u32 m0, %16, %10\n\ts_nop 0\n\tds_read_addtid_b32 %2\n\t"
+      "s_add_u32 m0, %16, %11\n\ts_nop 0\n\tds_read_addtid_b32 %3\n\t"
+      "s_add_u32 m0, %16, %12\n\ts_nop 0\n\tds_read_addtid_b32 %4\n\t"
+      "s_add_u32 m0, %16, %13\n\ts_nop 0\n\tds_read_addtid_b32 %5\n\t"
+      "s_add_u32 m0, %16, %14\n\ts_nop 0\n\tds_read_addtid_b32 %6\n\t"
+      "s_add_u32 m0, %16, %15\n\ts_nop 0\n\tds_read_addtid_b32 %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2]), "=&v"(k[3]), "=&v"(k[4]), "=&v"(k[5]), "=&v"(k[6]), "=&v"(k[7])
+      : "s"(o[0]), "s"(o[1]), "s"(o[2]), "s"(o[3]), "s"(o[4]), "s"(o[5]), "s"(o[6]), "s"(o[7]), "s"(tile_base)
+      : "m0", "scc", "memory");
+}
+
+// The same for two bins at once (sixteen reads in flight before the wait).
+__device__ __forceinline__ void read16_lane_rows(uint32_t (&a)[8], uint32_t (&b)[8], const uint32_t* __restrict__ oa,
+                                                 const uint32_t* __restrict__ ob, uint32_t tile_base) {
+  asm volatile(
+      "s_add_u32 m0, %16, %8\n\ts_nop 0\n\tds_read_addtid_b32 %0\n\t"
+      "s_add_u32 m0, %16, %9\n\ts_nop 0\n\tds_read_addtid_b32 %1\n\t"
+      "s_add_u32 m0, %16, %10\n\ts_nop 0\n\tds_read_addtid_b32 %2\n\t"
+      "s_add_u32 m0, %16, %11\n\ts_nop 0\n\tds_read_addtid_b32 %3\n\t"
+      "s_add_u32 m0, %16, %12\n\ts_nop 0\n\tds_read_addtid_b32 %4\n\t"
+      "s_add_u32 m0, %16, %13\n\ts_nop 0\n\tds_read_addtid_b32 %5\n\t"
+      "s_add_u32 m0, %16, %14\n\ts_nop 0\n\tds_read_addtid_b32 %6\n\t"
+      "s_add_u32 m0, %16, %15\n\ts_nop 0\n\tds_read_addtid_b32 %7"
+      : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3]), "=&v"(a[4]), "=&v"(a[5]), "=&v"(a[6]), "=&v"(a[7])
+      : "s"(oa[0]), "s"(oa[1]), "s"(oa[2]), "s"(oa[3]), "s"(oa[4]), "s"(oa[5]), "s"(oa[6]), "s"(oa[7]), "s"(tile_base)
+      : "m0", "scc", "memory");
+  asm volatile(
+      "s_add_u32 m0, %16, %8\n\ts_nop 0\n\tds_read_addtid_b32 %0\n\t"
+      "s_add_u32 m0, %16, %9\n\ts_nop 0\n\tds_read_addtid_b32 %1\n\t"
+      "s_add_u32 m0, %16, %10\n\ts_nop 0\n\tds_read_addtid_b32 %2\n\t"
+      "s_add_u32 m0, %16, %11\n\ts_nop 0\n\tds_read_addtid_b32 %3\n\t"
+      "s_add_u32 m0, %16, %12\n\ts_nop 0\n\tds_read_addtid_b32 %4\n\t"
+      "s_add_u32 m0, %16, %13\n\ts_nop 0\n\tds_read_addtid_b32 %5\n\t"
+      "s_add_u32 m0, %16, %14\n\ts_nop 0\n\tds_read_addtid_b32 %6\n\t"
+      "s_add_u32 m0, %16, %15\n\ts_nop 0\n\tds_read_addtid_b32 %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3]), "=&v"(b[4]), "=&v"(b[5]), "=&v"(b[6]), "=&v"(b[7])
+      : "s"(ob[0]), "s"(ob[1]), "s"(ob[2]), "s"(ob[3]), "s"(ob[4]), "s"(ob[5]), "s"(ob[6]), "s"(ob[7]), "s"(tile_base)
+      : "m0", "scc", "memory");
+  // (the first eight registers are filled only once the wait above has passed: nothing may read them earlier)
+  asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]));
+}
+
+// Winner position among the M keys of a bin; -1 when the bin has no entry.
+template <int M>
+__device__ __forceinline__ int dwta_winner(const uint32_t (&k)[M]) {
+  uint32_t best = k[0];                              // the largest key first (three-operand maxima) ...
+#pragma unroll
+  for (int p = 1; p < M; ++p) best = max(best, k[p]);
+  bool eq[M];                                        // ... then the lowest position that holds it
+#pragma unroll
+  for (int p = 0; p < M; ++p) eq[p] = k[p] == best;
+  int best_p = M - 1;
+#pragma unroll
+  for (int p = M - 2; p >= 0; --p) best_p = eq[p] ? p : best_p;
+  return best == 0u ? -1 : best_p;
+}
+
 template <int M, bool UNI>
-__device__ __forceinline__ int dwta_raw(const char* col0, const uint32_t* __restrict__ offs, int e) {
+__device__ __forceinline__ int dwta_raw(const char* col0, const uint32_t* __restrict__ offs, int e, uint32_t tile_base = 0) {
   const uint32_t* o = offs + (size_t)(UNI ? __builtin_amdgcn_readfirstlane(e) : e) * M;
   uint32_t k[M];
+  if constexpr (M == 8 && UNI) {
+    read8_lane_rows(k, o, tile_base);
+  } else {
 #pragma unroll
-  for (int p = 0; p < M; ++p) k[p] = *(const uint32_t*)(col0 + o[p]);
+    for (int p = 0; p < M; ++p) k[p] = *(const uint32_t*)(col0 + o[p]);
+  }
   uint32_t best = k[0];                              // the largest key first (three-operand maxima) ...
 #pragma unroll
   for (int p = 1; p < M; ++p) best = max(best, k[p]);
@@ -53,7 +124,7 @@ __device__ __forceinline__ int dwta_raw(const char* col0, const uint32_t* __rest
 
 template <int M, bool UNI>
 __device__ __forceinline__ uint32_t dwta_code(const HashDev& hd, const uint32_t* __restrict__ offs, const char* col0,
-                                              int pitch_bytes, int t, int& rowstate) {
+                                              int pitch_bytes, int t, int& rowstate, uint32_t tile_base) {
   // Empty bin: borrow the winner of another elementary hash (rare, per lane).
   auto borrow = [&](int e) -> int {
     if (rowstate < 0) {
@@ -73,14 +144,23 @@ __device__ __forceinline__ uint32_t dwta_code(const HashDev& hd, const uint32_t*
   const int e0 = t * hd.K;                           // uniform over the lanes of a table
   int k = 0;
   for (; k + 1 < hd.K; k += 2) {                     // two independent argmax chains in flight
-    int v0 = dwta_raw<M, UNI>(col0, offs, e0 + k);
-    int v1 = dwta_raw<M, UNI>(col0, offs, e0 + k + 1);
+    int v0, v1;
+    if constexpr (M == 8 && UNI) {
+      const uint32_t* o = offs + (size_t)__builtin_amdgcn_readfirstlane(e0 + k) * 8;
+      uint32_t ka[8], kb[8];
+      read16_lane_rows(ka, kb, o, o + 8, tile_base);
+      v0 = dwta_winner<8>(ka);
+      v1 = dwta_winner<8>(kb);
+    } else {
+      v0 = dwta_raw<M, UNI>(col0, offs, e0 + k, tile_base);
+      v1 = dwta_raw<M, UNI>(col0, offs, e0 + k + 1, tile_base);
+    }
     if (v0 < 0) v0 = borrow(e0 + k);
     if (v1 < 0) v1 = borrow(e0 + k + 1);
     code |= ((uint32_t)v0 << (k * hd.lgm)) | ((uint32_t)v1 << ((k + 1) * hd.lgm));
   }
   if (k < hd.K) {
-    int v0 = dwta_raw<M, UNI>(col0, offs, e0 + k);
+    int v0 = dwta_raw<M, UNI>(col0, offs, e0 + k, tile_base);
     if (v0 < 0) v0 = borrow(e0 + k);
     code |= (uint32_t)v0 << (k * hd.lgm);
   }
@@ -150,6 +230,7 @@ __global__ __launch_bounds__(1024) void hash_rows_kernel(HashDev hd, const uint3
   const int r = lane & (RPT - 1), sub = lane / RPT;
   const int64_t row = rid[r];
   const char* col0 = (const char*)(tile + r);
+  const uint32_t tile_base = (uint32_t)(uintptr_t)tile;   // (the low half of a generic LDS address is the LDS address)
   const int t_end = min((int)(blockIdx.y + 1) * tpb, hd.L);
   int rowstate = -1;
   for (int t0 = blockIdx.y * tpb + wave * tps; t0 < t_end; t0 += nw * tps) {
@@ -157,7 +238,7 @@ __global__ __launch_bounds__(1024) void hash_rows_kernel(HashDev hd, const uint3
     if (t >= t_end) continue;
     uint32_t code;
     if (MODE == 0) code = simhash_code<UNI>(hd, offs, col0, t);
-    else code = dwta_code<(MODE == 0 ? 2 : MODE), UNI>(hd, offs, col0, stride * 4, t, rowstate);
+    else code = dwta_code<(MODE == 0 ? 2 : MODE), UNI>(hd, offs, col0, stride * 4, t, rowstate, tile_base);
     if (row >= 0) codes[row * row_stride + (int64_t)t * tab_stride] = code;
   }
 }
