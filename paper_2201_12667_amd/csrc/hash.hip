@@ -85,19 +85,19 @@ __device__ __forceinline__ void read16_lane_rows(uint32_t (&a)[8], uint32_t (&b)
   asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]));
 }
 
-// Winner position among the M keys of a bin; -1 when the bin has no entry.
+// Winner position among the M keys of a bin, and the winning key (0: the bin has no entry).
 template <int M>
-__device__ __forceinline__ int dwta_winner(const uint32_t (&k)[M]) {
-  uint32_t best = k[0];                              // the largest key first (three-operand maxima) ...
+__device__ __forceinline__ uint32_t dwta_winner(const uint32_t (&k)[M], uint32_t& best) {
+  best = k[0];                                       // the largest key first (three-operand maxima) ...
 #pragma unroll
   for (int p = 1; p < M; ++p) best = max(best, k[p]);
   bool eq[M];                                        // ... then the lowest position that holds it
 #pragma unroll
   for (int p = 0; p < M; ++p) eq[p] = k[p] == best;
-  int best_p = M - 1;
+  uint32_t best_p = M - 1;
 #pragma unroll
-  for (int p = M - 2; p >= 0; --p) best_p = eq[p] ? p : best_p;
-  return best == 0u ? -1 : best_p;
+  for (int p = M - 2; p >= 0; --p) best_p = eq[p] ? (uint32_t)p : best_p;
+  return best_p;
 }
 
 template <int M, bool UNI>
@@ -141,23 +141,26 @@ __device__ __forceinline__ uint32_t dwta_code(const HashDev& hd, const uint32_t*
     return 0;
   };
   uint32_t code = 0;
-  const int e0 = t * hd.K;                           // uniform over the lanes of a table
+  const int e0 = UNI ? __builtin_amdgcn_readfirstlane(t * hd.K) : t * hd.K;   // uniform over the lanes of a table
   int k = 0;
   for (; k + 1 < hd.K; k += 2) {                     // two independent argmax chains in flight
-    int v0, v1;
     if constexpr (M == 8 && UNI) {
-      const uint32_t* o = offs + (size_t)__builtin_amdgcn_readfirstlane(e0 + k) * 8;
-      uint32_t ka[8], kb[8];
+      const uint32_t* o = offs + (size_t)(e0 + k) * 8;
+      uint32_t ka[8], kb[8], ba, bb;
       read16_lane_rows(ka, kb, o, o + 8, tile_base);
-      v0 = dwta_winner<8>(ka);
-      v1 = dwta_winner<8>(kb);
+      uint32_t v0 = dwta_winner<8>(ka, ba), v1 = dwta_winner<8>(kb, bb);
+      if (__any(min(ba, bb) == 0u)) {                // (an empty bin in some lane: rare)
+        if (ba == 0u) v0 = (uint32_t)borrow(e0 + k);
+        if (bb == 0u) v1 = (uint32_t)borrow(e0 + k + 1);
+      }
+      code |= (v0 << (k * hd.lgm)) | (v1 << ((k + 1) * hd.lgm));
     } else {
-      v0 = dwta_raw<M, UNI>(col0, offs, e0 + k, tile_base);
-      v1 = dwta_raw<M, UNI>(col0, offs, e0 + k + 1, tile_base);
+      int v0 = dwta_raw<M, UNI>(col0, offs, e0 + k, tile_base);
+      int v1 = dwta_raw<M, UNI>(col0, offs, e0 + k + 1, tile_base);
+      if (v0 < 0) v0 = borrow(e0 + k);
+      if (v1 < 0) v1 = borrow(e0 + k + 1);
+      code |= ((uint32_t)v0 << (k * hd.lgm)) | ((uint32_t)v1 << ((k + 1) * hd.lgm));
     }
-    if (v0 < 0) v0 = borrow(e0 + k);
-    if (v1 < 0) v1 = borrow(e0 + k + 1);
-    code |= ((uint32_t)v0 << (k * hd.lgm)) | ((uint32_t)v1 << ((k + 1) * hd.lgm));
   }
   if (k < hd.K) {
     int v0 = dwta_raw<M, UNI>(col0, offs, e0 + k, tile_base);

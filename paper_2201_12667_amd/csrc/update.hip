@@ -358,6 +358,7 @@ static hipError_t launch_up(int H, const RowUpdate& out, const RowUpdate& in, co
 // columns also takes the bias.  Sums run over ascending samples as in the plain kernel.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSlicedThreads = 1024;
+constexpr int kSlicedGroup = 1;          // rows a wave takes through each memory round trip
 constexpr int kSlicedPad = 4;            // floats between the LDS rows of two samples (spreads them over the banks)
 constexpr size_t kSlicedStatic = 10240;  // LDS the launch's other role (finish_role) declares statically
 
@@ -384,7 +385,7 @@ __device__ __forceinline__ void fma_cols(typename LaneCols<CPL>::type& g, float 
 // The workgroup fills its compute unit alone (the LDS slice), so nothing but the wave itself can hide
 // the chain header -> list entries -> coefficients: the headers are fetched three rows ahead, the
 // first 64 list entries two ahead, their coefficients one ahead.
-template <int CPL>
+template <int CPL, int R>
 __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const AdamDev& ad, const float* ldsV,
                                     const uint32_t* tpre, uint32_t* cursor, int part, int nparts) {
   typedef typename LaneCols<CPL>::type cols_t;
@@ -449,58 +450,88 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
     if (!ok) e.x = 0;
     return ok ? dv : 0.f;
   };
-  // Software pipeline over the wave's rows.  Vector loads and stores share one in-order counter on this
-  // target, and once both kinds are outstanding a wait for any load waits for everything, so the loop
-  // has one point per row where it waits (its top) and everything outstanding there was issued a whole
-  // row of LDS arithmetic earlier: row k's header was requested during row k-3, its first 64 list
-  // entries during k-2, their coefficients and the row's old w, m, v during k-1; row k's results are
-  // stored during k+1.
+  // Software pipeline over the wave's rows, R rows at a time.  Vector loads and stores share one in-order
+  // counter on this target, and once both kinds are outstanding a wait for any load waits for
+  // everything, so the loop has one point per group of R rows where it waits (its top), and everything
+  // outstanding there was issued a whole group of LDS arithmetic earlier: group g's headers were requested
+  // during group g-3, its first 64 list entries during g-2, their coefficients and the rows' old w, m, v
+  // during g-1; group g's results are stored during g+1.  (With short lists a row's arithmetic is far
+  // shorter than a memory round trip: R rows share each round trip.)
   auto scalar = [](const int4& m) {
     return make_int4(__builtin_amdgcn_readfirstlane(m.x), __builtin_amdgcn_readfirstlane(m.y),
                      __builtin_amdgcn_readfirstlane(m.z), 0);
   };
   auto row_offset = [&](const int4& m) -> size_t { return (size_t)m.x * H + col; };
-  int4 m0 = header(0), m1 = header(1), m2 = header(2);
-  int2 e0 = entry(m0, 0), e1 = entry(m1, 0);
-  float d0 = coefficient(m0, 0, e0);
-  cols_t w0, mo0, v0;                                      // old values of row k (requested during row k-1)
-  float b0w = 0.f, b0m = 0.f, b0v = 0.f;
-  if (col_ok && m0.z > 0) { const size_t ro = row_offset(m0); w0 = *(const cols_t*)(ru.W + ro); mo0 = *(const cols_t*)(ru.M + ro); v0 = *(const cols_t*)(ru.Vv + ro); }
-  if (bias_lane && m0.z > 0) { b0w = ru.bias[m0.x]; b0m = ru.mbias[m0.x]; b0v = ru.vbias[m0.x]; }
-  cols_t ws, ms, vs;                                       // results of the previous row, not stored yet
-  float bsw = 0.f, bsm = 0.f, bsv = 0.f;
-  size_t ro_s = 0;
-  int j_s = -1;                                            // row they belong to (-1: nothing pending)
-  for (int k = 0; k < count; ++k) {
-    const int4 cur = scalar(m0);                           // ---- the one waiting point of this row
-    if (cur.z < 0) break;                                  // (no more rows; uniform)
-    const int2 ecur = e0;
-    const float dcur = d0;
-    const cols_t wc = w0, mc = mo0, vc = v0;
-    const float bcw = b0w, bcm = b0m, bcv = b0v;
-    // ---- requests for the rows to come, and the previous row's stores
-    const int4 m3 = header(k + 3);
-    int2 e2 = entry(m2, 0);
-    float d1 = coefficient(m1, 0, e1);
-    if (col_ok && m1.z > 0) { const size_t ro = row_offset(m1); w0 = *(const cols_t*)(ru.W + ro); mo0 = *(const cols_t*)(ru.M + ro); v0 = *(const cols_t*)(ru.Vv + ro); }
-    if (bias_lane && m1.z > 0) { b0w = ru.bias[m1.x]; b0m = ru.mbias[m1.x]; b0v = ru.vbias[m1.x]; }
-    if (j_s >= 0) {
-      if (col_ok) { *(cols_t*)(ru.W + ro_s) = ws; *(cols_t*)(ru.M + ro_s) = ms; *(cols_t*)(ru.Vv + ro_s) = vs; }
-      if (bias_lane) { ru.bias[j_s] = bsw; ru.mbias[j_s] = bsm; ru.vbias[j_s] = bsv; }
-      j_s = -1;
+  int4 m0[R], m1[R], m2[R];
+  int2 e0[R], e1[R];
+  float d0[R];
+  cols_t w0[R], mo0[R], v0[R];                             // old values of the group's rows (requested a group earlier)
+  float b0w[R], b0m[R], b0v[R];
+  cols_t ws[R], ms[R], vs[R];                              // results of the previous group, not stored yet
+  float bsw[R], bsm[R], bsv[R];
+  size_t ro_s[R];
+  int j_s[R];                                              // row they belong to (-1: nothing pending)
+#pragma unroll
+  for (int r = 0; r < R; ++r) m0[r] = header(r);
+#pragma unroll
+  for (int r = 0; r < R; ++r) m1[r] = header(R + r);
+#pragma unroll
+  for (int r = 0; r < R; ++r) m2[r] = header(2 * R + r);
+#pragma unroll
+  for (int r = 0; r < R; ++r) { e0[r] = entry(m0[r], 0); e1[r] = entry(m1[r], 0); }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    d0[r] = coefficient(m0[r], 0, e0[r]);
+    b0w[r] = 0.f; b0m[r] = 0.f; b0v[r] = 0.f; bsw[r] = 0.f; bsm[r] = 0.f; bsv[r] = 0.f;
+    ro_s[r] = 0; j_s[r] = -1;
+    if (col_ok && m0[r].z > 0) { const size_t ro = row_offset(m0[r]); w0[r] = *(const cols_t*)(ru.W + ro); mo0[r] = *(const cols_t*)(ru.M + ro); v0[r] = *(const cols_t*)(ru.Vv + ro); }
+    if (bias_lane && m0[r].z > 0) { b0w[r] = ru.bias[m0[r].x]; b0m[r] = ru.mbias[m0[r].x]; b0v[r] = ru.vbias[m0[r].x]; }
+  }
+  for (int g = 0;; ++g) {
+    int4 cur[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) cur[r] = scalar(m0[r]);    // ---- the one waiting point of this group
+    if (cur[0].z < 0) break;                               // (no more rows: they are handed out in order; uniform)
+    int2 ecur[R];
+    float dcur[R], bcw[R], bcm[R], bcv[R];
+    cols_t wc[R], mc[R], vc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) { ecur[r] = e0[r]; dcur[r] = d0[r]; wc[r] = w0[r]; mc[r] = mo0[r]; vc[r] = v0[r]; bcw[r] = b0w[r]; bcm[r] = b0m[r]; bcv[r] = b0v[r]; }
+    // ---- requests for the groups to come, and the previous group's stores
+    int4 m3[R];
+    int2 e2[R];
+    float d1[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) m3[r] = header((g + 3) * R + r);
+#pragma unroll
+    for (int r = 0; r < R; ++r) e2[r] = entry(m2[r], 0);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      d1[r] = coefficient(m1[r], 0, e1[r]);
+      if (col_ok && m1[r].z > 0) { const size_t ro = row_offset(m1[r]); w0[r] = *(const cols_t*)(ru.W + ro); mo0[r] = *(const cols_t*)(ru.M + ro); v0[r] = *(const cols_t*)(ru.Vv + ro); }
+      if (bias_lane && m1[r].z > 0) { b0w[r] = ru.bias[m1[r].x]; b0m[r] = ru.mbias[m1[r].x]; b0v[r] = ru.vbias[m1[r].x]; }
     }
-    // ---- this row: gradient from LDS, Adam in registers
-    const int cn = cur.z;
-    if (cn > 0) {
-      cols_t g;
-      if constexpr (CPL == 2) g = make_float2(0.f, 0.f); else g = 0.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (j_s[r] >= 0) {
+        if (col_ok) { *(cols_t*)(ru.W + ro_s[r]) = ws[r]; *(cols_t*)(ru.M + ro_s[r]) = ms[r]; *(cols_t*)(ru.Vv + ro_s[r]) = vs[r]; }
+        if (bias_lane) { ru.bias[j_s[r]] = bsw[r]; ru.mbias[j_s[r]] = bsm[r]; ru.vbias[j_s[r]] = bsv[r]; }
+        j_s[r] = -1;
+      }
+    // ---- the group's rows: gradient from LDS, Adam in registers
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int cn = cur[r].z;
+      if (cn <= 0) continue;
+      cols_t gsum;
+      if constexpr (CPL == 2) gsum = make_float2(0.f, 0.f); else gsum = 0.f;
       float gb = 0.f;
-      int2 e = ecur;
-      float d = dcur;
+      int2 e = ecur[r];
+      float d = dcur[r];
       for (int q0 = 0; q0 < cn; q0 += 64) {
         int2 en = e;
         const bool more = q0 + 64 < cn;                    // (uniform; rows this long wait in place)
-        if (more) en = entry(cur, q0 + 64);
+        if (more) en = entry(cur[r], q0 + 64);
         const int n = min(64, cn - q0);
         for (int a0 = 0; a0 < n; a0 += 8) {                // lanes past the end hold (sample 0, 0.0)
           cols_t x[8];
@@ -512,26 +543,28 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
             x[a] = *(const cols_t*)(lds_mine + (size_t)si * PITCH);
           }
 #pragma unroll
-          for (int a = 0; a < 8; ++a) fma_cols<CPL>(g, dd[a], x[a]);
+          for (int a = 0; a < 8; ++a) fma_cols<CPL>(gsum, dd[a], x[a]);
         }
         if (bias_lane_any) gb += wave_sum_f32(d);          // (lanes past the end hold 0; fixed order)
-        if (more) { e = en; d = coefficient(cur, q0 + 64, e); }
+        if (more) { e = en; d = coefficient(cur[r], q0 + 64, e); }
       }
-      ws = wc; ms = mc; vs = vc;
-      if constexpr (CPL == 2) { adam1(ws.x, ms.x, vs.x, g.x, ad); adam1(ws.y, ms.y, vs.y, g.y, ad); }
-      else adam1(ws, ms, vs, g, ad);
-      bsw = bcw; bsm = bcm; bsv = bcv;
-      adam1(bsw, bsm, bsv, gb, ad);
-      ro_s = (size_t)cur.x * H + col;
-      j_s = cur.x;
+      ws[r] = wc[r]; ms[r] = mc[r]; vs[r] = vc[r];
+      if constexpr (CPL == 2) { adam1(ws[r].x, ms[r].x, vs[r].x, gsum.x, ad); adam1(ws[r].y, ms[r].y, vs[r].y, gsum.y, ad); }
+      else adam1(ws[r], ms[r], vs[r], gsum, ad);
+      bsw[r] = bcw[r]; bsm[r] = bcm[r]; bsv[r] = bcv[r];
+      adam1(bsw[r], bsm[r], bsv[r], gb, ad);
+      ro_s[r] = (size_t)cur[r].x * H + col;
+      j_s[r] = cur[r].x;
     }
-    m0 = m1; m1 = m2; m2 = m3;
-    e0 = e1; e1 = e2; d0 = d1;
+#pragma unroll
+    for (int r = 0; r < R; ++r) { m0[r] = m1[r]; m1[r] = m2[r]; m2[r] = m3[r]; e0[r] = e1[r]; e1[r] = e2[r]; d0[r] = d1[r]; }
   }
-  if (j_s >= 0) {
-    if (col_ok) { *(cols_t*)(ru.W + ro_s) = ws; *(cols_t*)(ru.M + ro_s) = ms; *(cols_t*)(ru.Vv + ro_s) = vs; }
-    if (bias_lane) { ru.bias[j_s] = bsw; ru.mbias[j_s] = bsm; ru.vbias[j_s] = bsv; }
-  }
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+    if (j_s[r] >= 0) {
+      if (col_ok) { *(cols_t*)(ru.W + ro_s[r]) = ws[r]; *(cols_t*)(ru.M + ro_s[r]) = ms[r]; *(cols_t*)(ru.Vv + ro_s[r]) = vs[r]; }
+      if (bias_lane) { ru.bias[j_s[r]] = bsw[r]; ru.mbias[j_s[r]] = bsm[r]; ru.vbias[j_s[r]] = bsv[r]; }
+    }
 }
 
 template <int CPL>
@@ -583,7 +616,7 @@ __global__ __launch_bounds__(kSlicedThreads) void update_sliced_kernel(int H, in
       }
     }
     __syncthreads();
-    rowgrad_adam_sliced<CPL>(H, c0, ru, ad, ldsV, dense ? tsum : nullptr, &row_cursor, part, parts);
+    rowgrad_adam_sliced<CPL, kSlicedGroup>(H, c0, ru, ad, ldsV, dense ? tsum : nullptr, &row_cursor, part, parts);
   }
 }
 
