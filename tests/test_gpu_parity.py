@@ -109,6 +109,10 @@ def test_degenerate_tables_all_rows_identical():
                                        input_dim=150001, nnz_mean=3.0, bucket_cap=8, feat_zipf_s=None)),
     ("wide-input-b600", synth.small(synth.HASH_DWTA, hidden_dim=32, K=3, L=5, batch=600, num_classes=4001,
                                     input_dim=400001, nnz_mean=4.0, bucket_cap=8)),
+    # a layer wide enough for the lookup workgroup to stage the sample's W1 rows in LDS, and samples with
+    # more features than the staging holds at once (48 rows here): three rounds of staging per sample
+    ("staged-hidden-three-rounds", synth.small(synth.HASH_DWTA, num_classes=200003, input_dim=5000, nnz_mean=120.0,
+                                               batch=8, L=9)),
     # the largest bucket capacity: every bucket holds more than 1024 neurons, 5120 candidates per sample
     ("cap1024", synth.small(synth.HASH_SIMHASH, K=4, L=5, bucket_cap=1024, num_classes=60000, batch=9)),
 ])
@@ -266,22 +270,33 @@ def test_step_with_label_entries_outside_the_layer_matches_oracle():
     model.destroy()
 
 
-def test_bad_batch_data_is_flagged_not_fatal():
-    _say("bad data")
+@pytest.mark.parametrize("num_classes,input_dim", [(3000, 500), (200003, 500), (3000, 300001)],
+                         ids=["wave-per-columns", "rows-staged-in-lds", "wave-per-feature-tile"])
+def test_bad_batch_data_is_flagged_not_fatal(num_classes, input_dim):
+    """Both forms of the lookup's hidden layer (the wide output layer lets the workgroup stage the W1 rows) and
+    both forms of the feature tiles (the wide input layer has a wave take a tile)."""
+    _say("bad data", num_classes, input_dim)
     from paper_2201_12667_amd import slide
-    wl = synth.small(synth.HASH_DWTA, batch=4, num_classes=3000, input_dim=500)
+    wl = synth.small(synth.HASH_DWTA, batch=4, num_classes=num_classes, input_dim=input_dim, L=9)
     gen, model, orc = make_pair(wl)
     model.build_tables()
+    orc.build_tables()
     b = gen.batch(0)
     b["x_indices"] = b["x_indices"].copy()
     b["y_indices"] = b["y_indices"].copy()
-    b["x_indices"][0] = 500                      # out of range
+    b["x_indices"][0] = input_dim                # out of range
     b["y_indices"][0] = -3                       # out of range
     b["x_indices"][b["x_indptr"][1]:b["x_indptr"][1] + 2] = b["x_indices"][b["x_indptr"][1]:b["x_indptr"][1] + 2][::-1]
     model.train_step(model.to_device(b))
     flags = model.status()
     assert flags == slide.FLAG_BAD_FEATURE | slide.FLAG_BAD_LABEL | slide.FLAG_UNSORTED
     assert model.status() == 0                   # cleared after being reported
+    # the flagged step leaves nothing behind that a later step would trip over (feature segments, counters):
+    # from the oracle's state again (after its own, clean, first step), a clean batch gives a clean, fully
+    # matching step
+    orc.train_step(gen.batch(0))
+    load_state(model, orc)
+    assert_ok(compare_step(model, orc, gen.batch(1)))
     # host-detected errors
     with pytest.raises(slide.SlideError) as e:
         db = model.to_device(gen.batch(1))
