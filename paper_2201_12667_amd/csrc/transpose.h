@@ -27,6 +27,7 @@ namespace slide {
 // LDS mask, so every pair is written straight to its final position: ascending samples per row,
 // no sort, no global atomics on the data.
 constexpr int kInFlight = 4;    // ids a thread requests before it uses the first
+constexpr int kTilesPerWave = 2; // feature tiles a wave takes, one after the other, when the waves take tiles
 
 template <bool FEAT, int TW, bool BITS = false>
 __device__ __forceinline__ void transpose_tile_t(const TransposeArgs& ta, int tileno, uint32_t* lds) {
@@ -359,10 +360,11 @@ __device__ __forceinline__ int feature_tile_group_t(const TransposeArgs& ta, int
   const int32_t* __restrict__ ids = ta.ids;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)blockDim.x >> 6;
-  int& nbig = big[16];                                   // big[0 .. 15]: tiles left to the workgroup (one per wave at most)
+  int& nbig = big[16];                                   // big[0 .. 15]: tiles left to the workgroup
   if (tid == 0) nbig = 0;
   __syncthreads();
-  const int tileno = group * nw + wave;
+  for (int rep = 0; rep < kTilesPerWave; ++rep) {
+  const int tileno = (group * kTilesPerWave + rep) * nw + wave;
   if (tileno < ta.ntiles) {
     const int row0 = tileno * ROWS;
     uint32_t* skey = lds + wave * 132;                   // [64] row in tile << 16 | sample
@@ -452,6 +454,7 @@ __device__ __forceinline__ int feature_tile_group_t(const TransposeArgs& ta, int
       }
     }
   }
+  }
   __syncthreads();
   return __builtin_amdgcn_readfirstlane(nbig);
 }
@@ -461,6 +464,7 @@ __device__ __forceinline__ int feature_tile_group_t(const TransposeArgs& ta, int
 template <int TW>
 __device__ __forceinline__ void feature_tile_role_t(const TransposeArgs& ta, int role, uint32_t* lds) {
   __shared__ int big[17];                                // [0 .. 15] tiles left to the whole workgroup, [16] their number
+  static_assert(kTilesPerWave * 8 <= 16, "one slot per tile of a group of eight waves");
   int nb = 1;
   if (ta.grouped) nb = feature_tile_group_t<TW>(ta, role, lds, big);
 #pragma unroll 1
@@ -497,7 +501,7 @@ __device__ __forceinline__ void transpose_tile(const TransposeArgs& ta, int tile
 
 // Workgroups a launch spends on the tiles of `t` (workgroups of `threads` threads).
 __host__ __device__ inline int transpose_roles(const TransposeArgs& t, int threads) {
-  const int per = threads >> 6;
+  const int per = (threads >> 6) * kTilesPerWave;
   return t.grouped ? (t.ntiles + per - 1) / per : t.ntiles;
 }
 
