@@ -385,7 +385,7 @@ __device__ __forceinline__ void fma_cols(typename LaneCols<CPL>::type& g, float 
 // The workgroup fills its compute unit alone (the LDS slice), so nothing but the wave itself can hide
 // the chain header -> list entries -> coefficients: the headers are fetched three rows ahead, the
 // first 64 list entries two ahead, their coefficients one ahead.
-template <int CPL, int R>
+template <int CPL, int R, bool LDSV>
 __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const AdamDev& ad, const float* ldsV,
                                     const uint32_t* tpre, uint32_t* cursor, int part, int nparts) {
   typedef typename LaneCols<CPL>::type cols_t;
@@ -540,7 +540,9 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
           for (int a = 0; a < 8; ++a) {
             const int si = __builtin_amdgcn_readlane(e.x, a0 + a);
             dd[a] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d), a0 + a));
-            x[a] = *(const cols_t*)(lds_mine + (size_t)si * PITCH);
+            if constexpr (LDSV) x[a] = *(const cols_t*)(lds_mine + (size_t)si * PITCH);
+            else if (col_ok) x[a] = *(const cols_t*)(ru.V + (size_t)si * H + col);     // (few pairs: from the caches)
+            else { if constexpr (CPL == 2) x[a] = make_float2(0.f, 0.f); else x[a] = 0.f; }
           }
 #pragma unroll
           for (int a = 0; a < 8; ++a) fma_cols<CPL>(gsum, dd[a], x[a]);
@@ -575,7 +577,7 @@ __global__ __launch_bounds__(kSlicedThreads) void update_sliced_kernel(int H, in
   constexpr int CW = 64 * CPL, PITCH = CW + kSlicedPad;
   uint32_t* tsum = (uint32_t*)(ldsV + (size_t)B * PITCH);
   __shared__ uint32_t wsum[kSlicedThreads / 64];
-  __shared__ uint32_t row_cursor;                          // next touched row of this workgroup's stretch
+  __shared__ uint32_t row_cursor[2];                       // next touched row of this workgroup's stretch (input / output layer)
   int blk = blockIdx.x;
   if (blk < fin.nblocks) { finish_role(H, fin, ad, blk); return; }
   blk -= fin.nblocks;
@@ -583,41 +585,44 @@ __global__ __launch_bounds__(kSlicedThreads) void update_sliced_kernel(int H, in
   // lists and coefficients at about the same time
   const int slice = blk % nslices, part = blk / nslices;
   const int c0 = slice * CW;
-  for (int which = 0; which < 2; ++which) {
-    const RowUpdate& ru = which == 0 ? in : out;
-    if (!ru.W) continue;
-    __syncthreads();                                       // the previous matrix's readers are done
-    for (int idx = threadIdx.x; idx < B * (CW / 4); idx += kSlicedThreads) {
-      const int i = idx / (CW / 4), q = idx - i * (CW / 4);
-      const int col = c0 + q * 4;
-      const float4 x = col < H ? *(const float4*)(ru.V + (size_t)i * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
-      *(float4*)(ldsV + (size_t)i * PITCH + q * 4) = x;
-    }
-    // running sum of the touched rows per tile (tsum[t] = rows in tiles before t), when it fits
-    const int nt = ru.pd.ntiles;
-    const bool dense = nt + 1 <= tile_words;
-    if (dense) {
-      uint32_t carry = 0;
-      for (int base = 0; base < nt; base += kSlicedThreads) {   // (uniform trip count)
-        const int t = base + (int)threadIdx.x;
-        const uint32_t v = t < nt ? (uint32_t)ru.pd.tile_nu[t] : 0u;
-        const uint32_t inc = wave_incl_scan_add(v);
-        __syncthreads();
-        if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
-        __syncthreads();
-        uint32_t before = 0, total = 0;
-        for (int w = 0; w < kSlicedThreads / 64; ++w) { const uint32_t x = wsum[w]; if (w < (int)(threadIdx.x >> 6)) before += x; total += x; }
-        if (t < nt) tsum[t] = carry + before + inc - v;
-        carry += total;
-      }
-      if (threadIdx.x == 0) {
-        tsum[nt] = carry;
-        row_cursor = (uint32_t)((uint64_t)carry * (uint32_t)part / (uint32_t)parts);
-      }
-    }
-    __syncthreads();
-    rowgrad_adam_sliced<CPL, kSlicedGroup>(H, c0, ru, ad, ldsV, dense ? tsum : nullptr, &row_cursor, part, parts);
+  // The batch's vectors for the output layer's rows (the slice): the input layer's rows are few, their
+  // vectors (the hidden gradient) are read from the caches, and the waves go from the one list to the
+  // other without meeting.
+  for (int idx = threadIdx.x; idx < B * (CW / 4); idx += kSlicedThreads) {
+    const int i = idx / (CW / 4), q = idx - i * (CW / 4);
+    const int col = c0 + q * 4;
+    const float4 x = col < H ? *(const float4*)(out.V + (size_t)i * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+    *(float4*)(ldsV + (size_t)i * PITCH + q * 4) = x;
   }
+  // running sum of the touched rows per tile (sums[t] = rows in tiles before t), when it fits
+  auto tile_sums = [&](const RowUpdate& ru, uint32_t* sums, uint32_t* cursor) {
+    const int nt = ru.pd.ntiles;
+    uint32_t carry = 0;
+    for (int base = 0; base < nt; base += kSlicedThreads) {   // (uniform trip count)
+      const int t = base + (int)threadIdx.x;
+      const uint32_t v = t < nt ? (uint32_t)ru.pd.tile_nu[t] : 0u;
+      const uint32_t inc = wave_incl_scan_add(v);
+      __syncthreads();
+      if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+      __syncthreads();
+      uint32_t before = 0, total = 0;
+      for (int w = 0; w < kSlicedThreads / 64; ++w) { const uint32_t x = wsum[w]; if (w < (int)(threadIdx.x >> 6)) before += x; total += x; }
+      if (t < nt) sums[t] = carry + before + inc - v;
+      carry += total;
+    }
+    if (threadIdx.x == 0) {
+      sums[nt] = carry;
+      *cursor = (uint32_t)((uint64_t)carry * (uint32_t)part / (uint32_t)parts);
+    }
+  };
+  const bool dense_in = in.W && in.pd.ntiles + 1 <= tile_words;
+  uint32_t* tsum_out = tsum + (dense_in ? in.pd.ntiles + 1 : 0);
+  const bool dense_out = out.pd.ntiles + 1 <= tile_words - (int)(tsum_out - tsum);
+  if (dense_in) tile_sums(in, tsum, &row_cursor[0]);
+  if (dense_out) tile_sums(out, tsum_out, &row_cursor[1]);
+  __syncthreads();
+  if (in.W) rowgrad_adam_sliced<CPL, kSlicedGroup, false>(H, c0, in, ad, ldsV, dense_in ? tsum : nullptr, &row_cursor[0], part, parts);
+  rowgrad_adam_sliced<CPL, kSlicedGroup, true>(H, c0, out, ad, ldsV, dense_out ? tsum_out : nullptr, &row_cursor[1], part, parts);
 }
 
 // Columns per slice for a batch of B vectors of length H (0: the sliced kernel does not apply).
