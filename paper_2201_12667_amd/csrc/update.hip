@@ -14,6 +14,17 @@
 
 namespace slide {
 
+typedef float slide_v4f __attribute__((ext_vector_type(4)));
+// Moment rows are touched once per step and by nothing else: streamed past the caches.
+__device__ __forceinline__ float4 load_stream(const float* p) {
+  const slide_v4f v = __builtin_nontemporal_load((const slide_v4f*)p);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(float* p, const float4& x) {
+  slide_v4f v; v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
+  __builtin_nontemporal_store(v, (slide_v4f*)p);
+}
+
 constexpr int kUpdateThreads = 256;
 
 // One element of the Adam update.  The square root and the reciprocal are the hardware's one-ulp
@@ -118,8 +129,8 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
       const int col = (c * LPR + sub) * 4;
       if (FULL || col < H) {
         w[c] = *(const float4*)(W + ro + col);
-        m[c] = *(const float4*)(M + ro + col);
-        v[c] = *(const float4*)(Vv + ro + col);
+        m[c] = load_stream(M + ro + col);
+        v[c] = load_stream(Vv + ro + col);
       }
     }
 #pragma unroll
@@ -129,8 +140,8 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
         adam1(w[c].x, m[c].x, v[c].x, g[c].x, ad); adam1(w[c].y, m[c].y, v[c].y, g[c].y, ad);
         adam1(w[c].z, m[c].z, v[c].z, g[c].z, ad); adam1(w[c].w, m[c].w, v[c].w, g[c].w, ad);
         *(float4*)(W + ro + col) = w[c];
-        *(float4*)(M + ro + col) = m[c];
-        *(float4*)(Vv + ro + col) = v[c];
+        store_stream(M + ro + col, m[c]);
+        store_stream(Vv + ro + col, v[c]);
       }
     }
     if (bias && sub == 0) {
@@ -169,8 +180,8 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
           const int col = (c * LPR + sub) * 4;
           if (FULL || col < H) {
             w[c] = *(const float4*)(W + ro + col);
-            m[c] = *(const float4*)(M + ro + col);
-            v[c] = *(const float4*)(Vv + ro + col);
+            m[c] = load_stream(M + ro + col);
+            v[c] = load_stream(Vv + ro + col);
           }
         }
         for (int k = 0; k < NW - 1; ++k) {
@@ -188,8 +199,8 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
             adam1(w[c].x, m[c].x, v[c].x, g[c].x, ad); adam1(w[c].y, m[c].y, v[c].y, g[c].y, ad);
             adam1(w[c].z, m[c].z, v[c].z, g[c].z, ad); adam1(w[c].w, m[c].w, v[c].w, g[c].w, ad);
             *(float4*)(W + ro + col) = w[c];
-            *(float4*)(M + ro + col) = m[c];
-            *(float4*)(Vv + ro + col) = v[c];
+            store_stream(M + ro + col, m[c]);
+            store_stream(Vv + ro + col, v[c]);
           }
         }
         if (bias && sub == 0) {
@@ -229,8 +240,8 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
       const int col = (c * LPR + sub) * 4;
       if (FULL || col < H) {
         w[c] = *(const float4*)(W + ro + col);
-        m[c] = *(const float4*)(M + ro + col);
-        v[c] = *(const float4*)(Vv + ro + col);
+        m[c] = load_stream(M + ro + col);
+        v[c] = load_stream(Vv + ro + col);
       }
     }
 #pragma unroll
@@ -240,8 +251,8 @@ __device__ void rowgrad_adam(int H, const RowUpdate& ru, const AdamDev& ad, int 
         adam1(w[c].x, m[c].x, v[c].x, g[c].x, ad); adam1(w[c].y, m[c].y, v[c].y, g[c].y, ad);
         adam1(w[c].z, m[c].z, v[c].z, g[c].z, ad); adam1(w[c].w, m[c].w, v[c].w, g[c].w, ad);
         *(float4*)(W + ro + col) = w[c];
-        *(float4*)(M + ro + col) = m[c];
-        *(float4*)(Vv + ro + col) = v[c];
+        store_stream(M + ro + col, m[c]);
+        store_stream(Vv + ro + col, v[c]);
       }
     }
     if (bias && sub == 0) {
@@ -376,6 +387,18 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
 template <int CPL> struct LaneCols { typedef float type; };
 template <> struct LaneCols<2> { typedef float2 type; };
 
+typedef float slide_v2f __attribute__((ext_vector_type(2)));
+template <int CPL>
+__device__ __forceinline__ typename LaneCols<CPL>::type load_cols_stream(const float* p) {
+  if constexpr (CPL == 2) { const slide_v2f v = __builtin_nontemporal_load((const slide_v2f*)p); return make_float2(v.x, v.y); }
+  else return __builtin_nontemporal_load(p);
+}
+template <int CPL>
+__device__ __forceinline__ void store_cols_stream(float* p, const typename LaneCols<CPL>::type& x) {
+  if constexpr (CPL == 2) { slide_v2f v; v.x = x.x; v.y = x.y; __builtin_nontemporal_store(v, (slide_v2f*)p); }
+  else __builtin_nontemporal_store(x, p);
+}
+
 template <int CPL>
 __device__ __forceinline__ void fma_cols(typename LaneCols<CPL>::type& g, float d, const typename LaneCols<CPL>::type& x) {
   if constexpr (CPL == 2) { g.x += d * x.x; g.y += d * x.y; } else { g += d * x; }
@@ -484,7 +507,7 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
     d0[r] = coefficient(m0[r], 0, e0[r]);
     b0w[r] = 0.f; b0m[r] = 0.f; b0v[r] = 0.f; bsw[r] = 0.f; bsm[r] = 0.f; bsv[r] = 0.f;
     ro_s[r] = 0; j_s[r] = -1;
-    if (col_ok && m0[r].z > 0) { const size_t ro = row_offset(m0[r]); w0[r] = *(const cols_t*)(ru.W + ro); mo0[r] = *(const cols_t*)(ru.M + ro); v0[r] = *(const cols_t*)(ru.Vv + ro); }
+    if (col_ok && m0[r].z > 0) { const size_t ro = row_offset(m0[r]); w0[r] = *(const cols_t*)(ru.W + ro); mo0[r] = load_cols_stream<CPL>(ru.M + ro); v0[r] = load_cols_stream<CPL>(ru.Vv + ro); }
     if (bias_lane && m0[r].z > 0) { b0w[r] = ru.bias[m0[r].x]; b0m[r] = ru.mbias[m0[r].x]; b0v[r] = ru.vbias[m0[r].x]; }
   }
   for (int g = 0;; ++g) {
@@ -508,13 +531,13 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       d1[r] = coefficient(m1[r], 0, e1[r]);
-      if (col_ok && m1[r].z > 0) { const size_t ro = row_offset(m1[r]); w0[r] = *(const cols_t*)(ru.W + ro); mo0[r] = *(const cols_t*)(ru.M + ro); v0[r] = *(const cols_t*)(ru.Vv + ro); }
+      if (col_ok && m1[r].z > 0) { const size_t ro = row_offset(m1[r]); w0[r] = *(const cols_t*)(ru.W + ro); mo0[r] = load_cols_stream<CPL>(ru.M + ro); v0[r] = load_cols_stream<CPL>(ru.Vv + ro); }
       if (bias_lane && m1[r].z > 0) { b0w[r] = ru.bias[m1[r].x]; b0m[r] = ru.mbias[m1[r].x]; b0v[r] = ru.vbias[m1[r].x]; }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r)
       if (j_s[r] >= 0) {
-        if (col_ok) { *(cols_t*)(ru.W + ro_s[r]) = ws[r]; *(cols_t*)(ru.M + ro_s[r]) = ms[r]; *(cols_t*)(ru.Vv + ro_s[r]) = vs[r]; }
+        if (col_ok) { *(cols_t*)(ru.W + ro_s[r]) = ws[r]; store_cols_stream<CPL>(ru.M + ro_s[r], ms[r]); store_cols_stream<CPL>(ru.Vv + ro_s[r], vs[r]); }
         if (bias_lane) { ru.bias[j_s[r]] = bsw[r]; ru.mbias[j_s[r]] = bsm[r]; ru.vbias[j_s[r]] = bsv[r]; }
         j_s[r] = -1;
       }
@@ -564,7 +587,7 @@ __device__ void rowgrad_adam_sliced(int H, int c0, const RowUpdate& ru, const Ad
 #pragma unroll
   for (int r = 0; r < R; ++r)
     if (j_s[r] >= 0) {
-      if (col_ok) { *(cols_t*)(ru.W + ro_s[r]) = ws[r]; *(cols_t*)(ru.M + ro_s[r]) = ms[r]; *(cols_t*)(ru.Vv + ro_s[r]) = vs[r]; }
+      if (col_ok) { *(cols_t*)(ru.W + ro_s[r]) = ws[r]; store_cols_stream<CPL>(ru.M + ro_s[r], ms[r]); store_cols_stream<CPL>(ru.Vv + ro_s[r], vs[r]); }
       if (bias_lane) { ru.bias[j_s[r]] = bsw[r]; ru.mbias[j_s[r]] = bsm[r]; ru.vbias[j_s[r]] = bsv[r]; }
     }
 }
