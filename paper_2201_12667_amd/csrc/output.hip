@@ -78,12 +78,17 @@ __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const 
       hv[c] = (FULL || col < H) ? *(const float4*)(h + (size_t)i * H + col) : make_float4(0.f, 0.f, 0.f, 0.f);
       acc[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    // the item's ids and their biases in one coalesced read each (lane l: neuron l of the item), handed to
+    // the row groups step by step: a step then waits for its rows only, not for an id first
+    const int my_j = ad.as_ids[first + (lane < n ? lane : 0)];
+    const float my_b = b2[my_j];
     float M = -INFINITY, s = 0.f;
     for (int q0 = 0; q0 < n; q0 += RPW) {
       const int q = q0 + grp;
       const bool valid = q < n;
       const int slot = first + (valid ? q : 0);
-      const int j = ad.as_ids[slot];
+      const int j = __shfl(my_j, valid ? q : 0);
+      const float bj = __shfl(my_b, valid ? q : 0);
       const float* wr = W2 + (size_t)j * H;
       float4 row[CH];
       float dot = 0.f;
@@ -94,7 +99,7 @@ __device__ __forceinline__ void forward_items(const ActiveDev& ad, int H, const 
         dot += row[c].x * hv[c].x + row[c].y * hv[c].y + row[c].z * hv[c].z + row[c].w * hv[c].w;
       }
       dot = group_sum<LPR>(dot);
-      const float zz = dot + b2[j];
+      const float zz = dot + bj;
       if (valid) {
         if (sub == 0) z[slot] = zz;
         const float Mn = fmaxf(M, zz);
