@@ -148,10 +148,13 @@ constexpr int kWaveSort = 64;      // queued buckets up to this size (within cap
 constexpr int kMedCap = kStageIds / 9 + 1;   // staged buckets of more than eight ids that a partition can hold
 constexpr int kSlotBatch = 16;     // 64-entry pieces of runs a wave keeps in flight
 
-// One workgroup per (partition d, table t): buckets (d << lb) .. (d << lb) + 2^lb - 1.  The partition's
-// entries are the runs of digit d of every slab.  Counts the low digit, writes the partition's offsets,
-// groups the ids by bucket -- in LDS when the partition fits, so that the table receives whole lines --
-// and sorts the small buckets; long and over-capacity buckets are queued.
+// One workgroup per (pair of partitions d, d + 1; table t); partition d holds the buckets (d << lb) ..
+// (d << lb) + 2^lb - 1 and its entries are the runs of digit d of every slab.  Per partition: counts the
+// low digit, writes the partition's offsets, groups the ids by bucket -- in LDS when the partition fits,
+// so that the table receives whole lines -- and sorts the small buckets; long and over-capacity buckets
+// are queued.  A partition's work starts with two dependent round trips to memory (its run boundaries,
+// then its entries) that take as long as all the rest: the workgroup makes them for both of its
+// partitions at once, so the second partition's entries sit in registers when its turn comes.
 __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __restrict__ entries,
                                                            const uint32_t* __restrict__ runs, int nslab,
                                                            const uint32_t* __restrict__ pbase, int nbins, int lb,
@@ -165,71 +168,102 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   const int nchunk = (nlo + 63) >> 6;    // 64 buckets per scan chunk
   uint32_t* cur = lds;                   // [nlo] counters, then bucket starts, then (after placing) bucket ends
   uint32_t* csum = cur + nlo;            // [nchunk] ids in the chunk, then in the chunks before it
-  uint32_t* ra = csum + nchunk;          // [nsb] start of the slab's run inside the slab's stretch
-  uint32_t* rn = ra + nsb;               // [nsb] its length
-  uint32_t* slots = rn + nsb;            // [nsb + kStageIds/64] 64-entry pieces of the runs: run | piece << 16
-  const uint32_t d = blockIdx.x;
-  const size_t t = blockIdx.y;
   const int slot_cap = nsb + kStageIds / 64;
-  int32_t* idl = (int32_t*)(slots + slot_cap);                 // [kStageIds] the partition's ids grouped by bucket
-  uint32_t* nslots_p = (uint32_t*)(idl + kStageIds);           // [1]
-  uint32_t* nmed_p = nslots_p + 1;                             // [2] staged buckets of 9 .. 16 ids / of 17 .. kRankMax
+  const int set_words = 2 * nsb + slot_cap;
+  uint32_t* sets = csum + nchunk;        // per partition of the pair: [nsb] start of the slab's run inside the slab's
+                                         // stretch, [nsb] its length, [slot_cap] 64-entry pieces of the runs: run | piece << 16
+  const size_t t = blockIdx.y;
+  int32_t* idl = (int32_t*)(sets + 2 * set_words);             // [kStageIds] the partition's ids grouped by bucket
+  uint32_t* nslots_p = (uint32_t*)(idl + kStageIds);           // [2] pieces of each partition of the pair
+  uint32_t* nmed_p = nslots_p + 2;                             // [2] staged buckets of 9 .. 16 ids / of 17 .. kRankMax
   uint32_t* medq = nmed_p + 2;                                 // [kMedCap] the former from the front, the latter from the back
   const uint32_t* tent = entries + t * N;
-  const uint32_t* truns = runs + t * nslab * (size_t)(nbins + 1) + d;
-  // The partition's entries are visited twice (count, then place).  The slabs are taken in blocks of nsb:
+  const uint32_t* truns0 = runs + t * nslab * (size_t)(nbins + 1);
+  auto ra_of = [&](int set) { return sets + set * set_words; };
+  auto rn_of = [&](int set) { return sets + set * set_words + nsb; };
+  auto slots_of = [&](int set) { return sets + set * set_words + 2 * nsb; };
+  // wave-wide: the pieces of the runs of one set, in run order
+  auto cut_pieces = [&](int set, int ns) {
+    const uint32_t* rn = rn_of(set);
+    uint32_t* slots = slots_of(set);
+    uint32_t carry = 0;
+    for (int q0 = 0; q0 < ns; q0 += 64) {
+      const int q = q0 + lane;
+      const uint32_t np = q < ns ? (rn[q] + 63u) >> 6 : 0u;
+      const uint32_t inc = wave_incl_scan_add(np);
+      uint32_t at = carry + inc - np;
+      for (uint32_t j = 0; j < np; ++j, ++at)
+        if (at < (uint32_t)slot_cap) slots[at] = (uint32_t)q | (j << 16);
+      carry += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+    }
+    if (lane == 0) nslots_p[set] = carry;
+  };
+  // A partition's entries are visited twice (count, then place).  The slabs are taken in blocks of nsb:
   // prepare() fetches the run boundaries of a block together and cuts the runs into pieces of 64
   // entries; a wave takes a piece, a lane an entry, kSlotBatch pieces per wave in flight at once.
-  auto prepare = [&](int sb) -> int {
+  auto prepare = [&](uint32_t d, int sb, int set) -> int {
     const int ns = min(nsb, nslab - sb);
+    uint32_t *ra = ra_of(set), *rn = rn_of(set);
     __syncthreads();
     for (int q = tid; q < ns; q += 256) {
-      const uint32_t* p = truns + (size_t)(sb + q) * (nbins + 1);
+      const uint32_t* p = truns0 + (size_t)(sb + q) * (nbins + 1) + d;
       const uint32_t a = p[0];
       ra[q] = a; rn[q] = p[1] - a;
     }
     __syncthreads();
-    if (wave == 0) {                               // pieces of every run, in run order
-      uint32_t carry = 0;
-      for (int q0 = 0; q0 < ns; q0 += 64) {
-        const int q = q0 + lane;
-        const uint32_t np = q < ns ? (rn[q] + 63u) >> 6 : 0u;
-        const uint32_t inc = wave_incl_scan_add(np);
-        uint32_t at = carry + inc - np;
-        for (uint32_t j = 0; j < np; ++j, ++at)
-          if (at < (uint32_t)slot_cap) slots[at] = (uint32_t)q | (j << 16);
-        carry += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
-      }
-      if (lane == 0) *nslots_p = carry;
-    }
+    if (wave == 0) cut_pieces(set, ns);
     __syncthreads();
     return ns;
   };
-  auto load_batch = [&](int sb, int base, int nslots, uint32_t (&x)[kSlotBatch], uint32_t (&rb)[kSlotBatch]) {
+  // the same for both partitions of the pair at once (one block of slabs): one round of reads, two waves cutting
+  auto prepare_pair = [&](uint32_t d, bool both) -> int {
+    const int ns = nslab;
+    __syncthreads();
+    for (int q = tid; q < ns; q += 256) {
+      const uint32_t* p = truns0 + (size_t)q * (nbins + 1) + d;
+      const uint32_t a0 = p[0], a1 = p[1];
+      ra_of(0)[q] = a0; rn_of(0)[q] = a1 - a0;
+      if (both) { ra_of(1)[q] = a1; rn_of(1)[q] = p[2] - a1; }
+    }
+    __syncthreads();
+    if (wave == 0 || (wave == 1 && both)) cut_pieces(wave, ns);
+    __syncthreads();
+    return ns;
+  };
+  auto load_batch = [&](int set, int sb, int base, int nslots, uint32_t (&x)[kSlotBatch]) {
+    const uint32_t *ra = ra_of(set), *rn = rn_of(set), *slots = slots_of(set);
 #pragma unroll
     for (int k = 0; k < kSlotBatch; ++k) {
       const int sl = base + 4 * k + wave;            // (wave-uniform)
-      x[k] = 0xffffffffu; rb[k] = 0;                 // (no entry has all bits set: at most 27 are used)
+      x[k] = 0xffffffffu;                            // (no entry has all bits set: at most 28 are used)
       if (sl < nslots) {
         const uint32_t info = slots[sl];
         const uint32_t q = info & 0xffffu, o = (info >> 16) * 64u + (uint32_t)lane;
-        rb[k] = (uint32_t)(sb + q) << kSlabBits;
-        if (o < rn[q]) x[k] = tent[(size_t)rb[k] + ra[q] + o];
+        if (o < rn[q]) x[k] = tent[(size_t)((uint32_t)(sb + q) << kSlabBits) + ra[q] + o];
       }
     }
   };
-  auto visit_block = [&](int sb, int ns, auto&& f) {   // f(global row, low digit) for every entry of the block
-    const int nslots = (int)*nslots_p;
+  // f(global row, low digit) for the entries a wave holds in x (pieces base + 4k + wave of the set)
+  auto visit_batch = [&](int set, int sb, int base, const uint32_t (&x)[kSlotBatch], auto&& f) {
+    const uint32_t* slots = slots_of(set);
+#pragma unroll
+    for (int k = 0; k < kSlotBatch; ++k)
+      if (x[k] != 0xffffffffu) {
+        const uint32_t rowbase = (uint32_t)(sb + (int)(slots[base + 4 * k + wave] & 0xffffu)) << kSlabBits;
+        f(rowbase + (x[k] & (uint32_t)(kSlab - 1)), x[k] >> kSlabBits);
+      }
+  };
+  auto visit_block = [&](int set, int sb, int ns, auto&& f) {   // f(global row, low digit) for every entry of the block
+    const int nslots = (int)nslots_p[set];
     if (nslots <= slot_cap) {
       for (int base = 0; base < nslots; base += 4 * kSlotBatch) {
-        uint32_t x[kSlotBatch], rb[kSlotBatch];
-        load_batch(sb, base, nslots, x, rb);
-#pragma unroll
-        for (int k = 0; k < kSlotBatch; ++k)
-          if (x[k] != 0xffffffffu) f(rb[k] + (x[k] & (uint32_t)(kSlab - 1)), x[k] >> kSlabBits);
+        uint32_t x[kSlotBatch];
+        load_batch(set, sb, base, nslots, x);
+        visit_batch(set, sb, base, x, f);
       }
     } else {
       // more pieces than the slot table holds (a partition far too large to stage): a wave per run
+      const uint32_t *ra = ra_of(set), *rn = rn_of(set);
       for (int q = wave; q < ns; q += 4) {
         const uint32_t a = ra[q], n = rn[q], rowbase = (uint32_t)(sb + q) << kSlabBits;
         for (uint32_t e = lane; e < n; e += 64) {
@@ -239,35 +273,25 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
       }
     }
   };
-  // Usual case: one block of slabs and at most 4*kSlotBatch pieces, so every entry of the partition sits
-  // in a register of some lane after one round of loads, and both visits use the registers.
   const bool single = nslab <= nsb;
-  uint32_t x0[kSlotBatch], rb0[kSlotBatch];
-  bool cached = false;
-  int ns0 = 0;
+  // One partition.  cached: every entry of the partition sits in a register of some lane (x: at most
+  // 4 * kSlotBatch pieces, fetched by the caller), and both visits use the registers.
+  auto run_partition = [&](const uint32_t d, const int set, const bool cached, const uint32_t (&x0)[kSlotBatch], const int ns0) {
   for (int b = tid; b < nlo; b += 256) cur[b] = 0;
   if (tid < 2) nmed_p[tid] = 0;
-  if (single) {
-    ns0 = prepare(0);
-    const int nslots = (int)*nslots_p;
-    cached = nslots <= 4 * kSlotBatch && nslots <= slot_cap;
-    if (cached) load_batch(0, 0, nslots, x0, rb0);
-  }
+  __syncthreads();
   const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
   const bool staged = s1 - s0 <= (uint32_t)kStageIds;
   auto visit = [&](auto&& f) {
     if (cached) {
-#pragma unroll
-      for (int k = 0; k < kSlotBatch; ++k)
-        if (x0[k] != 0xffffffffu) f(rb0[k] + (x0[k] & (uint32_t)(kSlab - 1)), x0[k] >> kSlabBits);
+      visit_batch(set, 0, 0, x0, f);
     } else if (single) {
-      visit_block(0, ns0, f);
+      visit_block(set, 0, ns0, f);
     } else {
-      for (int sb = 0; sb < nslab; sb += nsb) { const int ns = prepare(sb); visit_block(sb, ns, f); }
+      for (int sb = 0; sb < nslab; sb += nsb) { const int ns = prepare(d, sb, set); visit_block(set, sb, ns, f); }
     }
     __syncthreads();
   };
-  if (!single) __syncthreads();                    // (the counters are cleared before the first visit)
   visit([&](uint32_t, uint32_t low) { atomicAdd(&cur[low], 1u); });
   // exclusive scan of the counters: every wave scans chunks of 64 in registers, wave 0 the chunk sums
   for (int c = wave; c < nchunk; c += 4) {
@@ -407,6 +431,23 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
     }
   }
   if (over) atomicAdd(&ctrl->overflowed, over);
+  __syncthreads();                                   // (the next partition of the pair reuses the counters and the staging)
+  };
+  const uint32_t dA = 2u * blockIdx.x, dB = dA + 1u;
+  const bool both = dB < (uint32_t)nbins;
+  uint32_t xA[kSlotBatch], xB[kSlotBatch];
+  bool cachedA = false, cachedB = false;
+  int ns0 = 0;
+  if (single) {
+    ns0 = prepare_pair(dA, both);
+    const int nA = (int)nslots_p[0], nB = both ? (int)nslots_p[1] : 0;
+    cachedA = nA <= 4 * kSlotBatch && nA <= slot_cap;
+    cachedB = both && nB <= 4 * kSlotBatch && nB <= slot_cap;
+    if (cachedA) load_batch(0, 0, 0, nA, xA);
+    if (cachedB) load_batch(1, 0, 0, nB, xB);
+  }
+  run_partition(dA, 0, cachedA, xA, ns0);
+  if (both) run_partition(dB, 1, cachedB, xB, ns0);
 }
 
 // One wave per queued bucket of at most 64 ids (within capacity): a bitonic sort across the lanes.
@@ -542,7 +583,7 @@ size_t tables_pbase_words(int bits, int64_t N, int L) {
 static int run_block(int nslab) { return nslab < kRunBlock ? nslab : kRunBlock; }
 static size_t part_buckets_lds(int lb, int nsb) {
   const size_t nlo = (size_t)1 << lb;
-  return (nlo + ((nlo + 63) >> 6) + 3 * (size_t)nsb + kStageIds / 64 + kStageIds + 3 + kMedCap) * 4;
+  return (nlo + ((nlo + 63) >> 6) + 2 * (3 * (size_t)nsb + kStageIds / 64) + kStageIds + 4 + kMedCap) * 4;
 }
 static size_t slab_group_lds(int nbins) { return ((size_t)kSlab + (size_t)nbins + 20) * 4; }
 
@@ -618,7 +659,7 @@ hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const flo
                      bh, nslab, entries);
   hipLaunchKernelGGL(part_scan_kernel, dim3(td.L), dim3(1024), 0, s, bh, nslab, nbins, pbase, ctrl);
   const int nsb = run_block(nslab);
-  hipLaunchKernelGGL(part_buckets_kernel, dim3(nbins, td.L), dim3(256), part_buckets_lds(lb, nsb), s, entries, bh, nslab,
+  hipLaunchKernelGGL(part_buckets_kernel, dim3((nbins + 1) / 2, td.L), dim3(256), part_buckets_lds(lb, nsb), s, entries, bh, nslab,
                      pbase, nbins, lb, td.nb, td.N, td.C, td.off, td.ids, worklist, wl_cap, ctrl, nsb);
   hipLaunchKernelGGL(short_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, worklist, wl_cap, ctrl);
   hipLaunchKernelGGL(big_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, td.C, policy,
