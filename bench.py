@@ -30,17 +30,17 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # entry names the summary under profiles/ it was copied from, and is dropped (None) when a kernel it
 # covers has changed since that profile was taken.
 PROFILED_TRAFFIC = {
-    "cfg2-670k": {"update_kernel": 787.0e6, "forward_kernel": 221.9e6,
+    "cfg2-670k": {"update_kernel": 777.6e6, "forward_kernel": 209.9e6,
                   "source": "profiles/cfg2-670k_step_kernels.md (FETCH_SIZE x 2048 + WRITE_SIZE x 1024 bytes per "
                             "dispatch, mean of 45 dispatches, both factors from the copy kernel in the same runs)"},
-    "cfg1-shard167k": {"update_kernel": 214.4e6, "forward_kernel": 52.1e6,
+    "cfg1-shard167k": {"update_kernel": 212.2e6, "forward_kernel": 51.7e6,
                        "source": "profiles/cfg1-shard167k_step_kernels.md (mean of 45 dispatches)"},
-    "cfg4-825m": {"update_kernel": 623.0e6, "forward_kernel": 38.9e6,
+    "cfg4-825m": {"update_kernel": 587.2e6, "forward_kernel": 39.0e6,
                   "source": "profiles/cfg4-825m_step_kernels.md (mean of 45 dispatches)"},
-    "cfg3-wide325k": {"update_kernel": 451.8e6, "forward_kernel": 102.4e6,
+    "cfg3-wide325k": {"update_kernel": 425.1e6, "forward_kernel": 109.3e6,
                       "source": "profiles/cfg3-wide325k_step_kernels.md (update_sliced_kernel; mean of 45 dispatches "
                                 "of a workload whose touched rows shrink step by step)"},
-    "cfg5-text8-shape": {"update_kernel": 2052.5e6, "forward_kernel": 1164.2e6,
+    "cfg5-text8-shape": {"update_kernel": 2056.7e6, "forward_kernel": 1073.0e6,
                          "source": "profiles/cfg5-text8-shape_step_kernels.md (mean of 45 dispatches)"},
 }
 
