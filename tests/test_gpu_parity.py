@@ -496,6 +496,13 @@ def test_sampling_budget_steps_match_oracle(name, wl):
                               bucket_cap=32, row_major_mode=2)),
     ("h1024-b37", synth.small(synth.HASH_DWTA, hidden_dim=1024, K=2, L=6, num_classes=3001, input_dim=900,
                               bucket_cap=64, row_major_mode=2)),
+    # batches above 512 samples: their vectors do not fit the LDS by useful slices, the plain update runs
+    ("h64-b700", synth.small(synth.HASH_SIMHASH, hidden_dim=64, K=3, L=5, batch=700, num_classes=4001,
+                                        input_dim=700, nnz_mean=5.0, bucket_cap=32, row_major_mode=2)),
+    ("h200-b1024", synth.small(synth.HASH_SIMHASH, hidden_dim=200, K=4, L=6, batch=1024, num_classes=6007,
+                                          input_dim=0, bucket_cap=64, row_major_mode=2)),
+    ("h136-b513", synth.small(synth.HASH_DWTA, hidden_dim=136, K=2, L=7, batch=513, num_classes=3001,
+                                         input_dim=300, nnz_mean=4.0, bucket_cap=16, row_major_mode=2)),
     ("h64-b1100", synth.small(synth.HASH_SIMHASH, hidden_dim=64, K=3, L=5, batch=1100, num_classes=4001, input_dim=700,
                               nnz_mean=5.0, bucket_cap=32, row_major_mode=2)),
     ("h20-b2048-falls-back", synth.small(synth.HASH_SIMHASH, hidden_dim=20, K=3, L=4, batch=2048, num_classes=3001,
