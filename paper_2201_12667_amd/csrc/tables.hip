@@ -167,6 +167,8 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nchunk = (nlo + 63) >> 6;    // 64 buckets per scan chunk
   uint32_t* cur = lds;                   // [nlo] counters, then bucket starts, then (after placing) bucket ends
+  uint4* cur4 = reinterpret_cast<uint4*>(lds);
+  const bool vec = (nlo & 1023) == 0;    // many buckets per partition: the passes over them take four per lane
   uint32_t* csum = cur + nlo;            // [nchunk] ids in the chunk, then in the chunks before it
   const int slot_cap = nsb + kStageIds / 64;
   const int set_words = 2 * nsb + slot_cap;
@@ -277,7 +279,8 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   // One partition.  cached: every entry of the partition sits in a register of some lane (x: at most
   // 4 * kSlotBatch pieces, fetched by the caller), and both visits use the registers.
   auto run_partition = [&](const uint32_t d, const int set, const bool cached, const uint32_t (&x0)[kSlotBatch], const int ns0) {
-  for (int b = tid; b < nlo; b += 256) cur[b] = 0;
+  if (vec) for (int q = tid; q < nlo / 4; q += 256) cur4[q] = make_uint4(0u, 0u, 0u, 0u);
+  else for (int b = tid; b < nlo; b += 256) cur[b] = 0;
   if (tid < 2) nmed_p[tid] = 0;
   __syncthreads();
   const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
@@ -293,31 +296,55 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
     __syncthreads();
   };
   visit([&](uint32_t, uint32_t low) { atomicAdd(&cur[low], 1u); });
-  // exclusive scan of the counters: every wave scans chunks of 64 in registers, wave 0 the chunk sums
-  for (int c = wave; c < nchunk; c += 4) {
-    const int b = c * 64 + lane;
-    const uint32_t v = b < nlo ? cur[b] : 0u;
-    const uint32_t inc = wave_incl_scan_add(v);
-    if (b < nlo) cur[b] = inc - v;
-    if (lane == 63) csum[c] = inc;
+  // exclusive scan of the counters: every wave scans chunks of 64 lanes in registers, wave 0 the chunk
+  // sums.  Many buckets per partition (vec): a lane holds four neighbouring counters, a chunk is 256.
+  const int nch = vec ? nlo >> 8 : nchunk;
+  if (vec) {
+    for (int c = wave; c < nch; c += 4) {
+      const uint4 v = cur4[c * 64 + lane];
+      const uint32_t p1 = v.x, p2 = p1 + v.y, p3 = p2 + v.z, p4 = p3 + v.w;
+      const uint32_t inc = wave_incl_scan_add(p4), base = inc - p4;
+      cur4[c * 64 + lane] = make_uint4(base, base + p1, base + p2, base + p3);
+      if (lane == 63) csum[c] = inc;
+    }
+  } else {
+    for (int c = wave; c < nch; c += 4) {
+      const int b = c * 64 + lane;
+      const uint32_t v = b < nlo ? cur[b] : 0u;
+      const uint32_t inc = wave_incl_scan_add(v);
+      if (b < nlo) cur[b] = inc - v;
+      if (lane == 63) csum[c] = inc;
+    }
   }
   __syncthreads();
   if (wave == 0) {
     uint32_t carry = 0;
-    for (int c0 = 0; c0 < nchunk; c0 += 64) {
+    for (int c0 = 0; c0 < nch; c0 += 64) {
       const int c = c0 + lane;
-      const uint32_t v = c < nchunk ? csum[c] : 0u;
+      const uint32_t v = c < nch ? csum[c] : 0u;
       const uint32_t inc = wave_incl_scan_add(v);
-      if (c < nchunk) csum[c] = carry + inc - v;
+      if (c < nch) csum[c] = carry + inc - v;
       carry += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
     }
   }
   __syncthreads();
   uint32_t* orow = off + t * (nb + 1) + ((size_t)d << lb);
-  for (int b = tid; b < nlo; b += 256) {
-    const uint32_t st = cur[b] + csum[b >> 6];
-    cur[b] = st;
-    orow[b] = s0 + st;
+  if (vec) {
+    // (a table's offsets start at a multiple of nb + 1 words: word-aligned only)
+    struct __attribute__((packed, aligned(4))) Words4 { uint32_t x, y, z, w; };
+    for (int q = tid; q < nlo / 4; q += 256) {
+      uint4 v = cur4[q];
+      const uint32_t add = csum[q >> 6];
+      v.x += add; v.y += add; v.z += add; v.w += add;
+      cur4[q] = v;
+      reinterpret_cast<Words4*>(orow)[q] = Words4{s0 + v.x, s0 + v.y, s0 + v.z, s0 + v.w};
+    }
+  } else {
+    for (int b = tid; b < nlo; b += 256) {
+      const uint32_t st = cur[b] + csum[b >> 6];
+      cur[b] = st;
+      orow[b] = s0 + st;
+    }
   }
   if (d == (uint32_t)nbins - 1 && tid == 0) off[t * (nb + 1) + nb] = (uint32_t)N;
   int32_t* seg = ids + t * N + s0;
@@ -337,18 +364,17 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
     }
   };
   if (staged) {
-    // The ids sit in idl grouped by bucket, in arrival order; a thread takes a bucket.  Up to eight
-    // ids (nearly every bucket of a fresh layer) are sorted in registers by a fixed network of
-    // comparators -- the same instructions in every lane, whatever the bucket's size -- and go straight
-    // to the table.  Longer buckets are noted for the pass below; those beyond kRankMax or over
-    // capacity are copied as they are and queued.
-    for (int b0 = 0; b0 < nlo; b0 += 256) {
-      const int b = b0 + tid;                        // (every lane runs the loop: the network is wave-wide)
-      const uint32_t a = (b && b < nlo) ? cur[b - 1] : 0u, sz = b < nlo ? cur[b] - a : 0u;
+    // The ids sit in idl grouped by bucket, in arrival order, and are sorted where they are; the whole
+    // partition then goes to the table in one coalesced copy (a store per bucket costs far more than
+    // its bytes).  A thread takes a bucket.  Up to eight ids (nearly every bucket of a fresh layer) are
+    // sorted in registers by a fixed network of comparators -- the same instructions in every lane,
+    // whatever the bucket's size.  Longer buckets are noted for the pass below; those beyond kRankMax
+    // or over capacity stay as they are and are queued.
+    // bucket b = ids a .. a + sz - 1 (every lane of a wave calls it together: the network is wave-wide)
+    auto bucket = [&](const int b, const uint32_t a, const uint32_t sz) {
       if (sz > (uint32_t)C) ++over;
       const bool big = sz > (uint32_t)kRankMax || sz > (uint32_t)C;
       if (big) {
-        for (uint32_t q = a; q < a + sz; ++q) seg[q] = idl[q];
         enqueue(b, sz);
       } else if (sz > 16u) {
         medq[kMedCap - 1 - atomicAdd(&nmed_p[1], 1u)] = (uint32_t)b;   // (lane groups / waves order these below:
@@ -356,9 +382,14 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
         medq[atomicAdd(&nmed_p[0], 1u)] = (uint32_t)b;
       }
       const uint32_t n8 = (big || sz > 8u) ? 0u : sz;
-      if (!__any(n8 > 1u)) {                             // (sparse tables: nearly every bucket is empty or a single id)
-        if (n8 == 1u) seg[a] = idl[a];
-        continue;
+      if (!__any(n8 > 1u)) return;                       // (sparse tables: nearly every bucket is empty or a single id)
+      if (!__any(n8 > 2u)) {
+        if (n8 > 1u) {
+          const int32_t u0 = idl[a], u1 = idl[a + 1];
+          idl[a] = min(u0, u1);
+          idl[a + 1] = max(u0, u1);
+        }
+        return;
       }
       int32_t v[8];
 #pragma unroll
@@ -380,7 +411,29 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
 #undef SLIDE_CE
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        if ((uint32_t)i < n8) seg[a + i] = v[i];
+        if ((uint32_t)i < n8) idl[a + i] = v[i];
+    };
+    if (vec) {
+      // a wave takes 256 neighbouring buckets, a lane four of them; nearly always, with so many
+      // buckets, none of the 256 holds two ids and there is nothing to sort
+      for (int b0 = wave * 256; b0 < nlo; b0 += 1024) {
+        const int q = (b0 >> 2) + lane;
+        const uint4 e = cur4[q];
+        const uint32_t a = q ? cur[4 * q - 1] : 0u;
+        const uint32_t most = max(max(e.x - a, e.y - e.x), max(e.z - e.y, e.w - e.z));
+        if (__any(most > 1u)) {
+          bucket(4 * q, a, e.x - a);
+          bucket(4 * q + 1, e.x, e.y - e.x);
+          bucket(4 * q + 2, e.y, e.z - e.y);
+          bucket(4 * q + 3, e.z, e.w - e.z);
+        }
+      }
+    } else {
+      for (int b0 = 0; b0 < nlo; b0 += 256) {
+        const int b = b0 + tid;
+        const uint32_t a = (b && b < nlo) ? cur[b - 1] : 0u;
+        bucket(b, a, b < nlo ? cur[b] - a : 0u);
+      }
     }
     // Longer buckets (a trained layer has many): one thread sorting its bucket alone would hold up its
     // wave for the square of the bucket's length.  9 .. 16 ids: a row of 16 lanes each, an id per lane,
@@ -395,7 +448,7 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
       if (m < nrow) { const uint32_t b = medq[m]; a = b ? cur[b - 1] : 0u; sz = cur[b] - a; }
       const int32_t key = (uint32_t)l16 < sz ? idl[a + l16] : 0x7fffffff;
       const uint32_t rank = row_rank_i32(key);
-      if ((uint32_t)l16 < sz) seg[a + rank] = key;
+      if ((uint32_t)l16 < sz) idl[a + rank] = key;
     }
     for (uint32_t m = wave; m < nwav; m += 4) {
       const uint32_t b = medq[kMedCap - 1 - m];
@@ -410,8 +463,10 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
           const int32_t mn = key < other ? key : other, mx = key < other ? other : key;
           key = (lower == up) ? mn : mx;
         }
-      if ((uint32_t)lane < sz) seg[a + lane] = key;
+      if ((uint32_t)lane < sz) idl[a + lane] = key;
     }
+    __syncthreads();
+    for (uint32_t p = tid; p < s1 - s0; p += 256) seg[p] = idl[p];
   } else {
     for (int b = tid; b < nlo; b += 256) {
       const uint32_t a = b ? cur[b - 1] : 0u, sz = cur[b] - a;

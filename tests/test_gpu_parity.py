@@ -61,6 +61,35 @@ def test_tables_bit_exact_first_build_and_rebuild(kind, policy, C, N):
     model.destroy()
 
 
+@pytest.mark.parametrize("kind,K,N,C,policy", [(synth.HASH_DWTA, 6, 20011, 16, 1), (synth.HASH_DWTA, 5, 9001, 2, 0),
+                                               (synth.HASH_SIMHASH, 16, 5003, 8, 1)])
+def test_tables_with_far_more_buckets_than_neurons(kind, K, N, C, policy):
+    """Codes of 15 .. 18 bits over a few thousand neurons: a partition of the bucket kernel spans
+    2048 .. 8192 buckets, nearly all of them empty.  Every occupied bucket and its neighbours are
+    compared, and a sample of the others; the occupied ones must hold all N neurons."""
+    _say("sparse tables", kind, K, N, C, policy)
+    wl = synth.small(kind, K=K, L=5, bucket_cap=C, num_classes=N, overflow_policy=policy, input_dim=0)
+    gen, model, orc = make_pair(wl)
+    nb = wl.num_buckets
+    rng = np.random.default_rng(7)
+    for rebuild in (False, True):
+        model.build_tables()
+        T = orc.build_tables(first=not rebuild)
+        assert model.stats()["overflowed_buckets"] == T.overflowed
+        codes = orc.hash.codes(orc.p["W2"])
+        for t in range(wl.L):
+            occ = np.unique(codes[:, t]).astype(np.int64)
+            look = np.unique(np.concatenate([occ, occ - 1, occ + 1, rng.integers(0, nb, 3000), [0, nb - 1]]))
+            look = look[(look >= 0) & (look < nb)]
+            held = 0
+            for c in look:
+                got, want = model.debug_bucket(t, int(c)), T.bucket(t, int(c))
+                assert np.array_equal(got, want), (rebuild, t, int(c), got, want)
+                held += len(got)
+            assert held == T.entries(t)
+    model.destroy()
+
+
 def test_degenerate_tables_all_rows_identical():
     _say("tables degenerate")
     wl = synth.small(synth.HASH_DWTA, K=2, L=3, bucket_cap=8, num_classes=5000, input_dim=0)
