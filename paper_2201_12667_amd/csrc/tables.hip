@@ -553,18 +553,28 @@ __device__ __forceinline__ uint32_t overflow_prio(uint32_t j, uint32_t t, uint32
   return u;
 }
 
-// One workgroup per queued bucket.  size <= C: sort by id.  size > C: stream the members through
-// LDS keeping the C smallest (priority, id) keys, then sort the survivors by id.
+constexpr int kSelStage = 4096;    // members of an over-capacity bucket staged in LDS while its survivors are chosen
+
+// One workgroup per queued bucket.  size <= C: sort by id.  size > C: the survivors are the C members
+// with the smallest (priority, id) keys.  The C-th smallest key is found digit by digit from the top
+// (a 256-bin histogram of the candidates' next eight bits, a scan, the bin that holds rank C; the
+// search ends as soon as the bins up to the chosen one hold exactly the wanted number, which with
+// hashed priorities happens after two or three digits); then the members at or below it are gathered
+// and put in id order.  A handful of barriers per bucket where a full sort of the members took eighty.
 __global__ __launch_bounds__(256) void big_buckets_kernel(const uint32_t* __restrict__ off, int32_t* ids,
                                                           uint32_t nb, int64_t N, int C, int policy, uint32_t r,
                                                           uint32_t pa, uint32_t pb,
                                                           const uint64_t* __restrict__ worklist,
                                                           uint32_t wl_cap, const Ctrl* ctrl) {
   __shared__ uint64_t keys[kSortCap];
+  __shared__ uint32_t sid[kSelStage];
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t pick[4];                 // chosen digit, rank left inside it, 1 when the search is over, survivors gathered
   uint32_t n_items = ctrl->wl_count;
   if (n_items > wl_cap) n_items = wl_cap;
   int capp = 1;
   while (capp < C) capp <<= 1;
+  const int tid = threadIdx.x, lane = tid & 63;
   for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
     const uint64_t w = worklist[item];
     const uint64_t t = w >> 32;
@@ -575,38 +585,79 @@ __global__ __launch_bounds__(256) void big_buckets_kernel(const uint32_t* __rest
     if (s <= (uint32_t)C) {
       int n2 = 2;
       while ((uint32_t)n2 < s) n2 <<= 1;
-      for (int i = threadIdx.x; i < n2; i += 256) keys[i] = (uint32_t)i < s ? (uint64_t)(uint32_t)p[i] : ~0ull;
+      for (int i = tid; i < n2; i += 256) keys[i] = (uint32_t)i < s ? (uint64_t)(uint32_t)p[i] : ~0ull;
       __syncthreads();
       bitonic_sort_u64(keys, n2);
-      for (uint32_t i = threadIdx.x; i < s; i += 256) p[i] = (int32_t)(uint32_t)keys[i];
+      for (uint32_t i = tid; i < s; i += 256) p[i] = (int32_t)(uint32_t)keys[i];
     } else {
-      const uint32_t chunk = kSortCap - capp;
-      for (int i = threadIdx.x; i < capp; i += 256) keys[i] = ~0ull;
-      for (uint32_t base = 0; base < s; base += chunk) {
-        // the survivors so far plus the next members, padded to a power of two (often well below kSortCap)
-        const uint32_t m = s - base < chunk ? s - base : chunk;
-        int nsort = 2 * capp;
-        while ((uint32_t)nsort < (uint32_t)capp + m) nsort <<= 1;
-        for (uint32_t i = threadIdx.x; i < (uint32_t)(nsort - capp); i += 256) {
-          uint64_t k = ~0ull;
-          if (i < m) {
-            const uint32_t j = (uint32_t)p[base + i];
-            const uint32_t pr = policy == SLIDE_KEEP_LOWEST_ID ? 0u : overflow_prio(j, (uint32_t)t, r, pa, pb);
-            k = ((uint64_t)pr << 32) | j;
-          }
-          keys[capp + i] = k;
+      const bool in_lds = s <= (uint32_t)kSelStage;
+      if (in_lds) for (uint32_t i = tid; i < s; i += 256) sid[i] = (uint32_t)p[i];
+      hist[tid] = 0;
+      if (tid == 0) pick[3] = 0;
+      __syncthreads();
+      auto member = [&](uint32_t i) { return in_lds ? sid[i] : (uint32_t)p[i]; };
+      auto key_of = [&](uint32_t j) {
+        const uint32_t pr = policy == SLIDE_KEEP_LOWEST_ID ? 0u : overflow_prio(j, (uint32_t)t, r, pa, pb);
+        return ((uint64_t)pr << 32) | j;
+      };
+      uint64_t prefix = 0;                      // the digits chosen so far, in place
+      uint32_t want = (uint32_t)C;              // rank of the wanted key among the candidates (1-based)
+      int shift = policy == SLIDE_KEEP_LOWEST_ID ? 24 : 56;   // (without priorities the upper half of every key is zero)
+      for (;; shift -= 8) {
+        // candidates: the members whose digits above this one equal the chosen ones
+        for (uint32_t i = tid; i < s; i += 256) {
+          const uint64_t k = key_of(member(i));
+          if (shift == 56 || (k >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(uint32_t)(k >> shift) & 255u], 1u);
         }
         __syncthreads();
-        bitonic_sort_u64(keys, nsort);
+        if (tid < 64) {                         // lane l: bins 4l .. 4l + 3
+          const uint32_t c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+          hist[4 * lane] = 0; hist[4 * lane + 1] = 0; hist[4 * lane + 2] = 0; hist[4 * lane + 3] = 0;
+          const uint32_t tot = c0 + c1 + c2 + c3, incl = wave_incl_scan_add(tot), excl = incl - tot;
+          if (excl < want && want <= incl) {    // (one lane: the candidates number at least `want`)
+            uint32_t before = excl, digit = 4u * (uint32_t)lane, in_bin = c0;
+            if (before + in_bin < want) { before += in_bin; ++digit; in_bin = c1; }
+            if (before + in_bin < want) { before += in_bin; ++digit; in_bin = c2; }
+            if (before + in_bin < want) { before += in_bin; ++digit; in_bin = c3; }
+            pick[0] = digit;
+            pick[1] = want - before;
+            pick[2] = (before + in_bin == want || shift == 0) ? 1u : 0u;
+          }
+        }
+        __syncthreads();
+        prefix |= (uint64_t)pick[0] << shift;
+        want = pick[1];
+        const bool found = pick[2] != 0u;
+        if (found || shift == 0) break;         // (uniform; at shift 0 a bin holds one key, so the search ends there at the latest)
       }
-      uint64_t mine[kSortCap / 512];            // capp <= 1024: at most 4 per thread
-      for (int i = threadIdx.x, q = 0; i < capp; i += 256, ++q)
-        mine[q] = i < C ? (uint64_t)(uint32_t)keys[i] : ~0ull;
+      // every key up to the chosen digit with all lower digits set survives: exactly C of them
+      const uint64_t limit = prefix | (shift ? ((uint64_t)1 << shift) - 1u : 0u);
+      uint32_t* surv = reinterpret_cast<uint32_t*>(keys);
+      for (uint32_t i = tid; i < s; i += 256) {
+        const uint32_t j = member(i);
+        if (key_of(j) <= limit) {
+          const uint32_t slot = atomicAdd(&pick[3], 1u);
+          if (slot < (uint32_t)C) surv[slot] = j;
+        }
+      }
       __syncthreads();
-      for (int i = threadIdx.x, q = 0; i < capp; i += 256, ++q) keys[i] = mine[q];
-      __syncthreads();
-      bitonic_sort_u64(keys, capp);
-      for (int i = threadIdx.x; i < C; i += 256) p[i] = (int32_t)(uint32_t)keys[i];
+      if (C <= 256) {
+        // id order by counting: a survivor's place is the number of survivors with a smaller id
+        if (tid < C) {
+          const uint32_t mine = surv[tid];
+          uint32_t place = 0;
+          for (int q = 0; q < C; ++q) place += surv[q] < mine ? 1u : 0u;
+          p[place] = (int32_t)mine;
+        }
+      } else {
+        uint64_t mine[kSortCap / 512];            // capp <= 1024: at most 4 per thread
+        for (int i = tid, q = 0; i < capp; i += 256, ++q) mine[q] = i < C ? (uint64_t)surv[i] : ~0ull;
+        __syncthreads();
+        for (int i = tid, q = 0; i < capp; i += 256, ++q) keys[i] = mine[q];
+        __syncthreads();
+        bitonic_sort_u64(keys, capp);
+        for (int i = tid; i < C; i += 256) p[i] = (int32_t)(uint32_t)keys[i];
+      }
     }
     __syncthreads();
   }

@@ -90,9 +90,12 @@ def test_tables_with_far_more_buckets_than_neurons(kind, K, N, C, policy):
     model.destroy()
 
 
-def test_degenerate_tables_all_rows_identical():
-    _say("tables degenerate")
-    wl = synth.small(synth.HASH_DWTA, K=2, L=3, bucket_cap=8, num_classes=5000, input_dim=0)
+@pytest.mark.parametrize("N,policy", [(5000, 1), (12000, 1), (12000, 0)])
+def test_degenerate_tables_all_rows_identical(N, policy):
+    """Two buckets per table hold everything (4,000 identical rows; the all-zero rest, which at
+    N = 12,000 is more than the survivor search stages on chip)."""
+    _say("tables degenerate", N, policy)
+    wl = synth.small(synth.HASH_DWTA, K=2, L=3, bucket_cap=8, num_classes=N, input_dim=0, overflow_policy=policy)
     gen = synth.Generator(wl, 0)
     w = gen.weights()
     w["W2"][:] = w["W2"][0]                    # one bucket per table holds every neuron
