@@ -258,9 +258,10 @@ const char* slide_last_error(const slide_ctx* ctx);
 
 /* ---- read-backs for staged verification (synchronous; not part of the hot path) ---------- */
 
-/* Measurement aid: a plain device-to-device copy kernel (16 bytes per thread per step), the
- * yardstick against which hardware counters and achieved bandwidth are calibrated.  Enqueued on the
- * stream; pointers and bytes must be multiples of 16. */
+/* Measurement aid: a plain device-to-device copy kernel (four 16-byte words per thread in flight,
+ * streaming loads and stores: the fastest plain copy found on this device), the yardstick against
+ * which hardware counters and achieved bandwidth are calibrated.  Enqueued on the stream; pointers
+ * and bytes must be multiples of 16. */
 int slide_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream);
 /* Table codes of `rows` device vectors of length H with the context's hash functions. */
 int slide_debug_hash(slide_ctx* ctx, const float* d_vectors, int64_t rows,

@@ -593,3 +593,17 @@ def test_randomly_shaped_workloads_two_steps(name, wl):
         res = compare_step(model, orc, gen.batch(s))
         assert_ok(res)
     model.destroy()
+
+
+def test_copy_yardstick_copies_every_byte():
+    """The measurement aid behind the bandwidth figures: whole chunks, a ragged tail, less than a chunk."""
+    from paper_2201_12667_amd import slide
+    st = torch.cuda.current_stream().cuda_stream
+    for words in (1, 255, 1023, 1024, 1025, 3 * 1024 + 5, 70000 * 1024 + 777):
+        _say("copy", words, "x 16 bytes")
+        src = torch.randint(0, 256, (words * 16,), dtype=torch.uint8, device="cuda:0")
+        dst = torch.zeros(words * 16 + 16, dtype=torch.uint8, device="cuda:0")
+        slide.debug_copy(dst[:words * 16], src, st)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:words * 16], src)
+        assert int(dst[words * 16:].sum()) == 0
