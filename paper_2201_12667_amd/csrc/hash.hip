@@ -220,11 +220,28 @@ __global__ __launch_bounds__(1024) void hash_rows_kernel(HashDev hd, const uint3
   }
   if ((int)threadIdx.x < stride) tile[H * stride + threadIdx.x] = 0.0f;
   __syncthreads();
-  for (int idx = threadIdx.x; idx < RPT * H; idx += blockDim.x) {   // coalesced read, conflict-free store
-    const int r = idx / H, c = idx - r * H;
-    const int64_t row = rid[r];
-    const float x = row >= 0 ? V[row * H + c] : 0.0f;
-    tile[c * stride + r] = MODE == 0 ? x : __uint_as_float(dwta_key(x));
+  // coalesced reads, eight per thread in flight (a tile of long vectors is tens of elements per thread,
+  // and one at a time would be as many round trips to memory); conflict-free stores
+  constexpr int kTileBatch = 8;
+  const int total = RPT * H;
+  for (int base = 0; base < total; base += kTileBatch * (int)blockDim.x) {
+    float x[kTileBatch];
+    int at[kTileBatch];
+#pragma unroll
+    for (int u = 0; u < kTileBatch; ++u) {
+      const int idx = base + u * (int)blockDim.x + (int)threadIdx.x;
+      x[u] = 0.0f;
+      at[u] = -1;
+      if (idx < total) {
+        const int r = idx / H, c = idx - r * H;
+        const int64_t row = rid[r];
+        at[u] = c * stride + r;
+        if (row >= 0) x[u] = V[row * H + c];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kTileBatch; ++u)
+      if (at[u] >= 0) tile[at[u]] = MODE == 0 ? x[u] : __uint_as_float(dwta_key(x[u]));
   }
   __syncthreads();
   const int lane = threadIdx.x & 63;
