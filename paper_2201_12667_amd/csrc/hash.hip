@@ -13,7 +13,11 @@
 
 namespace slide {
 
-static int rows_per_tile(int H) { return H <= 512 ? 64 : (H <= 1024 ? 32 : 16); }
+// Vectors per tile of the row-tile kernel: 64 (a wave per table) while two tiles fit a compute unit's LDS;
+// beyond that 16, so that two workgroups still share a compute unit and one reads its tile while the
+// other hashes (with 32 vectors of 1,024 coordinates a single workgroup filled the LDS and the unit
+// idled through every tile read).
+static int rows_per_tile(int H) { return H <= 512 ? 64 : 16; }
 size_t hash_lds_bytes(int H) { return ((size_t)H + 1) * (rows_per_tile(H) + 1) * sizeof(float); }
 int hash_tile_pitch(int H) { return rows_per_tile(H) + 1; }
 
