@@ -155,10 +155,11 @@ __global__ __launch_bounds__(1024) void part_scan_kernel(const uint32_t* __restr
   if (t == 0 && tid == 0) { ctrl->wl_count = 0; ctrl->wl_short = 0; ctrl->overflowed = 0; }
 }
 
-constexpr int kStageIds = 4096;    // ids of a partition staged in LDS by part_buckets (larger partitions go through memory)
+constexpr int kStageIds = 4096;    // most ids of a partition staged in LDS by part_buckets (larger partitions go through memory)
+constexpr int kStageMin = 1024;    // the staging area is four mean partitions, within these two
 constexpr int kRankMax = 64;       // staged buckets up to this size are sorted where they are staged
 constexpr int kWaveSort = 64;      // queued buckets up to this size (within capacity) are sorted by one wave
-constexpr int kMedCap = kStageIds / 9 + 1;   // staged buckets of more than eight ids that a partition can hold
+static __host__ __device__ inline int med_cap(int stage) { return stage / 9 + 1; }   // staged buckets of more than eight ids
 constexpr int kSlotBatch = 16;     // 64-entry pieces of runs a wave keeps in flight
 
 // One workgroup per (pair of partitions d, d + 1; table t); partition d holds the buckets (d << lb) ..
@@ -174,7 +175,8 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
                                                            uint32_t nb, int64_t N, int C,
                                                            uint32_t* __restrict__ off,
                                                            int32_t* ids, uint64_t* worklist, uint32_t wl_cap,
-                                                           Ctrl* ctrl, int nsb /* min(nslab, kRunBlock) */) {
+                                                           Ctrl* ctrl, int nsb /* min(nslab, kRunBlock) */,
+                                                           int stage /* ids of a partition that fit the staging area */) {
   extern __shared__ uint32_t lds[];
   const int nlo = 1 << lb, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -183,15 +185,16 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   uint4* cur4 = reinterpret_cast<uint4*>(lds);
   const bool vec = (nlo & 1023) == 0;    // many buckets per partition: the passes over them take four per lane
   uint32_t* csum = cur + nlo;            // [nchunk] ids in the chunk, then in the chunks before it
-  const int slot_cap = nsb + kStageIds / 64;
+  const int slot_cap = nsb + stage / 64;
+  const int medcap = med_cap(stage);
   const int set_words = 2 * nsb + slot_cap;
   uint32_t* sets = csum + nchunk;        // per partition of the pair: [nsb] start of the slab's run inside the slab's
                                          // stretch, [nsb] its length, [slot_cap] 64-entry pieces of the runs: run | piece << 16
   const size_t t = blockIdx.y;
-  int32_t* idl = (int32_t*)(sets + 2 * set_words);             // [kStageIds] the partition's ids grouped by bucket
-  uint32_t* nslots_p = (uint32_t*)(idl + kStageIds);           // [2] pieces of each partition of the pair
+  int32_t* idl = (int32_t*)(sets + 2 * set_words);             // [stage] the partition's ids grouped by bucket
+  uint32_t* nslots_p = (uint32_t*)(idl + stage);           // [2] pieces of each partition of the pair
   uint32_t* nmed_p = nslots_p + 2;                             // [2] staged buckets of 9 .. 16 ids / of 17 .. kRankMax
-  uint32_t* medq = nmed_p + 2;                                 // [kMedCap] the former from the front, the latter from the back
+  uint32_t* medq = nmed_p + 2;                                 // [medcap] the former from the front, the latter from the back
   const uint32_t* tent = entries + t * N;
   const uint32_t* truns0 = runs + t * nslab * (size_t)(nbins + 1);
   auto ra_of = [&](int set) { return sets + set * set_words; };
@@ -297,7 +300,7 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
   if (tid < 2) nmed_p[tid] = 0;
   __syncthreads();
   const uint32_t s0 = pbase[t * (nbins + 1) + d], s1 = pbase[t * (nbins + 1) + d + 1];
-  const bool staged = s1 - s0 <= (uint32_t)kStageIds;
+  const bool staged = s1 - s0 <= (uint32_t)stage;
   auto visit = [&](auto&& f) {
     if (cached) {
       visit_batch(set, 0, 0, x0, f);
@@ -390,8 +393,8 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
       if (big) {
         enqueue(b, sz);
       } else if (sz > 16u) {
-        medq[kMedCap - 1 - atomicAdd(&nmed_p[1], 1u)] = (uint32_t)b;   // (lane groups / waves order these below:
-      } else if (sz > 8u) {                                             //  at most kStageIds / 9 of them exist)
+        medq[medcap - 1 - atomicAdd(&nmed_p[1], 1u)] = (uint32_t)b;   // (lane groups / waves order these below:
+      } else if (sz > 8u) {                                             //  at most stage / 9 of them exist)
         medq[atomicAdd(&nmed_p[0], 1u)] = (uint32_t)b;
       }
       const uint32_t n8 = (big || sz > 8u) ? 0u : sz;
@@ -464,7 +467,7 @@ __global__ __launch_bounds__(256) void part_buckets_kernel(const uint32_t* __res
       if ((uint32_t)l16 < sz) idl[a + rank] = key;
     }
     for (uint32_t m = wave; m < nwav; m += 4) {
-      const uint32_t b = medq[kMedCap - 1 - m];
+      const uint32_t b = medq[medcap - 1 - m];
       const uint32_t a = b ? cur[b - 1] : 0u, sz = cur[b] - a;
       int32_t key = (uint32_t)lane < sz ? idl[a + lane] : 0x7fffffff;
 #pragma unroll
@@ -700,9 +703,17 @@ size_t tables_pbase_words(int bits, int64_t N, int L) {
 }
 
 static int run_block(int nslab) { return nslab < kRunBlock ? nslab : kRunBlock; }
-static size_t part_buckets_lds(int lb, int nsb) {
+static size_t part_buckets_lds(int lb, int nsb, int stage) {
   const size_t nlo = (size_t)1 << lb;
-  return (nlo + ((nlo + 63) >> 6) + 2 * (3 * (size_t)nsb + kStageIds / 64) + kStageIds + 4 + kMedCap) * 4;
+  return (nlo + ((nlo + 63) >> 6) + 2 * (3 * (size_t)nsb + stage / 64) + stage + 4 + med_cap(stage)) * 4;
+}
+// The staging area of the bucket kernel: four mean partitions (a fresh layer's partitions stay within a
+// few percent of the mean, a trained one's within a few times), so that tables with many buckets per
+// partition, whose counters take most of the LDS, still fit another workgroup per compute unit.
+static int stage_ids(int64_t N, int nbins) {
+  const int64_t want = 4 * ((N + nbins - 1) / nbins);
+  const int64_t s = want < kStageMin ? kStageMin : (want > kStageIds ? kStageIds : want);
+  return (int)((s + 63) / 64 * 64);
 }
 static size_t slab_group_lds(int nbins) { return ((size_t)kSlab + (size_t)nbins + 20) * 4; }
 
@@ -742,7 +753,7 @@ hipError_t tables_setup_attributes() {
 #define SLIDE_SET(K, BYTES) \
   e = hipFuncSetAttribute((const void*)&K, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(BYTES)); \
   if (e != hipSuccess) return e;
-  SLIDE_SET(part_buckets_kernel, part_buckets_lds(13, kRunBlock))
+  SLIDE_SET(part_buckets_kernel, part_buckets_lds(13, kRunBlock, kStageIds))
   SLIDE_SET(slab_group_kernel, slab_group_lds(2048))
 #undef SLIDE_SET
   return hipSuccess;
@@ -778,8 +789,9 @@ hipError_t launch_build_tables(const HashDev& hd, const TablesDev& td, const flo
                      bh, nslab, entries);
   hipLaunchKernelGGL(part_scan_kernel, dim3(td.L), dim3(1024), 0, s, bh, nslab, nbins, pbase, ctrl);
   const int nsb = run_block(nslab);
-  hipLaunchKernelGGL(part_buckets_kernel, dim3((nbins + 1) / 2, td.L), dim3(256), part_buckets_lds(lb, nsb), s, entries, bh, nslab,
-                     pbase, nbins, lb, td.nb, td.N, td.C, td.off, td.ids, worklist, wl_cap, ctrl, nsb);
+  const int stage = stage_ids(td.N, nbins);
+  hipLaunchKernelGGL(part_buckets_kernel, dim3((nbins + 1) / 2, td.L), dim3(256), part_buckets_lds(lb, nsb, stage), s, entries, bh,
+                     nslab, pbase, nbins, lb, td.nb, td.N, td.C, td.off, td.ids, worklist, wl_cap, ctrl, nsb, stage);
   hipLaunchKernelGGL(short_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, worklist, wl_cap, ctrl);
   hipLaunchKernelGGL(big_buckets_kernel, dim3(2048), dim3(256), 0, s, td.off, td.ids, td.nb, td.N, td.C, policy,
                      r, prio_a, prio_b, worklist, wl_cap, ctrl);
