@@ -35,7 +35,7 @@ PROFILED_TRAFFIC = {
                             "dispatch, mean of 45 dispatches, both factors from the copy kernel in the same runs)"},
     "cfg1-shard167k": {"update_kernel": 212.2e6, "forward_kernel": 51.7e6,
                        "source": "profiles/cfg1-shard167k_step_kernels.md (mean of 45 dispatches)"},
-    "cfg4-825m": {"update_kernel": 587.1e6, "forward_kernel": 39.0e6,
+    "cfg4-825m": {"update_kernel": 587.0e6, "forward_kernel": 39.0e6,
                   "source": "profiles/cfg4-825m_step_kernels.md (mean of 45 dispatches)"},
     "cfg3-wide325k": {"update_kernel": 424.7e6, "forward_kernel": 109.4e6,
                       "source": "profiles/cfg3-wide325k_step_kernels.md (update_sliced_kernel; mean of 45 dispatches "
